@@ -1,0 +1,221 @@
+"""Oracle: batch-aware two-pointer restoration scheduler (Algorithm 1,
+Sec. 3.3) over an integer cost model, its brute-force optimum, and the
+strategy threshold L_delta (Sec. 3.1).
+
+TEST INFRASTRUCTURE ONLY (see package docstring).  Pure Python integers.
+
+Units (Sec. 3.1).  A token-wise request of n tokens has M = ceil(n / C)
+units; unit u is the chunk of tokens [u*C, min((u+1)*C, n)) through all L
+layers.  A layer-wise request has M = L units; unit u is layer u over all n
+tokens.  A request is token-wise iff n >= L_delta (Algorithm 1, mode rule).
+Pointers start at (0, M-1); compute walks up, I/O walks down.
+
+Readings taken where the text leaves room (each is listed in the design
+notes of this repository):
+ * a request stays live while p_comp <= p_io, so the unit where the pointers
+   meet is restored by exactly one engine (the text's "meet ... without
+   redundant work"; the printed termination test would drop that unit when
+   the unit count is odd);
+ * the lock-step loop is simulated event-driven with one compute clock and one
+   I/O clock (single source => one serial channel): at every step the compute
+   candidate is the next live request in round-robin index order at its
+   p_comp, the I/O candidate is the live request with the largest remaining
+   recompute cost at its p_io (re-evaluated after every claim, the
+   "progressive, chunk-level" update), and the engine whose candidate would
+   finish earlier claims it; a tie goes to compute;
+ * I/O priority ties go to the longer context, then to the lower index.
+"""
+from dataclasses import dataclass
+from itertools import product
+
+TOKEN_WISE = 0
+LAYER_WISE = 1
+
+KEY_REMAINING_COST = 0     # Sec. 3.3: "largest remaining recomputation cost"
+KEY_REMAINING_CELLS = 1    # "(i.e., longest length to restore)"
+KEY_MARGINAL = 2           # abstract: highest marginal reduction per I/O time
+
+
+@dataclass
+class CostModel:
+    """All picoseconds.  Per layer of recompute over t tokens starting at
+    position p0:  f_c + alpha*t + beta*ceil(pairs/1024)  with
+    pairs = t*p0 + t*(t+1)/2 causal (query, key) pairs.  Per copied unit:
+    f_io + ceil(bytes*gamma / 2^20)."""
+    f_c: int
+    alpha: int
+    beta: int
+    f_io: int
+    gamma: int
+
+
+@dataclass
+class PlanOpts:
+    chunk_tokens: int
+    l_delta: int
+    n_layers: int
+    kv_bytes_per_token_layer: int
+    force_mode: int = -1            # -1: by l_delta; 0 token-wise; 1 layer-wise
+    io_key: int = KEY_REMAINING_COST
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+def compute_cost(cm, n_layers, t, p0):
+    pairs = t * p0 + t * (t + 1) // 2
+    return n_layers * (cm.f_c + cm.alpha * t + cm.beta * ceil_div(pairs, 1024))
+
+
+def io_cost(cm, n_bytes):
+    return cm.f_io + ceil_div(n_bytes * cm.gamma, 1 << 20)
+
+
+def request_mode(opts, n):
+    if opts.force_mode in (TOKEN_WISE, LAYER_WISE):
+        return opts.force_mode
+    return TOKEN_WISE if n >= opts.l_delta else LAYER_WISE
+
+
+def unit_costs(cm, opts, n, mode):
+    """(a[u], b[u], tokens[u]) for the M units of one request."""
+    a, b, tok = [], [], []
+    if n <= 0:
+        return a, b, tok
+    if mode == TOKEN_WISE:
+        c = opts.chunk_tokens
+        for u in range(ceil_div(n, c)):
+            t = min((u + 1) * c, n) - u * c
+            a.append(compute_cost(cm, opts.n_layers, t, u * c))
+            b.append(io_cost(cm, t * opts.n_layers * opts.kv_bytes_per_token_layer))
+            tok.append(t)
+    else:
+        for _ in range(opts.n_layers):
+            a.append(compute_cost(cm, 1, n, 0))
+            b.append(io_cost(cm, n * opts.kv_bytes_per_token_layer))
+            tok.append(n)
+    return a, b, tok
+
+
+def _split_of(opts, n, mode, p_comp):
+    if mode == TOKEN_WISE:
+        return (mode, min(p_comp * opts.chunk_tokens, n), opts.n_layers)
+    return (mode, n, p_comp)
+
+
+def plan(cm, opts, n_ctx, trace=None):
+    """Run the scheduler.  Returns (splits, stats): splits[i] =
+    (mode, k_tokens, layer_cut); stats = dict(t_comp, t_io, makespan,
+    n_claims).  If `trace` is a list, every claim is appended to it as
+    (engine, request, unit) with engine 0 = compute, 1 = I/O."""
+    b_req = len(n_ctx)
+    modes = [request_mode(opts, n) for n in n_ctx]
+    costs = [unit_costs(cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
+    p_comp = [0] * b_req
+    p_io = [len(costs[i][0]) - 1 for i in range(b_req)]
+    t_c = t_io = 0
+    rr = 0
+    n_claims = 0
+
+    def live(i):
+        return p_comp[i] <= p_io[i]
+
+    def remaining_cost(i):
+        return sum(costs[i][0][p_comp[i]:p_io[i] + 1])
+
+    def remaining_cells(i):
+        per = opts.n_layers if modes[i] == TOKEN_WISE else 1
+        return sum(costs[i][2][p_comp[i]:p_io[i] + 1]) * per
+
+    while any(live(i) for i in range(b_req)):
+        # compute candidate: round-robin
+        ic = next((rr + d) % b_req for d in range(b_req) if live((rr + d) % b_req))
+        # I/O candidate: highest priority key
+        best = None
+        for i in range(b_req):
+            if not live(i):
+                continue
+            if best is None:
+                best = i
+                continue
+            if opts.io_key == KEY_REMAINING_COST:
+                ki, kb = remaining_cost(i), remaining_cost(best)
+            elif opts.io_key == KEY_REMAINING_CELLS:
+                ki, kb = remaining_cells(i), remaining_cells(best)
+            else:  # a_i/b_i vs a_best/b_best by cross-multiplication
+                ki = costs[i][0][p_io[i]] * costs[best][1][p_io[best]]
+                kb = costs[best][0][p_io[best]] * costs[i][1][p_io[i]]
+            if ki > kb or (ki == kb and n_ctx[i] > n_ctx[best]):
+                best = i
+        iio = best
+        fin_c = t_c + costs[ic][0][p_comp[ic]]
+        fin_io = t_io + costs[iio][1][p_io[iio]]
+        if fin_c <= fin_io:
+            if trace is not None:
+                trace.append((0, ic, p_comp[ic]))
+            t_c = fin_c
+            p_comp[ic] += 1
+            rr = (ic + 1) % b_req
+        else:
+            if trace is not None:
+                trace.append((1, iio, p_io[iio]))
+            t_io = fin_io
+            p_io[iio] -= 1
+        n_claims += 1
+
+    splits = [_split_of(opts, n_ctx[i], modes[i], p_comp[i]) for i in range(b_req)]
+    stats = dict(t_comp=t_c, t_io=t_io, makespan=max(t_c, t_io), n_claims=n_claims)
+    return splits, stats
+
+
+def split_times(cm, opts, n_ctx, unit_splits, modes=None):
+    """(t_comp, t_io) if request i recomputes its first unit_splits[i] units
+    and loads the rest."""
+    t_c = t_io = 0
+    for i, n in enumerate(n_ctx):
+        mode = request_mode(opts, n) if modes is None else modes[i]
+        a, b, _ = unit_costs(cm, opts, n, mode)
+        t_c += sum(a[:unit_splits[i]])
+        t_io += sum(b[unit_splits[i]:])
+    return t_c, t_io
+
+
+def brute_force(cm, opts, n_ctx):
+    """Minimum over all split vectors of max(sum claimed a, sum claimed b).
+    Exponential; tiny batches only.  Returns (best_makespan, best_vector)."""
+    modes = [request_mode(opts, n) for n in n_ctx]
+    ms = [len(unit_costs(cm, opts, n, m)[0]) for n, m in zip(n_ctx, modes)]
+    best, arg = None, None
+    for vec in product(*[range(m + 1) for m in ms]):
+        t_c, t_io = split_times(cm, opts, n_ctx, vec, modes)
+        j = max(t_c, t_io)
+        if best is None or j < best:
+            best, arg = j, vec
+    return best, arg
+
+
+def derive_l_delta(cm, opts, n_max):
+    """L_delta = min{N : T_token(N) <= T_layer(N)} (Sec. 3.1) on the grid of
+    multiples of C up to n_max, with T_* the single-request makespans under
+    the cost model.  Returns n_max + C if token-wise never wins."""
+    c = opts.chunk_tokens
+    n = c
+    while n <= n_max:
+        j = []
+        for mode in (TOKEN_WISE, LAYER_WISE):
+            o = PlanOpts(opts.chunk_tokens, 0, opts.n_layers,
+                         opts.kv_bytes_per_token_layer, mode, opts.io_key)
+            j.append(plan(cm, o, [n])[1]["makespan"])
+        if j[0] <= j[1]:
+            return n
+        n += c
+    return n_max + c
+
+
+def all_recompute(opts, n_ctx):
+    return [(TOKEN_WISE, n, opts.n_layers) for n in n_ctx]
+
+
+def all_load(opts, n_ctx):
+    return [(TOKEN_WISE, 0, opts.n_layers) for n in n_ctx]

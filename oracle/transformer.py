@@ -1,0 +1,237 @@
+"""Oracle: decoder-only transformer forward and hybrid-restore semantics.
+
+TEST INFRASTRUCTURE ONLY (see package docstring).
+
+The method is exact: a KV cache restored partly by recomputation and partly by
+loading must equal the cache a full prefill produces, because token t's state
+depends only on tokens <= t (causal dependency) and layer l's only on layers
+< l (feed-forward dependency) -- Sec. 1 items (i)-(ii), Sec. 3.1.  The oracle
+is therefore the plain definition of the forward pass, written out with numpy
+matmuls and no blocking or fusion.
+
+Model family (Sec. 4.1 names Llama-3.1-8B / Qwen3-8B; widths come from the
+benchmark configurations): pre-norm decoder, RMSNorm with unit-initialised
+gain, rotary position embedding in the rotate-half pairing (j, j + hd/2) with
+theta_j = base^(-2j/hd) and absolute positions, grouped-query attention where
+Q head j reads KV head j // (Hq/Hkv), SwiGLU MLP, no biases, untied LM head.
+
+All arithmetic runs in `dtype` (float64 by default; float32 on request for the
+timed baseline).  Rotary angles are always formed in float64.
+"""
+import numpy as np
+
+
+def rmsnorm(x, gain, eps, dtype=np.float64):
+    """x * rsqrt(mean(x^2) + eps) * gain, row-wise."""
+    x = np.asarray(x, dtype=dtype)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + dtype(eps)) * np.asarray(gain, dtype=dtype)
+
+
+def rope_angles(positions, head_dim, base):
+    """cos, sin of pos * base^(-2j/hd), j in [0, hd/2); float64."""
+    j = np.arange(head_dim // 2, dtype=np.float64)
+    theta = np.float64(base) ** (-2.0 * j / np.float64(head_dim))
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * theta[None, :]
+    return np.cos(ang), np.sin(ang)
+
+
+def rope(x, positions, base, dtype=np.float64):
+    """Rotate x[T, H, hd]: pair (j, j+hd/2) turns by angle pos*theta_j."""
+    x = np.asarray(x, dtype=dtype)
+    hd = x.shape[-1]
+    half = hd // 2
+    cos, sin = rope_angles(positions, hd, base)
+    cos = cos.astype(dtype)[:, None, :]
+    sin = sin.astype(dtype)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * cos - x2 * sin, x2 * cos + x1 * sin], axis=-1)
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def causal_attention(q, k, v, q_pos, dtype=np.float64):
+    """q[Tq,Hq,hd] at absolute positions q_pos[Tq]; k, v [Tk,Hkv,hd] hold
+    positions 0..Tk-1.  Query at position p sees keys 0..p."""
+    q = np.asarray(q, dtype=dtype)
+    k = np.asarray(k, dtype=dtype)
+    v = np.asarray(v, dtype=dtype)
+    tq, hq, hd = q.shape
+    tk, hkv, _ = k.shape
+    group = hq // hkv
+    scale = dtype(1.0) / np.sqrt(dtype(hd))
+    visible = np.arange(tk)[None, :] <= np.asarray(q_pos)[:, None]
+    out = np.empty((tq, hq, hd), dtype=dtype)
+    for h in range(hq):
+        g = h // group
+        s = (q[:, h, :] @ k[:, g, :].T) * scale
+        s = np.where(visible, s, -np.inf)
+        s = s - np.max(s, axis=-1, keepdims=True)
+        p = np.exp(s)
+        p = p / np.sum(p, axis=-1, keepdims=True)
+        out[:, h, :] = p @ v[:, g, :]
+    return out
+
+
+class KVCache:
+    """Per-layer K and V, [n_layers][T, Hkv, hd], unrounded."""
+
+    def __init__(self, n_layers):
+        self.k = [None] * n_layers
+        self.v = [None] * n_layers
+
+    def copy(self):
+        c = KVCache(len(self.k))
+        c.k = [None if a is None else a.copy() for a in self.k]
+        c.v = [None if a is None else a.copy() for a in self.v]
+        return c
+
+    def n_tokens(self, layer=0):
+        return 0 if self.k[layer] is None else self.k[layer].shape[0]
+
+
+def embed(weights, tokens, dtype=np.float64):
+    e = weights.f32("embed")
+    return e[np.asarray(tokens, dtype=np.int64)].astype(dtype)
+
+
+def layer_forward(shape, lw, gain, h, positions, k_past, v_past,
+                  dtype=np.float64):
+    """One decoder layer over rows h[T, d] at `positions`, attending to the
+    given past K/V (positions 0..P-1, contiguous, P == positions[0]) followed
+    by the rows' own K/V.  Returns (h_out, k_new, v_new)."""
+    s = shape
+    t = h.shape[0]
+    a = rmsnorm(h, gain, s.rms_eps, dtype)
+    qkv = a @ lw["wqkv"].astype(dtype).T
+    nq = s.n_q_heads * s.head_dim
+    nk = s.n_kv_heads * s.head_dim
+    q = qkv[:, :nq].reshape(t, s.n_q_heads, s.head_dim)
+    k = qkv[:, nq:nq + nk].reshape(t, s.n_kv_heads, s.head_dim)
+    v = qkv[:, nq + nk:].reshape(t, s.n_kv_heads, s.head_dim)
+    q = rope(q, positions, s.rope_base, dtype)
+    k = rope(k, positions, s.rope_base, dtype)
+    if k_past is not None and k_past.shape[0] > 0:
+        k_all = np.concatenate([np.asarray(k_past, dtype=dtype), k], axis=0)
+        v_all = np.concatenate([np.asarray(v_past, dtype=dtype), v], axis=0)
+    else:
+        k_all, v_all = k, v
+    o = causal_attention(q, k_all, v_all, positions, dtype)
+    h = h + o.reshape(t, nq) @ lw["wo"].astype(dtype).T
+    u = rmsnorm(h, gain, s.rms_eps, dtype)
+    gate = u @ lw["w_gate"].astype(dtype).T
+    up = u @ lw["w_up"].astype(dtype).T
+    h = h + (silu(gate) * up) @ lw["w_down"].astype(dtype).T
+    return h, k, v
+
+
+def prefill(shape, weights, tokens, past=None, n_layers=None,
+            dtype=np.float64, return_hidden=False):
+    """Run `tokens` (positions P..P+T-1 where P = tokens already in `past`)
+    through layers [0, n_layers).  Returns (KVCache of the new rows' K/V for
+    those layers, final hidden rows h[T, d])."""
+    n_layers = shape.n_layers if n_layers is None else n_layers
+    t = len(tokens)
+    p0 = 0 if past is None else past.n_tokens(0)
+    positions = np.arange(p0, p0 + t)
+    gain = weights.norm_gain()
+    h = embed(weights, tokens, dtype)
+    out = KVCache(shape.n_layers)
+    hidden_in = []
+    for l in range(n_layers):
+        if return_hidden:
+            hidden_in.append(h.copy())
+        lw = weights.layer_f32(l)
+        kp = None if past is None else past.k[l]
+        vp = None if past is None else past.v[l]
+        h, k, v = layer_forward(shape, lw, gain, h, positions, kp, vp, dtype)
+        out.k[l], out.v[l] = k, v
+    if return_hidden:
+        return out, h, hidden_in
+    return out, h
+
+
+def logits_last(shape, weights, h_last, dtype=np.float64):
+    """Final RMSNorm and LM head on one hidden row."""
+    a = rmsnorm(h_last[None, :], weights.norm_gain(), shape.rms_eps, dtype)
+    return (a @ weights.f32("lm_head").astype(dtype).T)[0]
+
+
+def restore(shape, weights, ctx_tokens, kv_full, k_tokens, layer_cut,
+            dtype=np.float64):
+    """Hybrid restoration of one request (Sec. 3.1): cells (token < k_tokens,
+    layer < layer_cut) are recomputed from the first k_tokens tokens alone;
+    every other cell is taken from the stored cache `kv_full`."""
+    n = len(ctx_tokens)
+    assert 0 <= k_tokens <= n and 0 <= layer_cut <= shape.n_layers
+    cache = KVCache(shape.n_layers)
+    for l in range(shape.n_layers):
+        cache.k[l] = np.array(kv_full.k[l][:n], dtype=dtype, copy=True)
+        cache.v[l] = np.array(kv_full.v[l][:n], dtype=dtype, copy=True)
+    if k_tokens > 0 and layer_cut > 0:
+        rec, _ = prefill(shape, weights, ctx_tokens[:k_tokens],
+                         n_layers=layer_cut, dtype=dtype)
+        for l in range(layer_cut):
+            cache.k[l][:k_tokens] = rec.k[l]
+            cache.v[l][:k_tokens] = rec.v[l]
+    return cache
+
+
+def first_token_logits(shape, weights, cache, new_tokens, dtype=np.float64):
+    """Prefill the new-turn tokens over a restored cache; return (logits at
+    the last new token, KVCache of the new tokens' own K/V)."""
+    kv_new, h = prefill(shape, weights, new_tokens, past=cache, dtype=dtype)
+    return logits_last(shape, weights, h[-1], dtype), kv_new
+
+
+def full_reference(shape, weights, ctx_tokens, new_tokens, dtype=np.float64):
+    """Full prefill of context then new tokens: (kv_ctx, kv_new, logits)."""
+    kv_ctx, _ = prefill(shape, weights, ctx_tokens, dtype=dtype)
+    logits, kv_new = first_token_logits(shape, weights, kv_ctx, new_tokens, dtype)
+    return kv_ctx, kv_new, logits
+
+
+def layer_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
+                              v_cache, dtype=np.float64):
+    """Teacher-forced check of one layer on a few sampled rows: given the
+    rows' input hidden states and the layer's K/V cache for positions
+    0..max(positions) (which must already include the rows' own K/V), return
+    (k_rows, v_rows, h_out_rows)."""
+    s = shape
+    t = h_rows.shape[0]
+    a = rmsnorm(h_rows, gain, s.rms_eps, dtype)
+    qkv = a @ lw["wqkv"].astype(dtype).T
+    nq = s.n_q_heads * s.head_dim
+    nk = s.n_kv_heads * s.head_dim
+    q = rope(qkv[:, :nq].reshape(t, s.n_q_heads, s.head_dim), positions,
+             s.rope_base, dtype)
+    k = rope(qkv[:, nq:nq + nk].reshape(t, s.n_kv_heads, s.head_dim), positions,
+             s.rope_base, dtype)
+    v = qkv[:, nq + nk:].reshape(t, s.n_kv_heads, s.head_dim)
+    o = causal_attention(q, k_cache, v_cache, positions, dtype)
+    h = np.asarray(h_rows, dtype=dtype) + o.reshape(t, nq) @ lw["wo"].astype(dtype).T
+    u = rmsnorm(h, gain, s.rms_eps, dtype)
+    h = h + (silu(u @ lw["w_gate"].astype(dtype).T) *
+             (u @ lw["w_up"].astype(dtype).T)) @ lw["w_down"].astype(dtype).T
+    return k, v, h
+
+
+def kv_to_pages(shape, cache, n_tokens, page_tokens=16):
+    """Lay a request's cache out as the host KV block:
+    [layer][page][K|V][kv_head][slot][hd] in the model's storage precision
+    (float32 here; callers round for 16-bit models).  Unused slots of the
+    last page are zero."""
+    s = shape
+    n_pages = -(-n_tokens // page_tokens)
+    out = np.zeros((s.n_layers, n_pages, 2, s.n_kv_heads, page_tokens,
+                    s.head_dim), dtype=np.float32)
+    for l in range(s.n_layers):
+        for which, src in ((0, cache.k[l]), (1, cache.v[l])):
+            pad = np.zeros((n_pages * page_tokens, s.n_kv_heads, s.head_dim),
+                           dtype=np.float32)
+            pad[:n_tokens] = src[:n_tokens]
+            out[l, :, which] = pad.reshape(n_pages, page_tokens, s.n_kv_heads,
+                                           s.head_dim).transpose(0, 2, 1, 3)
+    return out

@@ -1,0 +1,236 @@
+"""Pins for oracle/planner.py: Eq. 1 closed forms, brute force on tiny
+batches, structural properties of Algorithm 1 (Sec. 3.1-3.3).  CPU only."""
+import numpy as np
+import pytest
+
+from oracle import planner as P
+from workloads import hand_cost_model
+
+
+def cm_of(kind):
+    return P.CostModel(**hand_cost_model(kind))
+
+
+def rand_cm(rng, overheads=True):
+    return P.CostModel(
+        f_c=int(rng.integers(0, 50_000_000)) if overheads else 0,
+        alpha=int(rng.integers(100_000, 2_000_000)),
+        beta=int(rng.integers(0, 60_000)),
+        f_io=int(rng.integers(0, 20_000_000)) if overheads else 0,
+        gamma=int(rng.integers(5_000_000, 900_000_000)))
+
+
+# ------------------------------------------------------------ Algorithm 1 init
+def test_mode_rule_and_pointer_init():
+    opts = P.PlanOpts(512, 2048, 32, 4096)
+    assert P.request_mode(opts, 2048) == P.TOKEN_WISE       # N_c >= L_delta
+    assert P.request_mode(opts, 2047) == P.LAYER_WISE
+    a, b, tok = P.unit_costs(cm_of("balanced"), opts, 1300, P.TOKEN_WISE)
+    assert len(a) == 3 and tok == [512, 512, 276]           # ceil(N_c / C) chunks
+    a, b, tok = P.unit_costs(cm_of("balanced"), opts, 1300, P.LAYER_WISE)
+    assert len(a) == 32 and tok == [1300] * 32              # L units
+
+
+def test_cost_formula_by_hand():
+    cm = P.CostModel(f_c=7, alpha=3, beta=5, f_io=11, gamma=13)
+    # 2 layers, 4 tokens starting at position 6: pairs = 4*6 + 4*5/2 = 34 -> ceil(34/1024)=1
+    assert P.compute_cost(cm, 2, 4, 6) == 2 * (7 + 3 * 4 + 5 * 1)
+    assert P.compute_cost(cm, 1, 2048, 0) == 7 + 3 * 2048 + 5 * ((2048 * 2049 // 2 + 1023) // 1024)
+    assert P.io_cost(cm, 1 << 20) == 11 + 13
+    assert P.io_cost(cm, (1 << 20) + 1) == 11 + 14           # ceil
+
+
+def test_later_chunks_cost_more_to_recompute_not_to_load():
+    a, b, _ = P.unit_costs(cm_of("mi355x_like"), P.PlanOpts(512, 0, 32, 4096), 8192, P.TOKEN_WISE)
+    assert all(a[i] < a[i + 1] for i in range(len(a) - 1))   # quadratic attention term
+    assert len(set(b)) == 1                                  # I/O linear in bytes
+
+
+# ------------------------------------------------------------------ Eq. 1 pins
+@pytest.mark.parametrize("ratio", [0.25, 1.0, 3.0])
+def test_single_request_uniform_costs_meet_at_the_closed_form_split(ratio):
+    # layer-wise, uniform units: a per layer = alpha*n, b per layer = gamma*bytes/2^20
+    L, n = 64, 1024
+    alpha = 1_000_000
+    per_layer_bytes = 1 << 20
+    gamma = int(alpha * n * ratio)          # T_io / T_comp = ratio
+    cm = P.CostModel(0, alpha, 0, 0, gamma)
+    opts = P.PlanOpts(512, 0, L, per_layer_bytes // n, P.LAYER_WISE)
+    splits, st = P.plan(cm, opts, [n])
+    t_comp, t_io = L * alpha * n, L * gamma
+    l_star = L * t_io / (t_comp + t_io)                      # Eq. 1
+    t_star = t_comp * t_io / (t_comp + t_io)
+    assert abs(splits[0][2] - l_star) <= 1
+    assert splits[0][1] == n
+    unit = max(alpha * n, gamma)
+    assert t_star <= st["makespan"] <= t_star + unit
+    assert st["makespan"] <= min(t_comp, t_io)               # T* <= min(T_comp, T_io)
+
+
+def test_makespan_tends_to_the_harmonic_mean_as_units_shrink():
+    alpha, gamma_total = 1_000_000, 3_000_000 * 4096
+    gaps = []
+    for L in (8, 64, 512):
+        cm = P.CostModel(0, alpha * 512 // L, 0, 0, gamma_total // L)
+        opts = P.PlanOpts(512, 0, L, (1 << 20) // 4096, P.LAYER_WISE)
+        _, st = P.plan(cm, opts, [4096])
+        t_comp, t_io = P.split_times(cm, opts, [4096], [L])[0], P.split_times(cm, opts, [4096], [0])[1]
+        t_star = t_comp * t_io / (t_comp + t_io)
+        gaps.append(st["makespan"] / t_star - 1.0)
+    assert gaps[0] >= gaps[1] >= gaps[2] and gaps[2] < 0.01
+
+
+# ------------------------------------------------------------- brute force pins
+def test_single_request_matches_brute_force_exactly():
+    rng = np.random.default_rng(21)
+    for trial in range(300):
+        cm = rand_cm(rng)
+        mode = int(rng.integers(0, 2))
+        opts = P.PlanOpts(16 * int(rng.integers(1, 5)), 0, int(rng.integers(1, 9)),
+                          int(rng.choice([512, 4096])), mode)
+        n = int(rng.integers(1, 16 * 40))
+        _, st = P.plan(cm, opts, [n])
+        best, _ = P.brute_force(cm, opts, [n])
+        assert st["makespan"] == best, (trial, cm, opts, n)
+
+
+def test_tiny_batches_shared_model_full_chunks_match_brute_force():
+    rng = np.random.default_rng(22)
+    for trial in range(400):
+        cm = rand_cm(rng, overheads=False)
+        c = 64
+        opts = P.PlanOpts(c, 0, 4, 4096, P.TOKEN_WISE)
+        n_ctx = [c * int(rng.integers(1, 7)) for _ in range(int(rng.integers(1, 5)))]
+        _, st = P.plan(cm, opts, n_ctx)
+        best, _ = P.brute_force(cm, opts, n_ctx)
+        # one shared cost model, full chunks, equal I/O unit cost: compute takes the
+        # cheapest units first and I/O the dearest first, so the batch behaves as one
+        # global two-pointer and the schedule is optimal
+        assert st["makespan"] == best, (trial, n_ctx, cm)
+
+
+def test_tiny_batches_general_are_within_one_unit_of_brute_force():
+    rng = np.random.default_rng(23)
+    n_equal = 0
+    trials = 300
+    for trial in range(trials):
+        cm = rand_cm(rng)
+        opts = P.PlanOpts(32, int(rng.choice([0, 64, 10_000])), 3, 4096)
+        n_ctx = [int(rng.integers(1, 32 * 5)) for _ in range(int(rng.integers(1, 5)))]
+        splits, st = P.plan(cm, opts, n_ctx)
+        best, _ = P.brute_force(cm, opts, n_ctx)
+        worst_unit = 0
+        for n in n_ctx:
+            a, b, _ = P.unit_costs(cm, opts, n, P.request_mode(opts, n))
+            worst_unit = max(worst_unit, max(a), max(b))
+        assert best <= st["makespan"] <= best + worst_unit, (trial, n_ctx, cm)
+        n_equal += st["makespan"] == best
+    assert n_equal > trials // 4
+
+
+# ------------------------------------------------------------ structure of plans
+def _check_structure(cm, opts, n_ctx):
+    trace = []
+    splits, st = P.plan(cm, opts, n_ctx, trace=trace)
+    claimed = {}
+    for eng, i, u in trace:
+        assert (i, u) not in claimed                          # every unit claimed once
+        claimed[(i, u)] = eng
+    for i, n in enumerate(n_ctx):
+        mode = P.request_mode(opts, n)
+        m = len(P.unit_costs(cm, opts, n, mode)[0])
+        engines = [claimed[(i, u)] for u in range(m)]         # ... and every unit is claimed
+        assert engines == sorted(engines)                     # recomputed prefix, loaded suffix
+        n_comp = engines.count(0)
+        assert splits[i][0] == mode
+        if mode == P.TOKEN_WISE:
+            assert splits[i][1] == min(n_comp * opts.chunk_tokens, n) and splits[i][2] == opts.n_layers
+        else:
+            assert splits[i][1] == n and splits[i][2] == n_comp
+    t_c, t_io = P.split_times(cm, opts, n_ctx,
+                              [sum(1 for (j, u), e in claimed.items() if j == i and e == 0)
+                               for i in range(len(n_ctx))])
+    assert (t_c, t_io) == (st["t_comp"], st["t_io"])
+    all_c = P.split_times(cm, opts, n_ctx, [10 ** 9] * len(n_ctx))[0]
+    all_io = P.split_times(cm, opts, n_ctx, [0] * len(n_ctx))[1]
+    assert st["makespan"] <= min(all_c, all_io) or min(all_c, all_io) == 0
+    return splits, st, trace
+
+
+def test_structure_on_random_batches():
+    rng = np.random.default_rng(24)
+    for _ in range(200):
+        cm = rand_cm(rng)
+        opts = P.PlanOpts(64, int(rng.choice([0, 256, 100_000])), int(rng.integers(1, 12)), 4096,
+                          io_key=int(rng.integers(0, 3)))
+        n_ctx = [int(rng.integers(0, 2000)) for _ in range(int(rng.integers(1, 9)))]
+        _check_structure(cm, opts, n_ctx)
+
+
+def test_structure_on_benchmark_shaped_batch():
+    from workloads import make_batch
+    b = make_batch("cfg4")
+    opts = P.PlanOpts(512, 2048, 32, 4096)
+    splits, st, _ = _check_structure(cm_of("mi355x_like"), opts, b.n_ctx)
+    assert any(s[0] == P.LAYER_WISE for s in splits) and any(s[0] == P.TOKEN_WISE for s in splits)
+
+
+def test_io_goes_to_the_request_with_most_remaining_recompute():
+    cm = cm_of("balanced")
+    opts = P.PlanOpts(512, 0, 32, 4096, P.TOKEN_WISE)
+    trace = []
+    P.plan(cm, opts, [2048, 16384, 4096], trace=trace)
+    first_io = next(t for t in trace if t[0] == 1)
+    assert first_io[1:] == (1, 31)                            # longest request, its last chunk
+    # I/O claims first under a fast link, with both requests untouched: the
+    # tie on remaining cost and on length goes to the lower index
+    trace = []
+    P.plan(cm_of("mi355x_like"), opts, [4096, 4096], trace=trace)
+    assert trace[0] == (1, 0, 7)
+    # after compute took chunk 0 of request 0, request 1 has more left to recompute
+    trace = []
+    P.plan(cm, opts, [4096, 4096], trace=trace)
+    assert trace[0] == (0, 0, 0) and next(t for t in trace if t[0] == 1)[1] == 1
+
+
+def test_slower_io_never_shrinks_the_recomputed_part():
+    rng = np.random.default_rng(25)
+    for _ in range(60):
+        cm = rand_cm(rng)
+        opts = P.PlanOpts(64, 0, 4, 4096, P.TOKEN_WISE)
+        n = [int(rng.integers(64, 3000))]
+        k_prev = -1
+        for scale in (1, 2, 4, 8, 16):
+            cm2 = P.CostModel(cm.f_c, cm.alpha, cm.beta, cm.f_io * scale, cm.gamma * scale)
+            k = P.plan(cm2, opts, n)[0][0][1]
+            assert k >= k_prev
+            k_prev = k
+
+
+def test_degenerate_inputs():
+    cm = cm_of("balanced")
+    opts = P.PlanOpts(512, 0, 32, 4096)
+    splits, st = P.plan(cm, opts, [])
+    assert splits == [] and st["makespan"] == 0
+    splits, st = P.plan(cm, opts, [0, 5])
+    assert splits[0] == (P.TOKEN_WISE, 0, 32) and st["n_claims"] == 1
+    assert splits[1][1] in (0, 5)
+
+
+def test_l_delta_is_the_first_grid_point_where_token_wise_wins():
+    cm = cm_of("balanced")
+    opts = P.PlanOpts(512, 0, 32, 4096)
+    ld = P.derive_l_delta(cm, opts, 32768)
+    assert ld % 512 == 0 and 512 < ld <= 32768
+
+    def j(n, mode):
+        return P.plan(cm, P.PlanOpts(512, 0, 32, 4096, mode), [n])[1]["makespan"]
+    assert j(ld, P.TOKEN_WISE) <= j(ld, P.LAYER_WISE)
+    for n in range(512, ld, 512):
+        assert j(n, P.TOKEN_WISE) > j(n, P.LAYER_WISE)
+
+
+def test_baseline_plans():
+    opts = P.PlanOpts(512, 0, 32, 4096)
+    assert P.all_recompute(opts, [5, 7]) == [(0, 5, 32), (0, 7, 32)]
+    assert P.all_load(opts, [5, 7]) == [(0, 0, 32), (0, 0, 32)]
