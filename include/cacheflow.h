@@ -1,0 +1,285 @@
+/*
+ * cacheflow.h -- C ABI of the batched hybrid KV-cache restoration library for
+ * AMD MI355X (gfx950).
+ *
+ * Problem (Sec. 3 of the CacheFlow paper): a batch of requests arrives, each
+ * with a cached prefix of N_c tokens whose KV cache sits in external storage
+ * (here: pinned host memory).  Restore every request's KV cache into GPU
+ * memory as fast as possible by recomputing part of it on the GPU while the
+ * rest is loaded over the host link, then run the new-turn prompt over the
+ * restored cache to emit the first token (TTFT = restoration + that prefill).
+ *
+ * A restoration split for request i is (mode, k_tokens, layer_cut): cells
+ * (token t < k_tokens, layer l < layer_cut) are recomputed; every other cell
+ * of the request is loaded.  Token-wise mode (Sec. 3.1) yields layer_cut = L
+ * and k_tokens a multiple of the chunk size; layer-wise mode yields
+ * k_tokens = n_ctx and layer_cut = the cut-over layer.
+ *
+ * Conventions
+ *  - Every call returns an int status: CF_OK (0) or a negative cf_status.
+ *    No exception or abort crosses this boundary.  cf_last_error() returns a
+ *    thread-local human-readable message for the last failure.
+ *  - "host" pointers are ordinary CPU pointers; "device" pointers are HIP
+ *    device memory on the current device.  The library never frees caller
+ *    memory.  Objects it creates (cf_cache, cf_ctx) are destroyed by their
+ *    *_destroy call.
+ *  - Nothing here is thread-safe per object; use one object per thread.
+ *
+ * Matrix layout: every weight matrix is output-major, W[out][in], contiguous,
+ * so y = x W^T.  Element type is the model dtype (float or bf16); norm gains
+ * are always float.
+ *
+ * KV page layout (device pool and host blocks share it).  A page holds
+ * page_tokens = 16 consecutive tokens of ONE layer of one request:
+ *     K part: [kv_head][slot 0..15][head_dim]
+ *     V part: [kv_head][head_dim][slot 0..15]      (V is stored transposed so
+ *                                                   P*V reads 16-byte vectors)
+ * K part first, then V part; page_bytes = 2*Hkv*16*hd*sizeof(elem).
+ * Device pool : pool[layer][page_id]            (layer stride = n_pages pages)
+ * Host block  : host_kv[layer][page 0..ceil(n_ctx/16)-1]  (layer-major, so a
+ *               token suffix of one layer and a whole layer are contiguous).
+ *               Slots past n_ctx in the last page are ignored.
+ */
+#ifndef CACHEFLOW_H
+#define CACHEFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CF_PAGE_TOKENS 16
+
+enum cf_status {
+    CF_OK = 0,
+    CF_ERR_INVALID_ARG = -1,     /* null pointer, negative size, bad enum          */
+    CF_ERR_INVALID_PLAN = -2,    /* split outside [0,n_ctx] x [0,L]                */
+    CF_ERR_OUT_OF_PAGES = -3,    /* page pool exhausted                            */
+    CF_ERR_HIP = -4,             /* a HIP call failed; see cf_last_error()         */
+    CF_ERR_UNKNOWN_REQUEST = -5, /* req_id not allocated / already allocated       */
+    CF_ERR_WORKSPACE = -6,       /* workspace too small / batch exceeds ctx limits */
+    CF_ERR_UNSUPPORTED = -7      /* shape outside what the kernels were built for  */
+};
+
+enum cf_dtype { CF_F32 = 0, CF_BF16 = 1 };
+enum cf_mode { CF_TOKEN_WISE = 0, CF_LAYER_WISE = 1 };
+enum cf_io_key {
+    CF_KEY_REMAINING_COST = 0,   /* Sec. 3.3: largest remaining recomputation cost */
+    CF_KEY_REMAINING_CELLS = 1,  /* Sec. 3.3: "longest length to restore"           */
+    CF_KEY_MARGINAL = 2          /* abstract: highest recompute saved per I/O time  */
+};
+
+const char* cf_status_str(int status);
+const char* cf_last_error(void);
+
+/* ------------------------------------------------------------------ planner
+ * Batch-aware two-pointer scheduler, Algorithm 1 / Sec. 3.3, over an integer
+ * cost model.  Pure host code: no GPU, no context.                          */
+
+/* All picoseconds.  One layer of recompute over t tokens that start at
+ * position p0 costs  f_c + alpha*t + beta*ceil(pairs/1024)  with
+ * pairs = t*p0 + t*(t+1)/2 causal (query,key) pairs (Sec. 3.1: superlinear
+ * T_comp with fixed overheads).  Loading one unit of `bytes` bytes costs
+ * f_io + ceil(bytes*gamma / 2^20)  (Sec. 3.1: T_io linear, bandwidth-bound). */
+typedef struct cf_cost_model {
+    int64_t f_c, alpha, beta, f_io, gamma;
+} cf_cost_model;
+
+typedef struct cf_plan_opts {
+    int32_t chunk_tokens;             /* C (Sec. 3.1), > 0                           */
+    int32_t l_delta;                  /* token-wise iff n_ctx >= l_delta (Alg. 1)    */
+    int32_t n_layers;                 /* L                                           */
+    int32_t kv_bytes_per_token_layer; /* 2*Hkv*hd*sizeof(elem)                       */
+    int32_t force_mode;               /* -1 use l_delta; else a cf_mode for all      */
+    int32_t io_key;                   /* cf_io_key                                   */
+} cf_plan_opts;
+
+typedef struct cf_split {
+    int32_t mode;       /* cf_mode the planner used (informational for execution) */
+    int32_t k_tokens;   /* tokens [0,k_tokens) are recomputed ...                  */
+    int32_t layer_cut;  /* ... in layers [0,layer_cut); all other cells are loaded */
+} cf_split;
+
+typedef struct cf_claim {
+    int32_t engine;     /* 0 = compute, 1 = I/O */
+    int32_t request;
+    int32_t unit;       /* chunk index (token-wise) or layer index (layer-wise)   */
+} cf_claim;
+
+typedef struct cf_plan_stats {
+    int64_t t_comp, t_io, makespan;   /* predicted busy time of each engine, ps */
+    int32_t n_claims;                 /* units scheduled = sum of unit counts   */
+    int32_t n_trace;                  /* claims written to `trace`              */
+} cf_plan_stats;
+
+/* Plan a batch.  n_ctx: host int32[B] (each >= 0).  out_splits: host
+ * cf_split[B].  trace (may be NULL): host cf_claim[trace_cap], receives the
+ * claims in scheduling order (truncated at trace_cap).  stats may be NULL.
+ * Errors: CF_ERR_INVALID_ARG on null/negative/zero chunk or layers.         */
+int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                    const int32_t* n_ctx, cf_split* out_splits, cf_plan_stats* stats,
+                    cf_claim* trace, int32_t trace_cap);
+
+/* (t_comp, t_io) in ps of a given split vector under the cost model, with the
+ * same unit accounting as the planner (k_tokens rounded up to whole chunks in
+ * token-wise mode).  splits: host cf_split[B] whose `mode` fields are used.  */
+int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                 const int32_t* n_ctx, const cf_split* splits, int64_t* t_comp,
+                 int64_t* t_io);
+
+/* L_delta = min{N : T_token(N) <= T_layer(N)} (Sec. 3.1, adaptive strategy)
+ * searched on multiples of chunk_tokens up to n_max; n_max + C if none.     */
+int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t n_max,
+                      int32_t* l_delta);
+
+/* --------------------------------------------------------------- page table
+ * Paged KV cache bookkeeping (the serving substrate of Sec. 4.1).  Policy is
+ * part of the contract: an allocation takes the ceil(n/16) lowest-numbered
+ * free pages in ascending order.  Host-only object; `pool` is a device
+ * pointer that is stored, never dereferenced by these calls (may be NULL for
+ * host-only use).                                                           */
+typedef struct cf_cache cf_cache;
+
+/* n_pages = pool_bytes / (n_layers * page_bytes).                           */
+int cf_cache_create(void* pool, size_t pool_bytes, int32_t n_layers, int32_t n_kv_heads,
+                    int32_t head_dim, int32_t dtype, cf_cache** out);
+void cf_cache_destroy(cf_cache* cache);
+int cf_cache_n_pages(const cf_cache* cache);
+int cf_cache_n_free(const cf_cache* cache);
+size_t cf_cache_page_bytes(const cf_cache* cache);
+/* Reserve pages for n_tokens (context + new tokens) of request req_id.
+ * CF_ERR_UNKNOWN_REQUEST if req_id is live, CF_ERR_OUT_OF_PAGES if short.   */
+int cf_cache_alloc(cf_cache* cache, uint64_t req_id, int32_t n_tokens);
+int cf_cache_free(cf_cache* cache, uint64_t req_id);
+/* Copy the request's page ids to out[0..cap); *n_pages receives the count
+ * (even when cap is too small, in which case nothing is written past cap).  */
+int cf_cache_page_table(const cf_cache* cache, uint64_t req_id, int32_t* out, int32_t cap,
+                        int32_t* n_pages);
+
+/* Bytes of one request's host KV block for n_ctx tokens.                    */
+size_t cf_host_kv_bytes(int32_t n_layers, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                        int32_t n_ctx);
+
+/* ----------------------------------------------------------------- executor */
+typedef struct cf_model_desc {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;                 /* cf_dtype of weights, activations fed to GEMMs, KV */
+    float rope_base;               /* rotate-half RoPE, theta_j = base^(-2j/hd)         */
+    float rms_eps;
+} cf_model_desc;
+
+typedef struct cf_layer_weights {  /* device pointers, borrowed for the ctx lifetime */
+    const float* attn_norm;        /* [d]                                  */
+    const void* wqkv;              /* [(Hq+2Hkv)*hd, d]: Q heads, K heads, V heads */
+    const void* wo;                /* [d, Hq*hd]                           */
+    const float* mlp_norm;         /* [d]                                  */
+    const void* w_gate;            /* [ffn, d]                             */
+    const void* w_up;              /* [ffn, d]                             */
+    const void* w_down;            /* [d, ffn]                             */
+} cf_layer_weights;
+
+typedef struct cf_weights {
+    const void* embed;             /* device [vocab, d]                    */
+    const void* lm_head;           /* device [vocab, d]                    */
+    const float* final_norm;       /* device [d]                           */
+    const cf_layer_weights* layers;/* HOST array of n_layers entries (copied) */
+} cf_weights;
+
+typedef struct cf_ctx_opts {
+    int32_t max_batch;             /* most requests per cf_restore_batch           */
+    int32_t max_tokens;            /* most packed tokens in one forward phase:
+                                      max(sum k_i, sum n_new) over calls           */
+    int32_t max_positions;         /* RoPE table length: max n_ctx + n_new         */
+    int32_t chunk_rows;            /* token rows per kernel pass (0 = default)     */
+    int64_t staging_bytes;         /* host->device staging ring (0 = default)      */
+} cf_ctx_opts;
+
+typedef struct cf_ctx cf_ctx;
+
+/* Device workspace the context needs; the caller allocates it (e.g. with
+ * torch) and passes it to cf_ctx_create.                                    */
+int cf_workspace_bytes(const cf_model_desc* desc, const cf_ctx_opts* opts, size_t* bytes);
+
+/* compute_stream / copy_stream: hipStream_t handles (as void*), default
+ * priority, distinct for overlap.  workspace: device memory of at least
+ * cf_workspace_bytes, 256-byte aligned, owned by the caller and borrowed
+ * until cf_ctx_destroy.  Allocates small pinned host buffers and the RoPE
+ * table upload; no other device allocation.                                 */
+int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weights, const cf_ctx_opts* opts,
+                  void* workspace, size_t workspace_bytes, void* compute_stream,
+                  void* copy_stream, cf_ctx** out);
+void cf_ctx_destroy(cf_ctx* ctx);
+
+typedef struct cf_request {
+    uint64_t req_id;               /* must be allocated in the cache with
+                                      >= n_ctx + n_new tokens                      */
+    const int32_t* ctx_tokens;     /* host int32[n_ctx]; only [0,k_tokens) is read */
+    int32_t n_ctx;
+    int32_t n_new;
+    const void* host_kv;           /* PINNED host block (layout above); may be NULL
+                                      iff the split loads nothing                  */
+    const int32_t* new_tokens;     /* host int32[n_new]                            */
+} cf_request;
+
+typedef struct cf_timing {
+    float restore_ms;     /* call start -> both streams done with restoration    */
+    float compute_ms;     /* recompute phase on the compute stream               */
+    float copy_ms;        /* load+scatter phase on the copy stream               */
+    float suffix_ms;      /* new-token prefill + logits after the join           */
+    float total_ms;       /* call start -> logits ready (batch TTFT)             */
+    double recompute_flops; /* algorithmic: linear layers + causal pairs needed  */
+    double suffix_flops;
+    int64_t loaded_bytes; /* KV bytes that crossed the host link                 */
+    int64_t recomputed_cells; /* (token, layer) cells recomputed                  */
+    int64_t loaded_cells;
+} cf_timing;
+
+/* Restore the batch under the given splits, then prefill each request's new
+ * tokens over its restored cache and write first-token logits.
+ *   reqs, splits : host arrays of B entries; any split with 0<=k<=n_ctx and
+ *                  0<=cut<=L is accepted (planner's, forced, all-recompute,
+ *                  all-load).
+ *   logits_out   : DEVICE float[B][vocab], or NULL to skip the new-token phase
+ *                  (n_new may then be 0).
+ *   timing       : host, may be NULL.
+ * Blocking: returns after logits are ready and both streams are idle.
+ * Recompute runs on the compute stream, layer-major over the whole batch;
+ * loads run on the copy stream (pinned host -> staging -> page scatter).    */
+int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
+                     const cf_split* splits, float* logits_out, cf_timing* timing);
+
+/* Copy a request's first n_ctx tokens of KV from its pages to a pinned host
+ * block in the host layout (used to manufacture host KV; not a timed path). */
+int cf_offload(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv);
+
+/* Time a large pinned host->device copy on the copy stream: the bandwidth
+ * roofline of the load path.  host_buf pinned, dev_buf device, both >= bytes. */
+int cf_measure_h2d(cf_ctx* ctx, const void* host_buf, void* dev_buf, size_t bytes, int32_t reps,
+                   double* gb_per_s);
+
+/* Kernel selection for a context: simple_only != 0 routes every step through
+ * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
+ * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */
+int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only);
+
+/* One GEMM of the recompute path, exposed for parity tests and roofline
+ * measurement: acc[M,N] = A[M,K] * W[N,K]^T with A, W (and W2) device arrays
+ * in the context's model dtype, float accumulation, then the epilogue
+ *   epi 0: Cf = acc          epi 1: Cf += acc           (Cf device float[M,N])
+ *   epi 2: Dt = (dtype)acc   epi 3: Dt = (dtype)(silu(acc) * (A*W2^T))
+ *                                                        (Dt device dtype[M,N])
+ * (the QKV / O-proj and down-proj / - / gate-up steps of a layer).
+ * impl 0 = what cf_restore_batch would pick, 1 = plain FMA kernel, 2 = MFMA
+ * kernel (CF_ERR_UNSUPPORTED if it does not take the shape).  Runs `reps`
+ * times on the compute stream, blocks, and returns the mean time per run
+ * from HIP events in *avg_ms (may be NULL).                                 */
+int cf_op_gemm(cf_ctx* ctx, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
+               int32_t M, int32_t N, int32_t K, int32_t epi, int32_t impl, int32_t reps,
+               float* avg_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACHEFLOW_H */

@@ -1,0 +1,321 @@
+"""ctypes binding of include/cacheflow.h.  Argument marshalling only: names,
+argument order and meaning follow the C header one to one."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcacheflow.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is not built; run `python -m paper_2604_25080_amd.build` "
+        "(there is no fallback path)")
+lib = C.CDLL(LIB_PATH)
+
+CF_OK = 0
+CF_ERR_INVALID_ARG, CF_ERR_INVALID_PLAN, CF_ERR_OUT_OF_PAGES, CF_ERR_HIP = -1, -2, -3, -4
+CF_ERR_UNKNOWN_REQUEST, CF_ERR_WORKSPACE, CF_ERR_UNSUPPORTED = -5, -6, -7
+CF_F32, CF_BF16 = 0, 1
+CF_TOKEN_WISE, CF_LAYER_WISE = 0, 1
+CF_KEY_REMAINING_COST, CF_KEY_REMAINING_CELLS, CF_KEY_MARGINAL = 0, 1, 2
+EPI_STORE_F32, EPI_ADD_F32, EPI_STORE_T, EPI_SILU_MUL = 0, 1, 2, 3
+PAGE_TOKENS = 16
+
+
+class CfError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib.cf_last_error().decode()
+        super().__init__(f"{where}: {lib.cf_status_str(status).decode()} ({status}): {msg}")
+
+
+class cf_cost_model(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("f_c", "alpha", "beta", "f_io", "gamma")]
+
+
+class cf_plan_opts(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("chunk_tokens", "l_delta", "n_layers",
+                                         "kv_bytes_per_token_layer", "force_mode", "io_key")]
+
+
+class cf_split(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("mode", "k_tokens", "layer_cut")]
+
+
+class cf_claim(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("engine", "request", "unit")]
+
+
+class cf_plan_stats(C.Structure):
+    _fields_ = [("t_comp", C.c_int64), ("t_io", C.c_int64), ("makespan", C.c_int64),
+                ("n_claims", C.c_int32), ("n_trace", C.c_int32)]
+
+
+class cf_model_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads",
+                                         "head_dim", "d_ffn", "vocab", "dtype")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float)]
+
+
+class cf_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wqkv", "wo", "mlp_norm", "w_gate",
+                                          "w_up", "w_down")]
+
+
+class cf_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("layers", C.POINTER(cf_layer_weights))]
+
+
+class cf_ctx_opts(C.Structure):
+    _fields_ = [("max_batch", C.c_int32), ("max_tokens", C.c_int32), ("max_positions", C.c_int32),
+                ("chunk_rows", C.c_int32), ("staging_bytes", C.c_int64)]
+
+
+class cf_request(C.Structure):
+    _fields_ = [("req_id", C.c_uint64), ("ctx_tokens", C.c_void_p), ("n_ctx", C.c_int32),
+                ("n_new", C.c_int32), ("host_kv", C.c_void_p), ("new_tokens", C.c_void_p)]
+
+
+class cf_timing(C.Structure):
+    _fields_ = [("restore_ms", C.c_float), ("compute_ms", C.c_float), ("copy_ms", C.c_float),
+                ("suffix_ms", C.c_float), ("total_ms", C.c_float),
+                ("recompute_flops", C.c_double), ("suffix_flops", C.c_double),
+                ("loaded_bytes", C.c_int64), ("recomputed_cells", C.c_int64),
+                ("loaded_cells", C.c_int64)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+_P = C.POINTER
+lib.cf_status_str.restype = C.c_char_p
+lib.cf_status_str.argtypes = [C.c_int]
+lib.cf_last_error.restype = C.c_char_p
+lib.cf_last_error.argtypes = []
+lib.cf_restore_plan.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
+                                _P(cf_split), _P(cf_plan_stats), _P(cf_claim), C.c_int32]
+lib.cf_plan_eval.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
+                             _P(cf_split), _P(C.c_int64), _P(C.c_int64)]
+lib.cf_derive_l_delta.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, _P(C.c_int32)]
+lib.cf_cache_create.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                _P(C.c_void_p)]
+lib.cf_cache_destroy.argtypes = [C.c_void_p]
+lib.cf_cache_destroy.restype = None
+lib.cf_cache_n_pages.argtypes = [C.c_void_p]
+lib.cf_cache_n_free.argtypes = [C.c_void_p]
+lib.cf_cache_page_bytes.argtypes = [C.c_void_p]
+lib.cf_cache_page_bytes.restype = C.c_size_t
+lib.cf_cache_alloc.argtypes = [C.c_void_p, C.c_uint64, C.c_int32]
+lib.cf_cache_free.argtypes = [C.c_void_p, C.c_uint64]
+lib.cf_cache_page_table.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, _P(C.c_int32)]
+lib.cf_host_kv_bytes.argtypes = [C.c_int32] * 5
+lib.cf_host_kv_bytes.restype = C.c_size_t
+lib.cf_workspace_bytes.argtypes = [_P(cf_model_desc), _P(cf_ctx_opts), _P(C.c_size_t)]
+lib.cf_ctx_create.argtypes = [_P(cf_model_desc), _P(cf_weights), _P(cf_ctx_opts), C.c_void_p,
+                              C.c_size_t, C.c_void_p, C.c_void_p, _P(C.c_void_p)]
+lib.cf_ctx_destroy.argtypes = [C.c_void_p]
+lib.cf_ctx_destroy.restype = None
+lib.cf_ctx_set_kernel_set.argtypes = [C.c_void_p, C.c_int32]
+lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request), _P(cf_split),
+                                 C.c_void_p, _P(cf_timing)]
+lib.cf_offload.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]
+lib.cf_measure_h2d.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32,
+                               _P(C.c_double)]
+lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                           C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                           _P(C.c_float)]
+
+EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval",
+           "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
+           "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
+           "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
+           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_restore_batch", "cf_offload",
+           "cf_measure_h2d", "cf_op_gemm"]
+
+
+def _check(status, where):
+    if status != CF_OK:
+        raise CfError(status, where)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+# ------------------------------------------------------------------- planner
+def cost_model(f_c, alpha, beta, f_io, gamma):
+    return cf_cost_model(int(f_c), int(alpha), int(beta), int(f_io), int(gamma))
+
+
+def plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode=-1,
+              io_key=CF_KEY_REMAINING_COST):
+    return cf_plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode,
+                        io_key)
+
+
+def restore_plan(cost, opts, n_ctx, trace_cap=0):
+    """-> (splits [(mode,k,cut)], stats dict, trace [(engine,request,unit)])"""
+    n = _i32(n_ctx)
+    b = len(n)
+    splits = (cf_split * max(b, 1))()
+    stats = cf_plan_stats()
+    trace = (cf_claim * max(trace_cap, 1))()
+    _check(lib.cf_restore_plan(C.byref(cost), C.byref(opts), b, n.ctypes.data, splits,
+                               C.byref(stats), trace if trace_cap else None, trace_cap),
+           "cf_restore_plan")
+    out = [(splits[i].mode, splits[i].k_tokens, splits[i].layer_cut) for i in range(b)]
+    st = dict(t_comp=stats.t_comp, t_io=stats.t_io, makespan=stats.makespan,
+              n_claims=stats.n_claims)
+    tr = [(trace[i].engine, trace[i].request, trace[i].unit) for i in range(stats.n_trace)]
+    return out, st, tr
+
+
+def plan_eval(cost, opts, n_ctx, splits):
+    n = _i32(n_ctx)
+    arr = (cf_split * max(len(n), 1))(*[cf_split(*s) for s in splits])
+    tc, tio = C.c_int64(), C.c_int64()
+    _check(lib.cf_plan_eval(C.byref(cost), C.byref(opts), len(n), n.ctypes.data, arr,
+                            C.byref(tc), C.byref(tio)), "cf_plan_eval")
+    return tc.value, tio.value
+
+
+def derive_l_delta(cost, opts, n_max):
+    out = C.c_int32()
+    _check(lib.cf_derive_l_delta(C.byref(cost), C.byref(opts), n_max, C.byref(out)),
+           "cf_derive_l_delta")
+    return out.value
+
+
+# ---------------------------------------------------------------- page table
+class Cache:
+    """cf_cache handle.  `pool_ptr` is a device address (int) or 0."""
+
+    def __init__(self, pool_ptr, pool_bytes, n_layers, n_kv_heads, head_dim, dtype):
+        h = C.c_void_p()
+        _check(lib.cf_cache_create(pool_ptr or None, pool_bytes, n_layers, n_kv_heads, head_dim,
+                                   dtype, C.byref(h)), "cf_cache_create")
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            lib.cf_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    @property
+    def n_pages(self):
+        return lib.cf_cache_n_pages(self.handle)
+
+    @property
+    def n_free(self):
+        return lib.cf_cache_n_free(self.handle)
+
+    @property
+    def page_bytes(self):
+        return lib.cf_cache_page_bytes(self.handle)
+
+    def alloc(self, req_id, n_tokens):
+        _check(lib.cf_cache_alloc(self.handle, req_id, n_tokens), "cf_cache_alloc")
+
+    def free(self, req_id):
+        _check(lib.cf_cache_free(self.handle, req_id), "cf_cache_free")
+
+    def page_table(self, req_id):
+        n = C.c_int32()
+        _check(lib.cf_cache_page_table(self.handle, req_id, None, 0, C.byref(n)),
+               "cf_cache_page_table")
+        out = np.zeros(max(n.value, 1), dtype=np.int32)
+        _check(lib.cf_cache_page_table(self.handle, req_id, out.ctypes.data, n.value,
+                                       C.byref(n)), "cf_cache_page_table")
+        return out[:n.value].tolist()
+
+
+def host_kv_bytes(n_layers, n_kv_heads, head_dim, dtype, n_ctx):
+    return lib.cf_host_kv_bytes(n_layers, n_kv_heads, head_dim, dtype, n_ctx)
+
+
+# ------------------------------------------------------------------ executor
+def model_desc(shape):
+    """cf_model_desc from any object with the ModelShape fields."""
+    return cf_model_desc(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
+                         shape.head_dim, shape.d_ffn, shape.vocab,
+                         CF_F32 if shape.dtype == "f32" else CF_BF16,
+                         shape.rope_base, shape.rms_eps)
+
+
+def ctx_opts(max_batch, max_tokens, max_positions, chunk_rows=0, staging_bytes=0):
+    return cf_ctx_opts(max_batch, max_tokens, max_positions, chunk_rows, staging_bytes)
+
+
+def workspace_bytes(desc, opts):
+    n = C.c_size_t()
+    _check(lib.cf_workspace_bytes(C.byref(desc), C.byref(opts), C.byref(n)), "cf_workspace_bytes")
+    return n.value
+
+
+class Ctx:
+    """cf_ctx handle.  `weights` = dict(embed=ptr, lm_head=ptr, final_norm=ptr,
+    layers=[dict(attn_norm=ptr, wqkv=ptr, ...)]) of device addresses (ints)."""
+
+    def __init__(self, desc, weights, opts, workspace_ptr, workspace_bytes_, compute_stream,
+                 copy_stream):
+        layers = (cf_layer_weights * desc.n_layers)(*[
+            cf_layer_weights(*[lw[n] for n, _ in cf_layer_weights._fields_])
+            for lw in weights["layers"]])
+        w = cf_weights(weights["embed"], weights["lm_head"], weights["final_norm"], layers)
+        h = C.c_void_p()
+        _check(lib.cf_ctx_create(C.byref(desc), C.byref(w), C.byref(opts), workspace_ptr,
+                                 workspace_bytes_, compute_stream, copy_stream, C.byref(h)),
+               "cf_ctx_create")
+        self.handle = h
+        self.desc = desc
+
+    def close(self):
+        if self.handle:
+            lib.cf_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    def set_kernel_set(self, simple_only):
+        _check(lib.cf_ctx_set_kernel_set(self.handle, int(simple_only)), "cf_ctx_set_kernel_set")
+
+    def restore_batch(self, cache, requests, splits, logits_ptr):
+        """requests: list of dict(req_id, ctx_tokens (np.int32), n_new, host_kv (address or
+        0), new_tokens (np.int32)); splits: [(mode,k,cut)].  Returns the timing dict."""
+        b = len(requests)
+        keep = []
+        arr = (cf_request * max(b, 1))()
+        for i, r in enumerate(requests):
+            ct = _i32(r["ctx_tokens"])
+            nt = _i32(r["new_tokens"])
+            keep += [ct, nt]
+            arr[i] = cf_request(r["req_id"], ct.ctypes.data if len(ct) else None, len(ct),
+                                len(nt), r.get("host_kv") or None,
+                                nt.ctypes.data if len(nt) else None)
+        sp = (cf_split * max(b, 1))(*[cf_split(*s) for s in splits])
+        tm = cf_timing()
+        _check(lib.cf_restore_batch(self.handle, cache.handle, b, arr, sp, logits_ptr or None,
+                                    C.byref(tm)), "cf_restore_batch")
+        return tm.as_dict()
+
+    def offload(self, cache, req_id, n_ctx, host_ptr):
+        _check(lib.cf_offload(self.handle, cache.handle, req_id, n_ctx, host_ptr), "cf_offload")
+
+    def measure_h2d(self, host_ptr, dev_ptr, n_bytes, reps=5):
+        out = C.c_double()
+        _check(lib.cf_measure_h2d(self.handle, host_ptr, dev_ptr, n_bytes, reps, C.byref(out)),
+               "cf_measure_h2d")
+        return out.value
+
+    def op_gemm(self, A, W, W2, Cf, Dt, M, N, K, epi, impl=0, reps=1):
+        ms = C.c_float()
+        _check(lib.cf_op_gemm(self.handle, A, W, W2 or None, Cf or None, Dt or None, M, N, K, epi,
+                              impl, reps, C.byref(ms)), "cf_op_gemm")
+        return ms.value

@@ -1,0 +1,716 @@
+// Executor of batched hybrid KV-cache restoration (Sec. 3.1-3.3): for every
+// request the cells (token < k, layer < cut) are recomputed on the compute
+// stream, layer-major over the whole batch, while all other cells are copied
+// from pinned host memory and scattered into the same pages on the copy
+// stream; after the join the new-turn tokens are prefilled over the restored
+// pages and the first-token logits are produced (TTFT = restoration + that
+// prefill).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "cf_common.h"
+#include "kernels.h"
+
+namespace cf {
+
+#define CF_HIP(call)                                                                     \
+    do {                                                                                 \
+        hipError_t e_ = (call);                                                          \
+        if (e_ != hipSuccess)                                                            \
+            return cf::fail(CF_ERR_HIP, "%s:%d %s -> %s", __FILE__, __LINE__, #call,     \
+                            hipGetErrorString(e_));                                      \
+    } while (0)
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int PAGE_MOVE_SPLIT = 4;       // blocks per page in the page mover
+constexpr int N_STAGING_SLOTS = 2;
+
+struct Carve {
+    size_t rope, h, a, qkv, q, o, act, a_last, staging, meta, total;
+    size_t staging_bytes, meta_bytes;
+    int chunk_rows;
+};
+
+static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* c) {
+    if (m.n_layers <= 0 || m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 ||
+        m.head_dim <= 0 || m.d_ffn <= 0 || m.vocab <= 0 || (m.dtype != CF_F32 && m.dtype != CF_BF16))
+        return fail(CF_ERR_INVALID_ARG, "model descriptor has a non-positive field or bad dtype");
+    if (m.n_q_heads % m.n_kv_heads != 0 || (m.head_dim != 64 && m.head_dim != 128) ||
+        m.d_model % 8 != 0 || m.d_model > 8192 || m.d_ffn % 8 != 0)
+        return fail(CF_ERR_UNSUPPORTED,
+                    "need Hq %% Hkv == 0, head_dim in {64,128}, d_model %% 8 == 0 and <= 8192, "
+                    "d_ffn %% 8 == 0");
+    if (o.max_batch <= 0 || o.max_tokens <= 0 || o.max_positions <= 0 || o.chunk_rows < 0 ||
+        o.staging_bytes < 0)
+        return fail(CF_ERR_INVALID_ARG, "context options must be positive");
+    size_t es = elem_bytes(m.dtype);
+    int chunk = o.chunk_rows > 0 ? o.chunk_rows : 16384;
+    chunk = (int)align_up((size_t)std::min(chunk, std::max(o.max_tokens, 1)), 256);
+    size_t pb = page_bytes(m.n_kv_heads, m.head_dim, m.dtype);
+    size_t stg = o.staging_bytes > 0 ? (size_t)o.staging_bytes : ((size_t)128 << 20);
+    stg = std::max(stg / N_STAGING_SLOTS / pb, (size_t)1) * pb * N_STAGING_SLOTS;
+    size_t qcols = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    size_t pages_per_req = (size_t)o.max_positions / CF_PAGE_TOKENS + 2;
+    size_t meta = (size_t)2 * 12 * o.max_tokens                       // ids, positions, slots
+                  + (size_t)4 * o.max_batch * pages_per_req            // page tables
+                  + (size_t)sizeof(AttnWork) * (2 * ((size_t)o.max_tokens / ATTN_BLOCK_ROWS) +
+                                                4 * (size_t)o.max_batch +
+                                                2 * ((size_t)o.max_tokens / chunk + 2) * 2)
+                  + (size_t)sizeof(PageJob) * ((size_t)o.max_batch * m.n_layers * 2 + 4096) +
+                  (size_t)8 * o.max_batch + (1 << 16);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    c->rope = take((size_t)o.max_positions * (m.head_dim / 2) * sizeof(float2));
+    c->h = take((size_t)o.max_tokens * m.d_model * 4);
+    c->a = take((size_t)chunk * m.d_model * es);
+    c->qkv = take((size_t)chunk * qcols * 4);
+    c->q = take((size_t)chunk * m.n_q_heads * m.head_dim * es);
+    c->o = take((size_t)chunk * m.n_q_heads * m.head_dim * es);
+    c->act = take((size_t)chunk * m.d_ffn * es);
+    c->a_last = take((size_t)o.max_batch * m.d_model * es);
+    c->staging = take(stg);
+    c->meta = take(meta);
+    c->total = off;
+    c->staging_bytes = stg;
+    c->meta_bytes = meta;
+    c->chunk_rows = chunk;
+    return CF_OK;
+}
+
+}  // namespace cf
+
+using namespace cf;
+
+struct cf_ctx {
+    cf_model_desc m;
+    cf_ctx_opts opts;
+    cf_weights w;
+    std::vector<cf_layer_weights> layers;
+    hipStream_t cs = nullptr, ps = nullptr, ss = nullptr;  // compute, copy, scatter
+    bool own_ss = false;
+    char* ws = nullptr;
+    Carve cv;
+    char* meta_host = nullptr;
+    hipEvent_t ev_start = nullptr, ev_meta = nullptr, ev_comp = nullptr, ev_copy = nullptr,
+               ev_end = nullptr, ev_scat = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
+    hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
+    bool simple_only = false;
+
+    float* h() { return (float*)(ws + cv.h); }
+    void* a() { return ws + cv.a; }
+    float* qkv() { return (float*)(ws + cv.qkv); }
+    void* q() { return ws + cv.q; }
+    void* o() { return ws + cv.o; }
+    void* act() { return ws + cv.act; }
+    void* a_last() { return ws + cv.a_last; }
+    float2* rope() { return (float2*)(ws + cv.rope); }
+    char* staging() { return ws + cv.staging; }
+    char* meta_dev() { return ws + cv.meta; }
+};
+
+extern "C" int cf_workspace_bytes(const cf_model_desc* desc, const cf_ctx_opts* opts, size_t* bytes) {
+    if (!desc || !opts || !bytes) return fail(CF_ERR_INVALID_ARG, "cf_workspace_bytes: null argument");
+    Carve c;
+    int rc = carve_workspace(*desc, *opts, &c);
+    if (rc) return rc;
+    *bytes = c.total;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weights,
+                             const cf_ctx_opts* opts, void* workspace, size_t workspace_bytes,
+                             void* compute_stream, void* copy_stream, cf_ctx** out) {
+    if (!desc || !weights || !opts || !workspace || !out || !weights->layers || !weights->embed ||
+        !weights->lm_head || !weights->final_norm)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_create: null argument");
+    Carve cv;
+    int rc = carve_workspace(*desc, *opts, &cv);
+    if (rc) return rc;
+    if (workspace_bytes < cv.total)
+        return fail(CF_ERR_WORKSPACE, "cf_ctx_create: workspace %zu < needed %zu", workspace_bytes,
+                    cv.total);
+    if (((uintptr_t)workspace & 255) != 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_create: workspace must be 256-byte aligned");
+    for (int l = 0; l < desc->n_layers; ++l) {
+        const cf_layer_weights& lw = weights->layers[l];
+        if (!lw.attn_norm || !lw.wqkv || !lw.wo || !lw.mlp_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+            return fail(CF_ERR_INVALID_ARG, "cf_ctx_create: layer %d has a null weight", l);
+    }
+    cf_ctx* c = new cf_ctx;
+    c->m = *desc;
+    c->opts = *opts;
+    c->w = *weights;
+    c->layers.assign(weights->layers, weights->layers + desc->n_layers);
+    c->w.layers = c->layers.data();
+    c->cs = (hipStream_t)compute_stream;
+    c->ps = (hipStream_t)copy_stream;
+    c->ws = (char*)workspace;
+    c->cv = cv;
+    c->simple_only = false;
+    auto bail = [&](int code) { cf_ctx_destroy(c); return code; };
+#define CF_HIP_CTX(call)                                                                      \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return bail(fail(CF_ERR_HIP, "%s:%d %s -> %s", __FILE__, __LINE__, #call,         \
+                             hipGetErrorString(e_)));                                         \
+    } while (0)
+    CF_HIP_CTX(hipStreamCreateWithFlags(&c->ss, hipStreamNonBlocking));
+    c->own_ss = true;
+    CF_HIP_CTX(hipHostMalloc((void**)&c->meta_host, cv.meta_bytes, hipHostMallocDefault));
+    hipEvent_t* evs[] = {&c->ev_start, &c->ev_meta, &c->ev_comp, &c->ev_copy, &c->ev_end,
+                         &c->ev_scat, &c->ev_t0, &c->ev_t1};
+    for (hipEvent_t* e : evs) CF_HIP_CTX(hipEventCreate(e));
+    for (int i = 0; i < N_STAGING_SLOTS; ++i) {
+        CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_filled[i], hipEventDisableTiming));
+        CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
+    }
+    // RoPE table: angles formed in double, rounded once to float.
+    {
+        int half = desc->head_dim / 2;
+        std::vector<float2> tab((size_t)opts->max_positions * half);
+        std::vector<double> theta(half);
+        for (int j = 0; j < half; ++j)
+            theta[j] = std::pow((double)desc->rope_base, -2.0 * j / (double)desc->head_dim);
+        for (int p = 0; p < opts->max_positions; ++p)
+            for (int j = 0; j < half; ++j) {
+                double ang = (double)p * theta[j];
+                tab[(size_t)p * half + j] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+            }
+        CF_HIP_CTX(hipMemcpy(c->rope(), tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    }
+#undef CF_HIP_CTX
+    *out = c;
+    return CF_OK;
+}
+
+extern "C" void cf_ctx_destroy(cf_ctx* c) {
+    if (!c) return;
+    hipEvent_t evs[] = {c->ev_start, c->ev_meta, c->ev_comp, c->ev_copy, c->ev_end,
+                        c->ev_scat, c->ev_t0, c->ev_t1};
+    for (hipEvent_t e : evs)
+        if (e) (void)hipEventDestroy(e);
+    for (int i = 0; i < N_STAGING_SLOTS; ++i) {
+        if (c->ev_filled[i]) (void)hipEventDestroy(c->ev_filled[i]);
+        if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+    }
+    if (c->meta_host) (void)hipHostFree(c->meta_host);
+    if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
+    delete c;
+}
+
+extern "C" int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_kernel_set: null ctx");
+    ctx->simple_only = simple_only != 0;
+    return CF_OK;
+}
+
+namespace {
+
+// ---------------------------------------------------------------- host metadata
+struct Segment {        // rows of one request inside a packed phase
+    int req;            // index into the call's request array
+    int row0, n_rows;   // packed rows
+    int pos0;           // absolute position of the first row
+    int layers;         // rows are active in layers [0, layers)
+};
+
+struct ChunkInfo {
+    int r0, r1;         // packed row range
+    int work_off, n_work;
+};
+
+struct Phase {
+    int T = 0;
+    std::vector<Segment> segs;          // packed order; `layers` non-increasing
+    std::vector<ChunkInfo> chunks;
+    std::vector<AttnWork> work;
+    // device offsets (bytes into meta)
+    size_t off_ids = 0, off_pos = 0, off_slot = 0, off_work = 0;
+    int rows_active(int layer) const {
+        int t = 0;
+        for (const Segment& s : segs)
+            if (s.layers > layer) t = s.row0 + s.n_rows;
+        return t;
+    }
+};
+
+struct MetaWriter {
+    char* host;
+    size_t cap, off = 0;
+    bool overflow = false;
+    size_t put(const void* src, size_t bytes) {
+        size_t at = off;
+        size_t end = (off + bytes + 15) / 16 * 16;
+        if (end > cap) { overflow = true; return 0; }
+        if (bytes) std::memcpy(host + at, src, bytes);
+        off = end;
+        return at;
+    }
+};
+
+void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off) {
+    for (int r0 = 0; r0 < ph.T; r0 += chunk_rows) {
+        ChunkInfo ci;
+        ci.r0 = r0;
+        ci.r1 = std::min(ph.T, r0 + chunk_rows);
+        ci.work_off = (int)ph.work.size();
+        for (const Segment& s : ph.segs) {
+            int a = std::max(s.row0, ci.r0), b = std::min(s.row0 + s.n_rows, ci.r1);
+            for (int r = a; r < b; r += ATTN_BLOCK_ROWS) {
+                AttnWork w;
+                w.row0 = r - ci.r0;                       // relative to the chunk buffer
+                w.n_rows = std::min(ATTN_BLOCK_ROWS, b - r);
+                w.pos0 = s.pos0 + (r - s.row0);
+                w.pt_off = pt_off[s.req];
+                ph.work.push_back(w);
+            }
+        }
+        ci.n_work = (int)ph.work.size() - ci.work_off;
+        ph.chunks.push_back(ci);
+    }
+}
+
+void gemm(cf_ctx* c, const void* A, const void* W, const void* W2, float* Cf, void* Dt, int M,
+          int N, int K, int epi) {
+    if (!c->simple_only && gemm_mfma_supported(c->m.dtype, M, N, K, epi))
+        launch_gemm_mfma(c->cs, A, W, W2, Cf, Dt, M, N, K, epi);
+    else
+        launch_gemm_simple(c->cs, c->m.dtype, A, W, W2, Cf, Dt, M, N, K, epi);
+}
+
+// Run layers [0, n_layers_max) of one packed phase on the compute stream.
+void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
+    const cf_model_desc& m = c->m;
+    if (ph.T <= 0) return;
+    size_t es = elem_bytes(m.dtype);
+    char* md = c->meta_dev();
+    const int32_t* d_ids = (const int32_t*)(md + ph.off_ids);
+    const int32_t* d_pos = (const int32_t*)(md + ph.off_pos);
+    const int32_t* d_slot = (const int32_t*)(md + ph.off_slot);
+    const AttnWork* d_work = (const AttnWork*)(md + ph.off_work);
+    const int32_t* d_pt = (const int32_t*)md;      // page tables sit at offset 0
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_elems = (int64_t)(cache->page_bytes / es);
+    g.layer_stride = g.page_elems * cache->n_pages;
+    int qcols = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    int nq = m.n_q_heads * m.head_dim;
+    bool mfma_attn = !c->simple_only &&
+                     attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads);
+
+    launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, m.d_model);
+    for (int l = 0; l < n_layers_max; ++l) {
+        int Ta = ph.rows_active(l);
+        if (Ta <= 0) break;
+        const cf_layer_weights& lw = c->layers[l];
+        char* pool_layer = (char*)cache->pool + (size_t)l * g.layer_stride * es;
+        for (const ChunkInfo& ci : ph.chunks) {
+            if (ci.r0 >= Ta) break;
+            int r1 = std::min(ci.r1, Ta);
+            int Tc = r1 - ci.r0;
+            float* h = c->h() + (size_t)ci.r0 * m.d_model;
+            // active work items of this chunk: those whose rows lie below Ta
+            int n_work = 0;
+            for (int i = 0; i < ci.n_work; ++i)
+                if (ph.work[ci.work_off + i].row0 + ci.r0 < Ta) n_work = i + 1;
+            launch_rmsnorm(c->cs, m.dtype, h, lw.attn_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
+            gemm(c, c->a(), lw.wqkv, nullptr, c->qkv(), nullptr, Tc, qcols, m.d_model, EPI_STORE_F32);
+            launch_rope_write(c->cs, m.dtype, c->qkv(), d_pos + ci.r0, d_slot + ci.r0, c->rope(),
+                              c->q(), pool_layer, Tc, m.n_q_heads, g);
+            if (mfma_attn)
+                launch_attention_mfma(c->cs, c->q(), c->o(), pool_layer, d_work + ci.work_off,
+                                      n_work, d_pt, m.n_q_heads, g);
+            else
+                launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
+                                        d_work + ci.work_off, n_work, d_pt, m.n_q_heads, g);
+            gemm(c, c->o(), lw.wo, nullptr, h, nullptr, Tc, m.d_model, nq, EPI_ADD_F32);
+            launch_rmsnorm(c->cs, m.dtype, h, lw.mlp_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
+            gemm(c, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tc, m.d_ffn, m.d_model, EPI_SILU_MUL);
+            gemm(c, c->act(), lw.w_down, nullptr, h, nullptr, Tc, m.d_model, m.d_ffn, EPI_ADD_F32);
+        }
+    }
+}
+
+double linear_flops_per_token_layer(const cf_model_desc& m) {
+    double qcols = (double)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    return 2.0 * m.d_model * qcols + 2.0 * m.n_q_heads * m.head_dim * (double)m.d_model +
+           6.0 * m.d_model * (double)m.d_ffn;
+}
+
+struct CopyOp {
+    size_t dst_off;      // into staging
+    const char* src;
+    size_t bytes;
+};
+
+struct SlotPlan {
+    int slot;
+    int op_first, n_ops;
+    int job_first, n_jobs, n_blocks;
+};
+
+}  // namespace
+
+extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_request* reqs,
+                                const cf_split* splits, float* logits_out, cf_timing* timing) {
+    if (!c || !cache || B < 0 || (B > 0 && (!reqs || !splits)))
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: null argument");
+    const cf_model_desc& m = c->m;
+    if (cache->n_layers != m.n_layers || cache->n_kv_heads != m.n_kv_heads ||
+        cache->head_dim != m.head_dim || cache->dtype != m.dtype || !cache->pool)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: cache geometry does not match the model");
+    if (B > c->opts.max_batch)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_batch: batch %d > max_batch %d", B, c->opts.max_batch);
+    if (timing) std::memset(timing, 0, sizeof(*timing));
+    if (B == 0) return CF_OK;
+    size_t es = elem_bytes(m.dtype);
+    const int L = m.n_layers;
+
+    // ---- validate requests and splits on the host before anything is enqueued
+    std::vector<int> pt_off(B), n_pages_req(B);
+    std::vector<const int32_t*> pt(B);
+    int64_t sum_rec = 0, sum_new = 0;
+    int total_pt = 0;
+    for (int i = 0; i < B; ++i) {
+        const cf_request& r = reqs[i];
+        const cf_split& s = splits[i];
+        if (r.n_ctx < 0 || r.n_new < 0 || (r.n_new > 0 && !r.new_tokens))
+            return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d has bad sizes", i);
+        if (s.k_tokens < 0 || s.k_tokens > r.n_ctx || s.layer_cut < 0 || s.layer_cut > L)
+            return fail(CF_ERR_INVALID_PLAN, "cf_restore_batch: split %d = (k %d, cut %d) outside [0,%d]x[0,%d]",
+                        i, s.k_tokens, s.layer_cut, r.n_ctx, L);
+        int np = 0;
+        pt[i] = cache->table_of(r.req_id, &np);
+        if (!cache->has(r.req_id))
+            return fail(CF_ERR_UNKNOWN_REQUEST, "cf_restore_batch: request id %llu has no pages",
+                        (unsigned long long)r.req_id);
+        if ((int64_t)np * CF_PAGE_TOKENS < (int64_t)r.n_ctx + (logits_out ? r.n_new : 0))
+            return fail(CF_ERR_OUT_OF_PAGES, "cf_restore_batch: request %d holds %d pages, needs %d tokens",
+                        i, np, r.n_ctx + r.n_new);
+        if (r.n_ctx + r.n_new > c->opts.max_positions)
+            return fail(CF_ERR_WORKSPACE, "cf_restore_batch: request %d exceeds max_positions", i);
+        bool recomputes = s.k_tokens > 0 && s.layer_cut > 0;
+        bool loads = (s.k_tokens < r.n_ctx) || (s.layer_cut < L && r.n_ctx > 0);
+        if (recomputes && !r.ctx_tokens)
+            return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d recomputes but has no tokens", i);
+        if (loads && !r.host_kv)
+            return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d loads but has no host KV", i);
+        if (recomputes) {
+            sum_rec += s.k_tokens;
+            for (int t = 0; t < s.k_tokens; ++t)
+                if ((uint32_t)r.ctx_tokens[t] >= (uint32_t)m.vocab)
+                    return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d token %d out of vocab", i, t);
+        }
+        if (logits_out) {
+            if (r.n_new <= 0)
+                return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d needs n_new > 0 for logits", i);
+            sum_new += r.n_new;
+            for (int t = 0; t < r.n_new; ++t)
+                if ((uint32_t)r.new_tokens[t] >= (uint32_t)m.vocab)
+                    return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d new token %d out of vocab", i, t);
+        }
+        pt_off[i] = total_pt;
+        n_pages_req[i] = np;
+        total_pt += np;
+    }
+    if (sum_rec > c->opts.max_tokens || sum_new > c->opts.max_tokens)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_batch: %lld recompute / %lld new tokens > max_tokens %d",
+                    (long long)sum_rec, (long long)sum_new, c->opts.max_tokens);
+
+    // ---- metadata: page tables first (offset 0), then per-phase arrays, then jobs
+    MetaWriter mw{c->meta_host, c->cv.meta_bytes};
+    {
+        std::vector<int32_t> all_pt(std::max(total_pt, 1));
+        for (int i = 0; i < B; ++i)
+            if (n_pages_req[i]) std::memcpy(&all_pt[pt_off[i]], pt[i], (size_t)n_pages_req[i] * 4);
+        mw.put(all_pt.data(), all_pt.size() * 4);
+    }
+    auto slot_of = [&](int i, int t) { return pt[i][t / CF_PAGE_TOKENS] * CF_PAGE_TOKENS + t % CF_PAGE_TOKENS; };
+
+    // recompute phase: requests in order of descending layer cut so that the rows
+    // active in layer l are a prefix of the packed array
+    Phase rec, suf;
+    {
+        std::vector<int> order;
+        for (int i = 0; i < B; ++i)
+            if (splits[i].k_tokens > 0 && splits[i].layer_cut > 0) order.push_back(i);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int a, int b) { return splits[a].layer_cut > splits[b].layer_cut; });
+        std::vector<int32_t> ids, pos, slot;
+        for (int i : order) {
+            Segment s{i, rec.T, splits[i].k_tokens, 0, splits[i].layer_cut};
+            for (int t = 0; t < s.n_rows; ++t) {
+                ids.push_back(reqs[i].ctx_tokens[t]);
+                pos.push_back(t);
+                slot.push_back(slot_of(i, t));
+            }
+            rec.T += s.n_rows;
+            rec.segs.push_back(s);
+        }
+        build_chunks(rec, c->cv.chunk_rows, pt_off);
+        rec.off_ids = mw.put(ids.data(), ids.size() * 4);
+        rec.off_pos = mw.put(pos.data(), pos.size() * 4);
+        rec.off_slot = mw.put(slot.data(), slot.size() * 4);
+        rec.off_work = mw.put(rec.work.data(), rec.work.size() * sizeof(AttnWork));
+    }
+    std::vector<int32_t> last_rows;
+    if (logits_out) {
+        std::vector<int32_t> ids, pos, slot;
+        for (int i = 0; i < B; ++i) {
+            Segment s{i, suf.T, reqs[i].n_new, reqs[i].n_ctx, L};
+            for (int t = 0; t < s.n_rows; ++t) {
+                ids.push_back(reqs[i].new_tokens[t]);
+                pos.push_back(s.pos0 + t);
+                slot.push_back(slot_of(i, s.pos0 + t));
+            }
+            suf.T += s.n_rows;
+            suf.segs.push_back(s);
+            last_rows.push_back(suf.T - 1);
+        }
+        build_chunks(suf, c->cv.chunk_rows, pt_off);
+        suf.off_ids = mw.put(ids.data(), ids.size() * 4);
+        suf.off_pos = mw.put(pos.data(), pos.size() * 4);
+        suf.off_slot = mw.put(slot.data(), slot.size() * 4);
+        suf.off_work = mw.put(suf.work.data(), suf.work.size() * sizeof(AttnWork));
+    }
+    size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
+
+    // copy plan: runs of pages per (request, layer), top layer first and the
+    // longest request first (the I/O pointer walks down from the far end, Sec. 3.1)
+    std::vector<CopyOp> ops;
+    std::vector<PageJob> jobs;
+    std::vector<SlotPlan> slots;
+    int64_t loaded_bytes = 0, loaded_cells = 0, rec_cells = 0;
+    {
+        size_t pb = cache->page_bytes;
+        size_t slot_cap = c->cv.staging_bytes / N_STAGING_SLOTS;
+        SlotPlan cur{0, 0, 0, 0, 0, 0};
+        size_t fill = 0;
+        auto flush = [&]() {
+            if (cur.n_jobs == 0) return;
+            slots.push_back(cur);
+            int next = (cur.slot + 1) % N_STAGING_SLOTS;
+            cur = SlotPlan{next, (int)ops.size(), 0, (int)jobs.size(), 0, 0};
+            fill = 0;
+        };
+        std::vector<int> by_len(B);
+        for (int i = 0; i < B; ++i) by_len[i] = i;
+        std::stable_sort(by_len.begin(), by_len.end(),
+                         [&](int a, int b) { return reqs[a].n_ctx > reqs[b].n_ctx; });
+        for (int i : by_len) {
+            const cf_request& r = reqs[i];
+            const cf_split& s = splits[i];
+            int np_ctx = (int)ceil_div(r.n_ctx, CF_PAGE_TOKENS);
+            for (int l = L - 1; l >= 0; --l) {
+                int lo = (l < s.layer_cut) ? s.k_tokens : 0, hi = r.n_ctx;
+                if (l < s.layer_cut) rec_cells += s.k_tokens;
+                if (lo >= hi) continue;
+                loaded_cells += hi - lo;
+                int j = lo / CF_PAGE_TOKENS, j1 = np_ctx;
+                while (j < j1) {
+                    size_t room = (slot_cap - fill) / pb;
+                    if (room == 0) { flush(); continue; }
+                    int take = (int)std::min<size_t>(room, (size_t)(j1 - j));
+                    size_t dst = (size_t)cur.slot * slot_cap + fill;
+                    const char* src = (const char*)r.host_kv + ((size_t)l * np_ctx + j) * pb;
+                    size_t bytes = (size_t)take * pb;
+                    if (cur.n_ops > 0 && ops.back().src + ops.back().bytes == src &&
+                        ops.back().dst_off + ops.back().bytes == dst)
+                        ops.back().bytes += bytes;
+                    else { ops.push_back(CopyOp{dst, src, bytes}); ++cur.n_ops; }
+                    PageJob jb;
+                    jb.staging_off = (int64_t)dst;
+                    jb.layer = l;
+                    jb.pt_off = pt_off[i];
+                    jb.page_first = j;
+                    jb.n_pages = take;
+                    jb.tok_first = lo;
+                    jb.tok_end = hi;
+                    jb.block_first = cur.n_blocks;
+                    jb.pad = 0;
+                    jobs.push_back(jb);
+                    ++cur.n_jobs;
+                    cur.n_blocks += take * PAGE_MOVE_SPLIT;
+                    fill += bytes;
+                    loaded_bytes += bytes;
+                    j += take;
+                }
+            }
+        }
+        flush();
+    }
+    size_t off_jobs = mw.put(jobs.data(), jobs.size() * sizeof(PageJob));
+    if (mw.overflow)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_batch: batch metadata exceeds the context's limits");
+
+    // ---- enqueue
+    char* md = c->meta_dev();
+    CF_HIP(hipEventRecord(c->ev_start, c->cs));
+    CF_HIP(hipMemcpyAsync(md, c->meta_host, mw.off, hipMemcpyHostToDevice, c->cs));
+    CF_HIP(hipEventRecord(c->ev_meta, c->cs));
+    CF_HIP(hipStreamWaitEvent(c->ps, c->ev_meta, 0));
+    CF_HIP(hipStreamWaitEvent(c->ss, c->ev_meta, 0));
+
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_elems = (int64_t)(cache->page_bytes / es);
+    g.layer_stride = g.page_elems * cache->n_pages;
+
+    // copy stream: fill a staging slot by DMA, then the scatter stream places its pages
+    bool slot_used[N_STAGING_SLOTS] = {};
+    for (const SlotPlan& sp : slots) {
+        if (slot_used[sp.slot]) CF_HIP(hipStreamWaitEvent(c->ps, c->ev_free[sp.slot], 0));
+        for (int k = 0; k < sp.n_ops; ++k) {
+            const CopyOp& op = ops[sp.op_first + k];
+            CF_HIP(hipMemcpyAsync(c->staging() + op.dst_off, op.src, op.bytes, hipMemcpyHostToDevice, c->ps));
+        }
+        CF_HIP(hipEventRecord(c->ev_filled[sp.slot], c->ps));
+        CF_HIP(hipStreamWaitEvent(c->ss, c->ev_filled[sp.slot], 0));
+        launch_page_move(c->ss, m.dtype, c->staging(), cache->pool,
+                         (const PageJob*)(md + off_jobs) + sp.job_first, sp.n_jobs, sp.n_blocks,
+                         (const int32_t*)md, g, true);
+        CF_HIP(hipEventRecord(c->ev_free[sp.slot], c->ss));
+        slot_used[sp.slot] = true;
+    }
+    CF_HIP(hipEventRecord(c->ev_scat, c->ss));
+    CF_HIP(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
+    CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+
+    // compute stream: recompute, layer-major over the batch
+    int max_cut = 0;
+    for (const Segment& s : rec.segs) max_cut = std::max(max_cut, s.layers);
+    run_phase(c, cache, rec, max_cut);
+    CF_HIP(hipEventRecord(c->ev_comp, c->cs));
+
+    // join, then the new-turn prefill and first-token logits
+    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
+    CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+    if (logits_out) {
+        run_phase(c, cache, suf, L);
+        launch_rmsnorm(c->cs, m.dtype, c->h(), c->w.final_norm, c->a_last(), B, m.d_model, m.rms_eps,
+                       (const int32_t*)(md + off_last));
+        gemm(c, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
+    }
+    CF_HIP(hipEventRecord(c->ev_end, c->cs));
+    CF_HIP(hipGetLastError());
+    CF_HIP(hipStreamSynchronize(c->cs));
+    CF_HIP(hipStreamSynchronize(c->ps));
+    CF_HIP(hipStreamSynchronize(c->ss));
+
+    if (timing) {
+        float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
+        CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
+        CF_HIP(hipEventElapsedTime(&t_copy, c->ev_start, c->ev_copy));
+        CF_HIP(hipEventElapsedTime(&t_join, c->ev_start, c->ev_t0));
+        CF_HIP(hipEventElapsedTime(&t_end, c->ev_start, c->ev_end));
+        timing->compute_ms = t_comp;
+        timing->copy_ms = t_copy;
+        timing->restore_ms = std::max(t_join, std::max(t_comp, t_copy));
+        timing->suffix_ms = t_end - t_join;
+        timing->total_ms = t_end;
+        double lin = linear_flops_per_token_layer(m);
+        double pair = 4.0 * m.n_q_heads * m.head_dim;
+        double fr = 0, fs = 0;
+        for (const Segment& s : rec.segs)
+            fr += (double)s.layers * (s.n_rows * lin + pair * ((double)s.n_rows * (s.n_rows + 1) / 2));
+        for (const Segment& s : suf.segs)
+            fs += (double)L * (s.n_rows * lin + pair * ((double)s.n_rows * s.pos0 +
+                                                        (double)s.n_rows * (s.n_rows + 1) / 2));
+        if (logits_out) fs += 2.0 * m.d_model * (double)m.vocab * B;
+        timing->recompute_flops = fr;
+        timing->suffix_flops = fs;
+        timing->loaded_bytes = loaded_bytes;
+        timing->recomputed_cells = rec_cells;
+        timing->loaded_cells = loaded_cells;
+    }
+    return CF_OK;
+}
+
+extern "C" int cf_offload(cf_ctx* c, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv) {
+    if (!c || !cache || !host_kv || n_ctx < 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_offload: bad argument");
+    int np = 0;
+    const int32_t* pt = cache->table_of(req_id, &np);
+    if (!cache->has(req_id)) return fail(CF_ERR_UNKNOWN_REQUEST, "cf_offload: request %llu has no pages",
+                         (unsigned long long)req_id);
+    int np_ctx = (int)ceil_div(n_ctx, CF_PAGE_TOKENS);
+    if (np_ctx > np) return fail(CF_ERR_INVALID_ARG, "cf_offload: request holds fewer than n_ctx tokens");
+    if (np_ctx == 0) return CF_OK;
+    const cf_model_desc& m = c->m;
+    size_t es = elem_bytes(m.dtype), pb = cache->page_bytes;
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_elems = (int64_t)(pb / es);
+    g.layer_stride = g.page_elems * cache->n_pages;
+    size_t cap_pages = c->cv.staging_bytes / pb;
+    char* md = c->meta_dev();
+    if ((size_t)np * 4 + sizeof(PageJob) + 64 > c->cv.meta_bytes)
+        return fail(CF_ERR_WORKSPACE, "cf_offload: page table exceeds the context's metadata area");
+    std::memcpy(c->meta_host, pt, (size_t)np * 4);
+    size_t job_off = ((size_t)np * 4 + 15) / 16 * 16;
+    CF_HIP(hipMemcpy(md, c->meta_host, (size_t)np * 4, hipMemcpyHostToDevice));
+    for (int l = 0; l < m.n_layers; ++l) {
+        for (int j = 0; j < np_ctx; j += (int)cap_pages) {
+            int take = (int)std::min<size_t>(cap_pages, (size_t)(np_ctx - j));
+            PageJob jb{0, l, 0, j, take, 0, n_ctx, 0, 0};
+            CF_HIP(hipMemcpy(md + job_off, &jb, sizeof(jb), hipMemcpyHostToDevice));
+            launch_page_move(c->cs, m.dtype, c->staging(), cache->pool, (const PageJob*)(md + job_off),
+                             1, take * PAGE_MOVE_SPLIT, (const int32_t*)md, g, false);
+            CF_HIP(hipGetLastError());
+            CF_HIP(hipStreamSynchronize(c->cs));
+            CF_HIP(hipMemcpy((char*)host_kv + ((size_t)l * np_ctx + j) * pb, c->staging(),
+                             (size_t)take * pb, hipMemcpyDeviceToHost));
+        }
+    }
+    return CF_OK;
+}
+
+extern "C" int cf_measure_h2d(cf_ctx* c, const void* host_buf, void* dev_buf, size_t bytes,
+                              int32_t reps, double* gb_per_s) {
+    if (!c || !host_buf || !dev_buf || bytes == 0 || reps <= 0 || !gb_per_s)
+        return fail(CF_ERR_INVALID_ARG, "cf_measure_h2d: bad argument");
+    CF_HIP(hipMemcpyAsync(dev_buf, host_buf, bytes, hipMemcpyHostToDevice, c->ps));  // warm-up
+    CF_HIP(hipEventRecord(c->ev_t0, c->ps));
+    for (int i = 0; i < reps; ++i)
+        CF_HIP(hipMemcpyAsync(dev_buf, host_buf, bytes, hipMemcpyHostToDevice, c->ps));
+    CF_HIP(hipEventRecord(c->ev_t1, c->ps));
+    CF_HIP(hipStreamSynchronize(c->ps));
+    float ms = 0;
+    CF_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+    *gb_per_s = (double)bytes * reps / (ms * 1e-3) / 1e9;
+    return CF_OK;
+}
+
+extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W2, float* Cf,
+                          void* Dt, int32_t M, int32_t N, int32_t K, int32_t epi, int32_t impl,
+                          int32_t reps, float* avg_ms) {
+    if (!c || !A || !W || M <= 0 || N <= 0 || K <= 0 || reps <= 0 || epi < 0 || epi > EPI_SILU_MUL)
+        return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: bad argument");
+    if ((epi == EPI_SILU_MUL && !W2) || ((epi == EPI_STORE_F32 || epi == EPI_ADD_F32) && !Cf) ||
+        ((epi == EPI_STORE_T || epi == EPI_SILU_MUL) && !Dt))
+        return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: missing operand for this epilogue");
+    bool mfma_ok = gemm_mfma_supported(c->m.dtype, M, N, K, epi);
+    if (impl == 2 && !mfma_ok) return fail(CF_ERR_UNSUPPORTED, "cf_op_gemm: MFMA kernel does not take this problem");
+    bool use_mfma = impl == 2 || (impl == 0 && mfma_ok && !c->simple_only);
+    CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+    for (int i = 0; i < reps; ++i) {
+        if (use_mfma) launch_gemm_mfma(c->cs, A, W, W2, Cf, Dt, M, N, K, epi);
+        else launch_gemm_simple(c->cs, c->m.dtype, A, W, W2, Cf, Dt, M, N, K, epi);
+    }
+    CF_HIP(hipEventRecord(c->ev_t1, c->cs));
+    CF_HIP(hipGetLastError());
+    CF_HIP(hipStreamSynchronize(c->cs));
+    float ms = 0;
+    CF_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+    if (avg_ms) *avg_ms = ms / reps;
+    return CF_OK;
+}

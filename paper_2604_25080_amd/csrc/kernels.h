@@ -1,0 +1,73 @@
+// Kernel launchers of the restoration library (internal).  Every launcher
+// enqueues on the given stream and returns; none synchronises or allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace cf {
+
+// bf16 carried as its 16 raw bits; conversions are explicit.
+struct bf16 {
+    uint16_t x;
+};
+
+enum Epilogue {
+    EPI_STORE_F32 = 0,  // C[m,n] = acc                     (float out)
+    EPI_ADD_F32 = 1,    // C[m,n] += acc                    (float residual stream)
+    EPI_STORE_T = 2,    // D[m,n] = (T)acc                  (model dtype out)
+    EPI_SILU_MUL = 3    // D[m,n] = (T)(silu(acc) * acc2)   acc2 from second weight W2
+};
+
+// One q-block of attention work: rows [row0, row0+n_rows) of the packed query
+// buffer belong to one request, the first of them sits at absolute position
+// pos0, and the request's page ids start at page_tables[pt_off].
+struct AttnWork {
+    int32_t row0, n_rows, pos0, pt_off;
+};
+constexpr int ATTN_BLOCK_ROWS = 128;
+
+// One contiguous run of pages of one layer of one request, staged in order.
+struct PageJob {
+    int64_t staging_off;   // byte offset of the run's first page in the staging buffer
+    int32_t layer;
+    int32_t pt_off;        // request's page table offset
+    int32_t page_first;    // index into the request's page table of the first page
+    int32_t n_pages;
+    int32_t tok_first;     // first token (absolute in request) to move
+    int32_t tok_end;       // one past the last token to move
+    int32_t block_first;   // first block index of this job in the launch grid
+    int32_t pad;
+};
+
+struct KvGeom {
+    int n_kv_heads, head_dim;
+    int64_t page_elems;        // elements per page
+    int64_t layer_stride;      // elements between layers in the pool
+};
+
+void launch_embed(hipStream_t s, int dtype, const void* E, const int32_t* tok, float* h, int T, int d);
+void launch_rmsnorm(hipStream_t s, int dtype, const float* h, const float* gain, void* out, int T,
+                    int d, float eps, const int32_t* row_idx);
+// A[M,K], W[N,K] (and W2) in the model dtype; Cf float [M,N] or Dt model dtype [M,N].
+void launch_gemm_simple(hipStream_t s, int dtype, const void* A, const void* W, const void* W2,
+                        float* Cf, void* Dt, int M, int N, int K, int epi);
+// true if the MFMA kernel supports this problem (bf16, aligned K)
+bool gemm_mfma_supported(int dtype, int M, int N, int K, int epi);
+void launch_gemm_mfma(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf,
+                      void* Dt, int M, int N, int K, int epi);
+void launch_rope_write(hipStream_t s, int dtype, const float* qkv, const int32_t* pos,
+                       const int32_t* slot, const float2* cos_sin, void* q_out, void* pool_layer,
+                       int T, int n_q_heads, KvGeom g);
+void launch_attention_simple(hipStream_t s, int dtype, const void* q, void* out,
+                             const void* pool_layer, const AttnWork* work, int n_work,
+                             const int32_t* page_tables, int n_q_heads, KvGeom g);
+bool attention_mfma_supported(int dtype, int head_dim, int n_q_heads, int n_kv_heads);
+void launch_attention_mfma(hipStream_t s, const void* q, void* out, const void* pool_layer,
+                           const AttnWork* work, int n_work, const int32_t* page_tables,
+                           int n_q_heads, KvGeom g);
+// staging -> pages (to_pages = true) or pages -> staging (false; zero-fills unused slots)
+void launch_page_move(hipStream_t s, int dtype, void* staging, void* pool, const PageJob* jobs,
+                      int n_jobs, int n_blocks, const int32_t* page_tables, KvGeom g, bool to_pages);
+
+}  // namespace cf

@@ -1,0 +1,223 @@
+// Batch-aware two-pointer restoration scheduler (Algorithm 1, Sec. 3.3) over
+// an integer cost model.  Host only.
+//
+// Each request is cut into units: chunks of C tokens through all layers
+// (token-wise, Sec. 3.1) or single layers over all tokens (layer-wise).  A
+// compute pointer climbs from unit 0, an I/O pointer descends from the last
+// unit; the request is finished when they have crossed.  The batch shares one
+// compute engine and one I/O channel, each with its own clock.  At every step
+// the compute engine's candidate is the next unfinished request in round-robin
+// order, the I/O channel's candidate is the unfinished request with the most
+// recomputation still ahead of it (Sec. 3.3), and whichever engine would be
+// done with its candidate first takes it (ties: compute).  Priorities are
+// re-evaluated after every unit (the "progressive, chunk-level" update).
+#include <vector>
+
+#include "cf_common.h"
+
+namespace {
+
+struct Units {
+    int mode = CF_TOKEN_WISE;
+    int n = 0;                      // context tokens
+    std::vector<int64_t> a_prefix;  // a_prefix[u] = sum of recompute cost of units < u
+    std::vector<int64_t> b;         // load cost per unit
+    std::vector<int64_t> tok_prefix;
+    int m() const { return (int)b.size(); }
+    int64_t a(int u) const { return a_prefix[u + 1] - a_prefix[u]; }
+};
+
+int64_t layer_pass_cost(const cf_cost_model& cm, int64_t layers, int64_t t, int64_t p0) {
+    int64_t pairs = t * p0 + t * (t + 1) / 2;
+    return layers * (cm.f_c + cm.alpha * t + cm.beta * cf::ceil_div(pairs, 1024));
+}
+
+int64_t load_cost(const cf_cost_model& cm, int64_t bytes) {
+    // bytes*gamma can exceed 2^63 only for absurd inputs; use 128-bit to be exact
+    __int128 num = (__int128)bytes * cm.gamma;
+    __int128 q = (num + ((__int128)1 << 20) - 1) >> 20;
+    return cm.f_io + (int64_t)q;
+}
+
+int mode_of(const cf_plan_opts& o, int n) {
+    if (o.force_mode == CF_TOKEN_WISE || o.force_mode == CF_LAYER_WISE) return o.force_mode;
+    return n >= o.l_delta ? CF_TOKEN_WISE : CF_LAYER_WISE;
+}
+
+Units make_units(const cf_cost_model& cm, const cf_plan_opts& o, int n, int mode) {
+    Units u;
+    u.mode = mode;
+    u.n = n;
+    u.a_prefix.push_back(0);
+    u.tok_prefix.push_back(0);
+    if (n <= 0) return u;
+    if (mode == CF_TOKEN_WISE) {
+        int c = o.chunk_tokens;
+        for (int64_t s = 0; s < n; s += c) {
+            int64_t t = (s + c <= n) ? c : n - s;
+            u.a_prefix.push_back(u.a_prefix.back() + layer_pass_cost(cm, o.n_layers, t, s));
+            u.b.push_back(load_cost(cm, t * o.n_layers * (int64_t)o.kv_bytes_per_token_layer));
+            u.tok_prefix.push_back(u.tok_prefix.back() + t * o.n_layers);
+        }
+    } else {
+        for (int l = 0; l < o.n_layers; ++l) {
+            u.a_prefix.push_back(u.a_prefix.back() + layer_pass_cost(cm, 1, n, 0));
+            u.b.push_back(load_cost(cm, (int64_t)n * o.kv_bytes_per_token_layer));
+            u.tok_prefix.push_back(u.tok_prefix.back() + n);
+        }
+    }
+    return u;
+}
+
+int check(const cf_cost_model* cm, const cf_plan_opts* o, int32_t B, const int32_t* n_ctx,
+          const char* who) {
+    if (!cm || !o || B < 0 || (B > 0 && !n_ctx))
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: null argument or negative batch", who);
+    if (o->chunk_tokens <= 0 || o->n_layers <= 0 || o->kv_bytes_per_token_layer <= 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: chunk_tokens, n_layers and KV bytes must be > 0",
+                        who);
+    if (o->io_key < 0 || o->io_key > CF_KEY_MARGINAL || o->force_mode < -1 || o->force_mode > 1)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: bad io_key or force_mode", who);
+    if (cm->f_c < 0 || cm->alpha < 0 || cm->beta < 0 || cm->f_io < 0 || cm->gamma < 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: negative cost coefficient", who);
+    for (int i = 0; i < B; ++i)
+        if (n_ctx[i] < 0) return cf::fail(CF_ERR_INVALID_ARG, "%s: n_ctx[%d] < 0", who, i);
+    return CF_OK;
+}
+
+}  // namespace
+
+extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                               const int32_t* n_ctx, cf_split* out, cf_plan_stats* stats,
+                               cf_claim* trace, int32_t trace_cap) {
+    int rc = check(cost, opts, B, n_ctx, "cf_restore_plan");
+    if (rc) return rc;
+    if (B > 0 && !out) return cf::fail(CF_ERR_INVALID_ARG, "cf_restore_plan: null out_splits");
+    if (trace_cap < 0 || (trace_cap > 0 && !trace))
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_restore_plan: bad trace buffer");
+
+    std::vector<Units> req(B);
+    std::vector<int> pc(B, 0), pio(B);
+    int n_live = 0;
+    for (int i = 0; i < B; ++i) {
+        req[i] = make_units(*cost, *opts, n_ctx[i], mode_of(*opts, n_ctx[i]));
+        pio[i] = req[i].m() - 1;
+        n_live += pc[i] <= pio[i];
+    }
+    int64_t t_c = 0, t_io = 0;
+    int rr = 0, n_claims = 0, n_trace = 0;
+    auto live = [&](int i) { return pc[i] <= pio[i]; };
+
+    while (n_live > 0) {
+        int ic = rr;
+        while (!live(ic)) ic = (ic + 1 == B) ? 0 : ic + 1;
+        int best = -1;
+        for (int i = 0; i < B; ++i) {
+            if (!live(i)) continue;
+            if (best < 0) { best = i; continue; }
+            bool gt, eq;
+            if (opts->io_key == CF_KEY_MARGINAL) {
+                __int128 ki = (__int128)req[i].a(pio[i]) * req[best].b[pio[best]];
+                __int128 kb = (__int128)req[best].a(pio[best]) * req[i].b[pio[i]];
+                gt = ki > kb; eq = ki == kb;
+            } else {
+                const auto& pi = opts->io_key == CF_KEY_REMAINING_COST ? req[i].a_prefix
+                                                                        : req[i].tok_prefix;
+                const auto& pb = opts->io_key == CF_KEY_REMAINING_COST ? req[best].a_prefix
+                                                                        : req[best].tok_prefix;
+                int64_t ki = pi[pio[i] + 1] - pi[pc[i]];
+                int64_t kb = pb[pio[best] + 1] - pb[pc[best]];
+                gt = ki > kb; eq = ki == kb;
+            }
+            if (gt || (eq && n_ctx[i] > n_ctx[best])) best = i;
+        }
+        int64_t fin_c = t_c + req[ic].a(pc[ic]);
+        int64_t fin_io = t_io + req[best].b[pio[best]];
+        cf_claim cl;
+        if (fin_c <= fin_io) {
+            cl = {0, ic, pc[ic]};
+            t_c = fin_c;
+            ++pc[ic];
+            if (!live(ic)) --n_live;
+            rr = (ic + 1 == B) ? 0 : ic + 1;
+        } else {
+            cl = {1, best, pio[best]};
+            t_io = fin_io;
+            --pio[best];
+            if (!live(best)) --n_live;
+        }
+        if (n_trace < trace_cap) trace[n_trace++] = cl;
+        ++n_claims;
+    }
+    for (int i = 0; i < B; ++i) {
+        out[i].mode = req[i].mode;
+        if (req[i].mode == CF_TOKEN_WISE) {
+            int64_t k = (int64_t)pc[i] * opts->chunk_tokens;
+            out[i].k_tokens = (int32_t)(k < n_ctx[i] ? k : n_ctx[i]);
+            out[i].layer_cut = opts->n_layers;
+        } else {
+            out[i].k_tokens = n_ctx[i];
+            out[i].layer_cut = pc[i];
+        }
+    }
+    if (stats) {
+        stats->t_comp = t_c;
+        stats->t_io = t_io;
+        stats->makespan = t_c > t_io ? t_c : t_io;
+        stats->n_claims = n_claims;
+        stats->n_trace = n_trace;
+    }
+    return CF_OK;
+}
+
+extern "C" int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                            const int32_t* n_ctx, const cf_split* splits, int64_t* t_comp,
+                            int64_t* t_io) {
+    int rc = check(cost, opts, B, n_ctx, "cf_plan_eval");
+    if (rc) return rc;
+    if ((B > 0 && !splits) || !t_comp || !t_io)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_eval: null argument");
+    int64_t tc = 0, tio = 0;
+    for (int i = 0; i < B; ++i) {
+        const cf_split& s = splits[i];
+        if (s.k_tokens < 0 || s.k_tokens > n_ctx[i] || s.layer_cut < 0 ||
+            s.layer_cut > opts->n_layers || (s.mode != CF_TOKEN_WISE && s.mode != CF_LAYER_WISE))
+            return cf::fail(CF_ERR_INVALID_PLAN, "cf_plan_eval: split %d out of range", i);
+        Units u = make_units(*cost, *opts, n_ctx[i], s.mode);
+        int n_comp = s.mode == CF_TOKEN_WISE
+                         ? (int)cf::ceil_div(s.k_tokens, opts->chunk_tokens)
+                         : s.layer_cut;
+        if (n_comp > u.m()) n_comp = u.m();
+        tc += u.a_prefix[n_comp];
+        for (int v = n_comp; v < u.m(); ++v) tio += u.b[v];
+    }
+    *t_comp = tc;
+    *t_io = tio;
+    return CF_OK;
+}
+
+extern "C" int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts,
+                                 int32_t n_max, int32_t* l_delta) {
+    int32_t dummy = 0;
+    int rc = check(cost, opts, 1, &dummy, "cf_derive_l_delta");
+    if (rc) return rc;
+    if (!l_delta || n_max < 0) return cf::fail(CF_ERR_INVALID_ARG, "cf_derive_l_delta: bad argument");
+    cf_plan_opts o = *opts;
+    o.l_delta = 0;
+    int64_t c = opts->chunk_tokens;
+    for (int64_t n = c; n <= n_max; n += c) {
+        int32_t nn = (int32_t)n;
+        cf_split s;
+        cf_plan_stats st_tok, st_lay;
+        o.force_mode = CF_TOKEN_WISE;
+        cf_restore_plan(cost, &o, 1, &nn, &s, &st_tok, nullptr, 0);
+        o.force_mode = CF_LAYER_WISE;
+        cf_restore_plan(cost, &o, 1, &nn, &s, &st_lay, nullptr, 0);
+        if (st_tok.makespan <= st_lay.makespan) {
+            *l_delta = nn;
+            return CF_OK;
+        }
+    }
+    *l_delta = (int32_t)(n_max + c);
+    return CF_OK;
+}

@@ -1,0 +1,179 @@
+"""Host side of the library vs the oracle, bit-exact, and the C-ABI surface.
+CPU only: no GPU call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_25080_amd as cf
+from oracle import planner as P
+from oracle.pagetable import PageTable
+from workloads import churn_script, hand_cost_model, make_batch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def both_cost(d):
+    return P.CostModel(**d), cf.cost_model(**d)
+
+
+def both_opts(chunk, l_delta, n_layers, kvb, mode=-1, key=0):
+    return P.PlanOpts(chunk, l_delta, n_layers, kvb, mode, key), cf.plan_opts(chunk, l_delta, n_layers, kvb, mode, key)
+
+
+# ------------------------------------------------------------------ C-ABI surface
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "cacheflow.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(cf_[a-z0-9_]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    assert declared == set(cf.binding.EXPORTS)
+    for name in declared:
+        assert hasattr(cf.lib, name), name
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert ctypes.sizeof(cf.cf_cost_model) == 40
+    assert ctypes.sizeof(cf.cf_plan_opts) == 24
+    assert ctypes.sizeof(cf.cf_split) == 12
+    assert ctypes.sizeof(cf.cf_plan_stats) == 32
+    assert ctypes.sizeof(cf.cf_model_desc) == 40
+    assert ctypes.sizeof(cf.cf_request) == 40
+    assert ctypes.sizeof(cf.cf_timing) == 64
+
+
+def test_status_strings():
+    assert cf.lib.cf_status_str(0) == b"ok"
+    assert b"pages" in cf.lib.cf_status_str(cf.CF_ERR_OUT_OF_PAGES)
+
+
+# --------------------------------------------------------------------- planner
+def test_planner_matches_oracle_on_random_batches():
+    rng = np.random.default_rng(41)
+    for trial in range(1500):
+        d = dict(f_c=int(rng.integers(0, 50_000_000)), alpha=int(rng.integers(1, 2_000_000)),
+                 beta=int(rng.integers(0, 60_000)), f_io=int(rng.integers(0, 20_000_000)),
+                 gamma=int(rng.integers(1, 900_000_000)))
+        ocm, ccm = both_cost(d)
+        chunk = 16 * int(rng.integers(1, 40))
+        oo, co = both_opts(chunk, int(rng.choice([0, 300, 2000, 10 ** 6])), int(rng.integers(1, 40)),
+                           int(rng.choice([512, 4096, 1024])), int(rng.integers(-1, 2)),
+                           int(rng.integers(0, 3)))
+        n_ctx = [int(rng.integers(0, 6000)) for _ in range(int(rng.integers(1, 12)))]
+        otrace = []
+        osplits, ostats = P.plan(ocm, oo, n_ctx, trace=otrace)
+        csplits, cstats, ctrace = cf.restore_plan(ccm, co, n_ctx, trace_cap=100000)
+        assert csplits == osplits, (trial, n_ctx)
+        assert cstats == ostats
+        assert ctrace == otrace
+
+
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_planner_matches_oracle_on_benchmark_batches(cfg):
+    b = make_batch(cfg)
+    s = b.shape
+    for kind in ("mi355x_like", "balanced", "slow_io"):
+        ocm, ccm = both_cost(hand_cost_model(kind))
+        oo, co = both_opts(b.chunk_tokens, 2048, s.n_layers, s.kv_bytes_per_token_layer, b.forced_mode)
+        otrace = []
+        osplits, ostats = P.plan(ocm, oo, b.n_ctx, trace=otrace)
+        csplits, cstats, ctrace = cf.restore_plan(ccm, co, b.n_ctx, trace_cap=len(otrace) + 5)
+        assert (csplits, cstats, ctrace) == (osplits, ostats, otrace)
+
+
+def test_plan_eval_and_l_delta_match_oracle():
+    rng = np.random.default_rng(42)
+    for _ in range(100):
+        d = hand_cost_model(str(rng.choice(["mi355x_like", "balanced", "slow_io", "uniform"])))
+        ocm, ccm = both_cost(d)
+        oo, co = both_opts(64 * int(rng.integers(1, 9)), 0, int(rng.integers(1, 33)), 4096, int(rng.integers(0, 2)))
+        n_ctx = [int(rng.integers(1, 5000)) for _ in range(3)]
+        splits, _ = P.plan(ocm, oo, n_ctx)
+        units = [(-(-s[1] // oo.chunk_tokens) if s[0] == 0 else s[2]) for s in splits]
+        assert cf.plan_eval(ccm, co, n_ctx, splits) == P.split_times(ocm, oo, n_ctx, units)
+    for kind in ("mi355x_like", "balanced", "slow_io"):
+        ocm, ccm = both_cost(hand_cost_model(kind))
+        oo, co = both_opts(512, 0, 32, 4096)
+        assert cf.derive_l_delta(ccm, co, 20000) == P.derive_l_delta(ocm, oo, 20000)
+
+
+def test_planner_rejects_bad_arguments():
+    cm = cf.cost_model(**hand_cost_model("balanced"))
+    with pytest.raises(cf.CfError) as e:
+        cf.restore_plan(cm, cf.plan_opts(0, 0, 32, 4096), [100])
+    assert e.value.status == cf.CF_ERR_INVALID_ARG
+    with pytest.raises(cf.CfError):
+        cf.restore_plan(cm, cf.plan_opts(512, 0, 32, 4096), [-1])
+    with pytest.raises(cf.CfError) as e:
+        cf.plan_eval(cm, cf.plan_opts(512, 0, 32, 4096), [100], [(0, 101, 32)])
+    assert e.value.status == cf.CF_ERR_INVALID_PLAN
+    assert cf.restore_plan(cm, cf.plan_opts(512, 0, 32, 4096), [])[0] == []
+
+
+def test_planner_is_fast_enough_for_the_serving_path():
+    import time
+    b = make_batch("cfg4")
+    cm = cf.cost_model(**hand_cost_model("mi355x_like"))
+    o = cf.plan_opts(512, 2048, 32, 4096)
+    t0 = time.perf_counter()
+    for _ in range(20):
+        cf.restore_plan(cm, o, b.n_ctx)
+    assert (time.perf_counter() - t0) / 20 < 5e-3
+
+
+# ------------------------------------------------------------------ page table
+def test_page_table_matches_oracle_under_churn():
+    for seed in range(8):
+        n_pages = 96
+        page_bytes = 2 * 2 * 16 * 64 * 4
+        c = cf.Cache(0, n_pages * 3 * page_bytes + 17, 3, 2, 64, cf.CF_F32)
+        o = PageTable(n_pages)
+        assert c.n_pages == n_pages and c.page_bytes == page_bytes
+        for op in churn_script(seed, n_pages, n_ops=120):
+            if op[0] == "alloc":
+                c.alloc(op[1], op[2])
+                assert c.page_table(op[1]) == o.alloc(op[1], op[2])
+            else:
+                c.free(op[1])
+                o.release(op[1])
+            assert c.n_free == o.n_free()
+        for rid in o.tables:
+            assert c.page_table(rid) == o.table(rid)
+
+
+def test_page_table_errors():
+    c = cf.Cache(0, 4 * 2 * 1 * 16 * 64 * 2 * 2, 2, 1, 64, cf.CF_BF16)
+    assert c.n_pages == 4
+    c.alloc(7, 40)
+    with pytest.raises(cf.CfError) as e:
+        c.alloc(7, 1)
+    assert e.value.status == cf.CF_ERR_UNKNOWN_REQUEST
+    with pytest.raises(cf.CfError) as e:
+        c.alloc(8, 2 * 16 + 1)
+    assert e.value.status == cf.CF_ERR_OUT_OF_PAGES
+    with pytest.raises(cf.CfError) as e:
+        c.free(9)
+    assert e.value.status == cf.CF_ERR_UNKNOWN_REQUEST
+    c.alloc(8, 0)
+    assert c.page_table(8) == []
+    c.free(7)
+    assert c.n_free == 4
+
+
+def test_host_kv_bytes_follows_the_size_formula():
+    # 2 * L * Hkv * hd * N elements (Sec. 2), rounded up to whole 16-token pages
+    assert cf.host_kv_bytes(32, 8, 128, cf.CF_BF16, 4096) == 2 * 32 * 8 * 128 * 4096 * 2
+    assert cf.host_kv_bytes(2, 4, 64, cf.CF_F32, 17) == 2 * 2 * 4 * 64 * 32 * 4
+
+
+def test_workspace_and_ctx_argument_checks_need_no_gpu():
+    from workloads import SHAPES
+    d = cf.model_desc(SHAPES["tiny"])
+    assert cf.workspace_bytes(d, cf.ctx_opts(2, 256, 256)) > 0
+    bad = cf.model_desc(SHAPES["tiny"])
+    bad.head_dim = 96
+    with pytest.raises(cf.CfError) as e:
+        cf.workspace_bytes(bad, cf.ctx_opts(2, 256, 256))
+    assert e.value.status == cf.CF_ERR_UNSUPPORTED
