@@ -219,19 +219,22 @@ def layer_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
 
 
 def kv_to_pages(shape, cache, n_tokens, page_tokens=16):
-    """Lay a request's cache out as the host KV block:
-    [layer][page][K|V][kv_head][slot][hd] in the model's storage precision
-    (float32 here; callers round for 16-bit models).  Unused slots of the
-    last page are zero."""
+    """Lay a request's cache out as the host KV block of the boundary:
+    [layer][page] with each page = K part [kv_head][slot][hd] followed by the
+    V part stored transposed, [kv_head][hd][slot].  Returned as float32
+    [L, n_pages, 2*Hkv*page_tokens*hd] (callers round for 16-bit models).
+    Unused slots of the last page are zero."""
     s = shape
     n_pages = -(-n_tokens // page_tokens)
-    out = np.zeros((s.n_layers, n_pages, 2, s.n_kv_heads, page_tokens,
-                    s.head_dim), dtype=np.float32)
+    half = s.n_kv_heads * page_tokens * s.head_dim
+    out = np.zeros((s.n_layers, n_pages, 2 * half), dtype=np.float32)
     for l in range(s.n_layers):
-        for which, src in ((0, cache.k[l]), (1, cache.v[l])):
-            pad = np.zeros((n_pages * page_tokens, s.n_kv_heads, s.head_dim),
-                           dtype=np.float32)
-            pad[:n_tokens] = src[:n_tokens]
-            out[l, :, which] = pad.reshape(n_pages, page_tokens, s.n_kv_heads,
-                                           s.head_dim).transpose(0, 2, 1, 3)
+        kpad = np.zeros((n_pages * page_tokens, s.n_kv_heads, s.head_dim), dtype=np.float32)
+        vpad = np.zeros_like(kpad)
+        kpad[:n_tokens] = cache.k[l][:n_tokens]
+        vpad[:n_tokens] = cache.v[l][:n_tokens]
+        kp = kpad.reshape(n_pages, page_tokens, s.n_kv_heads, s.head_dim)
+        vp = vpad.reshape(n_pages, page_tokens, s.n_kv_heads, s.head_dim)
+        out[l, :, :half] = kp.transpose(0, 2, 1, 3).reshape(n_pages, half)   # [g][slot][hd]
+        out[l, :, half:] = vp.transpose(0, 2, 3, 1).reshape(n_pages, half)   # [g][hd][slot]
     return out

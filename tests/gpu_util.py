@@ -1,0 +1,54 @@
+"""Test-side helpers: decode raw KV pages into token-major arrays, build
+oracle references for a batch, compare with the bf16-aware tolerance."""
+import numpy as np
+
+from oracle import transformer as T
+from workloads import WeightSource, bits_to_f32, bf16_bits
+
+
+def decode_pages(shape, raw, n_tokens):
+    """raw uint8 [L, P, page_bytes] -> (K, V) float32 [L, n_tokens, Hkv, hd]."""
+    L, P, _ = raw.shape
+    hk, hd = shape.n_kv_heads, shape.head_dim
+    if shape.dtype == "f32":
+        vals = raw.view(np.float32)
+    else:
+        vals = bits_to_f32(raw.view(np.uint16).reshape(-1)).reshape(L, P, -1)
+    vals = vals.reshape(L, P, -1)
+    half = hk * 16 * hd
+    k = vals[:, :, :half].reshape(L, P, hk, 16, hd).transpose(0, 1, 3, 2, 4).reshape(L, P * 16, hk, hd)
+    v = vals[:, :, half:].reshape(L, P, hk, hd, 16).transpose(0, 1, 4, 2, 3).reshape(L, P * 16, hk, hd)
+    return k[:, :n_tokens].copy(), v[:, :n_tokens].copy()
+
+
+def host_block(shape, pages_f32):
+    """oracle float32 page array -> array in the model's storage format."""
+    if shape.dtype == "f32":
+        return np.ascontiguousarray(pages_f32, dtype=np.float32)
+    return bf16_bits(pages_f32)
+
+
+def oracle_batch(batch, dtype=np.float64, weights=None):
+    """Full-prefill reference per request: list of (kv_ctx, kv_new, logits)."""
+    ws = weights or WeightSource(batch.shape, batch.weight_seed, cache=True)
+    return [T.full_reference(batch.shape, ws, batch.ctx_tokens[i], batch.new_tokens[i], dtype)
+            for i in range(len(batch.n_ctx))], ws
+
+
+def stack_kv(shape, kv_ctx, kv_new):
+    """-> (K, V) float64 [L, n_ctx+n_new, Hkv, hd]"""
+    k = np.stack([np.concatenate([kv_ctx.k[l], kv_new.k[l]]) for l in range(shape.n_layers)])
+    v = np.stack([np.concatenate([kv_ctx.v[l], kv_new.v[l]]) for l in range(shape.n_layers)])
+    return k, v
+
+
+def kv_tolerance_ok(shape, got, ref):
+    """max-abs 1e-4 for float32 models; for bf16 models 2e-2 where |ref| < 8 and one bf16
+    ulp of ref above that.  Returns (ok, worst_abs_err, n_large)."""
+    err = np.abs(got.astype(np.float64) - ref)
+    if shape.dtype == "f32":
+        return bool(err.max(initial=0.0) <= 1e-4), float(err.max(initial=0.0)), 0
+    large = np.abs(ref) >= 8.0
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+    ok = np.where(large, err <= ulp, err <= 2e-2)
+    return bool(ok.all()), float(err.max(initial=0.0)), int(large.sum())

@@ -1,0 +1,148 @@
+"""GPU parity, configuration 1 (tiny float32 decoder, B=2, n=(128,64), forced
+splits k=(64,32), 16 new tokens each): page tables bit-exact, KV and
+first-token logits within 1e-4 of the oracle, loaded cells byte-identical."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transformer as T
+from oracle.pagetable import PageTable
+from workloads import WeightSource, churn_script, make_batch
+
+from gpu_util import decode_pages, host_block, kv_tolerance_ok, oracle_batch, stack_kv
+
+pytestmark = pytest.mark.gpu
+
+N_PAGES = 64
+
+
+@pytest.fixture(scope="module")
+def env():
+    from paper_2604_25080_amd.runtime import Session
+    b = make_batch("cfg1")
+    refs, ws = oracle_batch(b)
+    sess = Session(b.shape, ws, max_batch=4, max_tokens=512, max_positions=256, n_pages=N_PAGES,
+                   chunk_rows=256, pool_fill=0xFF)
+    host = [sess.pin_host_kv(host_block(b.shape, T.kv_to_pages(b.shape, refs[i][0], b.n_ctx[i])))
+            for i in range(len(b.n_ctx))]
+    yield b, refs, ws, sess, host
+    sess.close()
+
+
+def fragment(sess, oracle_pt, seed):
+    for op in churn_script(seed, N_PAGES, n_ops=40, max_tokens=60):
+        if op[0] == "alloc":
+            sess.cache.alloc(1000 + op[1], op[2])
+            oracle_pt.alloc(1000 + op[1], op[2])
+        else:
+            sess.cache.free(1000 + op[1])
+            oracle_pt.release(1000 + op[1])
+
+
+def run_and_check(env, splits, seed=3, check_logits=True):
+    b, refs, ws, sess, host = env
+    sess.pool.fill_(0xFF)                       # NaN pattern: every owned slot must be overwritten
+    opt = PageTable(N_PAGES)
+    stale = [r for r in list(opt.tables)]
+    assert not stale
+    fragment(sess, opt, seed)
+    reqs = []
+    try:
+        for i in range(len(b.n_ctx)):
+            rid = 1 + i
+            sess.cache.alloc(rid, b.n_ctx[i] + b.n_new[i])
+            assert sess.cache.page_table(rid) == opt.alloc(rid, b.n_ctx[i] + b.n_new[i])
+            reqs.append(dict(req_id=rid, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i],
+                             host_kv=host[i]))
+        logits, tm = sess.restore(reqs, [(0, k, c) for k, c in splits])
+        for i in range(len(b.n_ctx)):
+            n, m = b.n_ctx[i], b.n_new[i]
+            raw = sess.read_pages(1 + i, n + m)
+            k, v = decode_pages(b.shape, raw, n + m)
+            rk, rv = stack_kv(b.shape, refs[i][0], refs[i][1])
+            for got, ref, nm in ((k, rk, "K"), (v, rv, "V")):
+                assert np.isfinite(got).all(), f"request {i}: unwritten {nm} slot"
+                ok, worst, _ = kv_tolerance_ok(b.shape, got, ref)
+                assert ok, f"request {i} {nm}: max abs err {worst}"
+            # loaded cells are byte-identical to the host block
+            kk, cc = splits[i]
+            hk, hv = decode_pages(b.shape, host[i].numpy()[:sess.host_kv_bytes(n)].reshape(
+                b.shape.n_layers, -1, sess.page_bytes), n)
+            for l in range(b.shape.n_layers):
+                lo = kk if l < cc else 0
+                assert np.array_equal(k[l, lo:n], hk[l, lo:n]) and np.array_equal(v[l, lo:n], hv[l, lo:n])
+            if check_logits:
+                err = np.abs(logits[i].cpu().numpy().astype(np.float64) - refs[i][2]).max()
+                assert err <= 1e-4, f"request {i}: logits max abs err {err}"
+        return tm
+    finally:
+        for rid in list(opt.tables):
+            sess.cache.free(rid)
+        assert sess.cache.n_free == N_PAGES
+
+
+def test_cfg1_forced_splits(env):
+    b = env[0]
+    tm = run_and_check(env, b.forced_splits)
+    assert tm["recomputed_cells"] == (64 + 32) * 2
+    assert tm["loaded_cells"] == (64 + 32) * 2
+    assert tm["loaded_bytes"] >= tm["loaded_cells"] * b.shape.kv_bytes_per_token_layer
+
+
+def test_cfg1_all_recompute_and_all_load(env):
+    b = env[0]
+    run_and_check(env, [(n, 2) for n in b.n_ctx], seed=4)
+    tm = run_and_check(env, [(0, 2) for n in b.n_ctx], seed=5)
+    assert tm["recomputed_cells"] == 0
+    run_and_check(env, [(n, 0) for n in b.n_ctx], seed=5)     # cut 0: everything loaded
+
+
+def test_cfg1_every_cut_and_a_sweep_of_unaligned_splits(env):
+    b = env[0]
+    ks = [0, 1, 15, 16, 17, 31, 33, 47, 63, 64]
+    for c in (0, 1, 2):
+        for k in ks:
+            run_and_check(env, [(min(2 * k, b.n_ctx[0]), c), (k, 2 - c if k % 2 else c)], seed=6 + c,
+                          check_logits=(k % 16 == 1))
+
+
+def test_cfg1_pages_outside_the_batch_are_untouched(env):
+    b, refs, ws, sess, host = env
+    sess.pool.fill_(0xAB)
+    sess.cache.alloc(50, 16 * 3)            # guard pages 0..2
+    reqs = []
+    for i in range(2):
+        sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
+        reqs.append(dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=host[i]))
+    used = set(sess.cache.page_table(1) + sess.cache.page_table(2))
+    sess.restore(reqs, [(0, 64, 2), (0, 32, 2)])
+    view = sess.pool.view(b.shape.n_layers, N_PAGES, sess.page_bytes)
+    other = [p for p in range(N_PAGES) if p not in used]
+    assert bool((view[:, other] == 0xAB).all())
+    for rid in (50, 1, 2):
+        sess.cache.free(rid)
+
+
+def test_cfg1_error_paths_return_codes_not_faults(env):
+    import paper_2604_25080_amd as cf
+    b, refs, ws, sess, host = env
+    sess.cache.alloc(1, b.n_ctx[0] + b.n_new[0])
+    r = dict(req_id=1, ctx_tokens=b.ctx_tokens[0], new_tokens=b.new_tokens[0], host_kv=host[0])
+    try:
+        for bad, code in (((0, 129, 2), cf.CF_ERR_INVALID_PLAN), ((0, 64, 3), cf.CF_ERR_INVALID_PLAN)):
+            with pytest.raises(cf.CfError) as e:
+                sess.restore([r], [bad])
+            assert e.value.status == code
+        with pytest.raises(cf.CfError) as e:
+            sess.restore([dict(r, req_id=99)], [(0, 64, 2)])
+        assert e.value.status == cf.CF_ERR_UNKNOWN_REQUEST
+        with pytest.raises(cf.CfError) as e:
+            sess.restore([dict(r, host_kv=None)], [(0, 64, 2)])
+        assert e.value.status == cf.CF_ERR_INVALID_ARG
+        toks = b.ctx_tokens[0].copy()
+        toks[3] = 1000
+        with pytest.raises(cf.CfError):
+            sess.restore([dict(r, ctx_tokens=toks)], [(0, 64, 2)])
+        sess.restore([dict(r, host_kv=None)], [(0, 128, 2)])      # nothing loaded: no host KV needed
+    finally:
+        sess.cache.free(1)

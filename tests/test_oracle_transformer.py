@@ -292,8 +292,12 @@ def test_kv_to_pages_layout():
         cache.k[l] = idx.astype(np.float64)
         cache.v[l] = -idx.astype(np.float64)
     pages = T.kv_to_pages(shape, cache, n)
-    assert pages.shape == (shape.n_layers, 3, 2, shape.n_kv_heads, 16, shape.head_dim)
+    hk, hd = shape.n_kv_heads, shape.head_dim
+    assert pages.shape == (shape.n_layers, 3, 2 * hk * 16 * hd)
     for (l, t, g, j) in ((0, 0, 0, 0), (1, 17, 1, 3), (1, 36, 0, 7)):
-        assert pages[l, t // 16, 0, g, t % 16, j] == np.float32(cache.k[l][t, g, j])
-        assert pages[l, t // 16, 1, g, t % 16, j] == np.float32(cache.v[l][t, g, j])
-    assert np.all(pages[:, 2, :, :, 5:, :] == 0)
+        pg, sl = t // 16, t % 16
+        assert pages[l, pg, (g * 16 + sl) * hd + j] == np.float32(cache.k[l][t, g, j])
+        assert pages[l, pg, hk * 16 * hd + (g * hd + j) * 16 + sl] == np.float32(cache.v[l][t, g, j])
+    kpart = pages[:, 2, :hk * 16 * hd].reshape(shape.n_layers, hk, 16, hd)
+    vpart = pages[:, 2, hk * 16 * hd:].reshape(shape.n_layers, hk, hd, 16)
+    assert np.all(kpart[:, :, 5:, :] == 0) and np.all(vpart[:, :, :, 5:] == 0)
