@@ -1,0 +1,72 @@
+"""GPU kernel parity: the MFMA GEMM (all fused epilogues) and the plain FMA
+GEMM against the definition (a float64 matmul of the same bf16 inputs), at
+sizes that span several tiles with ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import SHAPES, WeightSource, bf16_bits, bits_to_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sess():
+    from paper_2604_25080_amd.runtime import Session
+    shape = SHAPES["mini-bf16"].with_layers(1)
+    s = Session(shape, WeightSource(shape, 5), max_batch=2, max_tokens=256, max_positions=256, n_pages=8)
+    yield s
+    s.close()
+
+
+def dev_bf16(x):
+    return torch.from_numpy(bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def from_bf16(t):
+    return bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)).reshape(t.shape)
+
+
+SHAPES_MNK = [(256, 256, 64), (300, 544, 512), (1000, 1408, 512), (129, 96, 1408), (2, 2000, 512),
+              (2048, 1280, 1024)]
+
+
+@pytest.mark.parametrize("impl", [2, 1])
+@pytest.mark.parametrize("mnk", SHAPES_MNK)
+def test_gemm_epilogues_match_float64_matmul(sess, impl, mnk):
+    import paper_2604_25080_amd as cf
+    M, N, K = mnk
+    rng = np.random.default_rng(M * 7 + N)
+    a = bits_to_f32(bf16_bits(rng.normal(size=(M, K)).astype(np.float32)))
+    w = bits_to_f32(bf16_bits((rng.normal(size=(N, K)) * 0.05).astype(np.float32)))
+    w2 = bits_to_f32(bf16_bits((rng.normal(size=(N, K)) * 0.05).astype(np.float32)))
+    ref = a.astype(np.float64) @ w.astype(np.float64).T
+    ref2 = a.astype(np.float64) @ w2.astype(np.float64).T
+    A, W, W2 = dev_bf16(a), dev_bf16(w), dev_bf16(w2)
+    Cf = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+    Dt = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+    tol = 1e-4 * np.sqrt(K / 512)
+
+    sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), 0, Cf.data_ptr(), 0, M, N, K, cf.EPI_STORE_F32, impl)
+    assert np.abs(Cf.cpu().numpy() - ref).max() <= tol
+    base = torch.from_numpy(rng.normal(size=(M, N)).astype(np.float32)).cuda()
+    Cf.copy_(base)
+    sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), 0, Cf.data_ptr(), 0, M, N, K, cf.EPI_ADD_F32, impl)
+    assert np.abs(Cf.cpu().numpy() - (ref + base.cpu().numpy())).max() <= tol
+    sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), 0, 0, Dt.data_ptr(), M, N, K, cf.EPI_STORE_T, impl)
+    got = from_bf16(Dt)
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + tol)      # one bf16 rounding
+    sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), W2.data_ptr(), 0, Dt.data_ptr(), M, N, K, cf.EPI_SILU_MUL, impl)
+    want = ref / (1.0 + np.exp(-ref)) * ref2
+    got = from_bf16(Dt)
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -8 + 4 * tol)
+
+
+def test_gemm_mfma_refuses_what_it_cannot_tile(sess):
+    import paper_2604_25080_amd as cf
+    A = torch.zeros(64, 40, dtype=torch.bfloat16, device="cuda")
+    Cf = torch.zeros(64, 64, dtype=torch.float32, device="cuda")
+    with pytest.raises(cf.CfError) as e:
+        sess.ctx.op_gemm(A.data_ptr(), A.data_ptr(), 0, Cf.data_ptr(), 0, 64, 64, 40, cf.EPI_STORE_F32, 2)
+    assert e.value.status == cf.CF_ERR_UNSUPPORTED
+    sess.ctx.op_gemm(A.data_ptr(), A.data_ptr(), 0, Cf.data_ptr(), 0, 64, 64, 40, cf.EPI_STORE_F32, 0)
