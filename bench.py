@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of batched hybrid KV-cache restoration on one MI355X.
+
+One step = one pass of the whole hot path over one batch: plan the splits
+(host scheduler over the calibrated cost model), recompute ‖ load+scatter,
+join, prefill the new-turn tokens over the restored pages, first-token logits.
+Inputs are synthetic (seeded token ids, random-init weights of the named
+shape) and already resident (weights in HBM, host KV in pinned memory) when
+the timed region starts.
+
+    python bench.py --gpus 1 --steps K --warmup W [--config cfg2] [--plan planner]
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(batch, n_tok=1024, n_layers=2):
+    """Time the CPU oracle (as it stands) on a bounded slice of the workload."""
+    import numpy as np
+    from oracle import transformer as T
+    from workloads import WeightSource
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    shape = batch.shape
+    ws = WeightSource(shape, batch.weight_seed, cache=True)
+    n_tok = min(n_tok, batch.n_ctx[0])
+    n_layers = min(n_layers, shape.n_layers)
+    ws.f32("embed")
+    for l in range(n_layers):
+        ws.layer_f32(l)
+    t0 = time.perf_counter()
+    T.prefill(shape, ws, batch.ctx_tokens[0][:n_tok], n_layers=n_layers, dtype=np.float32)
+    dt = time.perf_counter() - t0
+    tok_layers_per_s = n_tok * n_layers / dt
+    return {
+        "value": tok_layers_per_s / shape.n_layers, "unit": "restored tokens/s",
+        "cores": int(cores), "kind": "oracle",
+        "sample": (f"oracle float32 recompute of the first {n_tok} tokens of request 0 through "
+                   f"{n_layers} of {shape.n_layers} layers ({dt:.2f} s), scaled by layer count; "
+                   "loading is a memcpy and is not part of the sample"),
+        "token_layers_per_s": tok_layers_per_s,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--plan", default="planner",
+                    help="planner | all_recompute | all_load | cut=<L> (layer cut for every request)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink context lengths (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-rows", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+            f"--gpus {args.gpus} is not supported.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2604_25080_amd as cf
+    from paper_2604_25080_amd.runtime import Session
+    from workloads import WeightSource, make_batch
+
+    batch = make_batch(args.config, scale=args.scale)
+    shape = batch.shape
+    B = len(batch.n_ctx)
+    L = shape.n_layers
+    sum_ctx, sum_new = sum(batch.n_ctx), sum(batch.n_new)
+    log(f"[bench] {args.config}: {shape.name} B={B} sum n_ctx={sum_ctx} sum n_new={sum_new}")
+
+    t0 = time.perf_counter()
+    calib_tokens = 8192
+    pages = sum(-(-(n + m) // 16) for n, m in zip(batch.n_ctx, batch.n_new)) + calib_tokens // 16 + 64
+    sess = Session(shape, WeightSource(shape, batch.weight_seed), max_batch=max(B, 8),
+                   max_tokens=max(sum_ctx, sum_new, calib_tokens),
+                   max_positions=max(max(n + m for n, m in zip(batch.n_ctx, batch.n_new)), calib_tokens) + 16,
+                   n_pages=pages, chunk_rows=args.chunk_rows, gen_threads=16)
+    log(f"[bench] weights + pool + workspace ready in {time.perf_counter() - t0:.1f} s")
+
+    # ---- manufacture the host KV (not timed): full prefill on the GPU, then offload
+    t0 = time.perf_counter()
+    reqs = []
+    for i in range(B):
+        sess.cache.alloc(1 + i, batch.n_ctx[i] + batch.n_new[i])
+        reqs.append(dict(req_id=1 + i, ctx_tokens=batch.ctx_tokens[i], new_tokens=batch.new_tokens[i],
+                         host_kv=None))
+    _, tm_full = sess.restore(reqs, [(0, n, L) for n in batch.n_ctx], want_logits=False)
+    for i in range(B):
+        reqs[i]["host_kv"] = sess.offload(1 + i, batch.n_ctx[i])
+    log(f"[bench] host KV manufactured in {time.perf_counter() - t0:.1f} s "
+        f"(all-recompute pass: {tm_full['compute_ms']:.1f} ms, "
+        f"{tm_full['recompute_flops'] / tm_full['compute_ms'] / 1e9:.0f} TFLOP/s)")
+
+    # ---- measured rooflines of the load path and the cost model
+    big = max(reqs, key=lambda r: r["host_kv"].numel())["host_kv"]
+    h2d_bytes = min(big.numel(), 1 << 30)
+    dev_scratch = torch.empty(h2d_bytes, dtype=torch.uint8, device="cuda")
+    h2d_gbs = sess.ctx.measure_h2d(big.data_ptr(), dev_scratch.data_ptr(), h2d_bytes, reps=4)
+    del dev_scratch
+    need = sess.host_kv_bytes(calib_tokens)
+    scratch = big if big.numel() >= need else sess.pinned(need)
+    cm = sess.ctx.calibrate(sess.cache, scratch.data_ptr(), scratch.numel())
+    cost = dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io, gamma=cm.gamma)
+    opts = cf.plan_opts(batch.chunk_tokens, 0, L, shape.kv_bytes_per_token_layer, batch.forced_mode)
+    l_delta = cf.derive_l_delta(cm, opts, 32768)
+    opts.l_delta = l_delta
+    log(f"[bench] H2D {h2d_gbs:.1f} GB/s; cost model {cost}; L_delta {l_delta}")
+
+    def make_plan():
+        if args.plan == "planner":
+            if batch.forced_splits:
+                return [(0, k, c) for k, c in batch.forced_splits], None
+            splits, stats, _ = cf.restore_plan(cm, opts, batch.n_ctx)
+            return splits, stats
+        if args.plan == "all_recompute":
+            return [(0, n, L) for n in batch.n_ctx], None
+        if args.plan == "all_load":
+            return [(0, 0, L) for n in batch.n_ctx], None
+        if args.plan.startswith("cut="):
+            c = int(args.plan[4:])
+            return [(1, n, c) for n in batch.n_ctx], None
+        raise SystemExit(f"unknown plan {args.plan}")
+
+    gemm_kernels = ["gemm_qkv", "gemm_oproj", "gemm_gate_up", "gemm_down", "gemm_lm_head"]
+    prof_kernels = gemm_kernels + ["attention", "h2d_copy", "page_scatter"]
+
+    def step():
+        splits, stats = make_plan()
+        logits, tm = sess.restore(reqs, splits)
+        return splits, stats, tm
+
+    for _ in range(args.warmup):
+        step()
+    sess.ctx.profile(prof_kernels)
+    sess.ctx.profile_read(reset=True)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    tms = []
+    for _ in range(args.steps):
+        splits, stats, tm = step()
+        tms.append(tm)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    prof = sess.ctx.profile_read(reset=True)
+    sess.ctx.profile([])
+
+    ms_per_step = wall / args.steps * 1e3
+    mean = lambda k: float(np.mean([t[k] for t in tms]))
+    restore_ms, ttft_ms = mean("restore_ms"), mean("total_ms")
+    compute_ms, copy_ms, suffix_ms = mean("compute_ms"), mean("copy_ms"), mean("suffix_ms")
+    rec_flops, suf_flops = tms[-1]["recompute_flops"], tms[-1]["suffix_flops"]
+    loaded_bytes = tms[-1]["loaded_bytes"]
+
+    # dominant kernel of the recompute path: the gate/up GEMM (SiLU*mul epilogue)
+    dom = prof["gemm_gate_up"]
+    is_bf16 = shape.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
+    roofline = None
+    if dom["launches"]:
+        avg_ms = dom["total_ms"] / dom["launches"]
+        ach = dom["work"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(f"{args.config}:gemm_gate_up")
+        roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "gemm_gate_up (MFMA GEMM, SiLU*mul epilogue)",
+                    "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                    "traffic": traffic, "launches": dom["launches"], "avg_launch_ms": avg_ms,
+                    "flops_per_launch": dom["work"] / dom["launches"]}
+    kernels = {}
+    for k in prof_kernels:
+        p = prof[k]
+        if not p["launches"]:
+            continue
+        rate = p["work"] / (p["total_ms"] * 1e-3)
+        kernels[k] = {"launches": p["launches"], "total_ms_per_step": p["total_ms"] / args.steps,
+                      ("GB/s" if k in ("h2d_copy", "page_scatter") else "TFLOP/s"):
+                          rate / (1e9 if k in ("h2d_copy", "page_scatter") else 1e12)}
+    all_gemm_ms = sum(prof[k]["total_ms"] for k in gemm_kernels)
+    all_gemm_fl = sum(prof[k]["work"] for k in gemm_kernels)
+    copy_gbs = loaded_bytes / (copy_ms * 1e-3) / 1e9 if copy_ms > 0 and loaded_bytes else 0.0
+
+    out = {
+        "metric": "restored tokens/s", "value": sum_ctx * args.steps / wall, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config}: {shape.name} shape, B={B}, sum n_ctx={sum_ctx}, "
+                               f"n_new={sum_new}, plan={args.plan}, chunk C={batch.chunk_tokens}",
+                   "n_ctx": batch.n_ctx, "splits": [list(s) for s in splits]},
+        "ttft_ms": ttft_ms, "restore_ms": restore_ms, "compute_stream_ms": compute_ms,
+        "copy_stream_ms": copy_ms, "suffix_ms": suffix_ms,
+        "restore_tokens_per_s": sum_ctx / (restore_ms * 1e-3),
+        "recompute": {"tokens": int(sum(s[1] for s in splits if s[2] > 0)),
+                      "tflops": rec_flops / (compute_ms * 1e-3) / 1e12 if rec_flops else 0.0,
+                      "frac_of_mfma_peak": rec_flops / (compute_ms * 1e-3) / 1e12 / peak if rec_flops else 0.0,
+                      "all_gemm_tflops": all_gemm_fl / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else 0.0},
+        "copy": {"bytes": int(loaded_bytes), "GB/s": copy_gbs, "h2d_measured_GB/s": h2d_gbs,
+                 "frac_of_measured_h2d": copy_gbs / h2d_gbs if h2d_gbs else 0.0},
+        "all_recompute_pass": {"ms": tm_full["compute_ms"],
+                               "tflops": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9,
+                               "frac_of_mfma_peak": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9 / peak},
+        "planner": {"cost_model_ps": cost, "l_delta": l_delta,
+                    "predicted_ms": None if stats is None else stats["makespan"] / 1e9},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded slice ...")
+        out["cpu_baseline"] = cpu_baseline(batch)
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

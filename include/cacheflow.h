@@ -259,6 +259,37 @@ int cf_offload(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, voi
 int cf_measure_h2d(cf_ctx* ctx, const void* host_buf, void* dev_buf, size_t bytes, int32_t reps,
                    double* gb_per_s);
 
+/* Fit the integer cost model on this GPU (Sec. 3.1: T_comp and T_io come from
+ * profiling): times recompute passes of three sizes and two host->device loads
+ * through cf_restore_batch on scratch pages of `cache` (needs free pages for
+ * min(8192, ctx limits) tokens; request ids 0xCA11B000.. are used and freed)
+ * with the pinned scratch block `host_buf` (>= cf_host_kv_bytes of that many
+ * tokens; contents irrelevant), solves for the coefficients and rounds them
+ * to integer picoseconds.  A hardware measurement: not reproducible bit for
+ * bit, so plans are only comparable given the same table.                  */
+int cf_calibrate(cf_ctx* ctx, cf_cache* cache, void* host_buf, size_t host_bytes,
+                 cf_cost_model* out);
+
+/* Per-kernel timing inside cf_restore_batch, from HIP event pairs recorded
+ * around each selected launch on the stream it is launched on.             */
+enum cf_kernel {
+    CF_K_GEMM_QKV = 0, CF_K_GEMM_OPROJ = 1, CF_K_GEMM_GATE_UP = 2, CF_K_GEMM_DOWN = 3,
+    CF_K_GEMM_LM_HEAD = 4, CF_K_ATTENTION = 5, CF_K_RMSNORM = 6, CF_K_ROPE_WRITE = 7,
+    CF_K_EMBED = 8, CF_K_PAGE_SCATTER = 9, CF_K_H2D_COPY = 10, CF_N_KERNELS = 11
+};
+typedef struct cf_kernel_stat {
+    int32_t kernel;      /* cf_kernel                                              */
+    int32_t launches;
+    double total_ms;     /* sum of event-pair durations                            */
+    double work;         /* algorithmic FLOPs (GEMMs: 2MNK, attention: 4*Hq*hd per
+                            causal pair) or bytes (other kernels: bytes they must
+                            move; copies: bytes over the link)                      */
+} cf_kernel_stat;
+/* kernel_mask: bit i selects cf_kernel i; 0 turns profiling off (default). */
+int cf_ctx_profile(cf_ctx* ctx, uint32_t kernel_mask);
+/* out: host cf_kernel_stat[CF_N_KERNELS], totals since the last reset.     */
+int cf_ctx_profile_read(cf_ctx* ctx, cf_kernel_stat* out, int32_t reset);
+
 /* Kernel selection for a context: simple_only != 0 routes every step through
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
  * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */

@@ -90,6 +90,15 @@ class cf_timing(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class cf_kernel_stat(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double),
+                ("work", C.c_double)]
+
+
+KERNEL_NAMES = ["gemm_qkv", "gemm_oproj", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention",
+                "rmsnorm", "rope_write", "embed", "page_scatter", "h2d_copy"]
+CF_N_KERNELS = len(KERNEL_NAMES)
+
 _P = C.POINTER
 lib.cf_status_str.restype = C.c_char_p
 lib.cf_status_str.argtypes = [C.c_int]
@@ -124,6 +133,9 @@ lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_reques
 lib.cf_offload.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]
 lib.cf_measure_h2d.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32,
                                _P(C.c_double)]
+lib.cf_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, _P(cf_cost_model)]
+lib.cf_ctx_profile.argtypes = [C.c_void_p, C.c_uint32]
+lib.cf_ctx_profile_read.argtypes = [C.c_void_p, _P(cf_kernel_stat), C.c_int32]
 lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                            _P(C.c_float)]
@@ -133,7 +145,8 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
            "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_restore_batch", "cf_offload",
-           "cf_measure_h2d", "cf_op_gemm"]
+           "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
+           "cf_ctx_profile_read"]
 
 
 def _check(status, where):
@@ -313,6 +326,24 @@ class Ctx:
         _check(lib.cf_measure_h2d(self.handle, host_ptr, dev_ptr, n_bytes, reps, C.byref(out)),
                "cf_measure_h2d")
         return out.value
+
+    def calibrate(self, cache, host_ptr, host_bytes):
+        cm = cf_cost_model()
+        _check(lib.cf_calibrate(self.handle, cache.handle, host_ptr, host_bytes, C.byref(cm)),
+               "cf_calibrate")
+        return cm
+
+    def profile(self, kernel_names):
+        mask = 0
+        for n in kernel_names:
+            mask |= 1 << KERNEL_NAMES.index(n)
+        _check(lib.cf_ctx_profile(self.handle, mask), "cf_ctx_profile")
+
+    def profile_read(self, reset=True):
+        arr = (cf_kernel_stat * CF_N_KERNELS)()
+        _check(lib.cf_ctx_profile_read(self.handle, arr, int(reset)), "cf_ctx_profile_read")
+        return {KERNEL_NAMES[i]: dict(launches=arr[i].launches, total_ms=arr[i].total_ms,
+                                      work=arr[i].work) for i in range(CF_N_KERNELS)}
 
     def op_gemm(self, A, W, W2, Cf, Dt, M, N, K, epi, impl=0, reps=1):
         ms = C.c_float()

@@ -101,6 +101,44 @@ struct cf_ctx {
     hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
     bool simple_only = false;
 
+    // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
+    struct ProfRec { int cls; double work; hipEvent_t e0, e1; };
+    uint32_t prof_mask = 0;
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> prof_pool;
+    cf_kernel_stat prof_acc[CF_N_KERNELS] = {};
+    bool prof_on(int cls) const { return (prof_mask >> cls) & 1u; }
+    hipEvent_t prof_event() {
+        hipEvent_t e = nullptr;
+        if (!prof_pool.empty()) { e = prof_pool.back(); prof_pool.pop_back(); }
+        else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+        return e;
+    }
+    void prof_begin(int cls, double work, hipStream_t st) {
+        if (!prof_on(cls)) return;
+        ProfRec r{cls, work, prof_event(), prof_event()};
+        if (!r.e0 || !r.e1) return;
+        (void)hipEventRecord(r.e0, st);
+        prof_recs.push_back(r);
+    }
+    void prof_end(int cls, hipStream_t st) {
+        if (!prof_on(cls) || prof_recs.empty()) return;
+        (void)hipEventRecord(prof_recs.back().e1, st);
+    }
+    void prof_collect() {     // after the streams are idle
+        for (ProfRec& r : prof_recs) {
+            float ms = 0;
+            if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+                prof_acc[r.cls].launches += 1;
+                prof_acc[r.cls].total_ms += ms;
+                prof_acc[r.cls].work += r.work;
+            }
+            prof_pool.push_back(r.e0);
+            prof_pool.push_back(r.e1);
+        }
+        prof_recs.clear();
+    }
+
     float* h() { return (float*)(ws + cv.h); }
     void* a() { return ws + cv.a; }
     float* qkv() { return (float*)(ws + cv.qkv); }
@@ -199,6 +237,8 @@ extern "C" void cf_ctx_destroy(cf_ctx* c) {
         if (c->ev_filled[i]) (void)hipEventDestroy(c->ev_filled[i]);
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
     }
+    for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.e0); c->prof_pool.push_back(r.e1); }
+    for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     if (c->meta_host) (void)hipHostFree(c->meta_host);
     if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
     delete c;
@@ -276,12 +316,14 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off) {
     }
 }
 
-void gemm(cf_ctx* c, const void* A, const void* W, const void* W2, float* Cf, void* Dt, int M,
-          int N, int K, int epi) {
+void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
+          int M, int N, int K, int epi) {
+    c->prof_begin(cls, 2.0 * M * (double)N * K * (epi == EPI_SILU_MUL ? 2 : 1), c->cs);
     if (!c->simple_only && gemm_mfma_supported(c->m.dtype, M, N, K, epi))
         launch_gemm_mfma(c->cs, A, W, W2, Cf, Dt, M, N, K, epi);
     else
         launch_gemm_simple(c->cs, c->m.dtype, A, W, W2, Cf, Dt, M, N, K, epi);
+    c->prof_end(cls, c->cs);
 }
 
 // Run layers [0, n_layers_max) of one packed phase on the compute stream.
@@ -305,7 +347,9 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
     bool mfma_attn = !c->simple_only &&
                      attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads);
 
+    c->prof_begin(CF_K_EMBED, (double)ph.T * m.d_model * (es + 4), c->cs);
     launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, m.d_model);
+    c->prof_end(CF_K_EMBED, c->cs);
     for (int l = 0; l < n_layers_max; ++l) {
         int Ta = ph.rows_active(l);
         if (Ta <= 0) break;
@@ -320,20 +364,35 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
             int n_work = 0;
             for (int i = 0; i < ci.n_work; ++i)
                 if (ph.work[ci.work_off + i].row0 + ci.r0 < Ta) n_work = i + 1;
+            c->prof_begin(CF_K_RMSNORM, (double)Tc * m.d_model * (4 + es), c->cs);
             launch_rmsnorm(c->cs, m.dtype, h, lw.attn_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
-            gemm(c, c->a(), lw.wqkv, nullptr, c->qkv(), nullptr, Tc, qcols, m.d_model, EPI_STORE_F32);
+            c->prof_end(CF_K_RMSNORM, c->cs);
+            gemm(c, CF_K_GEMM_QKV, c->a(), lw.wqkv, nullptr, c->qkv(), nullptr, Tc, qcols, m.d_model, EPI_STORE_F32);
+            c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
             launch_rope_write(c->cs, m.dtype, c->qkv(), d_pos + ci.r0, d_slot + ci.r0, c->rope(),
                               c->q(), pool_layer, Tc, m.n_q_heads, g);
+            c->prof_end(CF_K_ROPE_WRITE, c->cs);
+            if (c->prof_on(CF_K_ATTENTION)) {
+                double pairs = 0;
+                for (int i = 0; i < n_work; ++i) {
+                    const AttnWork& aw = ph.work[ci.work_off + i];
+                    pairs += (double)aw.n_rows * aw.pos0 + (double)aw.n_rows * (aw.n_rows + 1) / 2;
+                }
+                c->prof_begin(CF_K_ATTENTION, pairs * 4.0 * m.n_q_heads * m.head_dim, c->cs);
+            }
             if (mfma_attn)
                 launch_attention_mfma(c->cs, c->q(), c->o(), pool_layer, d_work + ci.work_off,
                                       n_work, d_pt, m.n_q_heads, g);
             else
                 launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
                                         d_work + ci.work_off, n_work, d_pt, m.n_q_heads, g);
-            gemm(c, c->o(), lw.wo, nullptr, h, nullptr, Tc, m.d_model, nq, EPI_ADD_F32);
+            c->prof_end(CF_K_ATTENTION, c->cs);
+            gemm(c, CF_K_GEMM_OPROJ, c->o(), lw.wo, nullptr, h, nullptr, Tc, m.d_model, nq, EPI_ADD_F32);
+            c->prof_begin(CF_K_RMSNORM, (double)Tc * m.d_model * (4 + es), c->cs);
             launch_rmsnorm(c->cs, m.dtype, h, lw.mlp_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
-            gemm(c, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tc, m.d_ffn, m.d_model, EPI_SILU_MUL);
-            gemm(c, c->act(), lw.w_down, nullptr, h, nullptr, Tc, m.d_model, m.d_ffn, EPI_ADD_F32);
+            c->prof_end(CF_K_RMSNORM, c->cs);
+            gemm(c, CF_K_GEMM_GATE_UP, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tc, m.d_ffn, m.d_model, EPI_SILU_MUL);
+            gemm(c, CF_K_GEMM_DOWN, c->act(), lw.w_down, nullptr, h, nullptr, Tc, m.d_model, m.d_ffn, EPI_ADD_F32);
         }
     }
 }
@@ -568,15 +627,21 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     bool slot_used[N_STAGING_SLOTS] = {};
     for (const SlotPlan& sp : slots) {
         if (slot_used[sp.slot]) CF_HIP(hipStreamWaitEvent(c->ps, c->ev_free[sp.slot], 0));
+        double slot_bytes = 0;
+        for (int k = 0; k < sp.n_ops; ++k) slot_bytes += (double)ops[sp.op_first + k].bytes;
+        c->prof_begin(CF_K_H2D_COPY, slot_bytes, c->ps);
         for (int k = 0; k < sp.n_ops; ++k) {
             const CopyOp& op = ops[sp.op_first + k];
             CF_HIP(hipMemcpyAsync(c->staging() + op.dst_off, op.src, op.bytes, hipMemcpyHostToDevice, c->ps));
         }
+        c->prof_end(CF_K_H2D_COPY, c->ps);
         CF_HIP(hipEventRecord(c->ev_filled[sp.slot], c->ps));
         CF_HIP(hipStreamWaitEvent(c->ss, c->ev_filled[sp.slot], 0));
+        c->prof_begin(CF_K_PAGE_SCATTER, 2.0 * slot_bytes, c->ss);
         launch_page_move(c->ss, m.dtype, c->staging(), cache->pool,
                          (const PageJob*)(md + off_jobs) + sp.job_first, sp.n_jobs, sp.n_blocks,
                          (const int32_t*)md, g, true);
+        c->prof_end(CF_K_PAGE_SCATTER, c->ss);
         CF_HIP(hipEventRecord(c->ev_free[sp.slot], c->ss));
         slot_used[sp.slot] = true;
     }
@@ -597,13 +662,14 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         run_phase(c, cache, suf, L);
         launch_rmsnorm(c->cs, m.dtype, c->h(), c->w.final_norm, c->a_last(), B, m.d_model, m.rms_eps,
                        (const int32_t*)(md + off_last));
-        gemm(c, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
+        gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
     }
     CF_HIP(hipEventRecord(c->ev_end, c->cs));
     CF_HIP(hipGetLastError());
     CF_HIP(hipStreamSynchronize(c->cs));
     CF_HIP(hipStreamSynchronize(c->ps));
     CF_HIP(hipStreamSynchronize(c->ss));
+    c->prof_collect();
 
     if (timing) {
         float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
@@ -712,5 +778,104 @@ extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W
     float ms = 0;
     CF_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
     if (avg_ms) *avg_ms = ms / reps;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_profile(cf_ctx* c, uint32_t kernel_mask) {
+    if (!c) return fail(CF_ERR_INVALID_ARG, "cf_ctx_profile: null ctx");
+    c->prof_mask = kernel_mask & ((1u << CF_N_KERNELS) - 1);
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_profile_read(cf_ctx* c, cf_kernel_stat* out, int32_t reset) {
+    if (!c || !out) return fail(CF_ERR_INVALID_ARG, "cf_ctx_profile_read: null argument");
+    for (int i = 0; i < CF_N_KERNELS; ++i) {
+        out[i] = c->prof_acc[i];
+        out[i].kernel = i;
+        if (reset) c->prof_acc[i] = cf_kernel_stat{};
+    }
+    return CF_OK;
+}
+
+// ------------------------------------------------------------------ calibration
+// Times a few recompute passes and host->device loads through cf_restore_batch
+// itself and fits the integer cost model by solving the small linear systems
+// exactly, then quantises to picoseconds.
+extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t host_bytes,
+                            cf_cost_model* out) {
+    if (!c || !cache || !host_buf || !out) return fail(CF_ERR_INVALID_ARG, "cf_calibrate: null argument");
+    const cf_model_desc& m = c->m;
+    const int L = m.n_layers;
+    // probe sizes: bounded by the context limits
+    int t_big = std::min(std::min(c->opts.max_tokens, c->opts.max_positions), 8192);
+    t_big = t_big / 512 * 512;
+    if (t_big < 1024) return fail(CF_ERR_WORKSPACE, "cf_calibrate: context too small (needs >= 1024 tokens)");
+    int t_small = 512;
+    int n_split = std::min(8, c->opts.max_batch);          // t_big tokens as n_split short requests
+    int t_part = t_big / n_split / 16 * 16;
+    size_t need_host = cf_host_kv_bytes(L, m.n_kv_heads, m.head_dim, m.dtype, t_big);
+    if (host_bytes < need_host)
+        return fail(CF_ERR_WORKSPACE, "cf_calibrate: host scratch %zu < %zu", host_bytes, need_host);
+    std::vector<int32_t> toks(t_big);
+    for (int i = 0; i < t_big; ++i) toks[i] = (int32_t)(((int64_t)i * 7919 + 13) % m.vocab);
+    const uint64_t base_id = 0xCA11B000ull;
+    struct Probe { int n_req, n_tok, k; };      // k = tokens recomputed per request (0 = load all)
+    auto run = [&](const Probe& p, cf_timing* tm) -> int {
+        std::vector<cf_request> rq(p.n_req);
+        std::vector<cf_split> sp(p.n_req);
+        int rc = CF_OK;
+        int made = 0;
+        for (int i = 0; i < p.n_req && rc == CF_OK; ++i) {
+            rc = cf_cache_alloc(cache, base_id + i, p.n_tok);
+            if (rc == CF_OK) ++made;
+            rq[i] = cf_request{base_id + i, toks.data(), p.n_tok, 0, host_buf, nullptr};
+            sp[i] = cf_split{CF_TOKEN_WISE, p.k, L};
+        }
+        if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, tm);  // warm-up
+        if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, tm);
+        for (int i = 0; i < made; ++i) cf_cache_free(cache, base_id + i);
+        return rc;
+    };
+    cf_timing tm;
+    double y[3], T[3], P[3];
+    Probe probes[3] = {{1, t_small, t_small}, {1, t_big, t_big}, {n_split, t_part, t_part}};
+    for (int i = 0; i < 3; ++i) {
+        int rc = run(probes[i], &tm);
+        if (rc) return rc;
+        y[i] = (double)tm.compute_ms * 1e9 / L;                 // ps per layer
+        T[i] = (double)probes[i].n_req * probes[i].n_tok;
+        double n = probes[i].n_tok;
+        P[i] = probes[i].n_req * (n * (n + 1) / 2) / 1024.0;
+    }
+    // y = f + a*T + b*P, three equations: eliminate f, then solve the 2x2 system
+    double a11 = T[1] - T[0], a12 = P[1] - P[0], b1 = y[1] - y[0];
+    double a21 = T[2] - T[0], a22 = P[2] - P[0], b2 = y[2] - y[0];
+    double det = a11 * a22 - a12 * a21;
+    double alpha = 0, beta = 0;
+    if (std::fabs(det) > 1e-9) {
+        alpha = (b1 * a22 - a12 * b2) / det;
+        beta = (a11 * b2 - b1 * a21) / det;
+    }
+    if (alpha <= 0 || beta < 0) {      // degenerate fit: fall back to a pure per-token rate
+        beta = 0;
+        alpha = y[1] / T[1];
+    }
+    double f_c = std::max(0.0, y[0] - alpha * T[0] - beta * P[0]);
+    // I/O: one large and one small all-load
+    Probe io_big{1, t_big, 0}, io_small{1, t_small, 0};
+    int rc = run(io_big, &tm);
+    if (rc) return rc;
+    double t_big_ps = (double)tm.copy_ms * 1e9, mib_big = (double)tm.loaded_bytes / 1048576.0;
+    rc = run(io_small, &tm);
+    if (rc) return rc;
+    double t_small_ps = (double)tm.copy_ms * 1e9, mib_small = (double)tm.loaded_bytes / 1048576.0;
+    double gamma = (t_big_ps - t_small_ps) / std::max(mib_big - mib_small, 1e-9);
+    if (gamma <= 0) gamma = t_big_ps / std::max(mib_big, 1e-9);
+    double f_io = std::max(0.0, t_small_ps - gamma * mib_small);
+    out->f_c = (int64_t)std::llround(f_c);
+    out->alpha = std::max<int64_t>(1, (int64_t)std::llround(alpha));
+    out->beta = (int64_t)std::llround(beta);
+    out->f_io = (int64_t)std::llround(f_io);
+    out->gamma = std::max<int64_t>(1, (int64_t)std::llround(gamma));
     return CF_OK;
 }
