@@ -122,7 +122,8 @@ def main():
     need = sess.host_kv_bytes(calib_tokens)
     scratch = big if big.numel() >= need else sess.pinned(need)
     cm = sess.ctx.calibrate(sess.cache, scratch.data_ptr(), scratch.numel())
-    cost = dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io, gamma=cm.gamma)
+    cost = dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io, gamma=cm.gamma,
+                s_c=cm.s_c, s_io=cm.s_io)
     opts = cf.plan_opts(batch.chunk_tokens, 0, L, shape.kv_bytes_per_token_layer, batch.forced_mode)
     l_delta = cf.derive_l_delta(cm, opts, 32768)
     opts.l_delta = l_delta

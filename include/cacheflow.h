@@ -82,9 +82,12 @@ const char* cf_last_error(void);
  * position p0 costs  f_c + alpha*t + beta*ceil(pairs/1024)  with
  * pairs = t*p0 + t*(t+1)/2 causal (query,key) pairs (Sec. 3.1: superlinear
  * T_comp with fixed overheads).  Loading one unit of `bytes` bytes costs
- * f_io + ceil(bytes*gamma / 2^20)  (Sec. 3.1: T_io linear, bandwidth-bound). */
+ * f_io + ceil(bytes*gamma / 2^20)  (Sec. 3.1: T_io linear, bandwidth-bound).
+ * s_c / s_io are one-time start-up costs: the clock of an engine that takes
+ * any unit at all starts there (recompute is batched over all requests, so
+ * its launch-bound floor is paid once per batch, not once per chunk).       */
 typedef struct cf_cost_model {
-    int64_t f_c, alpha, beta, f_io, gamma;
+    int64_t f_c, alpha, beta, f_io, gamma, s_c, s_io;
 } cf_cost_model;
 
 typedef struct cf_plan_opts {
@@ -303,7 +306,8 @@ int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only);
  *                                                        (Dt device dtype[M,N])
  * (the QKV / O-proj and down-proj / - / gate-up steps of a layer).
  * impl 0 = what cf_restore_batch would pick, 1 = plain FMA kernel, 2 = MFMA
- * kernel (CF_ERR_UNSUPPORTED if it does not take the shape).  Runs `reps`
+ * kernel with its own tile choice, 3 / 4 = MFMA kernel forced to 256x256 /
+ * 128x128 block tiles (CF_ERR_UNSUPPORTED if MFMA does not take the shape).  Runs `reps`
  * times on the compute stream, blocks, and returns the mean time per run
  * from HIP events in *avg_ms (may be NULL).                                 */
 int cf_op_gemm(cf_ctx* ctx, const void* A, const void* W, const void* W2, float* Cf, void* Dt,

@@ -41,12 +41,15 @@ class CostModel:
     """All picoseconds.  Per layer of recompute over t tokens starting at
     position p0:  f_c + alpha*t + beta*ceil(pairs/1024)  with
     pairs = t*p0 + t*(t+1)/2 causal (query, key) pairs.  Per copied unit:
-    f_io + ceil(bytes*gamma / 2^20)."""
+    f_io + ceil(bytes*gamma / 2^20).  An engine that does any work at all pays
+    its start-up s_c / s_io once, before its first unit."""
     f_c: int
     alpha: int
     beta: int
     f_io: int
     gamma: int
+    s_c: int = 0      # one-time start-up of the compute engine (clock starts here)
+    s_io: int = 0     # one-time start-up of the I/O channel
 
 
 @dataclass
@@ -114,7 +117,8 @@ def plan(cm, opts, n_ctx, trace=None):
     costs = [unit_costs(cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
     p_comp = [0] * b_req
     p_io = [len(costs[i][0]) - 1 for i in range(b_req)]
-    t_c = t_io = 0
+    t_c, t_io = cm.s_c, cm.s_io        # each engine's clock starts after its start-up
+    n_c = n_io = 0
     rr = 0
     n_claims = 0
 
@@ -155,14 +159,21 @@ def plan(cm, opts, n_ctx, trace=None):
             if trace is not None:
                 trace.append((0, ic, p_comp[ic]))
             t_c = fin_c
+            n_c += 1
             p_comp[ic] += 1
             rr = (ic + 1) % b_req
         else:
             if trace is not None:
                 trace.append((1, iio, p_io[iio]))
             t_io = fin_io
+            n_io += 1
             p_io[iio] -= 1
         n_claims += 1
+
+    if n_c == 0:
+        t_c = 0            # an engine that claimed nothing never started
+    if n_io == 0:
+        t_io = 0
 
     splits = [_split_of(opts, n_ctx[i], modes[i], p_comp[i]) for i in range(b_req)]
     stats = dict(t_comp=t_c, t_io=t_io, makespan=max(t_c, t_io), n_claims=n_claims)
@@ -173,12 +184,15 @@ def split_times(cm, opts, n_ctx, unit_splits, modes=None):
     """(t_comp, t_io) if request i recomputes its first unit_splits[i] units
     and loads the rest."""
     t_c = t_io = 0
+    any_c = any_io = False
     for i, n in enumerate(n_ctx):
         mode = request_mode(opts, n) if modes is None else modes[i]
         a, b, _ = unit_costs(cm, opts, n, mode)
         t_c += sum(a[:unit_splits[i]])
         t_io += sum(b[unit_splits[i]:])
-    return t_c, t_io
+        any_c |= len(a[:unit_splits[i]]) > 0
+        any_io |= len(b[unit_splits[i]:]) > 0
+    return (t_c + cm.s_c if any_c else 0), (t_io + cm.s_io if any_io else 0)
 
 
 def brute_force(cm, opts, n_ctx):

@@ -32,7 +32,7 @@ class CfError(RuntimeError):
 
 
 class cf_cost_model(C.Structure):
-    _fields_ = [(n, C.c_int64) for n in ("f_c", "alpha", "beta", "f_io", "gamma")]
+    _fields_ = [(n, C.c_int64) for n in ("f_c", "alpha", "beta", "f_io", "gamma", "s_c", "s_io")]
 
 
 class cf_plan_opts(C.Structure):
@@ -159,8 +159,9 @@ def _i32(a):
 
 
 # ------------------------------------------------------------------- planner
-def cost_model(f_c, alpha, beta, f_io, gamma):
-    return cf_cost_model(int(f_c), int(alpha), int(beta), int(f_io), int(gamma))
+def cost_model(f_c, alpha, beta, f_io, gamma, s_c=0, s_io=0):
+    return cf_cost_model(int(f_c), int(alpha), int(beta), int(f_io), int(gamma), int(s_c),
+                         int(s_io))
 
 
 def plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode=-1,
@@ -213,7 +214,7 @@ class Cache:
         self.handle = h
 
     def close(self):
-        if self.handle:
+        if self.handle and lib is not None:
             lib.cf_cache_destroy(self.handle)
             self.handle = None
 
@@ -289,7 +290,7 @@ class Ctx:
         self.desc = desc
 
     def close(self):
-        if self.handle:
+        if self.handle and lib is not None:
             lib.cf_ctx_destroy(self.handle)
             self.handle = None
 

@@ -764,9 +764,12 @@ extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W
     if ((epi == EPI_SILU_MUL && !W2) || ((epi == EPI_STORE_F32 || epi == EPI_ADD_F32) && !Cf) ||
         ((epi == EPI_STORE_T || epi == EPI_SILU_MUL) && !Dt))
         return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: missing operand for this epilogue");
+    if (impl < 0 || impl > 4) return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: impl must be 0..4");
     bool mfma_ok = gemm_mfma_supported(c->m.dtype, M, N, K, epi);
-    if (impl == 2 && !mfma_ok) return fail(CF_ERR_UNSUPPORTED, "cf_op_gemm: MFMA kernel does not take this problem");
-    bool use_mfma = impl == 2 || (impl == 0 && mfma_ok && !c->simple_only);
+    if (impl >= 2 && !mfma_ok) return fail(CF_ERR_UNSUPPORTED, "cf_op_gemm: MFMA kernel does not take this problem");
+    bool use_mfma = impl >= 2 || (impl == 0 && mfma_ok && !c->simple_only);
+    gemm_mfma_force_tile(impl == 3 ? 256 : impl == 4 ? 128 : 0);
+    struct Reset { ~Reset() { gemm_mfma_force_tile(0); } } reset_on_exit;
     CF_HIP(hipEventRecord(c->ev_t0, c->cs));
     for (int i = 0; i < reps; ++i) {
         if (use_mfma) launch_gemm_mfma(c->cs, A, W, W2, Cf, Dt, M, N, K, epi);
@@ -838,7 +841,9 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
     };
     cf_timing tm;
     double y[3], T[3], P[3];
-    Probe probes[3] = {{1, t_small, t_small}, {1, t_big, t_big}, {n_split, t_part, t_part}};
+    // recompute is batched over requests, so the probes are batch-shaped: the intercept of the
+    // fit is a per-layer-pass floor paid once per batch (-> s_c), not once per chunk
+    Probe probes[3] = {{n_split, t_small, t_small}, {n_split, t_part, t_part}, {1, t_big, t_big}};
     for (int i = 0; i < 3; ++i) {
         int rc = run(probes[i], &tm);
         if (rc) return rc;
@@ -858,10 +863,10 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
     }
     if (alpha <= 0 || beta < 0) {      // degenerate fit: fall back to a pure per-token rate
         beta = 0;
-        alpha = y[1] / T[1];
+        alpha = y[2] / T[2];
     }
-    double f_c = std::max(0.0, y[0] - alpha * T[0] - beta * P[0]);
-    // I/O: one large and one small all-load
+    double floor_c = std::max(0.0, y[0] - alpha * T[0] - beta * P[0]);
+    // I/O: one large and one small all-load; the intercept is the channel's start-up
     Probe io_big{1, t_big, 0}, io_small{1, t_small, 0};
     int rc = run(io_big, &tm);
     if (rc) return rc;
@@ -871,11 +876,13 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
     double t_small_ps = (double)tm.copy_ms * 1e9, mib_small = (double)tm.loaded_bytes / 1048576.0;
     double gamma = (t_big_ps - t_small_ps) / std::max(mib_big - mib_small, 1e-9);
     if (gamma <= 0) gamma = t_big_ps / std::max(mib_big, 1e-9);
-    double f_io = std::max(0.0, t_small_ps - gamma * mib_small);
-    out->f_c = (int64_t)std::llround(f_c);
+    double start_io = std::max(0.0, t_small_ps - gamma * mib_small);
+    out->f_c = 0;
     out->alpha = std::max<int64_t>(1, (int64_t)std::llround(alpha));
     out->beta = (int64_t)std::llround(beta);
-    out->f_io = (int64_t)std::llround(f_io);
+    out->f_io = 0;
     out->gamma = std::max<int64_t>(1, (int64_t)std::llround(gamma));
+    out->s_c = (int64_t)std::llround(floor_c * L);
+    out->s_io = (int64_t)std::llround(start_io);
     return CF_OK;
 }

@@ -4,7 +4,8 @@
 // (O-proj, down-proj), bf16 store, or SiLU(gate)*up -> bf16 (gate/up pair).
 //
 // Tiling: 256x256 block tile, 4 wavefronts (2x2), each a 128x128 wave tile =
-// 4x4 MFMA 32x32x16 fragments (256 accumulator registers per lane).  K is
+// 4x4 MFMA 32x32x16 fragments (256 accumulator registers per lane); problems
+// too small to fill the chip with such tiles use 128x128 block tiles instead.  K is
 // walked in steps of BK = 64 through a double-buffered LDS tile; the next
 // K-step is fetched from global memory into registers while the current one
 // is multiplied, then written to the other LDS buffer.  LDS rows are
@@ -19,16 +20,14 @@ namespace cf {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;   // native 16-byte register vector
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BK = 64;
 constexpr int NCH = BK / 8;               // 16-byte chunks per LDS row
 constexpr int ROW_BYTES = BK * 2;
-constexpr int TILE_BYTES = BM * ROW_BYTES;  // one operand tile
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr int N_STAGES = 2;
-constexpr int LOADS = BM * NCH / 256;     // 16-byte loads per thread per operand tile (8)
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & (NCH - 1); }
 
@@ -38,7 +37,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) {
     return (uint16_t)(u >> 16);
 }
 
-template <int EPI>
+// BM x BN block tile (256x256 for large problems, 128x128 when that would leave CUs idle);
+// the 4 wavefronts form a 2x2 grid of (BM/2)x(BN/2) wave tiles.
+template <int EPI, int BM, int BN>
 __global__ void __launch_bounds__(256)
 gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                  const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
@@ -46,6 +47,11 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     extern __shared__ __align__(16) char smem[];
     constexpr bool SILU = (EPI == EPI_SILU_MUL);
     constexpr int BN_OUT = SILU ? BN / 2 : BN;    // output columns per block
+    constexpr int WM = BM / 2, WN = BN / 2;       // wave tile
+    constexpr int FM = WM / 32, FN = WN / 32;     // MFMA fragments per wave tile
+    constexpr int A_TILE = BM * ROW_BYTES, B_TILE = BN * ROW_BYTES;
+    constexpr int STAGE_BYTES = A_TILE + B_TILE;
+    constexpr int LA = BM * NCH / 256, LB = BN * NCH / 256;   // 16-byte loads per thread
 
     // ---- workgroup -> tile: XCD-contiguous renumbering, then 8-row groups
     int nb = tiles_m * tiles_n;
@@ -65,110 +71,133 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
 
     // ---- global -> register -> LDS loader: thread handles chunk (tid % NCH) of rows
     // tid / NCH + j * (256 / NCH), j = 0..LOADS-1, for both operand tiles
+    // Rows come from wave-uniform base pointers plus small per-thread element offsets.
     int ld_chunk = tid % NCH, ld_row0 = tid / NCH;
-    const bf16* a_src[LOADS];
-    const bf16* b_src[LOADS];
-    int lds_off[LOADS];
+    const bf16* a_tile = A + (int64_t)m0 * K;
+    const bf16* w_tile = W + (int64_t)n0 * K;
+    const bf16* w2_tile = SILU ? W2 + (int64_t)n0 * K : nullptr;
+    int a_off[LA], b_off[LB];
+    int a_lds[LA], b_lds[LB];
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
+    for (int j = 0; j < LA; ++j) {
         int r = ld_row0 + j * (256 / NCH);
-        int gm = min(m0 + r, M - 1);
-        a_src[j] = A + (int64_t)gm * K + ld_chunk * 8;
-        if (SILU) {
-            int gn = min(n0 + (r & 127), N - 1);
-            b_src[j] = (r < 128 ? W : W2) + (int64_t)gn * K + ld_chunk * 8;
-        } else {
-            int gn = min(n0 + r, N - 1);
-            b_src[j] = W + (int64_t)gn * K + ld_chunk * 8;
-        }
-        lds_off[j] = r * ROW_BYTES + ((ld_chunk ^ swz(r)) << 4);
+        a_off[j] = (min(m0 + r, M - 1) - m0) * K + ld_chunk * 8;
+        a_lds[j] = r * ROW_BYTES + ((ld_chunk ^ swz(r)) << 4);
     }
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        int r = ld_row0 + j * (256 / NCH);
+        // gate/up pair: tile rows [0, BN/2) are gate rows, [BN/2, BN) the same rows of up
+        int rn = SILU ? r % (BN / 2) : r;
+        b_off[j] = (min(n0 + rn, N - 1) - n0) * K + ld_chunk * 8;
+        b_lds[j] = A_TILE + r * ROW_BYTES + ((ld_chunk ^ swz(r)) << 4);
+    }
+#define CF_B_BASE(j) ((SILU && (j) >= LB / 2) ? w2_tile : w_tile)
 
     // ---- fragment read offsets: lane reads row (lane % 32) of a 32-row fragment,
     // chunk 2*kk + lane/32 (swizzled)
     int frow = lane & 31, fhalf = lane >> 5;
     int fswz = swz(frow);                   // fragment bases are multiples of 32 rows
-    int a_base = (wm * 128 + frow) * ROW_BYTES;
-    int b_row[4];
+    int a_base = (wm * WM + frow) * ROW_BYTES;
+    int b_row[FN];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int r = SILU ? ((j < 2) ? wn * 64 + j * 32 : 128 + wn * 64 + (j - 2) * 32) : wn * 128 + j * 32;
-        b_row[j] = (r + frow) * ROW_BYTES;
+    for (int j = 0; j < FN; ++j) {
+        // gate/up pair: the first FN/2 fragments are gate columns, the rest the same columns of up
+        int r = SILU ? ((j < FN / 2) ? wn * (WN / 2) + j * 32
+                                     : BN / 2 + wn * (WN / 2) + (j - FN / 2) * 32)
+                     : wn * WN + j * 32;
+        b_row[j] = A_TILE + (r + frow) * ROW_BYTES;
     }
 
-    f32x16_t acc[4][4];
+    f32x16_t acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[LOADS], rb[LOADS];
+    // Software pipeline: while K-step kt is multiplied out of one LDS buffer, K-step kt+1
+    // (fetched during the previous iteration) is written to the other buffer and K-step kt+2
+    // is fetched into registers.  The fetch sits at the end of the iteration and its consumer
+    // in the next one, so a full iteration of MFMAs covers the memory latency.
+    u32x4_t ra[LA], rb[LB];
     int nk = K / BK;
+    {
+        int koff_ = min(0, nk - 1) * BK;   // past the end: refetch the last step, unused
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        ra[j] = *reinterpret_cast<const uint4*>(a_src[j]);
-        rb[j] = *reinterpret_cast<const uint4*>(b_src[j]);
+        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
+#pragma unroll
+        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
     }
+    {
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        *reinterpret_cast<uint4*>(smem + lds_off[j]) = ra[j];
-        *reinterpret_cast<uint4*>(smem + TILE_BYTES + lds_off[j]) = rb[j];
+        for (int j = 0; j < LA; ++j) *reinterpret_cast<u32x4_t*>(smem + a_lds[j]) = ra[j];
+#pragma unroll
+        for (int j = 0; j < LB; ++j) *reinterpret_cast<u32x4_t*>(smem + b_lds[j]) = rb[j];
+    }
+    {
+        int koff_ = min(1, nk - 1) * BK;   // past the end: refetch the last step, unused
+#pragma unroll
+        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
+#pragma unroll
+        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
     }
     __syncthreads();
 
     for (int kt = 0; kt < nk; ++kt) {
         char* cur = smem + (kt & 1) * STAGE_BYTES;
         char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-        // fetch the next K-step (the last iteration refetches its own step; unused)
-        int koff = min(kt + 1, nk - 1) * BK;
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            ra[j] = *reinterpret_cast<const uint4*>(a_src[j] + koff);
-            rb[j] = *reinterpret_cast<const uint4*>(b_src[j] + koff);
-        }
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             int coff = ((2 * kk + fhalf) ^ fswz) << 4;
-            uint4 fa[4], fb[4];
+            u32x4_t fa[FM], fb[FN];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                fa[i] = *reinterpret_cast<const uint4*>(cur + a_base + i * 32 * ROW_BYTES + coff);
+            for (int i = 0; i < FM; ++i)
+                fa[i] = *reinterpret_cast<const u32x4_t*>(cur + a_base + i * 32 * ROW_BYTES + coff);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                fb[j] = *reinterpret_cast<const uint4*>(cur + TILE_BYTES + b_row[j] + coff);
+            for (int j = 0; j < FN; ++j)
+                fb[j] = *reinterpret_cast<const u32x4_t*>(cur + b_row[j] + coff);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < FN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8_t, fa[i]), __builtin_bit_cast(bf16x8_t, fb[j]),
                         acc[i][j], 0, 0, 0);
         }
+    {
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            *reinterpret_cast<uint4*>(nxt + lds_off[j]) = ra[j];
-            *reinterpret_cast<uint4*>(nxt + TILE_BYTES + lds_off[j]) = rb[j];
-        }
+        for (int j = 0; j < LA; ++j) *reinterpret_cast<u32x4_t*>(nxt + a_lds[j]) = ra[j];
+#pragma unroll
+        for (int j = 0; j < LB; ++j) *reinterpret_cast<u32x4_t*>(nxt + b_lds[j]) = rb[j];
+    }
+    {
+        int koff_ = min(kt + 2, nk - 1) * BK;   // past the end: refetch the last step, unused
+#pragma unroll
+        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
+#pragma unroll
+        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
+    }
         __syncthreads();
     }
 
+#undef CF_B_BASE
     // ---- epilogue.  Fragment (i,j), register r: row = 32i + 8(r/4) + 4(lane/32) + r%4,
     // column = 32j + lane%32.
     int col_l = lane & 31;
     int row_l = 4 * (lane >> 5);
     if (SILU) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int gn = n0 + wn * 64 + j * 32 + col_l;
+            for (int j = 0; j < FN / 2; ++j) {
+                int gn = n0 + wn * (WN / 2) + j * 32 + col_l;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int gm = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
+                    int gm = m0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
                     if (gm < M && gn < N) {
-                        float g = acc[i][j][r], u = acc[i][j + 2][r];
+                        float g = acc[i][j][r], u = acc[i][j + FN / 2][r];
                         float v = g / (1.0f + __expf(-g)) * u;
                         Dt[(int64_t)gm * N + gn].x = f32_to_bf16_bits(v);
                     }
@@ -176,13 +205,13 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
             }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int gn = n0 + wn * 128 + j * 32 + col_l;
+            for (int j = 0; j < FN; ++j) {
+                int gn = n0 + wn * WN + j * 32 + col_l;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int gm = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
+                    int gm = m0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
                     if (gm < M && gn < N) {
                         int64_t o = (int64_t)gm * N + gn;
                         float v = acc[i][j][r];
@@ -195,23 +224,40 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     }
 }
 
+template <int EPI, int BM, int BN>
+void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
+                 int M, int N, int K) {
+    constexpr int BN_OUT = (EPI == EPI_SILU_MUL) ? BN / 2 : BN;
+    constexpr int LDS = N_STAGES * (BM + BN) * ROW_BYTES;
+    int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN_OUT - 1) / BN_OUT;
+    static bool configured = false;
+    auto kern = gemm_mfma_kernel<EPI, BM, BN>;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        configured = true;
+    }
+    kern<<<tiles_m * tiles_n, 256, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf,
+                                             (bf16*)Dt, M, N, K, tiles_m, tiles_n);
+}
+
+int g_force_tile = 0;   // 0 = heuristic, 256 / 128 = forced (tuning hook)
+
 template <int EPI>
 void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt, int M,
             int N, int K) {
-    constexpr int BN_OUT = (EPI == EPI_SILU_MUL) ? BN / 2 : BN;
-    int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN_OUT - 1) / BN_OUT;
-    static bool configured = false;
-    auto kern = gemm_mfma_kernel<EPI>;
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  N_STAGES * STAGE_BYTES);
-        configured = true;
-    }
-    kern<<<tiles_m * tiles_n, 256, N_STAGES * STAGE_BYTES, s>>>(
-        (const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf, (bf16*)Dt, M, N, K, tiles_m, tiles_n);
+    constexpr int BN_OUT256 = (EPI == EPI_SILU_MUL) ? 128 : 256;
+    int64_t tiles256 = (int64_t)((M + 255) / 256) * ((N + BN_OUT256 - 1) / BN_OUT256);
+    // big tiles once they fill the 256 CUs several times over (thresholds measured per
+    // epilogue; the read-modify-write epilogue overlaps better with two small blocks per CU)
+    int64_t need = EPI == EPI_SILU_MUL ? 200 : EPI == EPI_STORE_F32 ? 768 : (int64_t)1 << 40;
+    bool big = g_force_tile ? g_force_tile == 256 : tiles256 >= need;
+    if (big) launch_tile<EPI, 256, 256>(s, A, W, W2, Cf, Dt, M, N, K);
+    else launch_tile<EPI, 128, 128>(s, A, W, W2, Cf, Dt, M, N, K);
 }
 
 }  // namespace
+
+void gemm_mfma_force_tile(int t) { g_force_tile = t; }
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K, int epi) {
     (void)epi;

@@ -54,6 +54,7 @@ void launch_gemm_simple(hipStream_t s, int dtype, const void* A, const void* W, 
                         float* Cf, void* Dt, int M, int N, int K, int epi);
 // true if the MFMA kernel supports this problem (bf16, aligned K)
 bool gemm_mfma_supported(int dtype, int M, int N, int K, int epi);
+void gemm_mfma_force_tile(int tile);   // 0 = heuristic, 256 or 128 = forced (tuning)
 void launch_gemm_mfma(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf,
                       void* Dt, int M, int N, int K, int epi);
 void launch_rope_write(hipStream_t s, int dtype, const float* qkv, const int32_t* pos,

@@ -78,7 +78,8 @@ int check(const cf_cost_model* cm, const cf_plan_opts* o, int32_t B, const int32
                         who);
     if (o->io_key < 0 || o->io_key > CF_KEY_MARGINAL || o->force_mode < -1 || o->force_mode > 1)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: bad io_key or force_mode", who);
-    if (cm->f_c < 0 || cm->alpha < 0 || cm->beta < 0 || cm->f_io < 0 || cm->gamma < 0)
+    if (cm->f_c < 0 || cm->alpha < 0 || cm->beta < 0 || cm->f_io < 0 || cm->gamma < 0 ||
+        cm->s_c < 0 || cm->s_io < 0)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: negative cost coefficient", who);
     for (int i = 0; i < B; ++i)
         if (n_ctx[i] < 0) return cf::fail(CF_ERR_INVALID_ARG, "%s: n_ctx[%d] < 0", who, i);
@@ -104,7 +105,8 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
         pio[i] = req[i].m() - 1;
         n_live += pc[i] <= pio[i];
     }
-    int64_t t_c = 0, t_io = 0;
+    int64_t t_c = cost->s_c, t_io = cost->s_io;   // clocks start after the engines' start-up
+    int n_c = 0, n_io = 0;
     int rr = 0, n_claims = 0, n_trace = 0;
     auto live = [&](int i) { return pc[i] <= pio[i]; };
 
@@ -137,12 +139,14 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
         if (fin_c <= fin_io) {
             cl = {0, ic, pc[ic]};
             t_c = fin_c;
+            ++n_c;
             ++pc[ic];
             if (!live(ic)) --n_live;
             rr = (ic + 1 == B) ? 0 : ic + 1;
         } else {
             cl = {1, best, pio[best]};
             t_io = fin_io;
+            ++n_io;
             --pio[best];
             if (!live(best)) --n_live;
         }
@@ -160,6 +164,8 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
             out[i].layer_cut = pc[i];
         }
     }
+    if (n_c == 0) t_c = 0;     // an engine that claimed nothing never started
+    if (n_io == 0) t_io = 0;
     if (stats) {
         stats->t_comp = t_c;
         stats->t_io = t_io;
@@ -178,6 +184,7 @@ extern "C" int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts,
     if ((B > 0 && !splits) || !t_comp || !t_io)
         return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_eval: null argument");
     int64_t tc = 0, tio = 0;
+    bool any_c = false, any_io = false;
     for (int i = 0; i < B; ++i) {
         const cf_split& s = splits[i];
         if (s.k_tokens < 0 || s.k_tokens > n_ctx[i] || s.layer_cut < 0 ||
@@ -190,9 +197,11 @@ extern "C" int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts,
         if (n_comp > u.m()) n_comp = u.m();
         tc += u.a_prefix[n_comp];
         for (int v = n_comp; v < u.m(); ++v) tio += u.b[v];
+        any_c |= n_comp > 0;
+        any_io |= n_comp < u.m();
     }
-    *t_comp = tc;
-    *t_io = tio;
+    *t_comp = any_c ? tc + cost->s_c : 0;
+    *t_io = any_io ? tio + cost->s_io : 0;
     return CF_OK;
 }
 

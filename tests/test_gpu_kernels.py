@@ -31,7 +31,7 @@ SHAPES_MNK = [(256, 256, 64), (300, 544, 512), (1000, 1408, 512), (129, 96, 1408
               (2048, 1280, 1024)]
 
 
-@pytest.mark.parametrize("impl", [2, 1])
+@pytest.mark.parametrize("impl", [3, 4, 1])
 @pytest.mark.parametrize("mnk", SHAPES_MNK)
 def test_gemm_epilogues_match_float64_matmul(sess, impl, mnk):
     import paper_2604_25080_amd as cf

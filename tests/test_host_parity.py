@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert ctypes.sizeof(cf.cf_cost_model) == 40
+    assert ctypes.sizeof(cf.cf_cost_model) == 56
     assert ctypes.sizeof(cf.cf_plan_opts) == 24
     assert ctypes.sizeof(cf.cf_split) == 12
     assert ctypes.sizeof(cf.cf_plan_stats) == 32
@@ -55,7 +55,8 @@ def test_planner_matches_oracle_on_random_batches():
     for trial in range(1500):
         d = dict(f_c=int(rng.integers(0, 50_000_000)), alpha=int(rng.integers(1, 2_000_000)),
                  beta=int(rng.integers(0, 60_000)), f_io=int(rng.integers(0, 20_000_000)),
-                 gamma=int(rng.integers(1, 900_000_000)))
+                 gamma=int(rng.integers(1, 900_000_000)),
+                 s_c=int(rng.choice([0, 0, 3_000_000_000])), s_io=int(rng.choice([0, 0, 400_000_000])))
         ocm, ccm = both_cost(d)
         chunk = 16 * int(rng.integers(1, 40))
         oo, co = both_opts(chunk, int(rng.choice([0, 300, 2000, 10 ** 6])), int(rng.integers(1, 40)),
@@ -74,7 +75,7 @@ def test_planner_matches_oracle_on_random_batches():
 def test_planner_matches_oracle_on_benchmark_batches(cfg):
     b = make_batch(cfg)
     s = b.shape
-    for kind in ("mi355x_like", "balanced", "slow_io"):
+    for kind in ("mi355x_like", "balanced", "slow_io", "startup"):
         ocm, ccm = both_cost(hand_cost_model(kind))
         oo, co = both_opts(b.chunk_tokens, 2048, s.n_layers, s.kv_bytes_per_token_layer, b.forced_mode)
         otrace = []
@@ -86,7 +87,7 @@ def test_planner_matches_oracle_on_benchmark_batches(cfg):
 def test_plan_eval_and_l_delta_match_oracle():
     rng = np.random.default_rng(42)
     for _ in range(100):
-        d = hand_cost_model(str(rng.choice(["mi355x_like", "balanced", "slow_io", "uniform"])))
+        d = hand_cost_model(str(rng.choice(["mi355x_like", "balanced", "slow_io", "uniform", "startup"])))
         ocm, ccm = both_cost(d)
         oo, co = both_opts(64 * int(rng.integers(1, 9)), 0, int(rng.integers(1, 33)), 4096, int(rng.integers(0, 2)))
         n_ctx = [int(rng.integers(1, 5000)) for _ in range(3)]

@@ -11,8 +11,10 @@ def cm_of(kind):
     return P.CostModel(**hand_cost_model(kind))
 
 
-def rand_cm(rng, overheads=True):
+def rand_cm(rng, overheads=True, startups=False):
     return P.CostModel(
+        s_c=int(rng.integers(0, 400_000_000)) if startups else 0,
+        s_io=int(rng.integers(0, 100_000_000)) if startups else 0,
         f_c=int(rng.integers(0, 50_000_000)) if overheads else 0,
         alpha=int(rng.integers(100_000, 2_000_000)),
         beta=int(rng.integers(0, 60_000)),
@@ -84,7 +86,7 @@ def test_makespan_tends_to_the_harmonic_mean_as_units_shrink():
 def test_single_request_matches_brute_force_exactly():
     rng = np.random.default_rng(21)
     for trial in range(300):
-        cm = rand_cm(rng)
+        cm = rand_cm(rng, startups=trial % 2 == 1)
         mode = int(rng.integers(0, 2))
         opts = P.PlanOpts(16 * int(rng.integers(1, 5)), 0, int(rng.integers(1, 9)),
                           int(rng.choice([512, 4096])), mode)

@@ -120,6 +120,9 @@ def hand_cost_model(kind="balanced"):
         # a 10 Gbit/s store: recompute wins almost everywhere
         "slow_io": dict(f_c=30_000_000, alpha=440_000, beta=16_800,
                         f_io=10_000_000, gamma=800_000_000),
+        # batched recompute: per-unit overheads folded into one-time engine start-ups
+        "startup": dict(f_c=0, alpha=464_000, beta=75_000, f_io=0, gamma=18_750_000,
+                        s_c=32_000_000_000, s_io=340_000_000),
         # no fixed overheads, no attention term: uniform unit costs
         "uniform": dict(f_c=0, alpha=1_000_000, beta=0, f_io=0,
                         gamma=64_000_000),
