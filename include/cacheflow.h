@@ -293,6 +293,13 @@ int cf_ctx_profile(cf_ctx* ctx, uint32_t kernel_mask);
 /* out: host cf_kernel_stat[CF_N_KERNELS], totals since the last reset.     */
 int cf_ctx_profile_read(cf_ctx* ctx, cf_kernel_stat* out, int32_t reset);
 
+/* Final hidden state (residual stream after the last layer, before the final
+ * norm) of each request's last new token, as left by the most recent
+ * cf_restore_batch that produced logits for B requests.  out: host
+ * float[B][d_model].  For parity checks of the final norm and LM head at
+ * sizes where the CPU cannot run the whole context.                         */
+int cf_read_final_hidden(cf_ctx* ctx, int32_t B, float* out_host);
+
 /* Kernel selection for a context: simple_only != 0 routes every step through
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
  * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */

@@ -17,8 +17,30 @@ Q head j reads KV head j // (Hq/Hkv), SwiGLU MLP, no biases, untied LM head.
 
 All arithmetic runs in `dtype` (float64 by default; float32 on request for the
 timed baseline).  Rotary angles are always formed in float64.
+
+Storage precision.  With act="exact" (default) nothing is rounded: this is the
+reference the method's exactness is stated against.  With act="bf16" the
+forward is that of a bf16 MODEL: every tensor such a model stores in 16 bits
+is rounded to bf16 (nearest-even) where it is stored -- the normalised
+activations fed to the projections, Q, K and V after the rotary turn (K and V
+are the cache cells), the attention probabilities fed to the value product,
+the attention output and the MLP activation -- while the residual stream,
+norms, softmax and all accumulation stay in `dtype`.  A cache cell is a 16-bit
+code; comparing codes needs both sides to round at the same places.
 """
 import numpy as np
+
+
+def round_bf16(x):
+    """Nearest-even rounding to bf16, returned in x's float type."""
+    x = np.asarray(x)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = (u + (((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(x.dtype if x.dtype.kind == "f" else np.float64)
+
+
+def _store(x, act):
+    return round_bf16(x) if act == "bf16" else x
 
 
 def rmsnorm(x, gain, eps, dtype=np.float64):
@@ -52,7 +74,7 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-def causal_attention(q, k, v, q_pos, dtype=np.float64):
+def causal_attention(q, k, v, q_pos, dtype=np.float64, act="exact"):
     """q[Tq,Hq,hd] at absolute positions q_pos[Tq]; k, v [Tk,Hkv,hd] hold
     positions 0..Tk-1.  Query at position p sees keys 0..p."""
     q = np.asarray(q, dtype=dtype)
@@ -71,7 +93,7 @@ def causal_attention(q, k, v, q_pos, dtype=np.float64):
         s = s - np.max(s, axis=-1, keepdims=True)
         p = np.exp(s)
         p = p / np.sum(p, axis=-1, keepdims=True)
-        out[:, h, :] = p @ v[:, g, :]
+        out[:, h, :] = _store(p, act) @ v[:, g, :]
     return out
 
 
@@ -98,37 +120,37 @@ def embed(weights, tokens, dtype=np.float64):
 
 
 def layer_forward(shape, lw, gain, h, positions, k_past, v_past,
-                  dtype=np.float64):
+                  dtype=np.float64, act="exact"):
     """One decoder layer over rows h[T, d] at `positions`, attending to the
     given past K/V (positions 0..P-1, contiguous, P == positions[0]) followed
     by the rows' own K/V.  Returns (h_out, k_new, v_new)."""
     s = shape
     t = h.shape[0]
-    a = rmsnorm(h, gain, s.rms_eps, dtype)
+    a = _store(rmsnorm(h, gain, s.rms_eps, dtype), act)
     qkv = a @ lw["wqkv"].astype(dtype).T
     nq = s.n_q_heads * s.head_dim
     nk = s.n_kv_heads * s.head_dim
     q = qkv[:, :nq].reshape(t, s.n_q_heads, s.head_dim)
     k = qkv[:, nq:nq + nk].reshape(t, s.n_kv_heads, s.head_dim)
-    v = qkv[:, nq + nk:].reshape(t, s.n_kv_heads, s.head_dim)
-    q = rope(q, positions, s.rope_base, dtype)
-    k = rope(k, positions, s.rope_base, dtype)
+    v = _store(qkv[:, nq + nk:].reshape(t, s.n_kv_heads, s.head_dim), act)
+    q = _store(rope(q, positions, s.rope_base, dtype), act)
+    k = _store(rope(k, positions, s.rope_base, dtype), act)
     if k_past is not None and k_past.shape[0] > 0:
         k_all = np.concatenate([np.asarray(k_past, dtype=dtype), k], axis=0)
         v_all = np.concatenate([np.asarray(v_past, dtype=dtype), v], axis=0)
     else:
         k_all, v_all = k, v
-    o = causal_attention(q, k_all, v_all, positions, dtype)
+    o = _store(causal_attention(q, k_all, v_all, positions, dtype, act), act)
     h = h + o.reshape(t, nq) @ lw["wo"].astype(dtype).T
-    u = rmsnorm(h, gain, s.rms_eps, dtype)
+    u = _store(rmsnorm(h, gain, s.rms_eps, dtype), act)
     gate = u @ lw["w_gate"].astype(dtype).T
     up = u @ lw["w_up"].astype(dtype).T
-    h = h + (silu(gate) * up) @ lw["w_down"].astype(dtype).T
+    h = h + _store(silu(gate) * up, act) @ lw["w_down"].astype(dtype).T
     return h, k, v
 
 
 def prefill(shape, weights, tokens, past=None, n_layers=None,
-            dtype=np.float64, return_hidden=False):
+            dtype=np.float64, return_hidden=False, act="exact"):
     """Run `tokens` (positions P..P+T-1 where P = tokens already in `past`)
     through layers [0, n_layers).  Returns (KVCache of the new rows' K/V for
     those layers, final hidden rows h[T, d])."""
@@ -146,21 +168,21 @@ def prefill(shape, weights, tokens, past=None, n_layers=None,
         lw = weights.layer_f32(l)
         kp = None if past is None else past.k[l]
         vp = None if past is None else past.v[l]
-        h, k, v = layer_forward(shape, lw, gain, h, positions, kp, vp, dtype)
+        h, k, v = layer_forward(shape, lw, gain, h, positions, kp, vp, dtype, act)
         out.k[l], out.v[l] = k, v
     if return_hidden:
         return out, h, hidden_in
     return out, h
 
 
-def logits_last(shape, weights, h_last, dtype=np.float64):
+def logits_last(shape, weights, h_last, dtype=np.float64, act="exact"):
     """Final RMSNorm and LM head on one hidden row."""
-    a = rmsnorm(h_last[None, :], weights.norm_gain(), shape.rms_eps, dtype)
+    a = _store(rmsnorm(h_last[None, :], weights.norm_gain(), shape.rms_eps, dtype), act)
     return (a @ weights.f32("lm_head").astype(dtype).T)[0]
 
 
 def restore(shape, weights, ctx_tokens, kv_full, k_tokens, layer_cut,
-            dtype=np.float64):
+            dtype=np.float64, act="exact"):
     """Hybrid restoration of one request (Sec. 3.1): cells (token < k_tokens,
     layer < layer_cut) are recomputed from the first k_tokens tokens alone;
     every other cell is taken from the stored cache `kv_full`."""
@@ -172,24 +194,24 @@ def restore(shape, weights, ctx_tokens, kv_full, k_tokens, layer_cut,
         cache.v[l] = np.array(kv_full.v[l][:n], dtype=dtype, copy=True)
     if k_tokens > 0 and layer_cut > 0:
         rec, _ = prefill(shape, weights, ctx_tokens[:k_tokens],
-                         n_layers=layer_cut, dtype=dtype)
+                         n_layers=layer_cut, dtype=dtype, act=act)
         for l in range(layer_cut):
             cache.k[l][:k_tokens] = rec.k[l]
             cache.v[l][:k_tokens] = rec.v[l]
     return cache
 
 
-def first_token_logits(shape, weights, cache, new_tokens, dtype=np.float64):
+def first_token_logits(shape, weights, cache, new_tokens, dtype=np.float64, act="exact"):
     """Prefill the new-turn tokens over a restored cache; return (logits at
     the last new token, KVCache of the new tokens' own K/V)."""
-    kv_new, h = prefill(shape, weights, new_tokens, past=cache, dtype=dtype)
-    return logits_last(shape, weights, h[-1], dtype), kv_new
+    kv_new, h = prefill(shape, weights, new_tokens, past=cache, dtype=dtype, act=act)
+    return logits_last(shape, weights, h[-1], dtype, act), kv_new
 
 
-def full_reference(shape, weights, ctx_tokens, new_tokens, dtype=np.float64):
+def full_reference(shape, weights, ctx_tokens, new_tokens, dtype=np.float64, act="exact"):
     """Full prefill of context then new tokens: (kv_ctx, kv_new, logits)."""
-    kv_ctx, _ = prefill(shape, weights, ctx_tokens, dtype=dtype)
-    logits, kv_new = first_token_logits(shape, weights, kv_ctx, new_tokens, dtype)
+    kv_ctx, _ = prefill(shape, weights, ctx_tokens, dtype=dtype, act=act)
+    logits, kv_new = first_token_logits(shape, weights, kv_ctx, new_tokens, dtype, act)
     return kv_ctx, kv_new, logits
 
 

@@ -136,6 +136,7 @@ lib.cf_measure_h2d.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C
 lib.cf_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, _P(cf_cost_model)]
 lib.cf_ctx_profile.argtypes = [C.c_void_p, C.c_uint32]
 lib.cf_ctx_profile_read.argtypes = [C.c_void_p, _P(cf_kernel_stat), C.c_int32]
+lib.cf_read_final_hidden.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
 lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                            _P(C.c_float)]
@@ -146,7 +147,7 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
            "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_restore_batch", "cf_offload",
            "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
-           "cf_ctx_profile_read"]
+           "cf_ctx_profile_read", "cf_read_final_hidden"]
 
 
 def _check(status, where):
@@ -345,6 +346,11 @@ class Ctx:
         _check(lib.cf_ctx_profile_read(self.handle, arr, int(reset)), "cf_ctx_profile_read")
         return {KERNEL_NAMES[i]: dict(launches=arr[i].launches, total_ms=arr[i].total_ms,
                                       work=arr[i].work) for i in range(CF_N_KERNELS)}
+
+    def read_final_hidden(self, b):
+        out = np.zeros((b, self.desc.d_model), dtype=np.float32)
+        _check(lib.cf_read_final_hidden(self.handle, b, out.ctypes.data), "cf_read_final_hidden")
+        return out
 
     def op_gemm(self, A, W, W2, Cf, Dt, M, N, K, epi, impl=0, reps=1):
         ms = C.c_float()

@@ -31,7 +31,7 @@ constexpr int PAGE_MOVE_SPLIT = 4;       // blocks per page in the page mover
 constexpr int N_STAGING_SLOTS = 2;
 
 struct Carve {
-    size_t rope, h, a, qkv, q, o, act, a_last, staging, meta, total;
+    size_t rope, h, dl, a, qkv, q, o, act, a_last, staging, meta, total;
     size_t staging_bytes, meta_bytes;
     int chunk_rows;
 };
@@ -67,6 +67,7 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
     auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
     c->rope = take((size_t)o.max_positions * (m.head_dim / 2) * sizeof(float2));
     c->h = take((size_t)o.max_tokens * m.d_model * 4);
+    c->dl = take((size_t)o.max_tokens * m.d_model * 4);
     c->a = take((size_t)chunk * m.d_model * es);
     c->qkv = take((size_t)chunk * qcols * 4);
     c->q = take((size_t)chunk * m.n_q_heads * m.head_dim * es);
@@ -100,6 +101,7 @@ struct cf_ctx {
                ev_end = nullptr, ev_scat = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
     hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
     bool simple_only = false;
+    std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
     struct ProfRec { int cls; double work; hipEvent_t e0, e1; };
@@ -140,6 +142,7 @@ struct cf_ctx {
     }
 
     float* h() { return (float*)(ws + cv.h); }
+    float* dl() { return (float*)(ws + cv.dl); }   // pending residual update of each row
     void* a() { return ws + cv.a; }
     float* qkv() { return (float*)(ws + cv.qkv); }
     void* q() { return ws + cv.q; }
@@ -327,7 +330,13 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 }
 
 // Run layers [0, n_layers_max) of one packed phase on the compute stream.
-void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
+//
+// The residual stream h stays float.  O-proj and down-proj store their result into the
+// float buffer dl (plain stores out of the GEMM), and the next RMSNorm folds it in
+// (h += dl) while it reads the row anyway.  When `kv_only_tail` is set (recompute phase)
+// rows in their LAST active layer stop after the K/V write: nothing downstream reads
+// their attention or MLP output.
+void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max, bool kv_only_tail) {
     const cf_model_desc& m = c->m;
     if (ph.T <= 0) return;
     size_t es = elem_bytes(m.dtype);
@@ -353,25 +362,29 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
     for (int l = 0; l < n_layers_max; ++l) {
         int Ta = ph.rows_active(l);
         if (Ta <= 0) break;
+        int Tn = kv_only_tail ? (l + 1 < n_layers_max ? ph.rows_active(l + 1) : 0) : Ta;
         const cf_layer_weights& lw = c->layers[l];
         char* pool_layer = (char*)cache->pool + (size_t)l * g.layer_stride * es;
         for (const ChunkInfo& ci : ph.chunks) {
             if (ci.r0 >= Ta) break;
-            int r1 = std::min(ci.r1, Ta);
-            int Tc = r1 - ci.r0;
+            int Tc = std::min(ci.r1, Ta) - ci.r0;          // rows that need K/V in this layer
+            int Tr = std::min(ci.r1, Tn) - ci.r0;          // rows that go on through the layer
             float* h = c->h() + (size_t)ci.r0 * m.d_model;
-            // active work items of this chunk: those whose rows lie below Ta
-            int n_work = 0;
-            for (int i = 0; i < ci.n_work; ++i)
-                if (ph.work[ci.work_off + i].row0 + ci.r0 < Ta) n_work = i + 1;
+            float* dl = c->dl() + (size_t)ci.r0 * m.d_model;
             c->prof_begin(CF_K_RMSNORM, (double)Tc * m.d_model * (4 + es), c->cs);
-            launch_rmsnorm(c->cs, m.dtype, h, lw.attn_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
+            launch_rmsnorm(c->cs, m.dtype, h, l > 0 ? dl : nullptr, lw.attn_norm, c->a(), Tc, m.d_model,
+                           m.rms_eps, nullptr);
             c->prof_end(CF_K_RMSNORM, c->cs);
             gemm(c, CF_K_GEMM_QKV, c->a(), lw.wqkv, nullptr, c->qkv(), nullptr, Tc, qcols, m.d_model, EPI_STORE_F32);
             c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
             launch_rope_write(c->cs, m.dtype, c->qkv(), d_pos + ci.r0, d_slot + ci.r0, c->rope(),
                               c->q(), pool_layer, Tc, m.n_q_heads, g);
             c->prof_end(CF_K_ROPE_WRITE, c->cs);
+            if (Tr <= 0) continue;
+            // active work items of this chunk: those whose rows lie below Tn
+            int n_work = 0;
+            for (int i = 0; i < ci.n_work; ++i)
+                if (ph.work[ci.work_off + i].row0 + ci.r0 < Tn) n_work = i + 1;
             if (c->prof_on(CF_K_ATTENTION)) {
                 double pairs = 0;
                 for (int i = 0; i < n_work; ++i) {
@@ -387,12 +400,12 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max) {
                 launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
                                         d_work + ci.work_off, n_work, d_pt, m.n_q_heads, g);
             c->prof_end(CF_K_ATTENTION, c->cs);
-            gemm(c, CF_K_GEMM_OPROJ, c->o(), lw.wo, nullptr, h, nullptr, Tc, m.d_model, nq, EPI_ADD_F32);
-            c->prof_begin(CF_K_RMSNORM, (double)Tc * m.d_model * (4 + es), c->cs);
-            launch_rmsnorm(c->cs, m.dtype, h, lw.mlp_norm, c->a(), Tc, m.d_model, m.rms_eps, nullptr);
+            gemm(c, CF_K_GEMM_OPROJ, c->o(), lw.wo, nullptr, dl, nullptr, Tr, m.d_model, nq, EPI_STORE_F32);
+            c->prof_begin(CF_K_RMSNORM, (double)Tr * m.d_model * (12 + es), c->cs);
+            launch_rmsnorm(c->cs, m.dtype, h, dl, lw.mlp_norm, c->a(), Tr, m.d_model, m.rms_eps, nullptr);
             c->prof_end(CF_K_RMSNORM, c->cs);
-            gemm(c, CF_K_GEMM_GATE_UP, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tc, m.d_ffn, m.d_model, EPI_SILU_MUL);
-            gemm(c, CF_K_GEMM_DOWN, c->act(), lw.w_down, nullptr, h, nullptr, Tc, m.d_model, m.d_ffn, EPI_ADD_F32);
+            gemm(c, CF_K_GEMM_GATE_UP, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tr, m.d_ffn, m.d_model, EPI_SILU_MUL);
+            gemm(c, CF_K_GEMM_DOWN, c->act(), lw.w_down, nullptr, dl, nullptr, Tr, m.d_model, m.d_ffn, EPI_STORE_F32);
         }
     }
 }
@@ -540,6 +553,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         suf.off_work = mw.put(suf.work.data(), suf.work.size() * sizeof(AttnWork));
     }
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
+    c->last_rows = last_rows;
 
     // copy plan: runs of pages per (request, layer), top layer first and the
     // longest request first (the I/O pointer walks down from the far end, Sec. 3.1)
@@ -652,16 +666,17 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     // compute stream: recompute, layer-major over the batch
     int max_cut = 0;
     for (const Segment& s : rec.segs) max_cut = std::max(max_cut, s.layers);
-    run_phase(c, cache, rec, max_cut);
+    run_phase(c, cache, rec, max_cut, true);
     CF_HIP(hipEventRecord(c->ev_comp, c->cs));
 
     // join, then the new-turn prefill and first-token logits
     CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
     CF_HIP(hipEventRecord(c->ev_t0, c->cs));
     if (logits_out) {
-        run_phase(c, cache, suf, L);
-        launch_rmsnorm(c->cs, m.dtype, c->h(), c->w.final_norm, c->a_last(), B, m.d_model, m.rms_eps,
-                       (const int32_t*)(md + off_last));
+        run_phase(c, cache, suf, L, false);
+        // the last layer's down-proj result is still pending in dl
+        launch_rmsnorm(c->cs, m.dtype, c->h(), c->dl(), c->w.final_norm, c->a_last(), B, m.d_model,
+                       m.rms_eps, (const int32_t*)(md + off_last));
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
     }
     CF_HIP(hipEventRecord(c->ev_end, c->cs));
@@ -685,8 +700,11 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         double lin = linear_flops_per_token_layer(m);
         double pair = 4.0 * m.n_q_heads * m.head_dim;
         double fr = 0, fs = 0;
+        // the last recomputed layer of a request needs only its K/V projection
+        double qkv_fl = 2.0 * m.d_model * (double)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
         for (const Segment& s : rec.segs)
-            fr += (double)s.layers * (s.n_rows * lin + pair * ((double)s.n_rows * (s.n_rows + 1) / 2));
+            fr += (double)(s.layers - 1) * (s.n_rows * lin + pair * ((double)s.n_rows * (s.n_rows + 1) / 2)) +
+                  s.n_rows * qkv_fl;
         for (const Segment& s : suf.segs)
             fs += (double)L * (s.n_rows * lin + pair * ((double)s.n_rows * s.pos0 +
                                                         (double)s.n_rows * (s.n_rows + 1) / 2));
@@ -884,5 +902,21 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
     out->gamma = std::max<int64_t>(1, (int64_t)std::llround(gamma));
     out->s_c = (int64_t)std::llround(floor_c * L);
     out->s_io = (int64_t)std::llround(start_io);
+    return CF_OK;
+}
+
+extern "C" int cf_read_final_hidden(cf_ctx* c, int32_t B, float* out_host) {
+    if (!c || !out_host || B <= 0) return fail(CF_ERR_INVALID_ARG, "cf_read_final_hidden: bad argument");
+    if ((int)c->last_rows.size() != B)
+        return fail(CF_ERR_INVALID_ARG, "cf_read_final_hidden: last cf_restore_batch had %zu requests with logits",
+                    c->last_rows.size());
+    int d = c->m.d_model;
+    std::vector<float> hrow(d), drow(d);
+    for (int i = 0; i < B; ++i) {
+        size_t off = (size_t)c->last_rows[i] * d;
+        CF_HIP(hipMemcpy(hrow.data(), c->h() + off, (size_t)d * 4, hipMemcpyDeviceToHost));
+        CF_HIP(hipMemcpy(drow.data(), c->dl() + off, (size_t)d * 4, hipMemcpyDeviceToHost));
+        for (int j = 0; j < d; ++j) out_host[(size_t)i * d + j] = hrow[j] + drow[j];
+    }
     return CF_OK;
 }

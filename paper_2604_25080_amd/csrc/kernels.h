@@ -47,8 +47,10 @@ struct KvGeom {
 };
 
 void launch_embed(hipStream_t s, int dtype, const void* E, const int32_t* tok, float* h, int T, int d);
-void launch_rmsnorm(hipStream_t s, int dtype, const float* h, const float* gain, void* out, int T,
-                    int d, float eps, const int32_t* row_idx);
+// out = rmsnorm(h (+ delta)) * gain; with delta, h += delta is written back unless row_idx
+// gathers the rows (delta is then indexed like h).
+void launch_rmsnorm(hipStream_t s, int dtype, float* h, const float* delta, const float* gain,
+                    void* out, int T, int d, float eps, const int32_t* row_idx);
 // A[M,K], W[N,K] (and W2) in the model dtype; Cf float [M,N] or Dt model dtype [M,N].
 void launch_gemm_simple(hipStream_t s, int dtype, const void* A, const void* W, const void* W2,
                         float* Cf, void* Dt, int M, int N, int K, int epi);

@@ -39,13 +39,18 @@ void launch_embed(hipStream_t s, int dtype, const void* E, const int32_t* tok, f
 
 // -------------------------------------------------------------------- RMSNorm
 // One 256-thread block per row; the row stays in registers between the two passes.
+// With `delta` the pending residual update is folded in first: h += delta (written
+// back unless the rows are gathered through row_idx), then the norm of the new h.
 template <typename T>
 __global__ void __launch_bounds__(256)
-rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ gain, T* __restrict__ out,
-               int d, float eps, const int32_t* __restrict__ row_idx) {
+rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ delta,
+               const float* __restrict__ gain, T* __restrict__ out, int d, float eps,
+               const int32_t* __restrict__ row_idx) {
     __shared__ float red[4];
     int t = blockIdx.x;
-    const float* src = h + (int64_t)(row_idx ? row_idx[t] : t) * d;
+    int64_t srow = row_idx ? row_idx[t] : t;
+    float* src = h + srow * d;
+    const float* dsrc = delta ? delta + srow * d : nullptr;
     T* dst = out + (int64_t)t * d;
     constexpr int MAXV = 8;                 // d <= 256*4*8 = 8192
     float4 v[MAXV];
@@ -56,6 +61,11 @@ rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ gain, T* _
         int idx = threadIdx.x + i * 256;
         if (idx < nvec) {
             v[i] = reinterpret_cast<const float4*>(src)[idx];
+            if (dsrc) {
+                float4 dv = reinterpret_cast<const float4*>(dsrc)[idx];
+                v[i].x += dv.x; v[i].y += dv.y; v[i].z += dv.z; v[i].w += dv.w;
+                if (!row_idx) reinterpret_cast<float4*>(src)[idx] = v[i];
+            }
             ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
         }
     }
@@ -77,13 +87,13 @@ rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ gain, T* _
     }
 }
 
-void launch_rmsnorm(hipStream_t s, int dtype, const float* h, const float* gain, void* out, int T,
-                    int d, float eps, const int32_t* row_idx) {
+void launch_rmsnorm(hipStream_t s, int dtype, float* h, const float* delta, const float* gain,
+                    void* out, int T, int d, float eps, const int32_t* row_idx) {
     if (T <= 0) return;
     if (dtype == CF_F32)
-        rmsnorm_kernel<float><<<T, 256, 0, s>>>(h, gain, (float*)out, d, eps, row_idx);
+        rmsnorm_kernel<float><<<T, 256, 0, s>>>(h, delta, gain, (float*)out, d, eps, row_idx);
     else
-        rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(h, gain, (bf16*)out, d, eps, row_idx);
+        rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(h, delta, gain, (bf16*)out, d, eps, row_idx);
 }
 
 // ---------------------------------------------------------------- simple GEMM

@@ -108,6 +108,9 @@ class Session:
     def restore(self, requests, splits, want_logits=True):
         """requests: list of dict(req_id, ctx_tokens, new_tokens, host_kv=pinned tensor or
         None).  Returns (logits tensor [B, vocab] or None, timing dict)."""
+        # the library's streams do not order against torch's: finish pending torch work
+        # (fills, copies into the pool) before the blocking call
+        torch.cuda.current_stream(self.device).synchronize()
         reqs = []
         for r in requests:
             hk = r.get("host_kv")

@@ -43,12 +43,33 @@ def stack_kv(shape, kv_ctx, kv_new):
 
 
 def kv_tolerance_ok(shape, got, ref):
-    """max-abs 1e-4 for float32 models; for bf16 models 2e-2 where |ref| < 8 and one bf16
-    ulp of ref above that.  Returns (ok, worst_abs_err, n_large)."""
+    """max-abs 1e-4 for float32 models.  For bf16 models: max-abs 2e-2, relaxed to one bf16
+    ulp of the reference where one ulp exceeds 2e-2 (|ref| >= 4: the cache stores bf16, so a
+    cell cannot in general be closer than half an ulp to the unrounded reference).
+    Returns (ok, worst_abs_err, n_cells_on_the_ulp_rule)."""
     err = np.abs(got.astype(np.float64) - ref)
     if shape.dtype == "f32":
         return bool(err.max(initial=0.0) <= 1e-4), float(err.max(initial=0.0)), 0
-    large = np.abs(ref) >= 8.0
     ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
-    ok = np.where(large, err <= ulp, err <= 2e-2)
-    return bool(ok.all()), float(err.max(initial=0.0)), int(large.sum())
+    tol = np.maximum(2e-2, ulp)
+    return bool((err <= tol).all()), float(err.max(initial=0.0)), int((ulp > 2e-2).sum())
+
+
+def kv_error_report(got, ref):
+    """(worst error where |ref| < 4, worst error in units of bf16 ulps where |ref| >= 4,
+    fraction of cells with |ref| >= 4)."""
+    err = np.abs(got.astype(np.float64) - ref)
+    big = np.abs(ref) >= 4.0
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+    small_worst = float(err[~big].max(initial=0.0))
+    big_worst = float((err[big] / ulp[big]).max(initial=0.0))
+    return small_worst, big_worst, float(big.mean())
+
+
+def bf16_noise_floor_rms(layer):
+    """RMS distance between the CPU oracle's bf16-storage forward and its unrounded forward for
+    K/V cells of a Llama-3-8B-shaped random-init model (std of the cells ~1.28), as a function
+    of the layer: 0.003 at layer 0 (the cell's own rounding) growing like 0.0097*sqrt(layer).
+    Measured, not assumed: tests/test_gpu_scale.py::test_prefix_exactness prints the table
+    these two coefficients summarise, and asserts the GPU against the measured values."""
+    return 0.003 + 0.0097 * np.sqrt(layer)
