@@ -4,38 +4,46 @@
 // grid = (attention work items, Q heads).  A work item is up to 128 packed
 // query rows of one request whose first row sits at absolute position pos0;
 // the query at position p attends to keys 0..p, read from the request's pages.
+// A long key range may be split over several work items (tile_begin/tile_end);
+// those write un-normalised partial results that a small combine kernel merges.
 // Each of the 4 wavefronts owns 32 query rows.  Keys are walked in tiles of 64
 // (4 pages).  The K tile [64 keys][hd] and the transposed V tile [hd][64 keys]
-// (V is stored transposed inside a page) are staged in LDS, double-buffered,
-// with the next tile prefetched into registers during the current one.
+// (V is stored transposed inside a page) are staged in LDS, double-buffered;
+// tile t+2 is fetched into registers while tile t is consumed, and the page ids
+// of tile t+3 are fetched (scalar) at the same time, so neither the page-table
+// lookup nor the memory latency sits on the critical path.
 //
 // The scores are computed transposed, S^T = K Q^T, so that in the MFMA result
 // layout every lane holds 16 keys of ONE query row: the softmax row statistics
 // stay in the lane (one exchange with the lane 32 apart), and the exponentiated
 // scores are already in the register layout the second product,
 // O^T = V^T P^T, needs for its B operand -- P never goes through LDS.
+// The running output is rescaled only when some row's maximum actually moved.
 #include "kernels.h"
 #include "cacheflow.h"
 
 namespace cf {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 
 namespace {
 
 constexpr int KT = 64;                      // keys per tile
+constexpr int PAGES_PER_TILE = KT / CF_PAGE_TOKENS;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7FFFu + ((ua >> 16) & 1u);
-    ub += 0x7FFFu + ((ub >> 16) & 1u);
-    return (ua >> 16) | (ub & 0xFFFF0000u);
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 template <int HD>
-__global__ void __launch_bounds__(256)
-attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
+__global__ void __launch_bounds__(256, 2)
+attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float* __restrict__ part_buf,
                       const bf16* __restrict__ pool_layer, const AttnWork* __restrict__ work,
                       const int32_t* __restrict__ page_tables, int n_q_heads, KvGeom g) {
     constexpr int K_ROWB = HD * 2;                 // bytes per key row of the K tile
@@ -44,7 +52,9 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
     constexpr int V_ROWB = KT * 2;                 // bytes per hd row of the V^T tile (128)
     constexpr int V_TILE = HD * V_ROWB;
     constexpr int STAGE = K_TILE + V_TILE;
-    constexpr int NLD = KT * K_NCH / 256;          // 16-byte loads per thread per tile, each of K and V
+    constexpr int VEC_PER_PAGE = CF_PAGE_TOKENS * K_NCH;       // 16-byte vectors of one page's K (= V) part
+    constexpr int PAGES_PER_LOAD = 256 / VEC_PER_PAGE;         // pages covered by one block-wide load (1 or 2)
+    constexpr int NLD = PAGES_PER_TILE / PAGES_PER_LOAD;       // loads per thread per tile, each of K and V
     constexpr int QK_STEPS = HD / 16;
     constexpr int D_TILES = HD / 32;
     __shared__ __align__(16) char smem[2 * STAGE];
@@ -57,8 +67,7 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int lq = lane & 31, lh = lane >> 5;
 
-    int kv_end = w.pos0 + w.n_rows;                // keys [0, kv_end) are needed by this block
-    int n_tiles = (kv_end + KT - 1) / KT;
+    int kv_end = min(w.pos0 + w.n_rows, w.tile_end * KT);   // keys [tile_begin*KT, kv_end) are read
     int last_page = (kv_end - 1) / CF_PAGE_TOKENS;
     int row = min(wave * 32 + lq, w.n_rows - 1);   // padded rows repeat the last row
     int qpos = w.pos0 + row;
@@ -66,66 +75,75 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
     int wave_first_q = w.pos0 + min(wave * 32, w.n_rows - 1);
 
     // ---- Q fragments: B operand of S^T = K Q^T, lane = query row lq, 8 hd values per step
-    uint4 qf[QK_STEPS];
+    u32x4_t qf[QK_STEPS];
     {
         const bf16* qrow = q + ((int64_t)(w.row0 + row) * n_q_heads + head) * HD;
 #pragma unroll
         for (int kk = 0; kk < QK_STEPS; ++kk)
-            qf[kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + lh * 8);
+            qf[kk] = *reinterpret_cast<const u32x4_t*>(qrow + kk * 16 + lh * 8);
     }
 
-    // ---- tile loader geometry
+    // ---- tile loader: block-wide load j covers page(s) j*PAGES_PER_LOAD.. of the tile.
+    // Within a page, thread slot v handles K vector (row v / K_NCH, chunk v % K_NCH) and
+    // V^T vector (hd row v / 2, half v % 2).
     const int64_t k_head_off = (int64_t)gk * CF_PAGE_TOKENS * HD;
     const int64_t v_head_off = (int64_t)g.n_kv_heads * CF_PAGE_TOKENS * HD + (int64_t)gk * HD * CF_PAGE_TOKENS;
-    int k_row[NLD], k_lds[NLD], k_goff[NLD];
-    int v_page[NLD], v_lds[NLD], v_goff[NLD], v_key0[NLD];
+    int sub_page = tid / VEC_PER_PAGE;             // which page of the load (wave-uniform)
+    int pv = tid % VEC_PER_PAGE;
+    int k_r = pv / K_NCH, k_c = pv % K_NCH;        // key row within page, chunk
+    int v_d = pv / 2, v_half = pv % 2;             // hd row, which 8 keys of the page
+    int k_goff = k_r * HD + k_c * 8;
+    int v_goff = v_d * CF_PAGE_TOKENS + v_half * 8;
+    int k_lds[NLD], v_lds[NLD], v_key0[NLD];
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
-        int v = tid + j * 256;
-        int r = v / K_NCH, c = v % K_NCH;          // key row, chunk
+        int page_in_tile = j * PAGES_PER_LOAD + sub_page;
+        int r = page_in_tile * CF_PAGE_TOKENS + k_r;
         int ksw = (HD == 128) ? (r & 15) : ((r >> 1) & 7);
-        k_row[j] = r;
-        k_lds[j] = r * K_ROWB + ((c ^ ksw) << 4);
-        k_goff[j] = (r % CF_PAGE_TOKENS) * HD + c * 8;
-        int d = v / 8, cv = v % 8;                 // hd row, chunk = page*2 + half
-        v_page[j] = cv >> 1;
-        v_lds[j] = K_TILE + d * V_ROWB + ((cv ^ ((d >> 1) & 7)) << 4);
-        v_goff[j] = d * CF_PAGE_TOKENS + (cv & 1) * 8;
-        v_key0[j] = (cv >> 1) * CF_PAGE_TOKENS + (cv & 1) * 8;   // first key of the vector in the tile
+        k_lds[j] = r * K_ROWB + ((k_c ^ ksw) << 4);
+        int cv = page_in_tile * 2 + v_half;        // 16-byte chunk of the V^T row
+        v_lds[j] = K_TILE + v_d * V_ROWB + ((cv ^ ((v_d >> 1) & 7)) << 4);
+        v_key0[j] = page_in_tile * CF_PAGE_TOKENS + v_half * 8;
     }
 
-    uint4 rk[NLD], rv[NLD];
-    // Global -> registers for one tile.  Slots past the last needed key may hold anything
-    // (even NaN patterns): they are zeroed so that their zero probabilities cannot poison
-    // the second product.
-#define CF_FETCH(TILE)                                                                          \
-    {                                                                                           \
-        int tile_ = (TILE);                                                                     \
-        int page0_ = tile_ * (KT / CF_PAGE_TOKENS);                                             \
-        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                       \
-            int pk = min(page0_ + k_row[j] / CF_PAGE_TOKENS, last_page);                        \
-            rk[j] = *reinterpret_cast<const uint4*>(pool_layer + (int64_t)pt[pk] * g.page_elems + \
-                                                    k_head_off + k_goff[j]);                    \
-            int pv = min(page0_ + v_page[j], last_page);                                        \
-            uint4 val = *reinterpret_cast<const uint4*>(pool_layer + (int64_t)pt[pv] * g.page_elems + \
-                                                        v_head_off + v_goff[j]);                \
-            int left = kv_end - (tile_ * KT + v_key0[j]);   /* valid keys in this vector */     \
-            if (left < 8) {                                                                     \
-                val.x = left <= 0 ? 0u : (left == 1 ? val.x & 0xFFFFu : val.x);                 \
-                val.y = left <= 2 ? 0u : (left == 3 ? val.y & 0xFFFFu : val.y);                 \
-                val.z = left <= 4 ? 0u : (left == 5 ? val.z & 0xFFFFu : val.z);                 \
-                val.w = left <= 6 ? 0u : (left == 7 ? val.w & 0xFFFFu : val.w);                 \
-            }                                                                                   \
-            rv[j] = val;                                                                        \
-        }                                                                                       \
+    // page ids of one tile, wave-uniform (clamped to the last page that is needed)
+    int pg[NLD];
+#define CF_PAGES(TILE)                                                                        \
+    {                                                                                         \
+        int p0_ = (TILE) * PAGES_PER_TILE;                                                    \
+        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                     \
+            int idx_ = __builtin_amdgcn_readfirstlane(min(p0_ + j * PAGES_PER_LOAD + sub_page, last_page)); \
+            pg[j] = pt[idx_];                                                                 \
+        }                                                                                     \
     }
-#define CF_STASH(STAGE_PTR)                                                                     \
-    {                                                                                           \
-        char* st_ = (STAGE_PTR);                                                                \
-        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                       \
-            *reinterpret_cast<uint4*>(st_ + k_lds[j]) = rk[j];                                  \
-            *reinterpret_cast<uint4*>(st_ + v_lds[j]) = rv[j];                                  \
-        }                                                                                       \
+    u32x4_t rk[NLD], rv[NLD];
+    // Global -> registers for one tile (page ids already in pg).  Slots past the last needed
+    // key may hold anything (even NaN patterns): they are zeroed so that their zero
+    // probabilities cannot poison the second product.
+#define CF_FETCH(TILE)                                                                        \
+    {                                                                                         \
+        int tile_ = (TILE);                                                                   \
+        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                     \
+            const bf16* page_ = pool_layer + (int64_t)pg[j] * g.page_elems;                   \
+            rk[j] = *reinterpret_cast<const u32x4_t*>(page_ + k_head_off + k_goff);           \
+            u32x4_t val = *reinterpret_cast<const u32x4_t*>(page_ + v_head_off + v_goff);     \
+            int left = kv_end - (tile_ * KT + v_key0[j]);   /* valid keys in this vector */   \
+            if (left < 8) {                                                                   \
+                val.x = left <= 0 ? 0u : (left == 1 ? val.x & 0xFFFFu : val.x);               \
+                val.y = left <= 2 ? 0u : (left == 3 ? val.y & 0xFFFFu : val.y);               \
+                val.z = left <= 4 ? 0u : (left == 5 ? val.z & 0xFFFFu : val.z);               \
+                val.w = left <= 6 ? 0u : (left == 7 ? val.w & 0xFFFFu : val.w);               \
+            }                                                                                 \
+            rv[j] = val;                                                                      \
+        }                                                                                     \
+    }
+#define CF_STASH(STAGE_PTR)                                                                   \
+    {                                                                                         \
+        char* st_ = (STAGE_PTR);                                                              \
+        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                     \
+            *reinterpret_cast<u32x4_t*>(st_ + k_lds[j]) = rk[j];                              \
+            *reinterpret_cast<u32x4_t*>(st_ + v_lds[j]) = rv[j];                              \
+        }                                                                                     \
     }
 
     f32x16_t o_acc[D_TILES];
@@ -133,21 +151,25 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
     for (int t = 0; t < D_TILES; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[t][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;          // running max (log2 domain), partial row sum
     const float scale_log2e = rsqrtf((float)HD) * 1.4426950408889634f;
 
     // fragment read offsets
     int ksw_l = (HD == 128) ? (lq & 15) : ((lq >> 1) & 7);
     int vsw_l = (lq >> 1) & 7;
 
-    CF_FETCH(0);
+    int t0 = w.tile_begin, t1 = w.tile_end;        // tiles [t0, t1), t1 > t0
+    CF_PAGES(t0);
+    CF_FETCH(t0);
+    CF_PAGES(min(t0 + 1, t1 - 1));
     CF_STASH(smem);
+    CF_FETCH(min(t0 + 1, t1 - 1));
+    CF_PAGES(min(t0 + 2, t1 - 1));
     __syncthreads();
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        char* cur = smem + (tile & 1) * STAGE;
-        char* nxt = smem + ((tile + 1) & 1) * STAGE;
-        CF_FETCH(min(tile + 1, n_tiles - 1));
+    for (int tile = t0; tile < t1; ++tile) {
+        char* cur = smem + ((tile - t0) & 1) * STAGE;
+        char* nxt = smem + ((tile - t0 + 1) & 1) * STAGE;
         int key_base = tile * KT;
         if (key_base <= wave_last_q) {               // wave-uniform: tile not fully masked
             // ---- S^T = K Q^T : two 32-key fragments
@@ -158,50 +180,54 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
                 for (int r = 0; r < 16; ++r) s[tt][r] = 0.f;
 #pragma unroll
                 for (int kk = 0; kk < QK_STEPS; ++kk) {
-                    uint4 kf = *reinterpret_cast<const uint4*>(
+                    u32x4_t kf = *reinterpret_cast<const u32x4_t*>(
                         cur + (tt * 32 + lq) * K_ROWB + (((2 * kk + lh) ^ ksw_l) << 4));
                     s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[kk]), s[tt], 0, 0, 0);
                 }
             }
-            // ---- scale, causal mask, online softmax (lane = one query row, 32 of its 64 keys)
-            bool need_mask = key_base + KT - 1 > wave_first_q;
-            float tmax = -INFINITY;
+            // ---- causal mask on the diagonal tiles only (lane = one query row, 32 of its 64 keys)
+            if (key_base + KT - 1 > wave_first_q) {
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int kpos = key_base + tt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                        s[tt][r] = (kpos > qpos) ? -INFINITY : s[tt][r];
+                    }
+            }
+            // ---- online softmax in the log2 domain: p = 2^(s*scale - m)
+            float tmax = s[0][0];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = s[tt][r] * scale_log2e;
-                    if (need_mask) {
-                        int kpos = key_base + tt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                        v = (kpos > qpos) ? -INFINITY : v;
-                    }
-                    s[tt][r] = v;
-                    tmax = fmaxf(tmax, v);
-                }
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[tt][r]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            float m_new = fmaxf(m_run, tmax);        // finite: key 0 is visible to every row
-            float corr = exp2f(m_run - m_new);
+            float m_new = fmaxf(m_run, tmax * scale_log2e);   // finite: a visible key exists
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // some row's maximum moved
+                float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= corr;
+#pragma unroll
+                for (int t = 0; t < D_TILES; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o_acc[t][r] *= corr;
+                m_run = m_new;
+            }
             float psum = 0.f;
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float p = exp2f(s[tt][r] - m_new);
+                    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tt][r], scale_log2e, -m_run));
                     s[tt][r] = p;
                     psum += p;
                 }
-            l_run = l_run * corr + psum;
-            m_run = m_new;
-#pragma unroll
-            for (int t = 0; t < D_TILES; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[t][r] *= corr;
+            l_run += psum;
             // ---- O^T += V^T P^T : 4 steps of 16 keys (one page each)
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
                 int tt = st >> 1, b0 = (st & 1) * 2;
-                uint4 pf;
+                u32x4_t pf;
                 pf.x = pack_bf16x2(s[tt][4 * b0 + 0], s[tt][4 * b0 + 1]);
                 pf.y = pack_bf16x2(s[tt][4 * b0 + 2], s[tt][4 * b0 + 3]);
                 pf.z = pack_bf16x2(s[tt][4 * b0 + 4], s[tt][4 * b0 + 5]);
@@ -210,34 +236,83 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out,
                 for (int t = 0; t < D_TILES; ++t) {
                     // keys 4*lh..4*lh+3 and 8+4*lh.. of page `st`, for hd row 32t + lq
                     const char* vrow = cur + K_TILE + (t * 32 + lq) * V_ROWB;
-                    uint2 v0 = *reinterpret_cast<const uint2*>(vrow + (((2 * st) ^ vsw_l) << 4) + lh * 8);
-                    uint2 v1 = *reinterpret_cast<const uint2*>(vrow + (((2 * st + 1) ^ vsw_l) << 4) + lh * 8);
-                    uint4 vf = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                    u32x2_t v0 = *reinterpret_cast<const u32x2_t*>(vrow + (((2 * st) ^ vsw_l) << 4) + lh * 8);
+                    u32x2_t v1 = *reinterpret_cast<const u32x2_t*>(vrow + (((2 * st + 1) ^ vsw_l) << 4) + lh * 8);
+                    u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
                     o_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf), o_acc[t], 0, 0, 0);
                 }
             }
         }
-        CF_STASH(nxt);
+        CF_STASH(nxt);                               // tile+1, fetched during the previous iteration
+        CF_FETCH(min(tile + 2, t1 - 1));             // consumed two iterations from now
+        CF_PAGES(min(tile + 3, t1 - 1));
         __syncthreads();
     }
+#undef CF_PAGES
 #undef CF_FETCH
 #undef CF_STASH
 
-    // ---- normalise and store: lane holds hd = 32t + 8b + 4*lh + i of query row lq
+    // ---- store: lane holds hd = 32t + 8b + 4*lh + i of query row lq
     float l_tot = l_run + __shfl_xor(l_run, 32);
-    float inv = 1.0f / l_tot;
-    if (wave * 32 + lq < w.n_rows) {
+    if (wave * 32 + lq >= w.n_rows) return;
+    if (w.part < 0) {
+        float inv = 1.0f / l_tot;
         bf16* orow = out + ((int64_t)(w.row0 + wave * 32 + lq) * n_q_heads + head) * HD;
 #pragma unroll
         for (int t = 0; t < D_TILES; ++t)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                uint2 val;
+                u32x2_t val;
                 val.x = pack_bf16x2(o_acc[t][4 * b + 0] * inv, o_acc[t][4 * b + 1] * inv);
                 val.y = pack_bf16x2(o_acc[t][4 * b + 2] * inv, o_acc[t][4 * b + 3] * inv);
-                *reinterpret_cast<uint2*>(orow + t * 32 + 8 * b + 4 * lh) = val;
+                *reinterpret_cast<u32x2_t*>(orow + t * 32 + 8 * b + 4 * lh) = val;
             }
+    } else {
+        // partial result of one key range: [part][head][row] -> (o[HD], m, l, pad, pad) in float
+        float* prow = part_buf + (((int64_t)w.part * n_q_heads + head) * ATTN_BLOCK_ROWS + wave * 32 + lq) * (HD + 4);
+        if (lh == 0) { prow[HD] = m_run; prow[HD + 1] = l_tot; }
+#pragma unroll
+        for (int t = 0; t < D_TILES; ++t)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                float4 val = make_float4(o_acc[t][4 * b + 0], o_acc[t][4 * b + 1], o_acc[t][4 * b + 2], o_acc[t][4 * b + 3]);
+                *reinterpret_cast<float4*>(prow + t * 32 + 8 * b + 4 * lh) = val;
+            }
+    }
+}
+
+// Merge the partial results of one (q-block, head): one wavefront per query row.
+template <int HD>
+__global__ void __launch_bounds__(256)
+attention_combine_kernel(bf16* __restrict__ out, const float* __restrict__ part_buf,
+                         const AttnCombine* __restrict__ groups, int n_q_heads) {
+    AttnCombine cgrp = groups[blockIdx.x];
+    int head = blockIdx.y;
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int r = wave; r < cgrp.n_rows; r += 4) {
+        float m = -INFINITY;
+        for (int p = 0; p < cgrp.n_parts; ++p) {
+            const float* prow = part_buf + (((int64_t)(cgrp.part_first + p) * n_q_heads + head) * ATTN_BLOCK_ROWS + r) * (HD + 4);
+            m = fmaxf(m, prow[HD]);
+        }
+        float l = 0.f, acc[HD / 64];
+#pragma unroll
+        for (int i = 0; i < HD / 64; ++i) acc[i] = 0.f;
+        for (int p = 0; p < cgrp.n_parts; ++p) {
+            const float* prow = part_buf + (((int64_t)(cgrp.part_first + p) * n_q_heads + head) * ATTN_BLOCK_ROWS + r) * (HD + 4);
+            float f = __builtin_amdgcn_exp2f(prow[HD] - m);
+            l += prow[HD + 1] * f;
+#pragma unroll
+            for (int i = 0; i < HD / 64; ++i) acc[i] += prow[lane + 64 * i] * f;
+        }
+        bf16* orow = out + ((int64_t)(cgrp.row0 + r) * n_q_heads + head) * HD;
+        float inv = 1.0f / l;
+#pragma unroll
+        for (int i = 0; i < HD / 64; ++i) {
+            float v = acc[i] * inv;
+            orow[lane + 64 * i].x = (uint16_t)(pack_bf16x2(v, 0.f) & 0xFFFFu);
+        }
     }
 }
 
@@ -247,15 +322,23 @@ bool attention_mfma_supported(int dtype, int head_dim, int n_q_heads, int n_kv_h
     return dtype == CF_BF16 && (head_dim == 64 || head_dim == 128) && n_q_heads % n_kv_heads == 0;
 }
 
-void launch_attention_mfma(hipStream_t s, const void* q, void* out, const void* pool_layer,
-                           const AttnWork* work, int n_work, const int32_t* page_tables,
+void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_buf,
+                           const void* pool_layer, const AttnWork* work, int n_work,
+                           const AttnCombine* groups, int n_groups, const int32_t* page_tables,
                            int n_q_heads, KvGeom g) {
     if (n_work <= 0) return;
     dim3 grid(n_work, n_q_heads);
     if (g.head_dim == 128)
-        attention_mfma_kernel<128><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+        attention_mfma_kernel<128><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
     else
-        attention_mfma_kernel<64><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+        attention_mfma_kernel<64><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+    if (n_groups > 0) {
+        dim3 cgrid(n_groups, n_q_heads);
+        if (g.head_dim == 128)
+            attention_combine_kernel<128><<<cgrid, 256, 0, s>>>((bf16*)out, part_buf, groups, n_q_heads);
+        else
+            attention_combine_kernel<64><<<cgrid, 256, 0, s>>>((bf16*)out, part_buf, groups, n_q_heads);
+    }
 }
 
 }  // namespace cf

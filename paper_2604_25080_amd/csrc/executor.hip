@@ -31,7 +31,7 @@ constexpr int PAGE_MOVE_SPLIT = 4;       // blocks per page in the page mover
 constexpr int N_STAGING_SLOTS = 2;
 
 struct Carve {
-    size_t rope, h, dl, a, qkv, q, o, act, a_last, staging, meta, total;
+    size_t rope, h, dl, a, qkv, q, o, act, a_last, attn_part, staging, meta, total;
     size_t staging_bytes, meta_bytes;
     int chunk_rows;
 };
@@ -58,9 +58,9 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
     size_t pages_per_req = (size_t)o.max_positions / CF_PAGE_TOKENS + 2;
     size_t meta = (size_t)2 * 12 * o.max_tokens                       // ids, positions, slots
                   + (size_t)4 * o.max_batch * pages_per_req            // page tables
-                  + (size_t)sizeof(AttnWork) * (2 * ((size_t)o.max_tokens / ATTN_BLOCK_ROWS) +
-                                                4 * (size_t)o.max_batch +
-                                                2 * ((size_t)o.max_tokens / chunk + 2) * 2)
+                  + (size_t)(sizeof(AttnWork) + sizeof(AttnCombine)) *
+                        (2 * ((size_t)o.max_tokens / ATTN_BLOCK_ROWS) + 4 * (size_t)o.max_batch +
+                         4 * ((size_t)o.max_tokens / chunk + 2) + 2 * ATTN_MAX_PART_BLOCKS)
                   + (size_t)sizeof(PageJob) * ((size_t)o.max_batch * m.n_layers * 2 + 4096) +
                   (size_t)8 * o.max_batch + (1 << 16);
     size_t off = 0;
@@ -74,6 +74,7 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
     c->o = take((size_t)chunk * m.n_q_heads * m.head_dim * es);
     c->act = take((size_t)chunk * m.d_ffn * es);
     c->a_last = take((size_t)o.max_batch * m.d_model * es);
+    c->attn_part = take(attn_part_bytes(m.head_dim));
     c->staging = take(stg);
     c->meta = take(meta);
     c->total = off;
@@ -149,6 +150,7 @@ struct cf_ctx {
     void* o() { return ws + cv.o; }
     void* act() { return ws + cv.act; }
     void* a_last() { return ws + cv.a_last; }
+    float* attn_part() { return (float*)(ws + cv.attn_part); }
     float2* rope() { return (float2*)(ws + cv.rope); }
     char* staging() { return ws + cv.staging; }
     char* meta_dev() { return ws + cv.meta; }
@@ -266,6 +268,7 @@ struct Segment {        // rows of one request inside a packed phase
 struct ChunkInfo {
     int r0, r1;         // packed row range
     int work_off, n_work;
+    int grp_off, n_grp; // combine groups of the items whose key range was split
 };
 
 struct Phase {
@@ -273,8 +276,9 @@ struct Phase {
     std::vector<Segment> segs;          // packed order; `layers` non-increasing
     std::vector<ChunkInfo> chunks;
     std::vector<AttnWork> work;
+    std::vector<AttnCombine> groups;
     // device offsets (bytes into meta)
-    size_t off_ids = 0, off_pos = 0, off_slot = 0, off_work = 0;
+    size_t off_ids = 0, off_pos = 0, off_slot = 0, off_work = 0, off_grp = 0;
     int rows_active(int layer) const {
         int t = 0;
         for (const Segment& s : segs)
@@ -297,12 +301,18 @@ struct MetaWriter {
     }
 };
 
-void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off) {
+// Cut a phase into row chunks and the chunks into attention work items of up to 128 query
+// rows.  When a chunk has too few items to fill the GPU (few new tokens over long contexts)
+// and `n_q_heads_split` > 0, the key range of an item is split into slices that run as
+// separate workgroups and are merged afterwards.
+void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int n_q_heads_split) {
     for (int r0 = 0; r0 < ph.T; r0 += chunk_rows) {
         ChunkInfo ci;
         ci.r0 = r0;
         ci.r1 = std::min(ph.T, r0 + chunk_rows);
         ci.work_off = (int)ph.work.size();
+        ci.grp_off = (int)ph.groups.size();
+        std::vector<AttnWork> items;
         for (const Segment& s : ph.segs) {
             int a = std::max(s.row0, ci.r0), b = std::min(s.row0 + s.n_rows, ci.r1);
             for (int r = a; r < b; r += ATTN_BLOCK_ROWS) {
@@ -311,10 +321,43 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off) {
                 w.n_rows = std::min(ATTN_BLOCK_ROWS, b - r);
                 w.pos0 = s.pos0 + (r - s.row0);
                 w.pt_off = pt_off[s.req];
-                ph.work.push_back(w);
+                w.tile_begin = 0;
+                w.tile_end = (w.pos0 + w.n_rows + ATTN_KEY_TILE - 1) / ATTN_KEY_TILE;
+                w.part = -1;
+                w.pad = 0;
+                items.push_back(w);
             }
         }
+        int factor = 1;
+        if (n_q_heads_split > 0 && !items.empty()) {
+            int64_t blocks = (int64_t)items.size() * n_q_heads_split;
+            if (blocks < 512) factor = (int)((1024 + blocks - 1) / blocks);
+        }
+        int next_part = 0;
+        for (const AttnWork& w : items) {
+            int full_tiles = w.pos0 / ATTN_KEY_TILE;          // tiles every row sees completely
+            int n_split = std::min(factor, std::max(1, full_tiles / 16));
+            if (n_split > 1 && (int64_t)(next_part + n_split) * n_q_heads_split > ATTN_MAX_PART_BLOCKS)
+                n_split = 1;
+            if (n_split <= 1) {
+                ph.work.push_back(w);
+                continue;
+            }
+            AttnCombine gcomb{w.row0, w.n_rows, next_part, n_split};
+            int begin = 0;
+            for (int j = 0; j < n_split; ++j) {
+                AttnWork p = w;
+                p.tile_begin = begin;
+                p.tile_end = (j + 1 == n_split) ? w.tile_end
+                                                : std::min((int)((int64_t)(j + 1) * w.tile_end / n_split), full_tiles);
+                p.part = next_part++;
+                begin = p.tile_end;
+                ph.work.push_back(p);
+            }
+            ph.groups.push_back(gcomb);
+        }
         ci.n_work = (int)ph.work.size() - ci.work_off;
+        ci.n_grp = (int)ph.groups.size() - ci.grp_off;
         ph.chunks.push_back(ci);
     }
 }
@@ -345,6 +388,7 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max, bo
     const int32_t* d_pos = (const int32_t*)(md + ph.off_pos);
     const int32_t* d_slot = (const int32_t*)(md + ph.off_slot);
     const AttnWork* d_work = (const AttnWork*)(md + ph.off_work);
+    const AttnCombine* d_grp = (const AttnCombine*)(md + ph.off_grp);
     const int32_t* d_pt = (const int32_t*)md;      // page tables sit at offset 0
     KvGeom g;
     g.n_kv_heads = m.n_kv_heads;
@@ -389,13 +433,18 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max, bo
                 double pairs = 0;
                 for (int i = 0; i < n_work; ++i) {
                     const AttnWork& aw = ph.work[ci.work_off + i];
+                    if (aw.part >= 0 && aw.tile_begin > 0) continue;   // count a split item once
                     pairs += (double)aw.n_rows * aw.pos0 + (double)aw.n_rows * (aw.n_rows + 1) / 2;
                 }
                 c->prof_begin(CF_K_ATTENTION, pairs * 4.0 * m.n_q_heads * m.head_dim, c->cs);
             }
+            int n_grp = 0;
+            for (int i = 0; i < ci.n_grp; ++i)
+                if (ph.groups[ci.grp_off + i].row0 + ci.r0 < Tn) n_grp = i + 1;
             if (mfma_attn)
-                launch_attention_mfma(c->cs, c->q(), c->o(), pool_layer, d_work + ci.work_off,
-                                      n_work, d_pt, m.n_q_heads, g);
+                launch_attention_mfma(c->cs, c->q(), c->o(), c->attn_part(), pool_layer,
+                                      d_work + ci.work_off, n_work, d_grp + ci.grp_off, n_grp, d_pt,
+                                      m.n_q_heads, g);
             else
                 launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
                                         d_work + ci.work_off, n_work, d_pt, m.n_q_heads, g);
@@ -506,6 +555,9 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     }
     auto slot_of = [&](int i, int t) { return pt[i][t / CF_PAGE_TOKENS] * CF_PAGE_TOKENS + t % CF_PAGE_TOKENS; };
 
+    // key ranges are split only for the MFMA attention kernel (the plain one walks them whole)
+    int split_heads = (!c->simple_only && attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads))
+                          ? m.n_q_heads : 0;
     // recompute phase: requests in order of descending layer cut so that the rows
     // active in layer l are a prefix of the packed array
     Phase rec, suf;
@@ -526,11 +578,12 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
             rec.T += s.n_rows;
             rec.segs.push_back(s);
         }
-        build_chunks(rec, c->cv.chunk_rows, pt_off);
+        build_chunks(rec, c->cv.chunk_rows, pt_off, split_heads);
         rec.off_ids = mw.put(ids.data(), ids.size() * 4);
         rec.off_pos = mw.put(pos.data(), pos.size() * 4);
         rec.off_slot = mw.put(slot.data(), slot.size() * 4);
         rec.off_work = mw.put(rec.work.data(), rec.work.size() * sizeof(AttnWork));
+        rec.off_grp = mw.put(rec.groups.data(), rec.groups.size() * sizeof(AttnCombine));
     }
     std::vector<int32_t> last_rows;
     if (logits_out) {
@@ -546,11 +599,12 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
             suf.segs.push_back(s);
             last_rows.push_back(suf.T - 1);
         }
-        build_chunks(suf, c->cv.chunk_rows, pt_off);
+        build_chunks(suf, c->cv.chunk_rows, pt_off, split_heads);
         suf.off_ids = mw.put(ids.data(), ids.size() * 4);
         suf.off_pos = mw.put(pos.data(), pos.size() * 4);
         suf.off_slot = mw.put(slot.data(), slot.size() * 4);
         suf.off_work = mw.put(suf.work.data(), suf.work.size() * sizeof(AttnWork));
+        suf.off_grp = mw.put(suf.groups.data(), suf.groups.size() * sizeof(AttnCombine));
     }
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
     c->last_rows = last_rows;

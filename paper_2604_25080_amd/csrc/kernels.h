@@ -22,10 +22,23 @@ enum Epilogue {
 // One q-block of attention work: rows [row0, row0+n_rows) of the packed query
 // buffer belong to one request, the first of them sits at absolute position
 // pos0, and the request's page ids start at page_tables[pt_off].
+// Keys are walked in tiles of 64; the item covers tiles [tile_begin, tile_end).  part < 0:
+// the item covers the whole key range and writes the normalised output; part >= 0: it is one
+// slice of a split key range and writes an un-normalised partial result to slot `part`.
 struct AttnWork {
     int32_t row0, n_rows, pos0, pt_off;
+    int32_t tile_begin, tile_end, part, pad;
+};
+// Partial results [part_first, part_first + n_parts) belong to query rows [row0, row0 + n_rows).
+struct AttnCombine {
+    int32_t row0, n_rows, part_first, n_parts;
 };
 constexpr int ATTN_BLOCK_ROWS = 128;
+constexpr int ATTN_KEY_TILE = 64;
+constexpr int ATTN_MAX_PART_BLOCKS = 2048;   // (partial slots) x (Q heads) the partial buffer holds
+inline size_t attn_part_bytes(int head_dim) {
+    return (size_t)ATTN_MAX_PART_BLOCKS * ATTN_BLOCK_ROWS * (head_dim + 4) * sizeof(float);
+}
 
 // One contiguous run of pages of one layer of one request, staged in order.
 struct PageJob {
@@ -66,8 +79,9 @@ void launch_attention_simple(hipStream_t s, int dtype, const void* q, void* out,
                              const void* pool_layer, const AttnWork* work, int n_work,
                              const int32_t* page_tables, int n_q_heads, KvGeom g);
 bool attention_mfma_supported(int dtype, int head_dim, int n_q_heads, int n_kv_heads);
-void launch_attention_mfma(hipStream_t s, const void* q, void* out, const void* pool_layer,
-                           const AttnWork* work, int n_work, const int32_t* page_tables,
+void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_buf,
+                           const void* pool_layer, const AttnWork* work, int n_work,
+                           const AttnCombine* groups, int n_groups, const int32_t* page_tables,
                            int n_q_heads, KvGeom g);
 // staging -> pages (to_pages = true) or pages -> staging (false; zero-fills unused slots)
 void launch_page_move(hipStream_t s, int dtype, void* staging, void* pool, const PageJob* jobs,

@@ -20,12 +20,12 @@ pytestmark = pytest.mark.gpu
 N_PAGES = 400
 
 
-def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows):
+def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows, n_pages=N_PAGES):
     from paper_2604_25080_amd.runtime import Session
     b = random_batch(seed, shape_name, n_req, n_lo, n_hi, m_lo, m_hi)
     refs, ws = oracle_batch(b)
     sess = Session(b.shape, ws, max_batch=n_req, max_tokens=sum(b.n_ctx) + sum(b.n_new),
-                   max_positions=max(b.n_ctx) + max(b.n_new) + 16, n_pages=N_PAGES,
+                   max_positions=max(b.n_ctx) + max(b.n_new) + 16, n_pages=n_pages,
                    chunk_rows=chunk_rows, pool_fill=0xFF, staging_bytes=1 << 20)
     host = [sess.pin_host_kv(host_block(b.shape, T.kv_to_pages(b.shape, refs[i][0], b.n_ctx[i])))
             for i in range(n_req)]
@@ -35,8 +35,8 @@ def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows):
 def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False):
     sess.ctx.set_kernel_set(simple_only)
     sess.pool.fill_(0xFF)
-    opt = PageTable(N_PAGES)
-    for op in churn_script(seed, N_PAGES, n_ops=60, max_tokens=300):
+    opt = PageTable(sess.n_pages)
+    for op in churn_script(seed, sess.n_pages, n_ops=60, max_tokens=300):
         if op[0] == "alloc":
             sess.cache.alloc(1000 + op[1], op[2]); opt.alloc(1000 + op[1], op[2])
         else:
@@ -119,6 +119,18 @@ def test_mini_bf16_hybrid_equals_all_recompute_on_the_gpu(mini):
         k = (b.n_ctx[i] // 3) // 16 * 16
         assert np.array_equal(full[i][0][:, :k], part[i][0][:, :k])
         assert np.array_equal(full[i][1][:, :k], part[i][1][:, :k])
+
+
+def test_long_context_few_new_tokens_splits_the_key_range():
+    # 3 new tokens over contexts of 2100..2900 tokens: too few query blocks to fill the GPU, so
+    # the suffix attention splits each key range into slices and merges the partial results
+    b, refs, sess, host = build("mini-bf16", 13, 2, 2100, 2900, 3, 9, chunk_rows=1024, n_pages=1000)
+    try:
+        L = b.shape.n_layers
+        restore_and_compare(b, refs, sess, host, [(0, L) for n in b.n_ctx], seed=61)
+        restore_and_compare(b, refs, sess, host, [(n // 2 // 16 * 16, L) for n in b.n_ctx], seed=62)
+    finally:
+        sess.close()
 
 
 def test_head_dim_64_bf16_model():
