@@ -182,10 +182,14 @@ def main():
     if dom["launches"]:
         avg_ms = dom["total_ms"] / dom["launches"]
         ach = dom["work"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        traffic = None          # HBM bytes per launch from rocprofv3 --pmc runs (profiles/)
+        tpath = os.path.join(ROOT, "profiles", "traffic.txt")
         if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get(f"{args.config}:gemm_gate_up")
+            for line in open(tpath):
+                f = line.split()
+                if len(f) == 4 and f[0] == f"{args.config}:gemm_gate_up":
+                    traffic = {"rows_per_launch": int(f[1]), "fetch_bytes": float(f[2]),
+                               "write_bytes": float(f[3]), "bytes": float(f[2]) + float(f[3])}
         roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "gemm_gate_up (MFMA GEMM, SiLU*mul epilogue)",
                     "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
                     "traffic": traffic, "launches": dom["launches"], "avg_launch_ms": avg_ms,
