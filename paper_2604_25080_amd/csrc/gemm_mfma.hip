@@ -41,19 +41,21 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) {
 
 // BM x BN block tile (256x256 for large problems, 128x128 when that would leave CUs idle);
 // the 4 wavefronts form a 2x2 grid of (BM/2)x(BN/2) wave tiles.
-template <int EPI, int BM, int BN>
-__global__ void __launch_bounds__(256)
+template <int EPI, int BM, int BN, int NW>
+__global__ void __launch_bounds__(64 * NW)
 gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                  const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
                  int N, int K, int tiles_m, int tiles_n, int map_mode, int group_m) {
     extern __shared__ __align__(16) char smem[];
     constexpr bool SILU = (EPI == EPI_SILU_MUL);
     constexpr int BN_OUT = SILU ? BN / 2 : BN;    // output columns per block
-    constexpr int WM = BM / 2, WN = BN / 2;       // wave tile
+    constexpr int WGN = NW / 2;                   // wavefront grid: 2 x WGN
+    constexpr int NT = 64 * NW;                   // threads
+    constexpr int WM = BM / 2, WN = BN / WGN;     // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;     // MFMA fragments per wave tile
     constexpr int A_TILE = BM * ROW_BYTES, B_TILE = BN * ROW_BYTES;
     constexpr int STAGE_BYTES = A_TILE + B_TILE;
-    constexpr int LA = BM * NCH / 256, LB = BN * NCH / 256;   // 16-byte loads per thread
+    constexpr int LA = BM * NCH / NT, LB = BN * NCH / NT;     // 16-byte loads per thread
 
     // ---- workgroup -> tile: XCD-contiguous renumbering, then 8-row groups
     int nb = tiles_m * tiles_n;
@@ -68,9 +70,18 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     int tile_m = first_m + (pid % in_group) % gsz;
     int tile_n = (pid % in_group) / gsz;
     int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+    constexpr bool BIG = (BM == 256 && NW == 4);
+    if constexpr (BIG) {
+        // Edge tiles are shifted back inside the matrix (the host guarantees M >= BM and
+        // N >= BN_OUT); the overlap is recomputed and stored twice with identical values.
+        // This keeps every row of a tile a fixed stride apart, so the loader needs one
+        // per-thread offset instead of one per row.
+        m0 = min(m0, M - BM);
+        n0 = min(n0, N - BN_OUT);
+    }
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int wm = wave >> 1, wn = wave & 1;
+    int wm = wave / WGN, wn = wave % WGN;
 
     // ---- global -> register -> LDS loader: thread handles chunk (tid % NCH) of rows
     // tid / NCH + j * (256 / NCH), j = 0..LOADS-1, for both operand tiles
@@ -83,13 +94,13 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     int a_lds[LA], b_lds[LB];
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        int r = ld_row0 + j * (256 / NCH);
+        int r = ld_row0 + j * (NT / NCH);
         a_off[j] = (min(m0 + r, M - 1) - m0) * K + ld_chunk * 8;
         a_lds[j] = r * ROW_BYTES + ((ld_chunk ^ swz(r)) << 4);
     }
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
-        int r = ld_row0 + j * (256 / NCH);
+        int r = ld_row0 + j * (NT / NCH);
         // gate/up pair: tile rows [0, BN/2) are gate rows, [BN/2, BN) the same rows of up
         int rn = SILU ? r % (BN / 2) : r;
         b_off[j] = (min(n0 + rn, N - 1) - n0) * K + ld_chunk * 8;
@@ -120,70 +131,149 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // Software pipeline: while K-step kt is multiplied out of one LDS buffer, K-step kt+1
-    // (fetched during the previous iteration) is written to the other buffer and K-step kt+2
-    // is fetched into registers.  The fetch sits at the end of the iteration and its consumer
-    // in the next one, so a full iteration of MFMAs covers the memory latency.
-    u32x4_t ra[LA], rb[LB];
+    // Software pipeline over K-steps of 64 (four 16-deep MFMA sub-steps each).  Tile kt is
+    // multiplied out of LDS buffer kt&1; fragments are double-buffered in registers and always
+    // read one sub-step ahead of the MFMAs that use them; one barrier per K-step, placed after
+    // sub-step 2, when every wave already holds its sub-step-3 fragments in registers.
     int nk = K / BK;
-    {
-        int koff_ = min(0, nk - 1) * BK;   // past the end: refetch the last step, unused
-#pragma unroll
-        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
-#pragma unroll
-        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
+#define CF_FETCH_A(KT, RA)                                                                    \
+    {                                                                                         \
+        int koff_ = min((KT), nk - 1) * BK;   /* past the end: refetch the last step, unused */ \
+        _Pragma("unroll") for (int j = 0; j < LA; ++j)                                        \
+            RA[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);             \
     }
-    {
-#pragma unroll
-        for (int j = 0; j < LA; ++j) *reinterpret_cast<u32x4_t*>(smem + a_lds[j]) = ra[j];
-#pragma unroll
-        for (int j = 0; j < LB; ++j) *reinterpret_cast<u32x4_t*>(smem + b_lds[j]) = rb[j];
+#define CF_FETCH_B(KT, RB)                                                                    \
+    {                                                                                         \
+        int koff_ = min((KT), nk - 1) * BK;                                                   \
+        _Pragma("unroll") for (int j = 0; j < LB; ++j)                                        \
+            RB[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);       \
     }
-    {
-        int koff_ = min(1, nk - 1) * BK;   // past the end: refetch the last step, unused
-#pragma unroll
-        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
-#pragma unroll
-        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
+#define CF_STASH_A(BUF, RA)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < LA; ++j) *reinterpret_cast<u32x4_t*>((BUF) + a_lds[j]) = RA[j];
+#define CF_STASH_B(BUF, RB)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < LB; ++j) *reinterpret_cast<u32x4_t*>((BUF) + b_lds[j]) = RB[j];
+#define CF_READ_FRAGS(FA, FB, BUF, KK)                                                        \
+    {                                                                                         \
+        const char* buf_ = (BUF);                                                             \
+        int coff_ = ((2 * (KK) + fhalf) ^ fswz) << 4;                                         \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i)                                        \
+            FA[i] = *reinterpret_cast<const u32x4_t*>(buf_ + a_base + i * 32 * ROW_BYTES + coff_); \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j)                                        \
+            FB[j] = *reinterpret_cast<const u32x4_t*>(buf_ + b_row[j] + coff_);               \
     }
-    __syncthreads();
+#define CF_MFMA(FA, FB)                                                                       \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i)                                            \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j)                                        \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                              \
+                __builtin_bit_cast(bf16x8_t, FA[i]), __builtin_bit_cast(bf16x8_t, FB[j]), acc[i][j], 0, 0, 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        char* cur = smem + (kt & 1) * STAGE_BYTES;
-        char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            int coff = ((2 * kk + fhalf) ^ fswz) << 4;
-            u32x4_t fa[FM], fb[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                fa[i] = *reinterpret_cast<const u32x4_t*>(cur + a_base + i * 32 * ROW_BYTES + coff);
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                fb[j] = *reinterpret_cast<const u32x4_t*>(cur + b_row[j] + coff);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8_t, fa[i]), __builtin_bit_cast(bf16x8_t, fb[j]),
-                        acc[i][j], 0, 0, 0);
+    u32x4_t fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+    if constexpr (BIG) {
+        // loader of the big tile: row j of a thread is 32 rows below row j-1, in global memory
+        // (wave-uniform base + one 32-bit per-thread byte offset) and in LDS (immediate offsets)
+        const unsigned a_voff = (unsigned)((ld_row0 * K + ld_chunk * 8) * 2);
+        const unsigned b_voff = a_voff;
+        const int lds0 = ld_row0 * ROW_BYTES + ((ld_chunk ^ swz(ld_row0)) << 4);
+        const int64_t row_stride_b = (int64_t)(NT / NCH) * K * 2;          // bytes between loader rows
+#define CF_BIG_FETCH_A(KT, RA)                                                                \
+        {                                                                                     \
+            const char* base_ = (const char*)a_tile + (int64_t)min((KT), nk - 1) * (BK * 2);  \
+            _Pragma("unroll") for (int j = 0; j < LA; ++j)                                    \
+                RA[j] = *reinterpret_cast<const u32x4_t*>(base_ + j * row_stride_b + a_voff); \
         }
-    {
-#pragma unroll
-        for (int j = 0; j < LA; ++j) *reinterpret_cast<u32x4_t*>(nxt + a_lds[j]) = ra[j];
-#pragma unroll
-        for (int j = 0; j < LB; ++j) *reinterpret_cast<u32x4_t*>(nxt + b_lds[j]) = rb[j];
-    }
-    {
-        int koff_ = min(kt + 2, nk - 1) * BK;   // past the end: refetch the last step, unused
-#pragma unroll
-        for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4_t*>(a_tile + koff_ + a_off[j]);
-#pragma unroll
-        for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4_t*>(CF_B_BASE(j) + koff_ + b_off[j]);
-    }
+#define CF_BIG_FETCH_B(KT, RB)                                                                \
+        {                                                                                     \
+            int64_t koffb_ = (int64_t)min((KT), nk - 1) * (BK * 2);                           \
+            _Pragma("unroll") for (int j = 0; j < LB; ++j) {                                  \
+                /* gate/up pair: loader rows [0, BN/2) come from W, [BN/2, BN) from W2 */     \
+                const char* base_ = (const char*)CF_B_BASE(j) + koffb_ +                      \
+                                    (SILU ? (j % (LB / 2)) : j) * row_stride_b;               \
+                RB[j] = *reinterpret_cast<const u32x4_t*>(base_ + b_voff);                    \
+            }                                                                                 \
+        }
+#define CF_BIG_STASH_A(BUF, RA)                                                               \
+        _Pragma("unroll") for (int j = 0; j < LA; ++j)                                        \
+            *reinterpret_cast<u32x4_t*>((BUF) + lds0 + j * (NT / NCH) * ROW_BYTES) = RA[j];
+#define CF_BIG_STASH_B(BUF, RB)                                                               \
+        _Pragma("unroll") for (int j = 0; j < LB; ++j)                                        \
+            *reinterpret_cast<u32x4_t*>((BUF) + A_TILE + lds0 + j * (NT / NCH) * ROW_BYTES) = RB[j];
+        // 16 MFMAs per sub-step and exactly 16 memory instructions beside them: 8 fragment reads
+        // plus 8 of {LDS fill of the A half, global fetch of the A half, LDS fill of the B half,
+        // global fetch of the B half} -- never more than one memory instruction per MFMA, which
+        // is what keeps the matrix pipe fed (two per MFMA cost ~25 %).  Two register sets hold
+        // tiles in flight: the set written to LDS in iteration kt was fetched in iteration kt-2,
+        // so two full K-steps of MFMAs cover the memory latency.  The host guarantees an even
+        // number of K-steps for this variant.
+        // Order hints (masks: 0x8 MFMA, 0x20 VMEM read, 0x100 LDS read, 0x200 LDS write); the
+        // builtin wants literal arguments.
+#define CF_GROUP(MASK, SIZE) __builtin_amdgcn_sched_group_barrier((MASK), (SIZE), 0)
+#define CF_REP4(X) X X X X
+#define CF_REP8(X) CF_REP4(X) CF_REP4(X)
+#define CF_SECTION(OTHER)                                                                     \
+        CF_REP8(CF_GROUP(0x8, 1); CF_GROUP(0x100, 1);) CF_REP8(CF_GROUP(0x8, 1); CF_GROUP((OTHER), 1);) \
+        __builtin_amdgcn_sched_barrier(0);
+#define CF_KSTEP(KT, RA, RB)                                                                  \
+        {                                                                                     \
+            char* cur = smem + ((KT) & 1) * STAGE_BYTES;                                      \
+            char* nxt = smem + (((KT) + 1) & 1) * STAGE_BYTES;                                \
+            CF_READ_FRAGS(fa1, fb1, cur, 1); CF_BIG_STASH_A(nxt, RA); CF_MFMA(fa0, fb0); CF_SECTION(0x200) \
+            CF_READ_FRAGS(fa0, fb0, cur, 2); CF_BIG_FETCH_A((KT) + 3, RA); CF_MFMA(fa1, fb1); CF_SECTION(0x20) \
+            CF_READ_FRAGS(fa1, fb1, cur, 3); CF_BIG_STASH_B(nxt, RB); CF_MFMA(fa0, fb0); CF_SECTION(0x200) \
+            __syncthreads();                                                                  \
+            CF_READ_FRAGS(fa0, fb0, nxt, 0); CF_BIG_FETCH_B((KT) + 3, RB); CF_MFMA(fa1, fb1); CF_SECTION(0x20) \
+        }
+        u32x4_t ra0[LA], rb0[LB], ra1[LA], rb1[LB];
+        CF_BIG_FETCH_A(0, ra0); CF_BIG_FETCH_B(0, rb0);
+        CF_BIG_STASH_A(smem, ra0); CF_BIG_STASH_B(smem, rb0);
+        CF_BIG_FETCH_A(1, ra1); CF_BIG_FETCH_B(1, rb1);
+        CF_BIG_FETCH_A(2, ra0); CF_BIG_FETCH_B(2, rb0);
         __syncthreads();
+        CF_READ_FRAGS(fa0, fb0, smem, 0);
+        for (int kt = 0; kt < nk; kt += 2) {
+            CF_KSTEP(kt, ra1, rb1);
+            CF_KSTEP(kt + 1, ra0, rb0);
+        }
+#undef CF_GROUP
+#undef CF_REP4
+#undef CF_REP8
+#undef CF_SECTION
+#undef CF_KSTEP
+#undef CF_BIG_FETCH_A
+#undef CF_BIG_FETCH_B
+#undef CF_BIG_STASH_A
+#undef CF_BIG_STASH_B
+    } else {
+        // Smaller tiles: tile kt+1 (fetched during the previous iteration) is written to the other
+        // buffer during sub-step 2 and tile kt+2 fetched during sub-step 3; instruction order is
+        // left to the compiler, which does better than explicit hints at 4 MFMAs per sub-step.
+        u32x4_t ra[LA], rb[LB];
+        CF_FETCH_A(0, ra); CF_FETCH_B(0, rb);
+        CF_STASH_A(smem, ra); CF_STASH_B(smem, rb);
+        CF_FETCH_A(1, ra); CF_FETCH_B(1, rb);
+        __syncthreads();
+        CF_READ_FRAGS(fa0, fb0, smem, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            char* cur = smem + (kt & 1) * STAGE_BYTES;
+            char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+            CF_READ_FRAGS(fa1, fb1, cur, 1);
+            CF_MFMA(fa0, fb0);
+            CF_READ_FRAGS(fa0, fb0, cur, 2);
+            CF_MFMA(fa1, fb1);
+            CF_READ_FRAGS(fa1, fb1, cur, 3);
+            CF_STASH_A(nxt, ra); CF_STASH_B(nxt, rb);
+            CF_MFMA(fa0, fb0);
+            __syncthreads();
+            CF_READ_FRAGS(fa0, fb0, nxt, 0);
+            CF_FETCH_A(kt + 2, ra); CF_FETCH_B(kt + 2, rb);
+            CF_MFMA(fa1, fb1);
+        }
     }
+#undef CF_FETCH_A
+#undef CF_FETCH_B
+#undef CF_STASH_A
+#undef CF_STASH_B
+#undef CF_READ_FRAGS
+#undef CF_MFMA
 
 #undef CF_B_BASE
     // ---- epilogue.  Fragment (i,j), register r: row = 32i + 8(r/4) + 4(lane/32) + r%4,
@@ -227,14 +317,14 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     }
 }
 
-template <int EPI, int BM, int BN>
+template <int EPI, int BM, int BN, int NW>
 void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
                  int M, int N, int K) {
     constexpr int BN_OUT = (EPI == EPI_SILU_MUL) ? BN / 2 : BN;
     constexpr int LDS = N_STAGES * (BM + BN) * ROW_BYTES;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN_OUT - 1) / BN_OUT;
     static bool configured = false;
-    auto kern = gemm_mfma_kernel<EPI, BM, BN>;
+    auto kern = gemm_mfma_kernel<EPI, BM, BN, NW>;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
@@ -246,7 +336,7 @@ void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, fl
         const char* gme = getenv("CF_GEMM_GM");
         group_m = gme ? atoi(gme) : 8;
     }
-    kern<<<tiles_m * tiles_n, 256, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf,
+    kern<<<tiles_m * tiles_n, 64 * NW, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf,
                                              (bf16*)Dt, M, N, K, tiles_m, tiles_n, map_mode, group_m);
 }
 
@@ -257,12 +347,13 @@ void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* 
             int N, int K) {
     constexpr int BN_OUT256 = (EPI == EPI_SILU_MUL) ? 128 : 256;
     int64_t tiles256 = (int64_t)((M + 255) / 256) * ((N + BN_OUT256 - 1) / BN_OUT256);
-    // big tiles once they fill the 256 CUs several times over (thresholds measured per
-    // epilogue; the read-modify-write epilogue overlaps better with two small blocks per CU)
-    int64_t need = EPI == EPI_SILU_MUL ? 200 : EPI == EPI_STORE_F32 ? 768 : (int64_t)1 << 40;
-    bool big = g_force_tile ? g_force_tile == 256 : tiles256 >= need;
-    if (big) launch_tile<EPI, 256, 256>(s, A, W, W2, Cf, Dt, M, N, K);
-    else launch_tile<EPI, 128, 128>(s, A, W, W2, Cf, Dt, M, N, K);
+    // big tiles once there is at least one per CU (thresholds measured per epilogue); the
+    // read-modify-write epilogue always takes the small tile (two blocks per CU overlap it)
+    int64_t need = EPI == EPI_SILU_MUL ? 200 : 256;
+    bool big = (g_force_tile ? g_force_tile >= 256 : tiles256 >= need) && K % (2 * BK) == 0 &&
+               M >= 256 && N >= BN_OUT256 && EPI != EPI_ADD_F32;
+    if (big) launch_tile<EPI, 256, 256, 4>(s, A, W, W2, Cf, Dt, M, N, K);
+    else launch_tile<EPI, 128, 128, 4>(s, A, W, W2, Cf, Dt, M, N, K);
 }
 
 }  // namespace
