@@ -64,7 +64,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--plan", default="planner",
                     help="planner | all_recompute | all_load | cut=<L> (layer cut for every request)")
@@ -150,6 +150,11 @@ def main():
     def step():
         splits, stats = make_plan()
         logits, tm = sess.restore(reqs, splits)
+        if stats is not None:
+            # closed loop: correct the cost model by what the two streams actually took (they
+            # slow each other down when they overlap, which calibration in isolation cannot see)
+            cf.cost_feedback(cm, stats["t_comp"], int(tm["compute_ms"] * 1e9), stats["t_io"],
+                             int(tm["copy_ms"] * 1e9))
         return splits, stats, tm
 
     for _ in range(args.warmup):
@@ -228,6 +233,8 @@ def main():
                                "tflops": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9,
                                "frac_of_mfma_peak": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9 / peak},
         "planner": {"cost_model_ps": cost, "l_delta": l_delta,
+                    "cost_model_after_feedback_ps": dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io,
+                                                         gamma=cm.gamma, s_c=cm.s_c, s_io=cm.s_io),
                     "predicted_ms": None if stats is None else stats["makespan"] / 1e9},
         "kernels": kernels,
         "roofline": roofline,

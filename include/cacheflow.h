@@ -132,6 +132,16 @@ int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
                  const int32_t* n_ctx, const cf_split* splits, int64_t* t_comp,
                  int64_t* t_io);
 
+/* Closed-loop correction after an executed batch (Sec. 3.3: scheduling adapts to
+ * evolving resource availability): scales f_c, alpha, beta, s_c by
+ * meas_comp/pred_comp and f_io, gamma, s_io by meas_io/pred_io, each ratio
+ * clamped to [1/4, 4], rounding to nearest (alpha, gamma stay >= 1).  pred_* are
+ * cf_plan_stats.t_comp / t_io of the plan that ran, meas_* the compute / copy
+ * stream times of cf_timing, all in picoseconds; a side with pred or meas == 0
+ * is left unchanged.  Pure host integer arithmetic.                          */
+int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t meas_comp, int64_t pred_io,
+                     int64_t meas_io);
+
 /* L_delta = min{N : T_token(N) <= T_layer(N)} (Sec. 3.1, adaptive strategy)
  * searched on multiples of chunk_tokens up to n_max; n_max + C if none.     */
 int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t n_max,

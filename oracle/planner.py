@@ -233,3 +233,26 @@ def all_recompute(opts, n_ctx):
 
 def all_load(opts, n_ctx):
     return [(TOKEN_WISE, 0, opts.n_layers) for n in n_ctx]
+
+
+def cost_feedback(cm, pred_comp, meas_comp, pred_io, meas_io):
+    """Closed-loop correction of the cost model after an executed batch: compute-side
+    coefficients times measured/predicted compute time, I/O-side ones times
+    measured/predicted I/O time, each ratio clamped to [1/4, 4], round to nearest."""
+    def scale(v, num, den):
+        if num > 4 * den:
+            num, den = 4, 1
+        if 4 * num < den:
+            num, den = 1, 4
+        return (v * num + den // 2) // den
+    out = CostModel(cm.f_c, cm.alpha, cm.beta, cm.f_io, cm.gamma, cm.s_c, cm.s_io)
+    if pred_comp > 0 and meas_comp > 0:
+        out.f_c = scale(cm.f_c, meas_comp, pred_comp)
+        out.alpha = max(1, scale(cm.alpha, meas_comp, pred_comp))
+        out.beta = scale(cm.beta, meas_comp, pred_comp)
+        out.s_c = scale(cm.s_c, meas_comp, pred_comp)
+    if pred_io > 0 and meas_io > 0:
+        out.f_io = scale(cm.f_io, meas_io, pred_io)
+        out.gamma = max(1, scale(cm.gamma, meas_io, pred_io))
+        out.s_io = scale(cm.s_io, meas_io, pred_io)
+    return out

@@ -108,6 +108,7 @@ lib.cf_restore_plan.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, 
                                 _P(cf_split), _P(cf_plan_stats), _P(cf_claim), C.c_int32]
 lib.cf_plan_eval.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
                              _P(cf_split), _P(C.c_int64), _P(C.c_int64)]
+lib.cf_cost_feedback.argtypes = [_P(cf_cost_model), C.c_int64, C.c_int64, C.c_int64, C.c_int64]
 lib.cf_derive_l_delta.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, _P(C.c_int32)]
 lib.cf_cache_create.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                 _P(C.c_void_p)]
@@ -141,7 +142,7 @@ lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_v
                            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                            _P(C.c_float)]
 
-EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval",
+EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", "cf_cost_feedback",
            "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
@@ -195,6 +196,13 @@ def plan_eval(cost, opts, n_ctx, splits):
     _check(lib.cf_plan_eval(C.byref(cost), C.byref(opts), len(n), n.ctypes.data, arr,
                             C.byref(tc), C.byref(tio)), "cf_plan_eval")
     return tc.value, tio.value
+
+
+def cost_feedback(cost, pred_comp, meas_comp, pred_io, meas_io):
+    """Updates `cost` in place."""
+    _check(lib.cf_cost_feedback(C.byref(cost), int(pred_comp), int(meas_comp), int(pred_io),
+                                int(meas_io)), "cf_cost_feedback")
+    return cost
 
 
 def derive_l_delta(cost, opts, n_max):

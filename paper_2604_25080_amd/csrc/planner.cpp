@@ -11,6 +11,7 @@
 // recomputation still ahead of it (Sec. 3.3), and whichever engine would be
 // done with its candidate first takes it (ties: compute).  Priorities are
 // re-evaluated after every unit (the "progressive, chunk-level" update).
+#include <algorithm>
 #include <vector>
 
 #include "cf_common.h"
@@ -228,5 +229,35 @@ extern "C" int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* 
         }
     }
     *l_delta = (int32_t)(n_max + c);
+    return CF_OK;
+}
+
+// Closed-loop correction of the cost model from one executed batch: the compute-side
+// coefficients are scaled by measured/predicted compute time, the I/O-side ones by
+// measured/predicted I/O time (each clamped to [1/4, 4] per update).  This is how the
+// scheduler adapts to what calibration in isolation cannot see: the two engines slow each
+// other down when they run together (Sec. 3.3: priorities follow evolving resource
+// availability).  Integer arithmetic, round to nearest.
+extern "C" int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t meas_comp,
+                                int64_t pred_io, int64_t meas_io) {
+    if (!cost || pred_comp < 0 || meas_comp < 0 || pred_io < 0 || meas_io < 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_cost_feedback: bad argument");
+    auto scale = [](int64_t v, int64_t num, int64_t den) -> int64_t {
+        if (num > 4 * den) { num = 4; den = 1; }
+        if (4 * num < den) { num = 1; den = 4; }
+        __int128 r = ((__int128)v * num + den / 2) / den;
+        return (int64_t)r;
+    };
+    if (pred_comp > 0 && meas_comp > 0) {
+        cost->f_c = scale(cost->f_c, meas_comp, pred_comp);
+        cost->alpha = std::max<int64_t>(1, scale(cost->alpha, meas_comp, pred_comp));
+        cost->beta = scale(cost->beta, meas_comp, pred_comp);
+        cost->s_c = scale(cost->s_c, meas_comp, pred_comp);
+    }
+    if (pred_io > 0 && meas_io > 0) {
+        cost->f_io = scale(cost->f_io, meas_io, pred_io);
+        cost->gamma = std::max<int64_t>(1, scale(cost->gamma, meas_io, pred_io));
+        cost->s_io = scale(cost->s_io, meas_io, pred_io);
+    }
     return CF_OK;
 }

@@ -100,6 +100,37 @@ def test_plan_eval_and_l_delta_match_oracle():
         assert cf.derive_l_delta(ccm, co, 20000) == P.derive_l_delta(ocm, oo, 20000)
 
 
+def test_cost_feedback_matches_oracle_and_balances_a_contended_plan():
+    rng = np.random.default_rng(43)
+    for _ in range(200):
+        d = dict(f_c=int(rng.integers(0, 10 ** 8)), alpha=int(rng.integers(1, 10 ** 6)), beta=int(rng.integers(0, 10 ** 5)),
+                 f_io=int(rng.integers(0, 10 ** 8)), gamma=int(rng.integers(1, 10 ** 9)),
+                 s_c=int(rng.integers(0, 10 ** 10)), s_io=int(rng.integers(0, 10 ** 9)))
+        ocm, ccm = both_cost(d)
+        args = [int(rng.integers(0, 10 ** 12)) for _ in range(4)]
+        want = P.cost_feedback(ocm, *args)
+        cf.cost_feedback(ccm, *args)
+        assert (ccm.f_c, ccm.alpha, ccm.beta, ccm.f_io, ccm.gamma, ccm.s_c, ccm.s_io) == \
+               (want.f_c, want.alpha, want.beta, want.f_io, want.gamma, want.s_c, want.s_io)
+    # hand case: compute ran 20 % slower than predicted, I/O as predicted
+    ccm = cf.cost_model(0, 1000, 10, 0, 2000, 500, 100)
+    cf.cost_feedback(ccm, 1_000_000, 1_200_000, 5_000, 5_000)
+    assert (ccm.alpha, ccm.beta, ccm.s_c, ccm.gamma, ccm.s_io) == (1200, 12, 600, 2000, 100)
+    # a world where compute is really 1.5x slower than the model says: a few rounds of
+    # feedback move the split until predicted compute and I/O times balance under the truth
+    true = P.CostModel(**hand_cost_model("startup"))
+    true = P.CostModel(true.f_c, true.alpha * 3 // 2, true.beta * 3 // 2, true.f_io, true.gamma, true.s_c, true.s_io)
+    model = cf.cost_model(**hand_cost_model("startup"))
+    opts_o, opts_c = both_opts(512, 0, 32, 4096, 0)
+    n_ctx = make_batch("cfg2").n_ctx
+    for _ in range(4):
+        splits, st, _ = cf.restore_plan(model, opts_c, n_ctx)
+        units = [-(-s[1] // 512) for s in splits]
+        t_c, t_io = P.split_times(true, opts_o, n_ctx, units)          # what "really" happens
+        cf.cost_feedback(model, st["t_comp"], t_c, st["t_io"], t_io)
+    assert abs(t_c - t_io) < 0.1 * max(t_c, t_io)
+
+
 def test_planner_rejects_bad_arguments():
     cm = cf.cost_model(**hand_cost_model("balanced"))
     with pytest.raises(cf.CfError) as e:
