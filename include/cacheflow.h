@@ -259,7 +259,8 @@ typedef struct cf_timing {
  *   timing       : host, may be NULL.
  * Blocking: returns after logits are ready and both streams are idle.
  * Recompute runs on the compute stream, layer-major over the whole batch;
- * loads run on the copy stream (pinned host -> staging -> page scatter).    */
+ * loads run on the copy stream (pinned host -> staging -> page scatter).
+ * max(sum k_i + sum n_new) must not exceed the context's max_tokens.         */
 int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
                      const cf_split* splits, float* logits_out, cf_timing* timing);
 
@@ -309,6 +310,14 @@ int cf_ctx_profile_read(cf_ctx* ctx, cf_kernel_stat* out, int32_t reset);
  * float[B][d_model].  For parity checks of the final norm and LM head at
  * sizes where the CPU cannot run the whole context.                         */
 int cf_read_final_hidden(cf_ctx* ctx, int32_t B, float* out_host);
+
+/* Join mode.  on != 0 (default): pipelined join -- the new-turn rows are packed
+ * with the recompute rows into one layer-major pass, loads are issued layer by
+ * layer from the bottom, and only the attention of the new-turn rows of layer l
+ * waits for layer l's loads, so the first-token prefill overlaps restoration.
+ * on == 0: sequential join -- recompute || load (top layer first), then wait
+ * for both, then the new-turn prefill.  Results are identical.               */
+int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on);
 
 /* Kernel selection for a context: simple_only != 0 routes every step through
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA

@@ -102,6 +102,8 @@ struct cf_ctx {
                ev_end = nullptr, ev_scat = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
     hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
     bool simple_only = false;
+    bool pipelined = true;            // new-turn rows ride along with the recompute pass
+    std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
     std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
@@ -213,6 +215,9 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
         CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_filled[i], hipEventDisableTiming));
         CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
     }
+    c->ev_layer.assign(desc->n_layers, nullptr);
+    for (int l = 0; l < desc->n_layers; ++l)
+        CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming));
     // RoPE table: angles formed in double, rounded once to float.
     {
         int half = desc->head_dim / 2;
@@ -242,11 +247,19 @@ extern "C" void cf_ctx_destroy(cf_ctx* c) {
         if (c->ev_filled[i]) (void)hipEventDestroy(c->ev_filled[i]);
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
     }
+    for (hipEvent_t e : c->ev_layer)
+        if (e) (void)hipEventDestroy(e);
     for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.e0); c->prof_pool.push_back(r.e1); }
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     if (c->meta_host) (void)hipHostFree(c->meta_host);
     if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
     delete c;
+}
+
+extern "C" int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_pipelined_join: null ctx");
+    ctx->pipelined = on != 0;
+    return CF_OK;
 }
 
 extern "C" int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only) {
@@ -263,12 +276,15 @@ struct Segment {        // rows of one request inside a packed phase
     int row0, n_rows;   // packed rows
     int pos0;           // absolute position of the first row
     int layers;         // rows are active in layers [0, layers)
+    bool is_new;        // new-turn rows: they read loaded KV and go through every layer fully
 };
 
 struct ChunkInfo {
     int r0, r1;         // packed row range
     int work_off, n_work;
     int grp_off, n_grp; // combine groups of the items whose key range was split
+    int r_mid;                   // rows [r0, r_mid) are recompute rows, [r_mid, r1) new-turn rows
+    int n_work_rec, n_grp_rec;   // leading items / groups that belong to recompute rows
 };
 
 struct Phase {
@@ -283,6 +299,21 @@ struct Phase {
         int t = 0;
         for (const Segment& s : segs)
             if (s.layers > layer) t = s.row0 + s.n_rows;
+        return t;
+    }
+    // packed order: recompute rows (layer cut non-increasing), then new-turn rows
+    int rec_rows() const {
+        int t = 0;
+        for (const Segment& s : segs)
+            if (!s.is_new) t = s.row0 + s.n_rows;
+        return t;
+    }
+    // recompute rows active in `layer` (a prefix), and those that go on past its K/V write
+    // because they have a further layer to feed (a prefix as well)
+    int rec_active(int layer, int ahead) const {
+        int t = 0;
+        for (const Segment& s : segs)
+            if (!s.is_new && s.layers > layer + ahead) t = s.row0 + s.n_rows;
         return t;
     }
 };
@@ -313,6 +344,8 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
         ci.work_off = (int)ph.work.size();
         ci.grp_off = (int)ph.groups.size();
         std::vector<AttnWork> items;
+        int n_items_rec = 0;
+        ci.r_mid = std::min(std::max(ph.rec_rows(), ci.r0), ci.r1);
         for (const Segment& s : ph.segs) {
             int a = std::max(s.row0, ci.r0), b = std::min(s.row0 + s.n_rows, ci.r1);
             for (int r = a; r < b; r += ATTN_BLOCK_ROWS) {
@@ -326,6 +359,7 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
                 w.part = -1;
                 w.pad = 0;
                 items.push_back(w);
+                if (!s.is_new) n_items_rec = (int)items.size();   // recompute segments come first
             }
         }
         int factor = 1;
@@ -333,8 +367,13 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
             int64_t blocks = (int64_t)items.size() * n_q_heads_split;
             if (blocks < 512) factor = (int)((1024 + blocks - 1) / blocks);
         }
-        int next_part = 0;
+        int next_part = 0, item_idx = 0;
+        ci.n_work_rec = ci.n_grp_rec = 0;
         for (const AttnWork& w : items) {
+            if (item_idx++ == n_items_rec) {       // everything before this came from recompute rows
+                ci.n_work_rec = (int)ph.work.size() - ci.work_off;
+                ci.n_grp_rec = (int)ph.groups.size() - ci.grp_off;
+            }
             int full_tiles = w.pos0 / ATTN_KEY_TILE;          // tiles every row sees completely
             int n_split = std::min(factor, std::max(1, full_tiles / 16));
             if (n_split > 1 && (int64_t)(next_part + n_split) * n_q_heads_split > ATTN_MAX_PART_BLOCKS)
@@ -358,6 +397,7 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
         }
         ci.n_work = (int)ph.work.size() - ci.work_off;
         ci.n_grp = (int)ph.groups.size() - ci.grp_off;
+        if (n_items_rec == (int)items.size()) { ci.n_work_rec = ci.n_work; ci.n_grp_rec = ci.n_grp; }
         ph.chunks.push_back(ci);
     }
 }
@@ -376,12 +416,22 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 //
 // The residual stream h stays float.  O-proj and down-proj store their result into the
 // float buffer dl (plain stores out of the GEMM), and the next RMSNorm folds it in
-// (h += dl) while it reads the row anyway.  When `kv_only_tail` is set (recompute phase)
-// rows in their LAST active layer stop after the K/V write: nothing downstream reads
-// their attention or MLP output.
-void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max, bool kv_only_tail) {
+// (h += dl) while it reads the row anyway.  Recompute rows in their LAST active layer stop
+// after the K/V write: nothing downstream reads their attention or MLP output.  New-turn
+// rows (packed after the recompute rows) go through every layer fully.
+//
+// `layer_ready` (may be null): per layer, the event after which the loaded KV of that layer is
+// in place (null entry = nothing is loaded for it); the attention of the new-turn rows of a
+// layer waits for it, everything else of the layer does not.  `ev_rec_done` is recorded after
+// the last layer in which a recompute row is active.
+int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
+              const hipEvent_t* layer_ready, hipEvent_t ev_rec_done) {
     const cf_model_desc& m = c->m;
-    if (ph.T <= 0) return;
+    int last_rec_layer = -1;
+    for (const Segment& sg : ph.segs)
+        if (!sg.is_new) last_rec_layer = std::max(last_rec_layer, sg.layers - 1);
+    if (last_rec_layer < 0 && ev_rec_done) CF_HIP(hipEventRecord(ev_rec_done, c->cs));
+    if (ph.T <= 0) return CF_OK;
     size_t es = elem_bytes(m.dtype);
     char* md = c->meta_dev();
     const int32_t* d_ids = (const int32_t*)(md + ph.off_ids);
@@ -395,68 +445,102 @@ void run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max, bo
     g.head_dim = m.head_dim;
     g.page_elems = (int64_t)(cache->page_bytes / es);
     g.layer_stride = g.page_elems * cache->n_pages;
-    int qcols = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
-    int nq = m.n_q_heads * m.head_dim;
+    const int qcols = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    const int nq = m.n_q_heads * m.head_dim;
+    const int d = m.d_model;
     bool mfma_attn = !c->simple_only &&
                      attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads);
+    const bool any_new = ph.rec_rows() < ph.T;
 
-    c->prof_begin(CF_K_EMBED, (double)ph.T * m.d_model * (es + 4), c->cs);
-    launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, m.d_model);
+    c->prof_begin(CF_K_EMBED, (double)ph.T * d * (es + 4), c->cs);
+    launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, d);
     c->prof_end(CF_K_EMBED, c->cs);
     for (int l = 0; l < n_layers_max; ++l) {
-        int Ta = ph.rows_active(l);
-        if (Ta <= 0) break;
-        int Tn = kv_only_tail ? (l + 1 < n_layers_max ? ph.rows_active(l + 1) : 0) : Ta;
+        const int Ta_rec = ph.rec_active(l, 0);    // recompute rows that need K/V in this layer
+        const int Tn_rec = ph.rec_active(l, 1);    // ... and go on through the layer
+        if (Ta_rec <= 0 && !any_new) break;
         const cf_layer_weights& lw = c->layers[l];
         char* pool_layer = (char*)cache->pool + (size_t)l * g.layer_stride * es;
         for (const ChunkInfo& ci : ph.chunks) {
-            if (ci.r0 >= Ta) break;
-            int Tc = std::min(ci.r1, Ta) - ci.r0;          // rows that need K/V in this layer
-            int Tr = std::min(ci.r1, Tn) - ci.r0;          // rows that go on through the layer
-            float* h = c->h() + (size_t)ci.r0 * m.d_model;
-            float* dl = c->dl() + (size_t)ci.r0 * m.d_model;
-            c->prof_begin(CF_K_RMSNORM, (double)Tc * m.d_model * (4 + es), c->cs);
-            launch_rmsnorm(c->cs, m.dtype, h, l > 0 ? dl : nullptr, lw.attn_norm, c->a(), Tc, m.d_model,
-                           m.rms_eps, nullptr);
-            c->prof_end(CF_K_RMSNORM, c->cs);
-            gemm(c, CF_K_GEMM_QKV, c->a(), lw.wqkv, nullptr, c->qkv(), nullptr, Tc, qcols, m.d_model, EPI_STORE_F32);
-            c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
-            launch_rope_write(c->cs, m.dtype, c->qkv(), d_pos + ci.r0, d_slot + ci.r0, c->rope(),
-                              c->q(), pool_layer, Tc, m.n_q_heads, g);
-            c->prof_end(CF_K_ROPE_WRITE, c->cs);
-            if (Tr <= 0) continue;
-            // active work items of this chunk: those whose rows lie below Tn
-            int n_work = 0;
-            for (int i = 0; i < ci.n_work; ++i)
-                if (ph.work[ci.work_off + i].row0 + ci.r0 < Tn) n_work = i + 1;
-            if (c->prof_on(CF_K_ATTENTION)) {
-                double pairs = 0;
-                for (int i = 0; i < n_work; ++i) {
-                    const AttnWork& aw = ph.work[ci.work_off + i];
-                    if (aw.part >= 0 && aw.tile_begin > 0) continue;   // count a split item once
-                    pairs += (double)aw.n_rows * aw.pos0 + (double)aw.n_rows * (aw.n_rows + 1) / 2;
-                }
-                c->prof_begin(CF_K_ATTENTION, pairs * 4.0 * m.n_q_heads * m.head_dim, c->cs);
+            // the chunk's rows: recompute rows [r0, r_mid) then new-turn rows [r_mid, r1)
+            int rec_end = std::min(ci.r_mid, Ta_rec), rec_cont = std::min(ci.r_mid, Tn_rec);
+            bool has_rec = rec_end > ci.r0, has_new = ci.r1 > ci.r_mid;
+            if (!has_rec && !has_new) continue;
+            // row ranges of this chunk in this layer: {x, y (rows needing K/V), ycont (rows going on)}
+            int ranges[2][3], n_ranges = 0;
+            if (has_rec && has_new && rec_cont == ci.r_mid) {
+                ranges[n_ranges][0] = ci.r0; ranges[n_ranges][1] = ci.r1; ranges[n_ranges][2] = ci.r1; ++n_ranges;
+            } else {
+                if (has_rec) { ranges[n_ranges][0] = ci.r0; ranges[n_ranges][1] = rec_end; ranges[n_ranges][2] = std::max(rec_cont, ci.r0); ++n_ranges; }
+                if (has_new) { ranges[n_ranges][0] = ci.r_mid; ranges[n_ranges][1] = ci.r1; ranges[n_ranges][2] = ci.r1; ++n_ranges; }
             }
-            int n_grp = 0;
-            for (int i = 0; i < ci.n_grp; ++i)
-                if (ph.groups[ci.grp_off + i].row0 + ci.r0 < Tn) n_grp = i + 1;
-            if (mfma_attn)
-                launch_attention_mfma(c->cs, c->q(), c->o(), c->attn_part(), pool_layer,
-                                      d_work + ci.work_off, n_work, d_grp + ci.grp_off, n_grp, d_pt,
-                                      m.n_q_heads, g);
-            else
-                launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
-                                        d_work + ci.work_off, n_work, d_pt, m.n_q_heads, g);
-            c->prof_end(CF_K_ATTENTION, c->cs);
-            gemm(c, CF_K_GEMM_OPROJ, c->o(), lw.wo, nullptr, dl, nullptr, Tr, m.d_model, nq, EPI_STORE_F32);
-            c->prof_begin(CF_K_RMSNORM, (double)Tr * m.d_model * (12 + es), c->cs);
-            launch_rmsnorm(c->cs, m.dtype, h, dl, lw.mlp_norm, c->a(), Tr, m.d_model, m.rms_eps, nullptr);
-            c->prof_end(CF_K_RMSNORM, c->cs);
-            gemm(c, CF_K_GEMM_GATE_UP, c->a(), lw.w_gate, lw.w_up, nullptr, c->act(), Tr, m.d_ffn, m.d_model, EPI_SILU_MUL);
-            gemm(c, CF_K_GEMM_DOWN, c->act(), lw.w_down, nullptr, dl, nullptr, Tr, m.d_model, m.d_ffn, EPI_STORE_F32);
+            for (int ri = 0; ri < n_ranges; ++ri) {
+                const int x = ranges[ri][0], y = ranges[ri][1], ycont = ranges[ri][2];
+                const int Tc = y - x, Tr = ycont - x, xo = x - ci.r0;   // xo: row offset inside the chunk buffers
+                float* h = c->h() + (size_t)x * d;
+                float* dl = c->dl() + (size_t)x * d;
+                char* a_buf = (char*)c->a() + (size_t)xo * d * es;
+                float* qkv_buf = c->qkv() + (size_t)xo * qcols;
+                char* q_buf = (char*)c->q() + (size_t)xo * nq * es;
+                char* o_buf = (char*)c->o() + (size_t)xo * nq * es;
+                char* act_buf = (char*)c->act() + (size_t)xo * m.d_ffn * es;
+                c->prof_begin(CF_K_RMSNORM, (double)Tc * d * (4 + es), c->cs);
+                launch_rmsnorm(c->cs, m.dtype, h, l > 0 ? dl : nullptr, lw.attn_norm, a_buf, Tc, d, m.rms_eps, nullptr);
+                c->prof_end(CF_K_RMSNORM, c->cs);
+                gemm(c, CF_K_GEMM_QKV, a_buf, lw.wqkv, nullptr, qkv_buf, nullptr, Tc, qcols, d, EPI_STORE_F32);
+                c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
+                launch_rope_write(c->cs, m.dtype, qkv_buf, d_pos + x, d_slot + x, c->rope(), q_buf, pool_layer,
+                                  Tc, m.n_q_heads, g);
+                c->prof_end(CF_K_ROPE_WRITE, c->cs);
+                if (Tr <= 0) continue;
+                // attention work items (row0 is relative to the chunk): recompute items lead, new-turn
+                // items trail.  Recompute rows run first; the new-turn rows also read this layer's
+                // loaded KV and therefore wait for the copy stream to have delivered it.
+                bool with_rec = x < ci.r_mid, with_new = ycont > ci.r_mid;
+                int rec_items = 0, rec_groups = 0;
+                if (with_rec) {
+                    int lim = std::min(ycont, ci.r_mid);
+                    for (int i = 0; i < ci.n_work_rec; ++i)
+                        if (ph.work[ci.work_off + i].row0 + ci.r0 < lim) rec_items = i + 1;
+                    for (int i = 0; i < ci.n_grp_rec; ++i)
+                        if (ph.groups[ci.grp_off + i].row0 + ci.r0 < lim) rec_groups = i + 1;
+                }
+                for (int part = 0; part < 2; ++part) {
+                    int w0, w1, g0, g1;
+                    if (part == 0) { if (!with_rec) continue; w0 = 0; w1 = rec_items; g0 = 0; g1 = rec_groups; }
+                    else { if (!with_new) continue; w0 = ci.n_work_rec; w1 = ci.n_work; g0 = ci.n_grp_rec; g1 = ci.n_grp; }
+                    if (w1 <= w0) continue;
+                    if (part == 1 && layer_ready && layer_ready[l])
+                        CF_HIP(hipStreamWaitEvent(c->cs, layer_ready[l], 0));
+                    if (c->prof_on(CF_K_ATTENTION)) {
+                        double pairs = 0;
+                        for (int i = w0; i < w1; ++i) {
+                            const AttnWork& aw = ph.work[ci.work_off + i];
+                            if (aw.part >= 0 && aw.tile_begin > 0) continue;   // count a split item once
+                            pairs += (double)aw.n_rows * aw.pos0 + (double)aw.n_rows * (aw.n_rows + 1) / 2;
+                        }
+                        c->prof_begin(CF_K_ATTENTION, pairs * 4.0 * m.n_q_heads * m.head_dim, c->cs);
+                    }
+                    if (mfma_attn)
+                        launch_attention_mfma(c->cs, c->q(), c->o(), c->attn_part(), pool_layer,
+                                              d_work + ci.work_off + w0, w1 - w0, d_grp + ci.grp_off + g0,
+                                              g1 - g0, d_pt, m.n_q_heads, g);
+                    else
+                        launch_attention_simple(c->cs, m.dtype, c->q(), c->o(), pool_layer,
+                                                d_work + ci.work_off + w0, w1 - w0, d_pt, m.n_q_heads, g);
+                    c->prof_end(CF_K_ATTENTION, c->cs);
+                }
+                gemm(c, CF_K_GEMM_OPROJ, o_buf, lw.wo, nullptr, dl, nullptr, Tr, d, nq, EPI_STORE_F32);
+                c->prof_begin(CF_K_RMSNORM, (double)Tr * d * (12 + es), c->cs);
+                launch_rmsnorm(c->cs, m.dtype, h, dl, lw.mlp_norm, a_buf, Tr, d, m.rms_eps, nullptr);
+                c->prof_end(CF_K_RMSNORM, c->cs);
+                gemm(c, CF_K_GEMM_GATE_UP, a_buf, lw.w_gate, lw.w_up, nullptr, act_buf, Tr, m.d_ffn, d, EPI_SILU_MUL);
+                gemm(c, CF_K_GEMM_DOWN, act_buf, lw.w_down, nullptr, dl, nullptr, Tr, d, m.d_ffn, EPI_STORE_F32);
+            }
         }
+        if (l == last_rec_layer && ev_rec_done) CF_HIP(hipEventRecord(ev_rec_done, c->cs));
     }
+    return CF_OK;
 }
 
 double linear_flops_per_token_layer(const cf_model_desc& m) {
@@ -560,7 +644,34 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                           ? m.n_q_heads : 0;
     // recompute phase: requests in order of descending layer cut so that the rows
     // active in layer l are a prefix of the packed array
+    // Packed rows.  Pipelined join (default): ONE phase holds the recompute rows followed by the
+    // new-turn rows, so the new-turn prefill of layer l runs right behind the recompute of layer
+    // l (same GEMM launches when the rows are adjacent) and only its attention waits for the
+    // loaded KV of that layer.  Sequential join: a recompute phase, then a new-token phase.
     Phase rec, suf;
+    std::vector<int32_t> last_rows;
+    const bool merged = c->pipelined && logits_out != nullptr;
+    auto add_segment = [&](Phase& ph, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
+                           std::vector<int32_t>& slot, int i, const int32_t* toks, int n_rows, int pos0,
+                           int layers, bool is_new) {
+        Segment sg{i, ph.T, n_rows, pos0, layers, is_new};
+        for (int t = 0; t < n_rows; ++t) {
+            ids.push_back(toks[t]);
+            pos.push_back(pos0 + t);
+            slot.push_back(slot_of(i, pos0 + t));
+        }
+        ph.T += n_rows;
+        ph.segs.push_back(sg);
+    };
+    auto finish_phase = [&](Phase& ph, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
+                            std::vector<int32_t>& slot) {
+        build_chunks(ph, c->cv.chunk_rows, pt_off, split_heads);
+        ph.off_ids = mw.put(ids.data(), ids.size() * 4);
+        ph.off_pos = mw.put(pos.data(), pos.size() * 4);
+        ph.off_slot = mw.put(slot.data(), slot.size() * 4);
+        ph.off_work = mw.put(ph.work.data(), ph.work.size() * sizeof(AttnWork));
+        ph.off_grp = mw.put(ph.groups.data(), ph.groups.size() * sizeof(AttnCombine));
+    };
     {
         std::vector<int> order;
         for (int i = 0; i < B; ++i)
@@ -568,53 +679,36 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         std::stable_sort(order.begin(), order.end(),
                          [&](int a, int b) { return splits[a].layer_cut > splits[b].layer_cut; });
         std::vector<int32_t> ids, pos, slot;
-        for (int i : order) {
-            Segment s{i, rec.T, splits[i].k_tokens, 0, splits[i].layer_cut};
-            for (int t = 0; t < s.n_rows; ++t) {
-                ids.push_back(reqs[i].ctx_tokens[t]);
-                pos.push_back(t);
-                slot.push_back(slot_of(i, t));
+        if (merged && sum_rec + sum_new > c->opts.max_tokens)
+            return fail(CF_ERR_WORKSPACE, "cf_restore_batch: %lld recompute + %lld new rows > max_tokens %d",
+                        (long long)sum_rec, (long long)sum_new, c->opts.max_tokens);
+        for (int i : order)
+            add_segment(rec, ids, pos, slot, i, reqs[i].ctx_tokens, splits[i].k_tokens, 0,
+                        splits[i].layer_cut, false);
+        if (merged)
+            for (int i = 0; i < B; ++i) {
+                add_segment(rec, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, reqs[i].n_ctx, L, true);
+                last_rows.push_back(rec.T - 1);
             }
-            rec.T += s.n_rows;
-            rec.segs.push_back(s);
-        }
-        build_chunks(rec, c->cv.chunk_rows, pt_off, split_heads);
-        rec.off_ids = mw.put(ids.data(), ids.size() * 4);
-        rec.off_pos = mw.put(pos.data(), pos.size() * 4);
-        rec.off_slot = mw.put(slot.data(), slot.size() * 4);
-        rec.off_work = mw.put(rec.work.data(), rec.work.size() * sizeof(AttnWork));
-        rec.off_grp = mw.put(rec.groups.data(), rec.groups.size() * sizeof(AttnCombine));
+        finish_phase(rec, ids, pos, slot);
     }
-    std::vector<int32_t> last_rows;
-    if (logits_out) {
+    if (logits_out && !merged) {
         std::vector<int32_t> ids, pos, slot;
         for (int i = 0; i < B; ++i) {
-            Segment s{i, suf.T, reqs[i].n_new, reqs[i].n_ctx, L};
-            for (int t = 0; t < s.n_rows; ++t) {
-                ids.push_back(reqs[i].new_tokens[t]);
-                pos.push_back(s.pos0 + t);
-                slot.push_back(slot_of(i, s.pos0 + t));
-            }
-            suf.T += s.n_rows;
-            suf.segs.push_back(s);
+            add_segment(suf, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, reqs[i].n_ctx, L, true);
             last_rows.push_back(suf.T - 1);
         }
-        build_chunks(suf, c->cv.chunk_rows, pt_off, split_heads);
-        suf.off_ids = mw.put(ids.data(), ids.size() * 4);
-        suf.off_pos = mw.put(pos.data(), pos.size() * 4);
-        suf.off_slot = mw.put(slot.data(), slot.size() * 4);
-        suf.off_work = mw.put(suf.work.data(), suf.work.size() * sizeof(AttnWork));
-        suf.off_grp = mw.put(suf.groups.data(), suf.groups.size() * sizeof(AttnCombine));
+        finish_phase(suf, ids, pos, slot);
     }
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
     c->last_rows = last_rows;
 
-    // copy plan: runs of pages per (request, layer), top layer first and the
-    // longest request first (the I/O pointer walks down from the far end, Sec. 3.1)
+    // copy plan: runs of pages per (request, layer), packed into staging slots
     std::vector<CopyOp> ops;
     std::vector<PageJob> jobs;
     std::vector<SlotPlan> slots;
     int64_t loaded_bytes = 0, loaded_cells = 0, rec_cells = 0;
+    std::vector<int> layer_last_slot(L, -1);   // slot (in issue order) holding a layer's last job
     {
         size_t pb = cache->page_bytes;
         size_t slot_cap = c->cv.staging_bytes / N_STAGING_SLOTS;
@@ -631,44 +725,54 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         for (int i = 0; i < B; ++i) by_len[i] = i;
         std::stable_sort(by_len.begin(), by_len.end(),
                          [&](int a, int b) { return reqs[a].n_ctx > reqs[b].n_ctx; });
-        for (int i : by_len) {
+        // order of (request, layer) runs.  Sequential join: per request, longest first, top layer
+        // first (the I/O pointer walks down from the far end, Sec. 3.1).  Pipelined join: layer by
+        // layer from the bottom, so layer l's loads land while the forward pass is still below l.
+        std::vector<std::pair<int, int>> runs;
+        if (merged) {
+            for (int l = 0; l < L; ++l)
+                for (int i : by_len) runs.emplace_back(i, l);
+        } else {
+            for (int i : by_len)
+                for (int l = L - 1; l >= 0; --l) runs.emplace_back(i, l);
+        }
+        for (auto [i, l] : runs) {
             const cf_request& r = reqs[i];
             const cf_split& s = splits[i];
             int np_ctx = (int)ceil_div(r.n_ctx, CF_PAGE_TOKENS);
-            for (int l = L - 1; l >= 0; --l) {
-                int lo = (l < s.layer_cut) ? s.k_tokens : 0, hi = r.n_ctx;
-                if (l < s.layer_cut) rec_cells += s.k_tokens;
-                if (lo >= hi) continue;
-                loaded_cells += hi - lo;
-                int j = lo / CF_PAGE_TOKENS, j1 = np_ctx;
-                while (j < j1) {
-                    size_t room = (slot_cap - fill) / pb;
-                    if (room == 0) { flush(); continue; }
-                    int take = (int)std::min<size_t>(room, (size_t)(j1 - j));
-                    size_t dst = (size_t)cur.slot * slot_cap + fill;
-                    const char* src = (const char*)r.host_kv + ((size_t)l * np_ctx + j) * pb;
-                    size_t bytes = (size_t)take * pb;
-                    if (cur.n_ops > 0 && ops.back().src + ops.back().bytes == src &&
-                        ops.back().dst_off + ops.back().bytes == dst)
-                        ops.back().bytes += bytes;
-                    else { ops.push_back(CopyOp{dst, src, bytes}); ++cur.n_ops; }
-                    PageJob jb;
-                    jb.staging_off = (int64_t)dst;
-                    jb.layer = l;
-                    jb.pt_off = pt_off[i];
-                    jb.page_first = j;
-                    jb.n_pages = take;
-                    jb.tok_first = lo;
-                    jb.tok_end = hi;
-                    jb.block_first = cur.n_blocks;
-                    jb.pad = 0;
-                    jobs.push_back(jb);
-                    ++cur.n_jobs;
-                    cur.n_blocks += take * PAGE_MOVE_SPLIT;
-                    fill += bytes;
-                    loaded_bytes += bytes;
-                    j += take;
-                }
+            int lo = (l < s.layer_cut) ? s.k_tokens : 0, hi = r.n_ctx;
+            if (l < s.layer_cut) rec_cells += s.k_tokens;
+            if (lo >= hi) continue;
+            loaded_cells += hi - lo;
+            int j = lo / CF_PAGE_TOKENS, j1 = np_ctx;
+            while (j < j1) {
+                size_t room = (slot_cap - fill) / pb;
+                if (room == 0) { flush(); continue; }
+                int take = (int)std::min<size_t>(room, (size_t)(j1 - j));
+                size_t dst = (size_t)cur.slot * slot_cap + fill;
+                const char* src = (const char*)r.host_kv + ((size_t)l * np_ctx + j) * pb;
+                size_t bytes = (size_t)take * pb;
+                if (cur.n_ops > 0 && ops.back().src + ops.back().bytes == src &&
+                    ops.back().dst_off + ops.back().bytes == dst)
+                    ops.back().bytes += bytes;
+                else { ops.push_back(CopyOp{dst, src, bytes}); ++cur.n_ops; }
+                PageJob jb;
+                jb.staging_off = (int64_t)dst;
+                jb.layer = l;
+                jb.pt_off = pt_off[i];
+                jb.page_first = j;
+                jb.n_pages = take;
+                jb.tok_first = lo;
+                jb.tok_end = hi;
+                jb.block_first = cur.n_blocks;
+                jb.pad = 0;
+                jobs.push_back(jb);
+                ++cur.n_jobs;
+                cur.n_blocks += take * PAGE_MOVE_SPLIT;
+                fill += bytes;
+                loaded_bytes += bytes;
+                j += take;
+                layer_last_slot[l] = (int)slots.size();     // index the current slot will get
             }
         }
         flush();
@@ -693,6 +797,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
 
     // copy stream: fill a staging slot by DMA, then the scatter stream places its pages
     bool slot_used[N_STAGING_SLOTS] = {};
+    int slot_idx = 0;
     for (const SlotPlan& sp : slots) {
         if (slot_used[sp.slot]) CF_HIP(hipStreamWaitEvent(c->ps, c->ev_free[sp.slot], 0));
         double slot_bytes = 0;
@@ -712,27 +817,43 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         c->prof_end(CF_K_PAGE_SCATTER, c->ss);
         CF_HIP(hipEventRecord(c->ev_free[sp.slot], c->ss));
         slot_used[sp.slot] = true;
+        if (merged)
+            for (int l = 0; l < L; ++l)
+                if (layer_last_slot[l] == slot_idx) CF_HIP(hipEventRecord(c->ev_layer[l], c->ss));
+        ++slot_idx;
     }
     CF_HIP(hipEventRecord(c->ev_scat, c->ss));
     CF_HIP(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
     CF_HIP(hipEventRecord(c->ev_copy, c->ps));
 
-    // compute stream: recompute, layer-major over the batch
+    // compute stream: layer-major over the batch
     int max_cut = 0;
-    for (const Segment& s : rec.segs) max_cut = std::max(max_cut, s.layers);
-    run_phase(c, cache, rec, max_cut, true);
-    CF_HIP(hipEventRecord(c->ev_comp, c->cs));
-
-    // join, then the new-turn prefill and first-token logits
-    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
-    CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+    for (const Segment& sg : rec.segs) max_cut = std::max(max_cut, sg.layers);
+    if (merged) {
+        std::vector<hipEvent_t> ready(L, nullptr);
+        for (int l = 0; l < L; ++l)
+            if (layer_last_slot[l] >= 0) ready[l] = c->ev_layer[l];
+        int rc2 = run_phase(c, cache, rec, L, ready.data(), c->ev_comp);
+        if (rc2) return rc2;
+        CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+    } else {
+        int rc2 = run_phase(c, cache, rec, max_cut, nullptr, c->ev_comp);
+        if (rc2) return rc2;
+        // join, then the new-turn prefill
+        CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
+        CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+        if (logits_out) {
+            rc2 = run_phase(c, cache, suf, L, nullptr, nullptr);
+            if (rc2) return rc2;
+        }
+    }
     if (logits_out) {
-        run_phase(c, cache, suf, L, false);
-        // the last layer's down-proj result is still pending in dl
+        // first-token logits; the last layer's down-proj result is still pending in dl
         launch_rmsnorm(c->cs, m.dtype, c->h(), c->dl(), c->w.final_norm, c->a_last(), B, m.d_model,
                        m.rms_eps, (const int32_t*)(md + off_last));
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
     }
+    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
     CF_HIP(hipEventRecord(c->ev_end, c->cs));
     CF_HIP(hipGetLastError());
     CF_HIP(hipStreamSynchronize(c->cs));
@@ -748,20 +869,27 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         CF_HIP(hipEventElapsedTime(&t_end, c->ev_start, c->ev_end));
         timing->compute_ms = t_comp;
         timing->copy_ms = t_copy;
-        timing->restore_ms = std::max(t_join, std::max(t_comp, t_copy));
-        timing->suffix_ms = t_end - t_join;
+        // restoration is complete when the last recomputed cell and the last loaded cell are in
+        // place; with the pipelined join most of the new-turn prefill has already run by then
+        timing->restore_ms = merged ? std::max(t_comp, t_copy) : std::max(t_join, std::max(t_comp, t_copy));
+        timing->suffix_ms = t_end - timing->restore_ms;
         timing->total_ms = t_end;
         double lin = linear_flops_per_token_layer(m);
         double pair = 4.0 * m.n_q_heads * m.head_dim;
         double fr = 0, fs = 0;
         // the last recomputed layer of a request needs only its K/V projection
         double qkv_fl = 2.0 * m.d_model * (double)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
-        for (const Segment& s : rec.segs)
+        for (const Segment& s : rec.segs) {
+            if (s.is_new) continue;
             fr += (double)(s.layers - 1) * (s.n_rows * lin + pair * ((double)s.n_rows * (s.n_rows + 1) / 2)) +
                   s.n_rows * qkv_fl;
-        for (const Segment& s : suf.segs)
-            fs += (double)L * (s.n_rows * lin + pair * ((double)s.n_rows * s.pos0 +
-                                                        (double)s.n_rows * (s.n_rows + 1) / 2));
+        }
+        for (const Phase* ph : {&rec, &suf})
+            for (const Segment& s : ph->segs) {
+                if (!s.is_new) continue;
+                fs += (double)L * (s.n_rows * lin + pair * ((double)s.n_rows * s.pos0 +
+                                                            (double)s.n_rows * (s.n_rows + 1) / 2));
+            }
         if (logits_out) fs += 2.0 * m.d_model * (double)m.vocab * B;
         timing->recompute_flops = fr;
         timing->suffix_flops = fs;

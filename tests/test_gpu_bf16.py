@@ -32,8 +32,9 @@ def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows, n_pages=N
     return b, refs, sess, host
 
 
-def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False):
+def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pipelined=True):
     sess.ctx.set_kernel_set(simple_only)
+    sess.ctx.set_pipelined_join(pipelined)
     sess.pool.fill_(0xFF)
     opt = PageTable(sess.n_pages)
     for op in churn_script(seed, sess.n_pages, n_ops=60, max_tokens=300):
@@ -74,6 +75,7 @@ def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False):
         for rid in list(opt.tables):
             sess.cache.free(rid)
         sess.ctx.set_kernel_set(False)
+        sess.ctx.set_pipelined_join(True)
 
 
 @pytest.fixture(scope="module")
@@ -95,8 +97,13 @@ def test_mini_bf16_hybrid_splits_match_oracle(mini):
         [(int(rng.integers(0, n + 1)), int(rng.integers(0, L + 1))) for n in b.n_ctx],  # anything
     ]
     for p, splits in enumerate(plans):
-        _, wkv, wlg, tm = restore_and_compare(b, refs, sess, host, splits, seed=20 + p)
+        out_p, wkv, wlg, tm = restore_and_compare(b, refs, sess, host, splits, seed=20 + p)
         print(f"plan {p}: worst KV err {wkv:.4g}, worst logit err {wlg:.4g}")
+        # the sequential join (recompute || load, wait, then the new-turn prefill) gives the same bits
+        out_s, *_ = restore_and_compare(b, refs, sess, host, splits, seed=20 + p, pipelined=False)
+        for i in out_p:
+            assert np.array_equal(out_p[i][0], out_s[i][0]) and np.array_equal(out_p[i][1], out_s[i][1])
+            assert np.abs(out_p[i][2] - out_s[i][2]).max() <= 2e-2
 
 
 def test_mini_bf16_mfma_kernels_agree_with_plain_kernels(mini):

@@ -89,6 +89,16 @@ def test_cfg1_forced_splits(env):
     assert tm["loaded_bytes"] >= tm["loaded_cells"] * b.shape.kv_bytes_per_token_layer
 
 
+def test_cfg1_sequential_join_mode(env):
+    b, refs, ws, sess, host = env
+    sess.ctx.set_pipelined_join(False)
+    try:
+        run_and_check(env, b.forced_splits, seed=9)
+        run_and_check(env, [(0, 2), (64, 1)], seed=10)
+    finally:
+        sess.ctx.set_pipelined_join(True)
+
+
 def test_cfg1_all_recompute_and_all_load(env):
     b = env[0]
     run_and_check(env, [(n, 2) for n in b.n_ctx], seed=4)
