@@ -71,6 +71,10 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink context lengths (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--load-path", choices=["auto", "staged", "direct"], default="auto",
+                    help="direct: load kernel reading pinned host memory; staged: DMA + scatter")
+    ap.add_argument("--load-workgroups", type=int, default=0,
+                    help="resident workgroups of the direct load kernel (0: library default)")
     ap.add_argument("--sequential-join", action="store_true",
                     help="restore, wait for both streams, then prefill the new tokens (default: pipelined join)")
     args = ap.parse_args()
@@ -101,6 +105,7 @@ def main():
                    n_pages=pages, chunk_rows=args.chunk_rows, gen_threads=16)
     log(f"[bench] weights + pool + workspace ready in {time.perf_counter() - t0:.1f} s")
     sess.ctx.set_pipelined_join(not args.sequential_join)
+    sess.ctx.set_load_path({"auto": 0, "staged": 1, "direct": 2}[args.load_path], args.load_workgroups)
 
     # ---- manufacture the host KV (not timed): full prefill on the GPU, then offload
     t0 = time.perf_counter()

@@ -319,6 +319,18 @@ int cf_read_final_hidden(cf_ctx* ctx, int32_t B, float* out_host);
  * for both, then the new-turn prefill.  Results are identical.               */
 int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on);
 
+/* Load path (the I/O side of Sec. 3.1's two pointers).  path 0 (default):
+ * automatic -- the direct path whenever every request's host block is pinned,
+ * device-mapped host memory, else the staged path.  path 2: direct -- a load
+ * kernel of n_workgroups resident workgroups (0 keeps the current value,
+ * default 8, at most 1024) reads the host block over the host link and writes
+ * the KV pages itself, one launch per layer; cf_restore_batch then fails with
+ * CF_ERR_INVALID_ARG for a host block that is not device-mapped.  path 1:
+ * staged -- DMA transfers into the workspace's staging slots followed by a
+ * scatter kernel (works for any host memory; pageable memory is slow).
+ * Results are identical.                                                    */
+int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgroups);
+
 /* Kernel selection for a context: simple_only != 0 routes every step through
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
  * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */

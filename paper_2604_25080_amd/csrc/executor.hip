@@ -103,6 +103,8 @@ struct cf_ctx {
     hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
     bool simple_only = false;
     bool pipelined = true;            // new-turn rows ride along with the recompute pass
+    int load_path = 0;                // 0 auto, 1 staged DMA + scatter, 2 direct load kernel
+    int load_wgs = 8;                 // resident workgroups of the direct load kernel
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
     std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
@@ -259,6 +261,16 @@ extern "C" void cf_ctx_destroy(cf_ctx* c) {
 extern "C" int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on) {
     if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_pipelined_join: null ctx");
     ctx->pipelined = on != 0;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgroups) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_load_path: null ctx");
+    if (path < 0 || path > 2) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_load_path: path %d not in 0..2", path);
+    if (n_workgroups < 0 || n_workgroups > 1024)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_load_path: n_workgroups %d not in 0..1024", n_workgroups);
+    ctx->load_path = path;
+    if (n_workgroups > 0) ctx->load_wgs = n_workgroups;
     return CF_OK;
 }
 
@@ -555,6 +567,10 @@ struct CopyOp {
     size_t bytes;
 };
 
+struct LayerLoad {            // direct path: one load-kernel launch
+    int layer, job_first, n_jobs, n_vblocks;
+    size_t bytes;
+};
 struct SlotPlan {
     int slot;
     int op_first, n_ops;
@@ -703,10 +719,34 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
     c->last_rows = last_rows;
 
-    // copy plan: runs of pages per (request, layer), packed into staging slots
+    // Load path.  Direct: a load kernel reads the pinned host block over the link and writes the
+    // pages itself (needs device-mapped host memory).  Staged: DMA into staging slots, then a
+    // scatter kernel.  Auto takes the direct path when every host block is device-mapped.
+    std::vector<const char*> host_dev(B, nullptr);
+    bool direct = c->load_path != 1;
+    for (int i = 0; i < B && direct; ++i) {
+        if (!reqs[i].host_kv) continue;
+        hipPointerAttribute_t at;
+        hipError_t e = hipPointerGetAttributes(&at, reqs[i].host_kv);
+        if (e != hipSuccess) { (void)hipGetLastError(); direct = false; break; }
+        void* dp = nullptr;
+        if (at.type != hipMemoryTypeHost ||
+            hipHostGetDevicePointer(&dp, const_cast<void*>(reqs[i].host_kv), 0) != hipSuccess || !dp) {
+            (void)hipGetLastError();
+            direct = false;
+            break;
+        }
+        host_dev[i] = (const char*)dp;
+    }
+    if (!direct && c->load_path == 2)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: the direct load path needs pinned, device-mapped host KV");
+
+    // copy plan: runs of pages per (request, layer); staged path: packed into staging slots;
+    // direct path: one launch per layer
     std::vector<CopyOp> ops;
     std::vector<PageJob> jobs;
     std::vector<SlotPlan> slots;
+    std::vector<LayerLoad> layer_loads;
     int64_t loaded_bytes = 0, loaded_cells = 0, rec_cells = 0;
     std::vector<int> layer_last_slot(L, -1);   // slot (in issue order) holding a layer's last job
     {
@@ -725,12 +765,16 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         for (int i = 0; i < B; ++i) by_len[i] = i;
         std::stable_sort(by_len.begin(), by_len.end(),
                          [&](int a, int b) { return reqs[a].n_ctx > reqs[b].n_ctx; });
-        // order of (request, layer) runs.  Sequential join: per request, longest first, top layer
-        // first (the I/O pointer walks down from the far end, Sec. 3.1).  Pipelined join: layer by
-        // layer from the bottom, so layer l's loads land while the forward pass is still below l.
+        // order of (request, layer) runs.  Pipelined join: layer by layer from the bottom, so
+        // layer l's loads land while the forward pass is still below l.  Sequential join: from
+        // the far end (Sec. 3.1, the I/O pointer walks down from the top layer) -- layer-major
+        // for the direct path, per request (longest first) for the staged one.
         std::vector<std::pair<int, int>> runs;
         if (merged) {
             for (int l = 0; l < L; ++l)
+                for (int i : by_len) runs.emplace_back(i, l);
+        } else if (direct) {
+            for (int l = L - 1; l >= 0; --l)
                 for (int i : by_len) runs.emplace_back(i, l);
         } else {
             for (int i : by_len)
@@ -745,6 +789,30 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
             if (lo >= hi) continue;
             loaded_cells += hi - lo;
             int j = lo / CF_PAGE_TOKENS, j1 = np_ctx;
+            if (direct) {
+                // the load kernel indexes a run's 16-byte vectors in 32 bits
+                if ((int64_t)(j1 - j) * (int64_t)(pb / 16) >= ((int64_t)1 << 31))
+                    return fail(CF_ERR_WORKSPACE, "cf_restore_batch: request %d loads more than 32 GiB per layer", i);
+                if (layer_loads.empty() || layer_loads.back().layer != l)
+                    layer_loads.push_back(LayerLoad{l, (int)jobs.size(), 0, 0, 0});
+                LayerLoad& ll = layer_loads.back();
+                PageJob jb;
+                jb.staging_off = (int64_t)(uintptr_t)(host_dev[i] + ((size_t)l * np_ctx + j) * pb);
+                jb.layer = l;
+                jb.pt_off = pt_off[i];
+                jb.page_first = j;
+                jb.n_pages = j1 - j;
+                jb.tok_first = lo;
+                jb.tok_end = hi;
+                jb.block_first = ll.n_vblocks;
+                jb.pad = 0;
+                jobs.push_back(jb);
+                ++ll.n_jobs;
+                ll.n_vblocks += (int)ceil_div((int64_t)(j1 - j) * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
+                ll.bytes += (size_t)(j1 - j) * pb;
+                loaded_bytes += (int64_t)(j1 - j) * pb;
+                continue;
+            }
             while (j < j1) {
                 size_t room = (slot_cap - fill) / pb;
                 if (room == 0) { flush(); continue; }
@@ -795,7 +863,17 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     g.page_elems = (int64_t)(cache->page_bytes / es);
     g.layer_stride = g.page_elems * cache->n_pages;
 
-    // copy stream: fill a staging slot by DMA, then the scatter stream places its pages
+    // copy stream, direct path: one load-kernel launch per layer, host memory -> pages
+    std::vector<char> layer_loaded(L, 0);
+    for (const LayerLoad& ll : layer_loads) {
+        c->prof_begin(CF_K_H2D_COPY, (double)ll.bytes, c->ps);
+        launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ll.job_first,
+                         ll.n_jobs, ll.n_vblocks, c->load_wgs, (const int32_t*)md, g);
+        c->prof_end(CF_K_H2D_COPY, c->ps);
+        layer_loaded[ll.layer] = 1;
+        if (merged) CF_HIP(hipEventRecord(c->ev_layer[ll.layer], c->ps));
+    }
+    // copy stream, staged path: fill a staging slot by DMA, then the scatter stream places its pages
     bool slot_used[N_STAGING_SLOTS] = {};
     int slot_idx = 0;
     for (const SlotPlan& sp : slots) {
@@ -819,7 +897,10 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         slot_used[sp.slot] = true;
         if (merged)
             for (int l = 0; l < L; ++l)
-                if (layer_last_slot[l] == slot_idx) CF_HIP(hipEventRecord(c->ev_layer[l], c->ss));
+                if (layer_last_slot[l] == slot_idx) {
+                    CF_HIP(hipEventRecord(c->ev_layer[l], c->ss));
+                    layer_loaded[l] = 1;
+                }
         ++slot_idx;
     }
     CF_HIP(hipEventRecord(c->ev_scat, c->ss));
@@ -832,7 +913,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     if (merged) {
         std::vector<hipEvent_t> ready(L, nullptr);
         for (int l = 0; l < L; ++l)
-            if (layer_last_slot[l] >= 0) ready[l] = c->ev_layer[l];
+            if (layer_loaded[l]) ready[l] = c->ev_layer[l];
         int rc2 = run_phase(c, cache, rec, L, ready.data(), c->ev_comp);
         if (rc2) return rc2;
         CF_HIP(hipEventRecord(c->ev_t0, c->cs));

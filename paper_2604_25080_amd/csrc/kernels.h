@@ -83,6 +83,13 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
                            const void* pool_layer, const AttnWork* work, int n_work,
                            const AttnCombine* groups, int n_groups, const int32_t* page_tables,
                            int n_q_heads, KvGeom g);
+// pinned host memory -> pages, directly: job.staging_off is the host ADDRESS of the run's first
+// page; block_first counts units of PAGE_LOAD_UNIT_VECS 16-byte vectors of the run (a run of p
+// pages has ceil(p * page_bytes / 16 / PAGE_LOAD_UNIT_VECS) units); n_workgroups resident
+// workgroups walk the units
+constexpr int PAGE_LOAD_UNIT_VECS = 4096;
+void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
+                      int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
 // staging -> pages (to_pages = true) or pages -> staging (false; zero-fills unused slots)
 void launch_page_move(hipStream_t s, int dtype, void* staging, void* pool, const PageJob* jobs,
                       int n_jobs, int n_blocks, const int32_t* page_tables, KvGeom g, bool to_pages);

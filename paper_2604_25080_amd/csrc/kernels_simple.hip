@@ -363,6 +363,90 @@ page_move_kernel(T* __restrict__ staging, T* __restrict__ pool, const PageJob* _
     }
 }
 
+// Host -> pages in one step: a few resident workgroups stream the loaded KV straight out of
+// pinned (device-mapped) host memory over the host link and store it into the page slots --
+// no staging copy, no per-transfer DMA set-up, full link bandwidth at any run length.  A job is
+// a run of consecutive pages of one (request, layer), contiguous in host memory; it is cut into
+// units of PAGE_LOAD_UNIT_VECS 16-byte vectors, and each workgroup walks the units
+// u = blockIdx.x, blockIdx.x + gridDim.x, ... with all of a unit's loads (16 per thread, 64 KiB
+// per workgroup) in flight before the first store: the link's bandwidth-delay product is about
+// 256 KiB, so a handful of workgroups saturates it.  job.staging_off holds the ADDRESS of the
+// run's first page in host memory, job.block_first the job's first unit.
+template <typename T>
+__global__ void __launch_bounds__(256)
+page_load_kernel(T* __restrict__ pool, const PageJob* __restrict__ jobs, int n_jobs, int n_units,
+                 const int32_t* __restrict__ page_tables, KvGeom g) {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    constexpr int VE = 16 / sizeof(T);
+    constexpr int U = PAGE_LOAD_UNIT_VECS / 256;
+    const int nvec = (int)(g.page_elems / VE);
+    const int64_t k_elems = (int64_t)g.n_kv_heads * CF_PAGE_TOKENS * g.head_dim;
+    for (int b = blockIdx.x; b < n_units; b += gridDim.x) {
+        int ji = 0, jhi = n_jobs - 1;
+        while (ji < jhi) {
+            int mid = (ji + jhi + 1) >> 1;
+            if (jobs[mid].block_first <= b) ji = mid; else jhi = mid - 1;
+        }
+        PageJob job = jobs[ji];
+        // 32-bit index arithmetic inside the unit (host code keeps n_pages * nvec below 2^31)
+        const unsigned job_vecs = (unsigned)job.n_pages * (unsigned)nvec;
+        const unsigned base = (unsigned)(b - job.block_first) * PAGE_LOAD_UNIT_VECS;
+        const unsigned pg0 = base / (unsigned)nvec, rem0 = base - pg0 * (unsigned)nvec;
+        typedef const v4u __attribute__((address_space(1))) * gsrc_t;   // global, not flat, loads
+        gsrc_t src = (gsrc_t)((uintptr_t)job.staging_off) + base;
+        T* layer_base = pool + (int64_t)job.layer * g.layer_stride;
+        const int32_t* table = page_tables + job.pt_off + job.page_first;
+        v4u val[U];
+        int pid[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // unconditional (clamped) so that all U loads are in flight together: a load under
+            // a branch is waited for before the branch rejoins
+            unsigned o = min((unsigned)(u * 256 + threadIdx.x), job_vecs - 1 - base);
+            val[u] = __builtin_nontemporal_load(src + o);
+            pid[u] = table[pg0 + (rem0 + o) / (unsigned)nvec];
+        }
+        // everything has landed before the first store, so that the stores below are not
+        // separated by waits of their own
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            unsigned o = u * 256 + threadIdx.x;
+            if (base + o >= job_vecs) continue;
+            int pg = (int)(pg0 + (rem0 + o) / (unsigned)nvec);
+            int v = (int)(rem0 + o - (unsigned)(pg - (int)pg0) * (unsigned)nvec);
+            int jpage = job.page_first + pg;
+            int lo = max(job.tok_first - jpage * CF_PAGE_TOKENS, 0);
+            int hi = min(job.tok_end - jpage * CF_PAGE_TOKENS, CF_PAGE_TOKENS);
+            T* dst = layer_base + (int64_t)pid[u] * g.page_elems;
+            if (lo == 0 && hi == CF_PAGE_TOKENS) {
+                reinterpret_cast<v4u*>(dst)[v] = val[u];
+                continue;
+            }
+            int64_t e = (int64_t)v * VE;
+            if (e < k_elems) {  // K part: the vector lies inside one slot row
+                int s16 = (int)((e / g.head_dim) % CF_PAGE_TOKENS);
+                if (s16 >= lo && s16 < hi) reinterpret_cast<v4u*>(dst)[v] = val[u];
+            } else {            // V part: the vector spans VE consecutive slots of one column
+                int s0 = (int)((e - k_elems) % CF_PAGE_TOKENS);
+                const T* sv = reinterpret_cast<const T*>(&val[u]);
+                for (int i = 0; i < VE; ++i)
+                    if (s0 + i >= lo && s0 + i < hi) dst[e + i] = sv[i];
+            }
+        }
+    }
+}
+
+void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
+                      int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g) {
+    if (n_jobs <= 0 || n_units <= 0) return;
+    int grid = n_workgroups < n_units ? n_workgroups : n_units;
+    if (dtype == CF_F32)
+        page_load_kernel<float><<<grid, 256, 0, s>>>((float*)pool, jobs, n_jobs, n_units, page_tables, g);
+    else
+        page_load_kernel<bf16><<<grid, 256, 0, s>>>((bf16*)pool, jobs, n_jobs, n_units, page_tables, g);
+}
+
 void launch_page_move(hipStream_t s, int dtype, void* staging, void* pool, const PageJob* jobs,
                       int n_jobs, int n_blocks, const int32_t* page_tables, KvGeom g,
                       bool to_pages) {

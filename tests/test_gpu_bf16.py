@@ -32,9 +32,10 @@ def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows, n_pages=N
     return b, refs, sess, host
 
 
-def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pipelined=True):
+def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pipelined=True, load_path=0):
     sess.ctx.set_kernel_set(simple_only)
     sess.ctx.set_pipelined_join(pipelined)
+    sess.ctx.set_load_path(load_path)
     sess.pool.fill_(0xFF)
     opt = PageTable(sess.n_pages)
     for op in churn_script(seed, sess.n_pages, n_ops=60, max_tokens=300):
@@ -76,6 +77,7 @@ def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pi
             sess.cache.free(rid)
         sess.ctx.set_kernel_set(False)
         sess.ctx.set_pipelined_join(True)
+        sess.ctx.set_load_path(0)
 
 
 @pytest.fixture(scope="module")
@@ -101,9 +103,14 @@ def test_mini_bf16_hybrid_splits_match_oracle(mini):
         print(f"plan {p}: worst KV err {wkv:.4g}, worst logit err {wlg:.4g}")
         # the sequential join (recompute || load, wait, then the new-turn prefill) gives the same bits
         out_s, *_ = restore_and_compare(b, refs, sess, host, splits, seed=20 + p, pipelined=False)
+        # ... and so does the staged load path (DMA into staging slots + scatter kernel) in place
+        # of the direct load kernel, in either join mode
+        out_d, *_ = restore_and_compare(b, refs, sess, host, splits, seed=20 + p, pipelined=(p % 2 == 0),
+                                        load_path=1)
         for i in out_p:
-            assert np.array_equal(out_p[i][0], out_s[i][0]) and np.array_equal(out_p[i][1], out_s[i][1])
-            assert np.abs(out_p[i][2] - out_s[i][2]).max() <= 2e-2
+            for other in (out_s, out_d):
+                assert np.array_equal(out_p[i][0], other[i][0]) and np.array_equal(out_p[i][1], other[i][1])
+                assert np.abs(out_p[i][2] - other[i][2]).max() <= 2e-2
 
 
 def test_mini_bf16_mfma_kernels_agree_with_plain_kernels(mini):

@@ -99,6 +99,36 @@ def test_cfg1_sequential_join_mode(env):
         sess.ctx.set_pipelined_join(True)
 
 
+def test_cfg1_staged_load_path_and_pageable_host_memory(env):
+    import paper_2604_25080_amd as cf
+    b, refs, ws, sess, host = env
+    try:
+        # staged path (DMA into staging slots + scatter kernel) instead of the direct load kernel
+        sess.ctx.set_load_path(1)
+        run_and_check(env, b.forced_splits, seed=12)
+        run_and_check(env, [(17, 1), (0, 2)], seed=13)
+        sess.ctx.set_pipelined_join(False)
+        run_and_check(env, [(33, 2), (47, 1)], seed=14)
+        sess.ctx.set_pipelined_join(True)
+        # host blocks in pageable memory: the automatic choice falls back to the staged path,
+        # the forced direct path refuses them with an error instead of faulting
+        pageable = [torch.from_numpy(h.numpy().copy()) for h in host]
+        assert not pageable[0].is_pinned()
+        env2 = (b, refs, ws, sess, pageable)
+        sess.ctx.set_load_path(0)
+        run_and_check(env2, b.forced_splits, seed=15)
+        sess.ctx.set_load_path(2)
+        with pytest.raises(cf.CfError) as e:
+            run_and_check(env2, b.forced_splits, seed=15)
+        assert e.value.status == cf.CF_ERR_INVALID_ARG
+        run_and_check(env, b.forced_splits, seed=16)          # forced direct path, pinned blocks
+        sess.ctx.set_load_path(2, 3)                          # fewer workgroups than virtual blocks
+        run_and_check(env, [(17, 1), (5, 2)], seed=17)
+    finally:
+        sess.ctx.set_pipelined_join(True)
+        sess.ctx.set_load_path(0, 8)
+
+
 def test_cfg1_all_recompute_and_all_load(env):
     b = env[0]
     run_and_check(env, [(n, 2) for n in b.n_ctx], seed=4)
