@@ -344,8 +344,9 @@ int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only);
  *                                                        (Dt device dtype[M,N])
  * (the QKV / O-proj and down-proj / - / gate-up steps of a layer).
  * impl 0 = what cf_restore_batch would pick, 1 = plain FMA kernel, 2 = MFMA
- * kernel with its own tile choice, 3 / 4 = MFMA kernel forced to 256x256 /
- * 128x128 block tiles (CF_ERR_UNSUPPORTED if MFMA does not take the shape).  Runs `reps`
+ * kernel with its own tile choice, 3 / 4 / 5 = MFMA kernel forced to 256x256 /
+ * 128x128 / 64x64 block tiles (epi 3 has no 64x64 tile and takes 128x128;
+ * CF_ERR_UNSUPPORTED if MFMA does not take the shape).  Runs `reps`
  * times on the compute stream, blocks, and returns the mean time per run
  * from HIP events in *avg_ms (may be NULL).                                 */
 int cf_op_gemm(cf_ctx* ctx, const void* A, const void* W, const void* W2, float* Cf, void* Dt,

@@ -356,7 +356,7 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
         ci.work_off = (int)ph.work.size();
         ci.grp_off = (int)ph.groups.size();
         std::vector<AttnWork> items;
-        int n_items_rec = 0;
+        int n_items_rec = 0, n_rec_attending = 0;
         ci.r_mid = std::min(std::max(ph.rec_rows(), ci.r0), ci.r1);
         for (const Segment& s : ph.segs) {
             int a = std::max(s.row0, ci.r0), b = std::min(s.row0 + s.n_rows, ci.r1);
@@ -371,20 +371,29 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
                 w.part = -1;
                 w.pad = 0;
                 items.push_back(w);
-                if (!s.is_new) n_items_rec = (int)items.size();   // recompute segments come first
+                if (!s.is_new) {
+                    n_items_rec = (int)items.size();      // recompute segments come first
+                    if (s.layers >= 2) ++n_rec_attending; // a request cut after layer 1 never attends
+                }
             }
         }
-        int factor = 1;
-        if (n_q_heads_split > 0 && !items.empty()) {
-            int64_t blocks = (int64_t)items.size() * n_q_heads_split;
-            if (blocks < 512) factor = (int)((1024 + blocks - 1) / blocks);
-        }
+        // The recompute items and the new-turn items of a layer are separate launches, so each
+        // group gets its own split factor: the one that brings its workgroup count to about 1024.
+        auto factor_for = [&](int n_items) {
+            if (n_q_heads_split <= 0 || n_items <= 0) return 1;
+            int64_t blocks = (int64_t)n_items * n_q_heads_split;
+            return blocks < 512 ? (int)((1024 + blocks - 1) / blocks) : 1;
+        };
+        const int factor_rec = factor_for(n_rec_attending);
+        const int factor_new = factor_for((int)items.size() - n_items_rec);
         int next_part = 0, item_idx = 0;
         ci.n_work_rec = ci.n_grp_rec = 0;
         for (const AttnWork& w : items) {
+            const int factor = item_idx < n_items_rec ? factor_rec : factor_new;
             if (item_idx++ == n_items_rec) {       // everything before this came from recompute rows
                 ci.n_work_rec = (int)ph.work.size() - ci.work_off;
                 ci.n_grp_rec = (int)ph.groups.size() - ci.grp_off;
+                next_part = 0;                     // the partial buffers are free again by then
             }
             int full_tiles = w.pos0 / ATTN_KEY_TILE;          // tiles every row sees completely
             int n_split = std::min(factor, std::max(1, full_tiles / 16));
@@ -1045,11 +1054,11 @@ extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W
     if ((epi == EPI_SILU_MUL && !W2) || ((epi == EPI_STORE_F32 || epi == EPI_ADD_F32) && !Cf) ||
         ((epi == EPI_STORE_T || epi == EPI_SILU_MUL) && !Dt))
         return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: missing operand for this epilogue");
-    if (impl < 0 || impl > 4) return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: impl must be 0..4");
+    if (impl < 0 || impl > 5) return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: impl must be 0..5");
     bool mfma_ok = gemm_mfma_supported(c->m.dtype, M, N, K, epi);
     if (impl >= 2 && !mfma_ok) return fail(CF_ERR_UNSUPPORTED, "cf_op_gemm: MFMA kernel does not take this problem");
     bool use_mfma = impl >= 2 || (impl == 0 && mfma_ok && !c->simple_only);
-    gemm_mfma_force_tile(impl == 3 ? 256 : impl == 4 ? 128 : 0);
+    gemm_mfma_force_tile(impl == 3 ? 256 : impl == 4 ? 128 : impl == 5 ? 64 : 0);
     struct Reset { ~Reset() { gemm_mfma_force_tile(0); } } reset_on_exit;
     CF_HIP(hipEventRecord(c->ev_t0, c->cs));
     for (int i = 0; i < reps; ++i) {

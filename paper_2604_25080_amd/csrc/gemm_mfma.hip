@@ -340,7 +340,8 @@ void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, fl
                                              (bf16*)Dt, M, N, K, tiles_m, tiles_n, map_mode, group_m);
 }
 
-int g_force_tile = 0;   // 0 = heuristic, 256 / 128 = forced (tuning hook)
+int g_force_tile = 0;   // 0 = heuristic, 256 / 128 / 64 = forced (tuning hook)
+int g_small_below = 160;   // 64x64 tiles when there are fewer 128x128 tiles than this
 
 template <int EPI>
 void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt, int M,
@@ -352,8 +353,16 @@ void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* 
     int64_t need = EPI == EPI_SILU_MUL ? 200 : 256;
     bool big = (g_force_tile ? g_force_tile >= 256 : tiles256 >= need) && K % (2 * BK) == 0 &&
                M >= 256 && N >= BN_OUT256 && EPI != EPI_ADD_F32;
-    if (big) launch_tile<EPI, 256, 256, 4>(s, A, W, W2, Cf, Dt, M, N, K);
-    else launch_tile<EPI, 128, 128, 4>(s, A, W, W2, Cf, Dt, M, N, K);
+    if (big) { launch_tile<EPI, 256, 256, 4>(s, A, W, W2, Cf, Dt, M, N, K); return; }
+    if constexpr (EPI != EPI_SILU_MUL) {
+        // few rows against a narrow weight (a tensor-parallel shard's QKV projection): 128x128
+        // tiles would leave most CUs idle, so quarter the tile.  The K order of every output
+        // element is the same for all tile shapes, so the result bits do not depend on the choice.
+        int64_t tiles128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+        bool small = g_force_tile ? g_force_tile == 64 : tiles128 < g_small_below;
+        if (small) { launch_tile<EPI, 64, 64, 4>(s, A, W, W2, Cf, Dt, M, N, K); return; }
+    }
+    launch_tile<EPI, 128, 128, 4>(s, A, W, W2, Cf, Dt, M, N, K);
 }
 
 }  // namespace
