@@ -29,7 +29,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(batch, n_tok=1024, n_layers=2):
+def cpu_baseline(batch, n_tok=4096, n_layers=6):
     """Time the CPU oracle (as it stands) on a bounded slice of the workload."""
     import numpy as np
     from oracle import transformer as T

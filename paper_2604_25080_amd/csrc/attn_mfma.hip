@@ -282,7 +282,9 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
     }
 }
 
-// Merge the partial results of one (q-block, head): one wavefront per query row.
+// Merge the partial results of one (q-block, head): one wavefront per query row, four rows
+// per workgroup (blockIdx.z picks the row quad), so the merge is spread over thousands of
+// wavefronts instead of walking 32 rows per wavefront through dependent loads.
 template <int HD>
 __global__ void __launch_bounds__(256)
 attention_combine_kernel(bf16* __restrict__ out, const float* __restrict__ part_buf,
@@ -290,7 +292,9 @@ attention_combine_kernel(bf16* __restrict__ out, const float* __restrict__ part_
     AttnCombine cgrp = groups[blockIdx.x];
     int head = blockIdx.y;
     int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int r = wave; r < cgrp.n_rows; r += 4) {
+    {
+        int r = blockIdx.z * 4 + wave;
+        if (r >= cgrp.n_rows) return;
         float m = -INFINITY;
         for (int p = 0; p < cgrp.n_parts; ++p) {
             const float* prow = part_buf + (((int64_t)(cgrp.part_first + p) * n_q_heads + head) * ATTN_BLOCK_ROWS + r) * (HD + 4);
@@ -333,7 +337,7 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
     else
         attention_mfma_kernel<64><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
     if (n_groups > 0) {
-        dim3 cgrid(n_groups, n_q_heads);
+        dim3 cgrid(n_groups, n_q_heads, ATTN_BLOCK_ROWS / 4);
         if (g.head_dim == 128)
             attention_combine_kernel<128><<<cgrid, 256, 0, s>>>((bf16*)out, part_buf, groups, n_q_heads);
         else
