@@ -259,13 +259,19 @@ typedef struct cf_timing {
  *   timing       : host, may be NULL.
  * Blocking: returns after logits are ready and both streams are idle.
  * Recompute runs on the compute stream, layer-major over the whole batch;
- * loads run on the copy stream (pinned host -> staging -> page scatter).
+ * loads run on the copy stream (pinned host -> pages by a load kernel, or
+ * host -> staging -> page scatter; see cf_ctx_set_load_path).
  * max(sum k_i + sum n_new) must not exceed the context's max_tokens.         */
 int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
                      const cf_split* splits, float* logits_out, cf_timing* timing);
 
-/* Copy a request's first n_ctx tokens of KV from its pages to a pinned host
- * block in the host layout (used to manufacture host KV; not a timed path). */
+/* Copy a request's first n_ctx tokens of KV from its pages to a host block
+ * of cf_host_kv_bytes(n_ctx) bytes in the host layout (whole pages; the
+ * eviction direction of Sec. 3's external storage, and how host KV is
+ * manufactured for the large configurations).  Blocking.  If the block is
+ * pinned, device-mapped memory a store kernel writes it over the host link in
+ * one launch; otherwise (or with load path 1) pages are gathered into the
+ * staging buffer and copied out layer by layer.  Same bytes either way.      */
 int cf_offload(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv);
 
 /* Time a large pinned host->device copy on the copy stream: the bandwidth

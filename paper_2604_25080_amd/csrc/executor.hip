@@ -1013,6 +1013,34 @@ extern "C" int cf_offload(cf_ctx* c, cf_cache* cache, uint64_t req_id, int32_t n
         return fail(CF_ERR_WORKSPACE, "cf_offload: page table exceeds the context's metadata area");
     std::memcpy(c->meta_host, pt, (size_t)np * 4);
     size_t job_off = ((size_t)np * 4 + 15) / 16 * 16;
+    // direct path: the host block is pinned, device-mapped memory -> one store kernel writes it
+    // over the host link, all layers in one launch
+    void* host_dev = nullptr;
+    if (c->load_path != 1) {
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, host_kv) != hipSuccess || at.type != hipMemoryTypeHost ||
+            hipHostGetDevicePointer(&host_dev, host_kv, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            host_dev = nullptr;
+        }
+        if (!host_dev && c->load_path == 2)
+            return fail(CF_ERR_INVALID_ARG, "cf_offload: the direct path needs pinned, device-mapped host memory");
+    }
+    if (host_dev && (int64_t)np_ctx * (int64_t)(pb / 16) < ((int64_t)1 << 31) &&
+        job_off + (size_t)m.n_layers * sizeof(PageJob) <= c->cv.meta_bytes) {
+        PageJob* jobs = (PageJob*)(c->meta_host + job_off);
+        int units_per_layer = (int)ceil_div((int64_t)np_ctx * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
+        for (int l = 0; l < m.n_layers; ++l)
+            jobs[l] = PageJob{(int64_t)(uintptr_t)((char*)host_dev + (size_t)l * np_ctx * pb), l, 0, 0, np_ctx,
+                              0, n_ctx, l * units_per_layer, 0};
+        CF_HIP(hipMemcpyAsync(md, c->meta_host, job_off + (size_t)m.n_layers * sizeof(PageJob),
+                              hipMemcpyHostToDevice, c->cs));
+        launch_page_store(c->cs, m.dtype, cache->pool, (const PageJob*)(md + job_off), m.n_layers,
+                          m.n_layers * units_per_layer, 2 * c->load_wgs, (const int32_t*)md, g);
+        CF_HIP(hipGetLastError());
+        CF_HIP(hipStreamSynchronize(c->cs));
+        return CF_OK;
+    }
     CF_HIP(hipMemcpy(md, c->meta_host, (size_t)np * 4, hipMemcpyHostToDevice));
     for (int l = 0; l < m.n_layers; ++l) {
         for (int j = 0; j < np_ctx; j += (int)cap_pages) {

@@ -42,7 +42,8 @@ inline size_t attn_part_bytes(int head_dim) {
 
 // One contiguous run of pages of one layer of one request, staged in order.
 struct PageJob {
-    int64_t staging_off;   // byte offset of the run's first page in the staging buffer
+    int64_t staging_off;   // byte offset of the run's first page in the staging buffer (staged
+                           // path) or its ADDRESS in device-mapped host memory (direct path)
     int32_t layer;
     int32_t pt_off;        // request's page table offset
     int32_t page_first;    // index into the request's page table of the first page
@@ -90,6 +91,9 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
 constexpr int PAGE_LOAD_UNIT_VECS = 4096;
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
+// pages -> pinned host memory, directly (whole pages; job fields as for launch_page_load)
+void launch_page_store(hipStream_t s, int dtype, const void* pool, const PageJob* jobs, int n_jobs,
+                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
 // staging -> pages (to_pages = true) or pages -> staging (false; zero-fills unused slots)
 void launch_page_move(hipStream_t s, int dtype, void* staging, void* pool, const PageJob* jobs,
                       int n_jobs, int n_blocks, const int32_t* page_tables, KvGeom g, bool to_pages);

@@ -437,6 +437,57 @@ page_load_kernel(T* __restrict__ pool, const PageJob* __restrict__ jobs, int n_j
     }
 }
 
+// Pages -> pinned host memory, the mirror image of page_load_kernel: whole pages of a run are
+// read from the pool (16 loads per thread in flight) and stored straight into the host block
+// over the host link.  job.staging_off holds the host ADDRESS of the run's first page.
+template <typename T>
+__global__ void __launch_bounds__(256)
+page_store_kernel(const T* __restrict__ pool, const PageJob* __restrict__ jobs, int n_jobs, int n_units,
+                  const int32_t* __restrict__ page_tables, KvGeom g) {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    constexpr int VE = 16 / sizeof(T);
+    constexpr int U = PAGE_LOAD_UNIT_VECS / 256;
+    const int nvec = (int)(g.page_elems / VE);
+    for (int b = blockIdx.x; b < n_units; b += gridDim.x) {
+        int ji = 0, jhi = n_jobs - 1;
+        while (ji < jhi) {
+            int mid = (ji + jhi + 1) >> 1;
+            if (jobs[mid].block_first <= b) ji = mid; else jhi = mid - 1;
+        }
+        PageJob job = jobs[ji];
+        const unsigned job_vecs = (unsigned)job.n_pages * (unsigned)nvec;
+        const unsigned base = (unsigned)(b - job.block_first) * PAGE_LOAD_UNIT_VECS;
+        const unsigned pg0 = base / (unsigned)nvec, rem0 = base - pg0 * (unsigned)nvec;
+        v4u* dst = reinterpret_cast<v4u*>((uintptr_t)job.staging_off) + base;
+        const T* layer_base = pool + (int64_t)job.layer * g.layer_stride;
+        const int32_t* table = page_tables + job.pt_off + job.page_first;
+        v4u val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            unsigned o = min((unsigned)(u * 256 + threadIdx.x), job_vecs - 1 - base);   // clamped, unconditional
+            unsigned pg = pg0 + (rem0 + o) / (unsigned)nvec;
+            unsigned v = rem0 + o - (pg - pg0) * (unsigned)nvec;
+            const T* src = layer_base + (int64_t)table[pg] * g.page_elems;
+            val[u] = reinterpret_cast<const v4u*>(src)[v];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            unsigned o = u * 256 + threadIdx.x;
+            if (base + o < job_vecs) __builtin_nontemporal_store(val[u], dst + o);
+        }
+    }
+}
+
+void launch_page_store(hipStream_t s, int dtype, const void* pool, const PageJob* jobs, int n_jobs,
+                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g) {
+    if (n_jobs <= 0 || n_units <= 0) return;
+    int grid = n_workgroups < n_units ? n_workgroups : n_units;
+    if (dtype == CF_F32)
+        page_store_kernel<float><<<grid, 256, 0, s>>>((const float*)pool, jobs, n_jobs, n_units, page_tables, g);
+    else
+        page_store_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)pool, jobs, n_jobs, n_units, page_tables, g);
+}
+
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g) {
     if (n_jobs <= 0 || n_units <= 0) return;

@@ -129,6 +129,34 @@ def test_cfg1_staged_load_path_and_pageable_host_memory(env):
         sess.ctx.set_load_path(0, 8)
 
 
+def test_cfg1_offload_returns_the_oracle_pages_on_both_paths(env):
+    """Pages -> host block: the store kernel (pinned block) and the staged copy (pageable block or
+    forced) give the same bytes, and they decode to the oracle's K/V within the float32 bound."""
+    b, refs, ws, sess, host = env
+    for i in range(len(b.n_ctx)):
+        sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
+    reqs = [dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=None)
+            for i in range(len(b.n_ctx))]
+    try:
+        sess.restore(reqs, [(0, n, b.shape.n_layers) for n in b.n_ctx], want_logits=False)
+        for i, n in enumerate(b.n_ctx):
+            nbytes = sess.host_kv_bytes(n)
+            direct = sess.offload(1 + i, n).numpy()[:nbytes].copy()
+            sess.ctx.set_load_path(1)
+            staged = sess.offload(1 + i, n).numpy()[:nbytes].copy()
+            sess.ctx.set_load_path(0)
+            pageable = torch.zeros(nbytes, dtype=torch.uint8)
+            sess.ctx.offload(sess.cache, 1 + i, n, pageable.data_ptr())
+            assert np.array_equal(direct, staged) and np.array_equal(direct, pageable.numpy())
+            k, v = decode_pages(b.shape, direct.reshape(b.shape.n_layers, -1, sess.page_bytes), n)
+            rk, rv = stack_kv(b.shape, refs[i][0], refs[i][1])
+            assert np.abs(k - rk[:, :n]).max() <= 1e-4 and np.abs(v - rv[:, :n]).max() <= 1e-4
+    finally:
+        sess.ctx.set_load_path(0)
+        for i in range(len(b.n_ctx)):
+            sess.cache.free(1 + i)
+
+
 def test_cfg1_all_recompute_and_all_load(env):
     b = env[0]
     run_and_check(env, [(n, 2) for n in b.n_ctx], seed=4)
