@@ -75,6 +75,8 @@ def main():
                     help="direct: load kernel reading pinned host memory; staged: DMA + scatter")
     ap.add_argument("--load-workgroups", type=int, default=0,
                     help="resident workgroups of the direct load kernel (0: library default)")
+    ap.add_argument("--link-gbps", type=float, default=0.0,
+                    help="pace the copy stream to this many Gbit/s (emulates a slower storage tier; 0: off)")
     ap.add_argument("--sequential-join", action="store_true",
                     help="restore, wait for both streams, then prefill the new tokens (default: pipelined join)")
     args = ap.parse_args()
@@ -126,6 +128,8 @@ def main():
         f"(offload {offload_gbs:.1f} GB/s, "
         f"all-recompute pass: {tm_full['compute_ms']:.1f} ms, "
         f"{tm_full['recompute_flops'] / tm_full['compute_ms'] / 1e9:.0f} TFLOP/s)")
+
+    sess.ctx.set_link_throttle(args.link_gbps / 8.0)
 
     # ---- measured rooflines of the load path and the cost model
     big = max(reqs, key=lambda r: r["host_kv"].numel())["host_kv"]
@@ -247,7 +251,7 @@ def main():
                       "all_gemm_tflops": all_gemm_fl / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else 0.0},
         "copy": {"bytes": int(loaded_bytes), "GB/s": copy_gbs, "h2d_measured_GB/s": h2d_gbs,
                  "frac_of_measured_h2d": copy_gbs / h2d_gbs if h2d_gbs else 0.0,
-                 "offload_d2h_GB/s": offload_gbs},
+                 "offload_d2h_GB/s": offload_gbs, "link_throttle_GB/s": args.link_gbps / 8.0},
         "all_recompute_pass": {"ms": tm_full["compute_ms"],
                                "tflops": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9,
                                "frac_of_mfma_peak": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9 / peak},

@@ -337,6 +337,15 @@ int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on);
  * Results are identical.                                                    */
 int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgroups);
 
+/* Emulation of a slower storage tier or link (the bandwidth ablation of the
+ * paper's evaluation): with gb_per_s > 0 the copy stream of cf_restore_batch
+ * is held after every transfer unit until the bytes moved so far would have
+ * crossed a link of that rate (a one-lane wait kernel on the constant-rate
+ * device clock; bounded spin).  0 (default) switches it off.  cf_calibrate run
+ * afterwards measures the throttled link; cf_measure_h2d always measures the
+ * real one.  Results are unaffected.                                        */
+int cf_ctx_set_link_throttle(cf_ctx* ctx, double gb_per_s);
+
 /* Kernel selection for a context: simple_only != 0 routes every step through
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
  * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */

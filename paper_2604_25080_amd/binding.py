@@ -131,6 +131,7 @@ lib.cf_ctx_destroy.restype = None
 lib.cf_ctx_set_kernel_set.argtypes = [C.c_void_p, C.c_int32]
 lib.cf_ctx_set_pipelined_join.argtypes = [C.c_void_p, C.c_int32]
 lib.cf_ctx_set_load_path.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+lib.cf_ctx_set_link_throttle.argtypes = [C.c_void_p, C.c_double]
 lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request), _P(cf_split),
                                  C.c_void_p, _P(cf_timing)]
 lib.cf_offload.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]
@@ -148,7 +149,7 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", 
            "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
-           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_restore_batch", "cf_offload",
+           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_restore_batch", "cf_offload",
            "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
            "cf_ctx_profile_read", "cf_read_final_hidden"]
 
@@ -317,6 +318,10 @@ class Ctx:
     def set_load_path(self, path, n_workgroups=0):
         """path: 0 auto, 1 staged DMA + scatter, 2 direct load kernel."""
         _check(lib.cf_ctx_set_load_path(self.handle, int(path), int(n_workgroups)), "cf_ctx_set_load_path")
+
+    def set_link_throttle(self, gb_per_s):
+        """Pace the copy stream to gb_per_s GB/s (0: off)."""
+        _check(lib.cf_ctx_set_link_throttle(self.handle, float(gb_per_s)), "cf_ctx_set_link_throttle")
 
     def restore_batch(self, cache, requests, splits, logits_ptr):
         """requests: list of dict(req_id, ctx_tokens (np.int32), n_new, host_kv (address or

@@ -34,6 +34,7 @@ struct Carve {
     size_t rope, h, dl, a, qkv, q, o, act, a_last, attn_part, staging, meta, total;
     size_t staging_bytes, meta_bytes;
     int chunk_rows;
+    size_t pace;
 };
 
 static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* c) {
@@ -77,6 +78,7 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
     c->attn_part = take(attn_part_bytes(m.head_dim));
     c->staging = take(stg);
     c->meta = take(meta);
+    c->pace = take(256);
     c->total = off;
     c->staging_bytes = stg;
     c->meta_bytes = meta;
@@ -105,6 +107,8 @@ struct cf_ctx {
     bool pipelined = true;            // new-turn rows ride along with the recompute pass
     int load_path = 0;                // 0 auto, 1 staged DMA + scatter, 2 direct load kernel
     int load_wgs = 8;                 // resident workgroups of the direct load kernel
+    double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
+    double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
     std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
@@ -158,6 +162,7 @@ struct cf_ctx {
     float2* rope() { return (float2*)(ws + cv.rope); }
     char* staging() { return ws + cv.staging; }
     char* meta_dev() { return ws + cv.meta; }
+    void* pace_dev() { return ws + cv.pace; }
 };
 
 extern "C" int cf_workspace_bytes(const cf_model_desc* desc, const cf_ctx_opts* opts, size_t* bytes) {
@@ -271,6 +276,20 @@ extern "C" int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgro
         return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_load_path: n_workgroups %d not in 0..1024", n_workgroups);
     ctx->load_path = path;
     if (n_workgroups > 0) ctx->load_wgs = n_workgroups;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_set_link_throttle(cf_ctx* ctx, double gb_per_s) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_link_throttle: null ctx");
+    if (!(gb_per_s >= 0) || gb_per_s > 1e6)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_link_throttle: rate must be in [0, 1e6] GB/s");
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+        ctx->wall_hz = 1e3 * khz;
+    else
+        (void)hipGetLastError();
+    ctx->throttle_gbs = gb_per_s;
     return CF_OK;
 }
 
@@ -872,12 +891,23 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     g.page_elems = (int64_t)(cache->page_bytes / es);
     g.layer_stride = g.page_elems * cache->n_pages;
 
-    // copy stream, direct path: one load-kernel launch per layer, host memory -> pages
+    // copy stream, direct path: one load-kernel launch per layer, host memory -> pages.
+    // With a link throttle set, a wait kernel holds the stream after every unit until the bytes
+    // moved so far would have crossed a link of that rate.
+    double paced_bytes = 0;
+    auto pace = [&](double bytes) {
+        if (c->throttle_gbs <= 0) return;
+        paced_bytes += bytes;
+        launch_pace_wait(c->ps, c->pace_dev(),
+                         (unsigned long long)(paced_bytes / (c->throttle_gbs * 1e9) * c->wall_hz));
+    };
+    if (c->throttle_gbs > 0) launch_pace_mark(c->ps, c->pace_dev());
     std::vector<char> layer_loaded(L, 0);
     for (const LayerLoad& ll : layer_loads) {
         c->prof_begin(CF_K_H2D_COPY, (double)ll.bytes, c->ps);
         launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ll.job_first,
                          ll.n_jobs, ll.n_vblocks, c->load_wgs, (const int32_t*)md, g);
+        pace((double)ll.bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
         layer_loaded[ll.layer] = 1;
         if (merged) CF_HIP(hipEventRecord(c->ev_layer[ll.layer], c->ps));
@@ -894,6 +924,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
             const CopyOp& op = ops[sp.op_first + k];
             CF_HIP(hipMemcpyAsync(c->staging() + op.dst_off, op.src, op.bytes, hipMemcpyHostToDevice, c->ps));
         }
+        pace(slot_bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
         CF_HIP(hipEventRecord(c->ev_filled[sp.slot], c->ps));
         CF_HIP(hipStreamWaitEvent(c->ss, c->ev_filled[sp.slot], 0));

@@ -91,6 +91,10 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
 constexpr int PAGE_LOAD_UNIT_VECS = 4096;
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
+// copy-stream pacing: mark stores the wall clock at *t0 (device, 8 bytes), wait holds the stream
+// until `ticks` wall-clock ticks have passed since the mark (bounded spin)
+void launch_pace_mark(hipStream_t s, void* t0);
+void launch_pace_wait(hipStream_t s, const void* t0, unsigned long long ticks);
 // pages -> pinned host memory, directly (whole pages; job fields as for launch_page_load)
 void launch_page_store(hipStream_t s, int dtype, const void* pool, const PageJob* jobs, int n_jobs,
                        int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);

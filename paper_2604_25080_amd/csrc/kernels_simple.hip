@@ -488,6 +488,25 @@ void launch_page_store(hipStream_t s, int dtype, const void* pool, const PageJob
         page_store_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)pool, jobs, n_jobs, n_units, page_tables, g);
 }
 
+// Pacing of the copy stream (emulation of a slower storage tier): a mark kernel stores the
+// constant-rate wall clock, a wait kernel holds the stream until `ticks` of that clock have
+// passed since the mark.  One lane; the spin is bounded (2^26 sleeps of ~1 us), so the kernel
+// always ends.
+__global__ void pace_mark_kernel(unsigned long long* t0) { *t0 = wall_clock64(); }
+
+__global__ void pace_wait_kernel(const unsigned long long* t0, unsigned long long ticks) {
+    unsigned long long start = *t0;
+    for (int i = 0; i < (1 << 26); ++i) {
+        if (wall_clock64() - start >= ticks) break;
+        __builtin_amdgcn_s_sleep(32);
+    }
+}
+
+void launch_pace_mark(hipStream_t s, void* t0) { pace_mark_kernel<<<1, 1, 0, s>>>((unsigned long long*)t0); }
+void launch_pace_wait(hipStream_t s, const void* t0, unsigned long long ticks) {
+    pace_wait_kernel<<<1, 1, 0, s>>>((const unsigned long long*)t0, ticks);
+}
+
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g) {
     if (n_jobs <= 0 || n_units <= 0) return;

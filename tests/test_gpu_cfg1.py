@@ -157,6 +157,25 @@ def test_cfg1_offload_returns_the_oracle_pages_on_both_paths(env):
             sess.cache.free(1 + i)
 
 
+def test_cfg1_link_throttle_paces_the_copy_stream_and_changes_no_result(env):
+    b, refs, ws, sess, host = env
+    rate = 0.05                                   # GB/s
+    try:
+        for path in (0, 1):
+            sess.ctx.set_load_path(path)
+            sess.ctx.set_link_throttle(rate)
+            tm = run_and_check(env, b.forced_splits, seed=21 + path)
+            floor_ms = tm["loaded_bytes"] / (rate * 1e9) * 1e3
+            assert tm["copy_ms"] >= 0.95 * floor_ms, (tm["copy_ms"], floor_ms)
+            assert tm["copy_ms"] <= floor_ms + 20.0, (tm["copy_ms"], floor_ms)
+            sess.ctx.set_link_throttle(0.0)
+            tm = run_and_check(env, b.forced_splits, seed=21 + path)
+            assert tm["copy_ms"] < 0.5 * floor_ms
+    finally:
+        sess.ctx.set_link_throttle(0.0)
+        sess.ctx.set_load_path(0)
+
+
 def test_cfg1_all_recompute_and_all_load(env):
     b = env[0]
     run_and_check(env, [(n, 2) for n in b.n_ctx], seed=4)
