@@ -41,8 +41,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-template <int HD>
-__global__ void __launch_bounds__(256, 2)
+// HPB = query heads per workgroup (1 or 2): with 2, wavefronts 0-3 and 4-7 work on two heads of
+// the same KV group and share every K/V tile in LDS, which halves the L2 -> LDS traffic per
+// FLOP (what bounds this kernel); 8 wavefronts per CU either way.
+template <int HD, int HPB>
+__global__ void __launch_bounds__(256 * HPB, 3 - HPB)
 attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float* __restrict__ part_buf,
                       const bf16* __restrict__ pool_layer, const AttnWork* __restrict__ work,
                       const int32_t* __restrict__ page_tables, int n_q_heads, KvGeom g) {
@@ -53,7 +56,9 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
     constexpr int V_TILE = HD * V_ROWB;
     constexpr int STAGE = K_TILE + V_TILE;
     constexpr int VEC_PER_PAGE = CF_PAGE_TOKENS * K_NCH;       // 16-byte vectors of one page's K (= V) part
-    constexpr int PAGES_PER_LOAD = 256 / VEC_PER_PAGE;         // pages covered by one block-wide load (1 or 2)
+    constexpr int NT = 256 * HPB;
+    constexpr int PAGES_PER_LOAD = NT / VEC_PER_PAGE;          // pages covered by one block-wide load (1, 2 or 4)
+    static_assert(PAGES_PER_LOAD >= 1 && PAGES_PER_LOAD <= PAGES_PER_TILE, "loader shape");
     constexpr int NLD = PAGES_PER_TILE / PAGES_PER_LOAD;       // loads per thread per tile, each of K and V
     constexpr int QK_STEPS = HD / 16;
     constexpr int D_TILES = HD / 32;
@@ -61,10 +66,11 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
 
     // heaviest work items (largest positions) are scheduled first
     AttnWork w = work[gridDim.x - 1 - blockIdx.x];
-    int head = blockIdx.y;
-    int gk = head / (n_q_heads / g.n_kv_heads);
+    int tid = threadIdx.x, lane = tid & 63;
+    int wave = (tid >> 6) & 3;                     // which 32 query rows
+    int head = blockIdx.y * HPB + (tid >> 8);      // wavefronts 4-7 take the second head of the pair
+    int gk = head / (n_q_heads / g.n_kv_heads);    // the same KV head for both (group size is even)
     const int32_t* pt = page_tables + w.pt_off;
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int lq = lane & 31, lh = lane >> 5;
 
     int kv_end = min(w.pos0 + w.n_rows, w.tile_end * KT);   // keys [tile_begin*KT, kv_end) are read
@@ -94,15 +100,20 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
     int v_d = pv / 2, v_half = pv % 2;             // hd row, which 8 keys of the page
     int k_goff = k_r * HD + k_c * 8;
     int v_goff = v_d * CF_PAGE_TOKENS + v_half * 8;
-    int k_lds[NLD], v_lds[NLD], v_key0[NLD];
+    int k_lds[NLD], v_lds0[NLD], v_lds1[NLD], v_key0[NLD];
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
         int page_in_tile = j * PAGES_PER_LOAD + sub_page;
         int r = page_in_tile * CF_PAGE_TOKENS + k_r;
         int ksw = (HD == 128) ? (r & 15) : ((r >> 1) & 7);
         k_lds[j] = r * K_ROWB + ((k_c ^ ksw) << 4);
-        int cv = page_in_tile * 2 + v_half;        // 16-byte chunk of the V^T row
-        v_lds[j] = K_TILE + v_d * V_ROWB + ((cv ^ ((v_d >> 1) & 7)) << 4);
+        // V^T row v_d, page p: chunk 2p+h holds [keys 4h..4h+3 | keys 8+4h..8+4h+3] of the page,
+        // i.e. exactly the 16 bytes lane half h of the second product needs (one 16-byte read).
+        // This thread's vector (keys 8*v_half .. +7) therefore goes out as two 8-byte pieces:
+        // keys +0..3 into chunk 2p, keys +4..7 into chunk 2p+1, both at half v_half.
+        int vsw = (v_d >> 1) & 7;
+        v_lds0[j] = K_TILE + v_d * V_ROWB + (((page_in_tile * 2) ^ vsw) << 4) + v_half * 8;
+        v_lds1[j] = K_TILE + v_d * V_ROWB + (((page_in_tile * 2 + 1) ^ vsw) << 4) + v_half * 8;
         v_key0[j] = page_in_tile * CF_PAGE_TOKENS + v_half * 8;
     }
 
@@ -142,7 +153,8 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
         char* st_ = (STAGE_PTR);                                                              \
         _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                     \
             *reinterpret_cast<u32x4_t*>(st_ + k_lds[j]) = rk[j];                              \
-            *reinterpret_cast<u32x4_t*>(st_ + v_lds[j]) = rv[j];                              \
+            *reinterpret_cast<u32x2_t*>(st_ + v_lds0[j]) = u32x2_t{rv[j].x, rv[j].y};         \
+            *reinterpret_cast<u32x2_t*>(st_ + v_lds1[j]) = u32x2_t{rv[j].z, rv[j].w};         \
         }                                                                                     \
     }
 
@@ -177,13 +189,14 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[tt][r] = 0.f;
-#pragma unroll
                 for (int kk = 0; kk < QK_STEPS; ++kk) {
                     u32x4_t kf = *reinterpret_cast<const u32x4_t*>(
                         cur + (tt * 32 + lq) * K_ROWB + (((2 * kk + lh) ^ ksw_l) << 4));
+                    // the first step starts from a zero accumulator operand (no register clearing)
                     s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[kk]), s[tt], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[kk]),
+                        kk == 0 ? f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}
+                                : s[tt], 0, 0, 0);
                 }
             }
             // ---- causal mask on the diagonal tiles only (lane = one query row, 32 of its 64 keys)
@@ -234,11 +247,9 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
                 pf.w = pack_bf16x2(s[tt][4 * b0 + 6], s[tt][4 * b0 + 7]);
 #pragma unroll
                 for (int t = 0; t < D_TILES; ++t) {
-                    // keys 4*lh..4*lh+3 and 8+4*lh.. of page `st`, for hd row 32t + lq
-                    const char* vrow = cur + K_TILE + (t * 32 + lq) * V_ROWB;
-                    u32x2_t v0 = *reinterpret_cast<const u32x2_t*>(vrow + (((2 * st) ^ vsw_l) << 4) + lh * 8);
-                    u32x2_t v1 = *reinterpret_cast<const u32x2_t*>(vrow + (((2 * st + 1) ^ vsw_l) << 4) + lh * 8);
-                    u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
+                    // keys 4*lh..4*lh+3 and 8+4*lh.. of page `st`, for hd row 32t + lq: one chunk
+                    u32x4_t vf = *reinterpret_cast<const u32x4_t*>(
+                        cur + K_TILE + (t * 32 + lq) * V_ROWB + (((2 * st + lh) ^ vsw_l) << 4));
                     o_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf), o_acc[t], 0, 0, 0);
                 }
@@ -322,6 +333,10 @@ attention_combine_kernel(bf16* __restrict__ out, const float* __restrict__ part_
 
 }  // namespace
 
+int attention_mfma_heads_per_block(int n_q_heads, int n_kv_heads) {
+    return (n_q_heads / n_kv_heads) % 2 == 0 ? 2 : 1;
+}
+
 bool attention_mfma_supported(int dtype, int head_dim, int n_q_heads, int n_kv_heads) {
     return dtype == CF_BF16 && (head_dim == 64 || head_dim == 128) && n_q_heads % n_kv_heads == 0;
 }
@@ -331,11 +346,16 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
                            const AttnCombine* groups, int n_groups, const int32_t* page_tables,
                            int n_q_heads, KvGeom g) {
     if (n_work <= 0) return;
-    dim3 grid(n_work, n_q_heads);
-    if (g.head_dim == 128)
-        attention_mfma_kernel<128><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+    const bool pair = attention_mfma_heads_per_block(n_q_heads, g.n_kv_heads) == 2;
+    dim3 grid(n_work, pair ? n_q_heads / 2 : n_q_heads);
+    if (g.head_dim == 128 && pair)
+        attention_mfma_kernel<128, 2><<<grid, 512, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+    else if (g.head_dim == 128)
+        attention_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+    else if (pair)
+        attention_mfma_kernel<64, 2><<<grid, 512, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
     else
-        attention_mfma_kernel<64><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
+        attention_mfma_kernel<64, 1><<<grid, 256, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
     if (n_groups > 0) {
         dim3 cgrid(n_groups, n_q_heads, ATTN_BLOCK_ROWS / 4);
         if (g.head_dim == 128)

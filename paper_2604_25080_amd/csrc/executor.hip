@@ -367,7 +367,8 @@ struct MetaWriter {
 // rows.  When a chunk has too few items to fill the GPU (few new tokens over long contexts)
 // and `n_q_heads_split` > 0, the key range of an item is split into slices that run as
 // separate workgroups and are merged afterwards.
-void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int n_q_heads_split) {
+void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int n_q_heads_split,
+                  int heads_per_block) {
     for (int r0 = 0; r0 < ph.T; r0 += chunk_rows) {
         ChunkInfo ci;
         ci.r0 = r0;
@@ -398,10 +399,12 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
         }
         // The recompute items and the new-turn items of a layer are separate launches, so each
         // group gets its own split factor: the one that brings its workgroup count to about 1024.
+        // workgroups that fit the chip at once: 2 per CU of 4 wavefronts, or 1 per CU of 8
+        const int64_t resident = heads_per_block == 2 ? 256 : 512;
         auto factor_for = [&](int n_items) {
             if (n_q_heads_split <= 0 || n_items <= 0) return 1;
-            int64_t blocks = (int64_t)n_items * n_q_heads_split;
-            return blocks < 512 ? (int)((1024 + blocks - 1) / blocks) : 1;
+            int64_t blocks = (int64_t)n_items * (n_q_heads_split / heads_per_block);
+            return blocks < resident ? (int)((2 * resident + blocks - 1) / blocks) : 1;
         };
         const int factor_rec = factor_for(n_rec_attending);
         const int factor_new = factor_for((int)items.size() - n_items_rec);
@@ -709,7 +712,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     };
     auto finish_phase = [&](Phase& ph, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
                             std::vector<int32_t>& slot) {
-        build_chunks(ph, c->cv.chunk_rows, pt_off, split_heads);
+        build_chunks(ph, c->cv.chunk_rows, pt_off, split_heads,
+                     split_heads ? attention_mfma_heads_per_block(m.n_q_heads, m.n_kv_heads) : 1);
         ph.off_ids = mw.put(ids.data(), ids.size() * 4);
         ph.off_pos = mw.put(pos.data(), pos.size() * 4);
         ph.off_slot = mw.put(slot.data(), slot.size() * 4);

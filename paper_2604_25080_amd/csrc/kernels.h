@@ -80,6 +80,8 @@ void launch_attention_simple(hipStream_t s, int dtype, const void* q, void* out,
                              const void* pool_layer, const AttnWork* work, int n_work,
                              const int32_t* page_tables, int n_q_heads, KvGeom g);
 bool attention_mfma_supported(int dtype, int head_dim, int n_q_heads, int n_kv_heads);
+// query heads one workgroup of the MFMA attention kernel works on (they share the K/V tiles)
+int attention_mfma_heads_per_block(int n_q_heads, int n_kv_heads);
 void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_buf,
                            const void* pool_layer, const AttnWork* work, int n_work,
                            const AttnCombine* groups, int n_groups, const int32_t* page_tables,
