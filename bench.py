@@ -175,9 +175,12 @@ def main():
                              int(tm["copy_ms"] * 1e9))
         return splits, stats, tm
 
+    # HIP events bracket every launch of a profiled kernel class and cost stream time, so the
+    # warm-up and the timed steps time the dominant kernel only (the roofline needs its live
+    # average over the timed region); the per-kernel table comes from one extra step afterwards
+    sess.ctx.profile(["gemm_gate_up"])
     for _ in range(args.warmup):
         step()
-    sess.ctx.profile(prof_kernels)
     sess.ctx.profile_read(reset=True)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
@@ -188,6 +191,9 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
     prof = sess.ctx.profile_read(reset=True)
+    sess.ctx.profile(prof_kernels)
+    step()
+    prof_all = sess.ctx.profile_read(reset=True)
     sess.ctx.profile([])
 
     ms_per_step = wall / args.steps * 1e3
@@ -217,17 +223,17 @@ def main():
                     "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
                     "traffic": traffic, "launches": dom["launches"], "avg_launch_ms": avg_ms,
                     "flops_per_launch": dom["work"] / dom["launches"]}
-    kernels = {}
+    kernels = {}      # from the one extra step after the timed region, every class profiled
     for k in prof_kernels:
-        p = prof[k]
+        p = prof_all[k]
         if not p["launches"]:
             continue
         rate = p["work"] / (p["total_ms"] * 1e-3)
-        kernels[k] = {"launches": p["launches"], "total_ms_per_step": p["total_ms"] / args.steps,
+        kernels[k] = {"launches": p["launches"], "total_ms_per_step": p["total_ms"],
                       ("GB/s" if k in ("h2d_copy", "page_scatter") else "TFLOP/s"):
                           rate / (1e9 if k in ("h2d_copy", "page_scatter") else 1e12)}
-    all_gemm_ms = sum(prof[k]["total_ms"] for k in gemm_kernels)
-    all_gemm_fl = sum(prof[k]["work"] for k in gemm_kernels)
+    all_gemm_ms = sum(prof_all[k]["total_ms"] for k in gemm_kernels)
+    all_gemm_fl = sum(prof_all[k]["work"] for k in gemm_kernels)
     copy_gbs = loaded_bytes / (copy_ms * 1e-3) / 1e9 if copy_ms > 0 and loaded_bytes else 0.0
 
     out = {
