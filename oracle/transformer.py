@@ -201,6 +201,33 @@ def restore(shape, weights, ctx_tokens, kv_full, k_tokens, layer_cut,
     return cache
 
 
+def restore_stage(shape, weights, boundary_h, kv_full, k_tokens, layer_cut,
+                  layer_begin, layer_end, n_tokens, dtype=np.float64, act="exact"):
+    """Restoration of ONE pipeline stage's layers [layer_begin, layer_end) of a
+    request (Sec. 3.2): the stage holds the hidden states entering its first
+    layer ("boundary activations", boundary_h[n, d]) and recomputes cells
+    (token < k_tokens, layer_begin <= layer < layer_begin + layer_cut) from the
+    first k_tokens rows of them, with no input from any other stage; every
+    other cell of the stage is taken from the stored cache.  Layers outside
+    the stage are left as None.  layer_begin = 0 with boundary_h = the token
+    embeddings is plain `restore`."""
+    assert 0 <= layer_begin < layer_end <= shape.n_layers
+    assert 0 <= k_tokens <= n_tokens and 0 <= layer_cut <= layer_end - layer_begin
+    cache = KVCache(shape.n_layers)
+    for l in range(layer_begin, layer_end):
+        cache.k[l] = np.array(kv_full.k[l][:n_tokens], dtype=dtype, copy=True)
+        cache.v[l] = np.array(kv_full.v[l][:n_tokens], dtype=dtype, copy=True)
+    if k_tokens > 0 and layer_cut > 0:
+        h = np.asarray(boundary_h[:k_tokens], dtype=dtype)
+        positions = np.arange(k_tokens)
+        gain = weights.norm_gain()
+        for l in range(layer_begin, layer_begin + layer_cut):
+            h, k, v = layer_forward(shape, weights.layer_f32(l), gain, h, positions, None, None, dtype, act)
+            cache.k[l][:k_tokens] = k
+            cache.v[l][:k_tokens] = v
+    return cache
+
+
 def first_token_logits(shape, weights, cache, new_tokens, dtype=np.float64, act="exact"):
     """Prefill the new-turn tokens over a restored cache; return (logits at
     the last new token, KVCache of the new tokens' own K/V)."""

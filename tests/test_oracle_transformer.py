@@ -347,3 +347,35 @@ def test_bf16_storage_alone_moves_kv_by_more_than_2e_2_at_width_4096():
     assert 1.0 < exact.k[1].std() < 1.6
     assert np.abs(stored.k[1] - exact.k[1]).max() > 2e-2
     assert np.abs(stored.k[1] - exact.k[1]).max() < 0.2          # ... but it is rounding, not a bug
+
+
+def test_stage_restore_from_boundary_activations_equals_full_prefill():
+    """Sec. 3.2: a pipeline stage restores its own layers from the hidden states entering its
+    first layer, with nothing from the stages below.  For every stage of a 3-layer model and
+    every (k, cut) the stage's cells equal the full prefill; stage [0, L) from the embeddings is
+    plain restore; the stages together tile the model (Eq. 2 divides the work by S)."""
+    shape = SHAPES["mini-bf16"].with_layers(3).with_vocab(300)
+    ws = WeightSource(shape, 77, cache=True)
+    rng = np.random.default_rng(5)
+    toks = rng.integers(0, 300, size=40).astype(np.int32)
+    full, _, hidden_in = T.prefill(shape, ws, toks, return_hidden=True)
+    assert np.array_equal(hidden_in[0], T.embed(ws, toks))
+    for b, e in ((0, 3), (0, 1), (1, 3), (1, 2), (2, 3)):
+        for k in (0, 1, 17, 40):
+            for cut in range(0, e - b + 1):
+                # poison what a correct stage restore must overwrite
+                stored = full.copy()
+                for l in range(b, b + cut):
+                    stored.k[l][:k] = np.nan
+                    stored.v[l][:k] = np.nan
+                got = T.restore_stage(shape, ws, hidden_in[b], stored, k, cut, b, e, len(toks))
+                for l in range(shape.n_layers):
+                    if b <= l < e:
+                        assert np.abs(got.k[l] - full.k[l]).max() <= 1e-10
+                        assert np.abs(got.v[l] - full.v[l]).max() <= 1e-10
+                    else:
+                        assert got.k[l] is None and got.v[l] is None
+    plain = T.restore(shape, ws, toks, full, 17, 2)
+    staged = T.restore_stage(shape, ws, T.embed(ws, toks), full, 17, 2, 0, 3, len(toks))
+    for l in range(3):
+        assert np.array_equal(plain.k[l], staged.k[l]) and np.array_equal(plain.v[l], staged.v[l])
