@@ -234,6 +234,13 @@ typedef struct cf_request {
     const void* host_kv;           /* PINNED host block (layout above); may be NULL
                                       iff the split loads nothing                  */
     const int32_t* new_tokens;     /* host int32[n_new]                            */
+    const float* boundary_h;       /* host float[n_ctx][d_model] (pinned for speed):
+                                      the hidden states entering the stage's first
+                                      layer (Sec. 3.2, boundary activations); rows
+                                      [0,k_tokens) are read.  Needed iff the context
+                                      restores a stage that starts above layer 0
+                                      (cf_ctx_set_stage) and the split recomputes;
+                                      NULL otherwise                               */
 } cf_request;
 
 typedef struct cf_timing {
@@ -336,6 +343,27 @@ int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on);
  * scatter kernel (works for any host memory; pageable memory is slow).
  * Results are identical.                                                    */
 int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgroups);
+
+/* Stage restriction (Sec. 3.2, Eq. 2: with S pipeline stages every stage
+ * restores its own layers independently, from the hidden states it cached at
+ * its input).  After cf_ctx_set_stage(ctx, b, e), 0 <= b < e <= n_layers,
+ * cf_restore_batch touches only layers [b, e): a split's layer_cut is counted
+ * from b (0..e-b), recompute of tokens [0,k) starts from cf_request.boundary_h
+ * instead of the token embeddings when b > 0, loads cover the stage's layers
+ * of the host block (which keeps the full-model layout), and logits_out must
+ * be NULL unless the stage is the whole model.  Plan a stage with
+ * cf_plan_opts.n_layers = e - b.  Default: the whole model.                  */
+int cf_ctx_set_stage(cf_ctx* ctx, int32_t layer_begin, int32_t layer_end);
+
+/* One-shot capture of boundary activations: during the NEXT cf_restore_batch,
+ * when the compute stream reaches `layer` (model numbering), the residual
+ * stream of the packed rows active in that layer is copied to dev_out, a
+ * DEVICE float[cap_rows][d_model].  Packed row order: recompute rows of the
+ * requests in order of descending layer cut (call order among equals), then
+ * the new-turn rows when logits are produced.  This is how a stage's
+ * cf_request.boundary_h is manufactured from a full prefill.  The call fails
+ * with CF_ERR_WORKSPACE if more than cap_rows rows are active.               */
+int cf_ctx_capture_boundary(cf_ctx* ctx, int32_t layer, float* dev_out, int64_t cap_rows);
 
 /* Emulation of a slower storage tier or link (the bandwidth ablation of the
  * paper's evaluation): with gb_per_s > 0 the copy stream of cf_restore_batch

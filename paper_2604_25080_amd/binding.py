@@ -76,7 +76,8 @@ class cf_ctx_opts(C.Structure):
 
 class cf_request(C.Structure):
     _fields_ = [("req_id", C.c_uint64), ("ctx_tokens", C.c_void_p), ("n_ctx", C.c_int32),
-                ("n_new", C.c_int32), ("host_kv", C.c_void_p), ("new_tokens", C.c_void_p)]
+                ("n_new", C.c_int32), ("host_kv", C.c_void_p), ("new_tokens", C.c_void_p),
+                ("boundary_h", C.c_void_p)]
 
 
 class cf_timing(C.Structure):
@@ -132,6 +133,8 @@ lib.cf_ctx_set_kernel_set.argtypes = [C.c_void_p, C.c_int32]
 lib.cf_ctx_set_pipelined_join.argtypes = [C.c_void_p, C.c_int32]
 lib.cf_ctx_set_load_path.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
 lib.cf_ctx_set_link_throttle.argtypes = [C.c_void_p, C.c_double]
+lib.cf_ctx_set_stage.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+lib.cf_ctx_capture_boundary.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
 lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request), _P(cf_split),
                                  C.c_void_p, _P(cf_timing)]
 lib.cf_offload.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]
@@ -149,7 +152,7 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", 
            "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
-           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_restore_batch", "cf_offload",
+           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_ctx_set_stage", "cf_ctx_capture_boundary", "cf_restore_batch", "cf_offload",
            "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
            "cf_ctx_profile_read", "cf_read_final_hidden"]
 
@@ -319,6 +322,15 @@ class Ctx:
         """path: 0 auto, 1 staged DMA + scatter, 2 direct load kernel."""
         _check(lib.cf_ctx_set_load_path(self.handle, int(path), int(n_workgroups)), "cf_ctx_set_load_path")
 
+    def set_stage(self, layer_begin, layer_end):
+        """Restrict restore_batch to layers [layer_begin, layer_end) (one pipeline stage)."""
+        _check(lib.cf_ctx_set_stage(self.handle, int(layer_begin), int(layer_end)), "cf_ctx_set_stage")
+
+    def capture_boundary(self, layer, dev_ptr, cap_rows):
+        """One shot: the next restore_batch copies the rows entering `layer` to dev_ptr (float[cap_rows][d])."""
+        _check(lib.cf_ctx_capture_boundary(self.handle, int(layer), dev_ptr, int(cap_rows)),
+               "cf_ctx_capture_boundary")
+
     def set_link_throttle(self, gb_per_s):
         """Pace the copy stream to gb_per_s GB/s (0: off)."""
         _check(lib.cf_ctx_set_link_throttle(self.handle, float(gb_per_s)), "cf_ctx_set_link_throttle")
@@ -335,7 +347,7 @@ class Ctx:
             keep += [ct, nt]
             arr[i] = cf_request(r["req_id"], ct.ctypes.data if len(ct) else None, len(ct),
                                 len(nt), r.get("host_kv") or None,
-                                nt.ctypes.data if len(nt) else None)
+                                nt.ctypes.data if len(nt) else None, r.get("boundary_h") or None)
         sp = (cf_split * max(b, 1))(*[cf_split(*s) for s in splits])
         tm = cf_timing()
         _check(lib.cf_restore_batch(self.handle, cache.handle, b, arr, sp, logits_ptr or None,

@@ -107,6 +107,10 @@ struct cf_ctx {
     bool pipelined = true;            // new-turn rows ride along with the recompute pass
     int load_path = 0;                // 0 auto, 1 staged DMA + scatter, 2 direct load kernel
     int load_wgs = 8;                 // resident workgroups of the direct load kernel
+    int stage_begin = 0, stage_end = 0;   // layers this context restores (one pipeline stage)
+    int capture_layer = -1;               // next call: copy the rows entering this layer ...
+    float* capture_out = nullptr;         // ... to this device array [rows][d]
+    int64_t capture_cap_rows = 0;
     double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
@@ -203,6 +207,8 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
     c->ps = (hipStream_t)copy_stream;
     c->ws = (char*)workspace;
     c->cv = cv;
+    c->stage_begin = 0;
+    c->stage_end = desc->n_layers;
     c->simple_only = false;
     auto bail = [&](int code) { cf_ctx_destroy(c); return code; };
 #define CF_HIP_CTX(call)                                                                      \
@@ -279,6 +285,26 @@ extern "C" int cf_ctx_set_load_path(cf_ctx* ctx, int32_t path, int32_t n_workgro
     return CF_OK;
 }
 
+extern "C" int cf_ctx_set_stage(cf_ctx* ctx, int32_t layer_begin, int32_t layer_end) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_stage: null ctx");
+    if (layer_begin < 0 || layer_begin >= layer_end || layer_end > ctx->m.n_layers)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_stage: need 0 <= begin < end <= %d, got [%d, %d)",
+                    ctx->m.n_layers, layer_begin, layer_end);
+    ctx->stage_begin = layer_begin;
+    ctx->stage_end = layer_end;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_capture_boundary(cf_ctx* ctx, int32_t layer, float* dev_out, int64_t cap_rows) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_capture_boundary: null ctx");
+    if (layer < 0 || layer >= ctx->m.n_layers || !dev_out || cap_rows <= 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_capture_boundary: bad layer or buffer");
+    ctx->capture_layer = layer;
+    ctx->capture_out = dev_out;
+    ctx->capture_cap_rows = cap_rows;
+    return CF_OK;
+}
+
 extern "C" int cf_ctx_set_link_throttle(cf_ctx* ctx, double gb_per_s) {
     if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_link_throttle: null ctx");
     if (!(gb_per_s >= 0) || gb_per_s > 1e6)
@@ -321,6 +347,7 @@ struct ChunkInfo {
 struct Phase {
     int T = 0;
     std::vector<Segment> segs;          // packed order; `layers` non-increasing
+    std::vector<const float*> seg_boundary;   // per segment: host hidden states of its rows, or null
     std::vector<ChunkInfo> chunks;
     std::vector<AttnWork> work;
     std::vector<AttnCombine> groups;
@@ -467,8 +494,12 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 // in place (null entry = nothing is loaded for it); the attention of the new-turn rows of a
 // layer waits for it, everything else of the layer does not.  `ev_rec_done` is recorded after
 // the last layer in which a recompute row is active.
+// Layers are counted from the context's stage: layer l here is layer stage_begin + l of the model.
+// A stage above layer 0 has no embedding to start from: its rows start from the boundary
+// activations the caller holds for them (copied into h ahead of the first layer).
 int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
               const hipEvent_t* layer_ready, hipEvent_t ev_rec_done) {
+    const int layer0 = c->stage_begin;
     const cf_model_desc& m = c->m;
     int last_rec_layer = -1;
     for (const Segment& sg : ph.segs)
@@ -495,15 +526,34 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                      attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads);
     const bool any_new = ph.rec_rows() < ph.T;
 
-    c->prof_begin(CF_K_EMBED, (double)ph.T * d * (es + 4), c->cs);
-    launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, d);
-    c->prof_end(CF_K_EMBED, c->cs);
+    if (layer0 == 0) {
+        c->prof_begin(CF_K_EMBED, (double)ph.T * d * (es + 4), c->cs);
+        launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, d);
+        c->prof_end(CF_K_EMBED, c->cs);
+    } else {
+        for (size_t si = 0; si < ph.segs.size(); ++si) {
+            const Segment& sg = ph.segs[si];
+            if (sg.n_rows <= 0) continue;
+            CF_HIP(hipMemcpyAsync(c->h() + (size_t)sg.row0 * d, ph.seg_boundary[si],
+                                  (size_t)sg.n_rows * d * sizeof(float), hipMemcpyHostToDevice, c->cs));
+        }
+    }
     for (int l = 0; l < n_layers_max; ++l) {
         const int Ta_rec = ph.rec_active(l, 0);    // recompute rows that need K/V in this layer
         const int Tn_rec = ph.rec_active(l, 1);    // ... and go on through the layer
         if (Ta_rec <= 0 && !any_new) break;
-        const cf_layer_weights& lw = c->layers[l];
-        char* pool_layer = (char*)cache->pool + (size_t)l * g.layer_stride * es;
+        const cf_layer_weights& lw = c->layers[layer0 + l];
+        char* pool_layer = (char*)cache->pool + (size_t)(layer0 + l) * g.layer_stride * es;
+        if (c->capture_out && c->capture_layer == layer0 + l) {
+            // boundary activations: the residual stream of the rows entering this layer
+            int rows = any_new ? ph.T : Ta_rec;
+            if (rows > c->capture_cap_rows)
+                return fail(CF_ERR_WORKSPACE, "cf_restore_batch: boundary capture needs %d rows, buffer holds %lld",
+                            rows, (long long)c->capture_cap_rows);
+            launch_residual_rows(c->cs, c->capture_out, c->h(), l > 0 ? c->dl() : nullptr, rows, d);
+            c->capture_out = nullptr;          // one shot
+            c->capture_layer = -1;
+        }
         for (const ChunkInfo& ci : ph.chunks) {
             // the chunk's rows: recompute rows [r0, r_mid) then new-turn rows [r_mid, r1)
             int rec_end = std::min(ci.r_mid, Ta_rec), rec_cont = std::min(ci.r_mid, Tn_rec);
@@ -623,7 +673,11 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     if (timing) std::memset(timing, 0, sizeof(*timing));
     if (B == 0) return CF_OK;
     size_t es = elem_bytes(m.dtype);
-    const int L = m.n_layers;
+    // the context's stage: layers [Lb, Lb + L) of the model; layer indices below are relative to Lb
+    const int Lb = c->stage_begin, L = c->stage_end - c->stage_begin;
+    if (logits_out && L != m.n_layers)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: logits need the whole model, the context is "
+                    "restricted to layers [%d, %d)", c->stage_begin, c->stage_end);
 
     // ---- validate requests and splits on the host before anything is enqueued
     std::vector<int> pt_off(B), n_pages_req(B);
@@ -652,6 +706,9 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         bool loads = (s.k_tokens < r.n_ctx) || (s.layer_cut < L && r.n_ctx > 0);
         if (recomputes && !r.ctx_tokens)
             return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d recomputes but has no tokens", i);
+        if (recomputes && Lb > 0 && !r.boundary_h)
+            return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d recomputes in a stage that starts at "
+                        "layer %d but has no boundary activations", i, Lb);
         if (loads && !r.host_kv)
             return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d loads but has no host KV", i);
         if (recomputes) {
@@ -702,6 +759,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                            std::vector<int32_t>& slot, int i, const int32_t* toks, int n_rows, int pos0,
                            int layers, bool is_new) {
         Segment sg{i, ph.T, n_rows, pos0, layers, is_new};
+        ph.seg_boundary.push_back(is_new ? nullptr : reqs[i].boundary_h);
         for (int t = 0; t < n_rows; ++t) {
             ids.push_back(toks[t]);
             pos.push_back(pos0 + t);
@@ -748,6 +806,9 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         }
         finish_phase(suf, ids, pos, slot);
     }
+    if (c->capture_out && std::max(rec.T, suf.T) > c->capture_cap_rows)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_batch: boundary capture buffer holds %lld rows, the call packs %d",
+                    (long long)c->capture_cap_rows, std::max(rec.T, suf.T));
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
     c->last_rows = last_rows;
 
@@ -829,8 +890,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                     layer_loads.push_back(LayerLoad{l, (int)jobs.size(), 0, 0, 0});
                 LayerLoad& ll = layer_loads.back();
                 PageJob jb;
-                jb.staging_off = (int64_t)(uintptr_t)(host_dev[i] + ((size_t)l * np_ctx + j) * pb);
-                jb.layer = l;
+                jb.staging_off = (int64_t)(uintptr_t)(host_dev[i] + ((size_t)(Lb + l) * np_ctx + j) * pb);
+                jb.layer = Lb + l;
                 jb.pt_off = pt_off[i];
                 jb.page_first = j;
                 jb.n_pages = j1 - j;
@@ -850,7 +911,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                 if (room == 0) { flush(); continue; }
                 int take = (int)std::min<size_t>(room, (size_t)(j1 - j));
                 size_t dst = (size_t)cur.slot * slot_cap + fill;
-                const char* src = (const char*)r.host_kv + ((size_t)l * np_ctx + j) * pb;
+                const char* src = (const char*)r.host_kv + ((size_t)(Lb + l) * np_ctx + j) * pb;
                 size_t bytes = (size_t)take * pb;
                 if (cur.n_ops > 0 && ops.back().src + ops.back().bytes == src &&
                     ops.back().dst_off + ops.back().bytes == dst)
@@ -858,7 +919,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                 else { ops.push_back(CopyOp{dst, src, bytes}); ++cur.n_ops; }
                 PageJob jb;
                 jb.staging_off = (int64_t)dst;
-                jb.layer = l;
+                jb.layer = Lb + l;
                 jb.pt_off = pt_off[i];
                 jb.page_first = j;
                 jb.n_pages = take;
@@ -1161,6 +1222,9 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
                             cf_cost_model* out) {
     if (!c || !cache || !host_buf || !out) return fail(CF_ERR_INVALID_ARG, "cf_calibrate: null argument");
     const cf_model_desc& m = c->m;
+    if (c->stage_begin != 0 || c->stage_end != m.n_layers)
+        return fail(CF_ERR_INVALID_ARG, "cf_calibrate: calibrate on the whole model (the per-layer costs "
+                    "it measures hold for any stage)");
     const int L = m.n_layers;
     // probe sizes: bounded by the context limits
     int t_big = std::min(std::min(c->opts.max_tokens, c->opts.max_positions), 8192);

@@ -93,6 +93,8 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
 constexpr int PAGE_LOAD_UNIT_VECS = 4096;
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
+// out[T][d] = h (+ dl when non-null): the residual stream of packed rows entering a layer (d % 4 == 0)
+void launch_residual_rows(hipStream_t s, float* out, const float* h, const float* dl, int T, int d);
 // copy-stream pacing: mark stores the wall clock at *t0 (device, 8 bytes), wait holds the stream
 // until `ticks` wall-clock ticks have passed since the mark (bounded spin)
 void launch_pace_mark(hipStream_t s, void* t0);

@@ -507,6 +507,26 @@ void launch_pace_wait(hipStream_t s, const void* t0, unsigned long long ticks) {
     pace_wait_kernel<<<1, 1, 0, s>>>((const unsigned long long*)t0, ticks);
 }
 
+// out[i] = h[i] (+ dl[i]): the residual stream of packed rows as it enters a layer
+__global__ void __launch_bounds__(256)
+residual_rows_kernel(float* __restrict__ out, const float* __restrict__ h, const float* __restrict__ dl,
+                     int64_t n4) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float4 a = reinterpret_cast<const float4*>(h)[i];
+    if (dl) {
+        float4 b = reinterpret_cast<const float4*>(dl)[i];
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    reinterpret_cast<float4*>(out)[i] = a;
+}
+
+void launch_residual_rows(hipStream_t s, float* out, const float* h, const float* dl, int T, int d) {
+    int64_t n4 = (int64_t)T * d / 4;
+    if (n4 <= 0) return;
+    residual_rows_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, s>>>(out, h, dl, n4);
+}
+
 void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs, int n_jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g) {
     if (n_jobs <= 0 || n_units <= 0) return;

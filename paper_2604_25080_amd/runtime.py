@@ -107,16 +107,18 @@ class Session:
     # ------------------------------------------------------------------ the path
     def restore(self, requests, splits, want_logits=True):
         """requests: list of dict(req_id, ctx_tokens, new_tokens, host_kv=pinned tensor or
-        None).  Returns (logits tensor [B, vocab] or None, timing dict)."""
+        None[, boundary_h=float32 host tensor [n_ctx, d] for a stage above layer 0]).
+        Returns (logits tensor [B, vocab] or None, timing dict)."""
         # the library's streams do not order against torch's: finish pending torch work
         # (fills, copies into the pool) before the blocking call
         torch.cuda.current_stream(self.device).synchronize()
         reqs = []
         for r in requests:
-            hk = r.get("host_kv")
+            hk, bh = r.get("host_kv"), r.get("boundary_h")
             reqs.append(dict(req_id=r["req_id"], ctx_tokens=r["ctx_tokens"],
                              new_tokens=r["new_tokens"],
-                             host_kv=hk.data_ptr() if hk is not None else 0))
+                             host_kv=hk.data_ptr() if hk is not None else 0,
+                             boundary_h=(bh.data_ptr() if hasattr(bh, "data_ptr") else bh) if bh is not None else 0))
         tm = self.ctx.restore_batch(self.cache, reqs, splits,
                                     self.logits.data_ptr() if want_logits else 0)
         return (self.logits[:len(requests)] if want_logits else None), tm

@@ -155,3 +155,98 @@ def test_head_dim_64_bf16_model():
         restore_and_compare(b, refs, sess, host, [((n // 2), 1) for n in b.n_ctx], seed=52)
     finally:
         sess.close()
+
+
+def test_stage_restore_from_boundary_activations(mini):
+    """One pipeline stage's share (Sec. 3.2): the context is restricted to layers [b, e), recompute
+    starts from the oracle's hidden states entering layer b, loads cover only the stage's layers
+    of the host block; layers outside the stage keep their sentinel bytes."""
+    import paper_2604_25080_amd as cf
+    b, refs, sess, host = mini
+    L = b.shape.n_layers
+    ws = WeightSource(b.shape, b.weight_seed, cache=True)
+    hidden = [T.prefill(b.shape, ws, b.ctx_tokens[i], return_hidden=True)[2] for i in range(len(b.n_ctx))]
+    rng = np.random.default_rng(9)
+    try:
+        for (lb, le) in ((1, 3), (1, 2), (2, 3), (0, 2)):
+            sess.ctx.set_stage(lb, le)
+            sess.pool.fill_(0xFF)
+            reqs, splits = [], []
+            for i, n in enumerate(b.n_ctx):
+                sess.cache.alloc(1 + i, n + b.n_new[i])
+                bh = torch.from_numpy(np.ascontiguousarray(hidden[i][lb], dtype=np.float32)).pin_memory()
+                reqs.append(dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i],
+                                 host_kv=host[i], boundary_h=bh.data_ptr(), _keep=bh))
+                splits.append((0, int(rng.integers(0, n + 1)), int(rng.integers(0, le - lb + 1))))
+            splits[0] = (0, b.n_ctx[0], le - lb)              # one request recomputes its whole stage
+            # logits need the whole model
+            with pytest.raises(cf.CfError):
+                sess.restore(reqs, splits, want_logits=True)
+            _, tm = sess.restore(reqs, splits, want_logits=False)
+            assert tm["loaded_cells"] + tm["recomputed_cells"] == sum(b.n_ctx) * (le - lb)
+            for i, n in enumerate(b.n_ctx):
+                raw = sess.read_pages(1 + i, n)
+                k, v = decode_pages(b.shape, raw, n)
+                rk, rv = stack_kv(b.shape, refs[i][0], refs[i][1])
+                for l in range(L):
+                    if lb <= l < le:
+                        for got, ref, nm in ((k[l], rk[l, :n], "K"), (v[l], rv[l, :n], "V")):
+                            ok, worst, _ = kv_tolerance_ok(b.shape, got, ref)
+                            assert ok, f"stage [{lb},{le}) request {i} layer {l} {nm}: {worst} (split {splits[i]})"
+                    else:
+                        full_pages = n // 16
+                        assert (raw[l, :full_pages] == 0xFF).all(), f"layer {l} outside the stage was written"
+                sess.cache.free(1 + i)
+            if lb > 0:
+                # recompute in a stage above layer 0 without boundary activations is refused
+                sess.cache.alloc(1, b.n_ctx[0] + b.n_new[0])
+                with pytest.raises(cf.CfError):
+                    sess.restore([dict(reqs[0], boundary_h=None)], [splits[0]], want_logits=False)
+                sess.cache.free(1)
+    finally:
+        sess.ctx.set_stage(0, L)
+        for i in range(len(b.n_ctx)):
+            try:
+                sess.cache.free(1 + i)
+            except Exception:
+                pass
+
+
+def test_captured_boundary_reproduces_the_full_prefill_bit_for_bit(mini):
+    """cf_ctx_capture_boundary during a full GPU prefill, then a stage restore that recomputes from
+    the captured rows: the stage's pages are bit-identical to the full prefill's, and the captured
+    rows are the oracle's hidden states entering that layer (to bf16-pipeline accuracy)."""
+    b, refs, sess, host = mini
+    L, d = b.shape.n_layers, b.shape.d_model
+    ws = WeightSource(b.shape, b.weight_seed, cache=True)
+    B = len(b.n_ctx)
+    reqs = [dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=None)
+            for i in range(B)]
+    try:
+        for i in range(B):
+            sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
+        lb = 1
+        cap = torch.zeros(sum(b.n_ctx), d, dtype=torch.float32, device="cuda")
+        sess.ctx.capture_boundary(lb, cap.data_ptr(), cap.shape[0])
+        sess.restore(reqs, [(0, n, L) for n in b.n_ctx], want_logits=False)
+        full = [sess.read_pages(1 + i, b.n_ctx[i]).copy() for i in range(B)]
+        rows = cap.cpu()
+        off = 0
+        for i, n in enumerate(b.n_ctx):                      # packed order = call order (equal cuts)
+            ref = T.prefill(b.shape, ws, b.ctx_tokens[i], return_hidden=True)[2][lb]
+            got = rows[off:off + n].numpy()
+            assert np.abs(got - ref).max() <= 2e-2 * max(1.0, np.abs(ref).max())
+            reqs[i]["boundary_h"] = rows[off:off + n].contiguous().pin_memory()
+            off += n
+        sess.pool.fill_(0xFF)
+        sess.ctx.set_stage(lb, L)
+        sess.restore(reqs, [(0, n, L - lb) for n in b.n_ctx], want_logits=False)
+        for i, n in enumerate(b.n_ctx):
+            got = sess.read_pages(1 + i, n)
+            k0, v0 = decode_pages(b.shape, full[i][lb:], n)
+            k1, v1 = decode_pages(b.shape, got[lb:], n)
+            assert np.array_equal(k0, k1) and np.array_equal(v0, v1), f"request {i}"
+    finally:
+        sess.ctx.set_stage(0, L)
+        for i in range(B):
+            sess.cache.free(1 + i)

@@ -40,7 +40,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_split) == 12
     assert ctypes.sizeof(cf.cf_plan_stats) == 32
     assert ctypes.sizeof(cf.cf_model_desc) == 40
-    assert ctypes.sizeof(cf.cf_request) == 40
+    assert ctypes.sizeof(cf.cf_request) == 48
     assert ctypes.sizeof(cf.cf_timing) == 64
 
 
