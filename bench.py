@@ -75,6 +75,9 @@ def main():
                     help="direct: load kernel reading pinned host memory; staged: DMA + scatter")
     ap.add_argument("--load-workgroups", type=int, default=0,
                     help="resident workgroups of the direct load kernel (0: library default)")
+    ap.add_argument("--stage", default="",
+                    help="b:e -- restore only layers [b, e), one pipeline stage's share, recomputing from "
+                         "boundary activations captured at layer b (no logits; value = the stage's tokens/s)")
     ap.add_argument("--link-gbps", type=float, default=0.0,
                     help="pace the copy stream to this many Gbit/s (emulates a slower storage tier; 0: off)")
     ap.add_argument("--sequential-join", action="store_true",
@@ -116,7 +119,19 @@ def main():
         sess.cache.alloc(1 + i, batch.n_ctx[i] + batch.n_new[i])
         reqs.append(dict(req_id=1 + i, ctx_tokens=batch.ctx_tokens[i], new_tokens=batch.new_tokens[i],
                          host_kv=None))
+    stage = tuple(int(x) for x in args.stage.split(":")) if args.stage else None
+    if stage:
+        cap = torch.empty(sum_ctx, shape.d_model, dtype=torch.float32, device="cuda")
+        sess.ctx.capture_boundary(stage[0], cap.data_ptr(), sum_ctx)
     _, tm_full = sess.restore(reqs, [(0, n, L) for n in batch.n_ctx], want_logits=False)
+    if stage:      # packed order of an all-recompute pass with equal cuts = call order
+        off = 0
+        for i in range(B):
+            bh = torch.empty(batch.n_ctx[i], shape.d_model, dtype=torch.float32, pin_memory=True)
+            bh.copy_(cap[off:off + batch.n_ctx[i]])
+            reqs[i]["boundary_h"] = bh
+            off += batch.n_ctx[i]
+        del cap
     for i in range(B):
         reqs[i]["host_kv"] = sess.pinned(sess.host_kv_bytes(batch.n_ctx[i]))
     t_off = time.perf_counter()
@@ -142,6 +157,12 @@ def main():
     cm = sess.ctx.calibrate(sess.cache, scratch.data_ptr(), scratch.numel())
     cost = dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io, gamma=cm.gamma,
                 s_c=cm.s_c, s_io=cm.s_io)
+    if stage:
+        # the stage's share: plan and restore layers [b, e) only; the compute start-up that
+        # calibration measured is per layer of the pass
+        sess.ctx.set_stage(*stage)
+        cm.s_c = cm.s_c * (stage[1] - stage[0]) // L
+        L = stage[1] - stage[0]
     opts = cf.plan_opts(batch.chunk_tokens, 0, L, shape.kv_bytes_per_token_layer, batch.forced_mode)
     l_delta = cf.derive_l_delta(cm, opts, 32768)
     opts.l_delta = l_delta
@@ -167,7 +188,7 @@ def main():
 
     def step():
         splits, stats = make_plan()
-        logits, tm = sess.restore(reqs, splits)
+        logits, tm = sess.restore(reqs, splits, want_logits=not stage)
         if stats is not None:
             # closed loop: correct the cost model by what the two streams actually took (they
             # slow each other down when they overlap, which calibration in isolation cannot see)
@@ -243,6 +264,9 @@ def main():
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{args.config}: {shape.name} shape, B={B}, sum n_ctx={sum_ctx}, "
                                f"n_new={sum_new}, plan={args.plan}, chunk C={batch.chunk_tokens}, "
+                               + (f"stage layers [{stage[0]},{stage[1]}) of {shape.n_layers} from boundary activations, "
+                                  if stage else "") +
+                               
                                f"{'sequential' if args.sequential_join else 'pipelined'} join",
                    "n_ctx": batch.n_ctx, "splits": [list(s) for s in splits]},
         "ttft_ms": ttft_ms, "restore_ms": restore_ms, "compute_stream_ms": compute_ms,
