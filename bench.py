@@ -168,12 +168,30 @@ def main():
     opts.l_delta = l_delta
     log(f"[bench] H2D {h2d_gbs:.1f} GB/s; cost model {cost}; L_delta {l_delta}")
 
+    def plan_model():
+        """The cost table the planner sees: with the pipelined join the new-turn prefill shares
+        the compute stream with the recompute, so its cost starts the compute clock."""
+        if stage or args.sequential_join:
+            return cm
+        m2 = cf.cost_model(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io, gamma=cm.gamma,
+                           s_c=cm.s_c, s_io=cm.s_io)
+        m2.s_c += cf.prefill_cost(cm, shape.n_layers, batch.n_ctx, batch.n_new)
+        return m2
+
     def make_plan():
         if args.plan == "planner":
             if batch.forced_splits:
                 return [(0, k, c) for k, c in batch.forced_splits], None
-            splits, stats, _ = cf.restore_plan(cm, opts, batch.n_ctx)
+            splits, stats, _ = cf.restore_plan(plan_model(), opts, batch.n_ctx)
             return splits, stats
+        if args.plan == "per_request":
+            # comparison plan: every request planned alone, as if it had both engines to itself
+            # (a per-request bidirectional planner); no batch awareness
+            out = []
+            for n in batch.n_ctx:
+                sp, _, _ = cf.restore_plan(plan_model(), opts, [n])
+                out.append(sp[0])
+            return out, None
         if args.plan == "all_recompute":
             return [(0, n, L) for n in batch.n_ctx], None
         if args.plan == "all_load":

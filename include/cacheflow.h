@@ -142,6 +142,15 @@ int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
 int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t meas_comp, int64_t pred_io,
                      int64_t meas_io);
 
+/* Compute-clock cost (ps) of the new-turn prefill of a batch: request i runs
+ * n_new[i] tokens from position n_ctx[i] through n_layers layers, priced with
+ * the recompute formula above (Sec. 3: TTFT = restoration + this prefill).
+ * With the pipelined join that work shares the compute stream with the
+ * recompute, so a caller adds the result to cf_cost_model.s_c before
+ * cf_restore_plan; the planner itself schedules restoration only.  Pure host. */
+int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int32_t B, const int32_t* n_ctx,
+                    const int32_t* n_new, int64_t* out_ps);
+
 /* L_delta = min{N : T_token(N) <= T_layer(N)} (Sec. 3.1, adaptive strategy)
  * searched on multiples of chunk_tokens up to n_max; n_max + C if none.     */
 int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t n_max,

@@ -235,6 +235,15 @@ def all_load(opts, n_ctx):
     return [(TOKEN_WISE, 0, opts.n_layers) for n in n_ctx]
 
 
+def prefill_cost(cm, n_layers, n_ctx, n_new):
+    """Compute-clock cost of the new-turn prefill of a batch: request i runs its n_new[i] new
+    tokens from position n_ctx[i] through all layers (the cost formula of a recompute unit,
+    Sec. 3.1, applied to those rows).  With the pipelined join this work rides on the compute
+    stream beside the recompute, so the caller adds it to the compute start-up s_c before
+    planning; the paper's TTFT = restoration + this."""
+    return sum(compute_cost(cm, n_layers, m, n) for n, m in zip(n_ctx, n_new) if m > 0)
+
+
 def cost_feedback(cm, pred_comp, meas_comp, pred_io, meas_io):
     """Closed-loop correction of the cost model after an executed batch: compute-side
     coefficients times measured/predicted compute time, I/O-side ones times

@@ -110,6 +110,8 @@ lib.cf_restore_plan.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, 
 lib.cf_plan_eval.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
                              _P(cf_split), _P(C.c_int64), _P(C.c_int64)]
 lib.cf_cost_feedback.argtypes = [_P(cf_cost_model), C.c_int64, C.c_int64, C.c_int64, C.c_int64]
+lib.cf_prefill_cost.argtypes = [_P(cf_cost_model), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                _P(C.c_int64)]
 lib.cf_derive_l_delta.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, _P(C.c_int32)]
 lib.cf_cache_create.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                 _P(C.c_void_p)]
@@ -148,7 +150,7 @@ lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_v
                            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                            _P(C.c_float)]
 
-EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", "cf_cost_feedback",
+EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", "cf_cost_feedback", "cf_prefill_cost",
            "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
@@ -202,6 +204,16 @@ def plan_eval(cost, opts, n_ctx, splits):
     _check(lib.cf_plan_eval(C.byref(cost), C.byref(opts), len(n), n.ctypes.data, arr,
                             C.byref(tc), C.byref(tio)), "cf_plan_eval")
     return tc.value, tio.value
+
+
+def prefill_cost(cost, n_layers, n_ctx, n_new):
+    """Compute-clock cost (ps) of the new-turn prefill of a batch under the cost model."""
+    a = np.ascontiguousarray(n_ctx, dtype=np.int32)
+    b = np.ascontiguousarray(n_new, dtype=np.int32)
+    out = C.c_int64()
+    _check(lib.cf_prefill_cost(C.byref(cost), int(n_layers), len(a), a.ctypes.data, b.ctypes.data,
+                               C.byref(out)), "cf_prefill_cost")
+    return out.value
 
 
 def cost_feedback(cost, pred_comp, meas_comp, pred_io, meas_io):

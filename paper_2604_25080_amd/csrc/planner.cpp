@@ -235,6 +235,22 @@ extern "C" int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* 
 // Closed-loop correction of the cost model from one executed batch: the compute-side
 // coefficients are scaled by measured/predicted compute time, the I/O-side ones by
 // measured/predicted I/O time (each clamped to [1/4, 4] per update).  This is how the
+// Compute-clock cost of the new-turn prefill of a batch (the recompute cost formula applied to
+// rows n_ctx[i] .. n_ctx[i]+n_new[i]-1 through n_layers layers).
+extern "C" int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int32_t B,
+                               const int32_t* n_ctx, const int32_t* n_new, int64_t* out_ps) {
+    if (!cost || !out_ps || n_layers < 0 || B < 0 || (B > 0 && (!n_ctx || !n_new)))
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_prefill_cost: bad argument");
+    int64_t total = 0;
+    for (int i = 0; i < B; ++i) {
+        if (n_ctx[i] < 0 || n_new[i] < 0)
+            return cf::fail(CF_ERR_INVALID_ARG, "cf_prefill_cost: request %d has a negative length", i);
+        if (n_new[i] > 0) total += layer_pass_cost(*cost, n_layers, n_new[i], n_ctx[i]);
+    }
+    *out_ps = total;
+    return CF_OK;
+}
+
 // scheduler adapts to what calibration in isolation cannot see: the two engines slow each
 // other down when they run together (Sec. 3.3: priorities follow evolving resource
 // availability).  Integer arithmetic, round to nearest.

@@ -100,6 +100,22 @@ def test_plan_eval_and_l_delta_match_oracle():
         assert cf.derive_l_delta(ccm, co, 20000) == P.derive_l_delta(ocm, oo, 20000)
 
 
+def test_prefill_cost_matches_oracle_and_the_formula_by_hand():
+    cm_kw = hand_cost_model("balanced")
+    ocm, ccm = P.CostModel(**cm_kw), cf.cost_model(**cm_kw)
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        B = int(rng.integers(1, 9))
+        n_ctx = [int(x) for x in rng.integers(0, 20000, size=B)]
+        n_new = [int(x) for x in rng.integers(0, 600, size=B)]
+        L = int(rng.integers(1, 81))
+        assert cf.prefill_cost(ccm, L, n_ctx, n_new) == P.prefill_cost(ocm, L, n_ctx, n_new)
+    # by hand: 3 tokens from position 10 through 2 layers: pairs = 3*10 + 3*4/2 = 36 -> 1 block
+    want = 2 * (ocm.f_c + 3 * ocm.alpha + 1 * ocm.beta)
+    assert cf.prefill_cost(ccm, 2, [10], [3]) == want == P.prefill_cost(ocm, 2, [10], [3])
+    assert cf.prefill_cost(ccm, 2, [10], [0]) == 0
+
+
 def test_cost_feedback_matches_oracle_and_balances_a_contended_plan():
     rng = np.random.default_rng(43)
     for _ in range(200):
