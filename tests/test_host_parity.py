@@ -225,3 +225,14 @@ def test_workspace_and_ctx_argument_checks_need_no_gpu():
     with pytest.raises(cf.CfError) as e:
         cf.workspace_bytes(bad, cf.ctx_opts(2, 256, 256))
     assert e.value.status == cf.CF_ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    """The benchmark runs on one GPU; asking for more ends with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
