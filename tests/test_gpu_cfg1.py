@@ -233,3 +233,45 @@ def test_cfg1_error_paths_return_codes_not_faults(env):
         sess.restore([dict(r, host_kv=None)], [(0, 128, 2)])      # nothing loaded: no host KV needed
     finally:
         sess.cache.free(1)
+
+
+def test_cfg1_degenerate_batches(env):
+    """Empty batch; a request with no context at all (pure new-turn prefill); one new token;
+    a context of one token; all in one batch with an ordinary request."""
+    b, refs, ws, sess, host = env
+    shape = b.shape
+    # empty batch: nothing to do, no error
+    logits, tm = sess.restore([], [])
+    assert tm["loaded_cells"] == 0 and tm["recomputed_cells"] == 0
+    rng = np.random.default_rng(12)
+    cases = [(0, 5), (1, 1), (17, 3), (b.n_ctx[1], b.n_new[1])]
+    toks = [(rng.integers(0, shape.vocab, size=n).astype(np.int32), rng.integers(0, shape.vocab, size=m).astype(np.int32))
+            for n, m in cases[:-1]] + [(b.ctx_tokens[1], b.new_tokens[1])]
+    ref = []
+    for c, nw in toks:
+        if len(c):
+            ref.append(T.full_reference(shape, ws, c, nw))
+        else:                                     # no context: the new turn is the whole sequence
+            kv_new, h = T.prefill(shape, ws, nw)
+            ref.append((None, kv_new, T.logits_last(shape, ws, h[-1])))
+    sess.pool.fill_(0xFF)
+    reqs, splits = [], []
+    try:
+        for i, ((n, m), (c, nw)) in enumerate(zip(cases, toks)):
+            sess.cache.alloc(1 + i, n + m)
+            hk = sess.pin_host_kv(host_block(shape, T.kv_to_pages(shape, ref[i][0], n))) if n else None
+            reqs.append(dict(req_id=1 + i, ctx_tokens=c, new_tokens=nw, host_kv=hk))
+            splits.append((0, n // 2, shape.n_layers))
+        logits, tm = sess.restore(reqs, splits)
+        for i, (n, m) in enumerate(cases):
+            k, v = decode_pages(shape, sess.read_pages(1 + i, n + m), n + m)
+            if n:
+                rk, rv = stack_kv(shape, ref[i][0], ref[i][1])
+            else:
+                rk, rv = np.stack(ref[i][1].k), np.stack(ref[i][1].v)
+            assert np.isfinite(k).all() and np.isfinite(v).all()
+            assert np.abs(k - rk).max() <= 1e-4 and np.abs(v - rv).max() <= 1e-4, f"case {cases[i]}"
+            assert np.abs(logits[i].cpu().numpy() - ref[i][2]).max() <= 1e-4, f"case {cases[i]} logits"
+    finally:
+        for i in range(len(cases)):
+            sess.cache.free(1 + i)
