@@ -163,7 +163,11 @@ def main():
         sess.ctx.set_stage(*stage)
         cm.s_c = cm.s_c * (stage[1] - stage[0]) // L
         L = stage[1] - stage[0]
-    opts = cf.plan_opts(batch.chunk_tokens, 0, L, shape.kv_bytes_per_token_layer, batch.forced_mode)
+    # the executor stops a request's last recomputed layer after its K/V write: price it so
+    qkv_fl = 2.0 * shape.d_model * shape.qkv_cols
+    lin_fl = qkv_fl + 2.0 * shape.n_q_heads * shape.head_dim * shape.d_model + 6.0 * shape.d_model * shape.d_ffn
+    opts = cf.plan_opts(batch.chunk_tokens, 0, L, shape.kv_bytes_per_token_layer, batch.forced_mode,
+                        kv_only_permille=int(round(1000 * qkv_fl / lin_fl)))
     l_delta = cf.derive_l_delta(cm, opts, 32768)
     opts.l_delta = l_delta
     log(f"[bench] H2D {h2d_gbs:.1f} GB/s; cost model {cost}; L_delta {l_delta}")
@@ -210,7 +214,14 @@ def main():
         if stats is not None:
             # closed loop: correct the cost model by what the two streams actually took (they
             # slow each other down when they overlap, which calibration in isolation cannot see)
-            cf.cost_feedback(cm, stats["t_comp"], int(tm["compute_ms"] * 1e9), stats["t_io"],
+            # The plan's t_comp is when the compute stream would finish ALL its work, the
+            # new-turn prefill included.  cf_timing.compute_ms marks the end of the last
+            # recomputed layer, which is the same thing for token-wise splits (cut = L) but not
+            # for a low layer cut, where the new-turn rows still have the upper layers to go:
+            # when the compute stream finishes well after the copy stream, its end is the
+            # measurement.
+            meas_comp = tm["total_ms"] if tm["total_ms"] > 1.02 * tm["copy_ms"] else tm["compute_ms"]
+            cf.cost_feedback(cm, stats["t_comp"], int(meas_comp * 1e9), stats["t_io"],
                              int(tm["copy_ms"] * 1e9))
         return splits, stats, tm
 

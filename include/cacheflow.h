@@ -97,6 +97,17 @@ typedef struct cf_plan_opts {
     int32_t kv_bytes_per_token_layer; /* 2*Hkv*hd*sizeof(elem)                       */
     int32_t force_mode;               /* -1 use l_delta; else a cf_mode for all      */
     int32_t io_key;                   /* cf_io_key                                   */
+    int32_t kv_only_permille;         /* 0: every recomputed layer is priced in full.
+                                         > 0: the executor stops a request's LAST
+                                         recomputed layer after its K/V write, so
+                                         that layer costs f_c + alpha*t*permille/1000
+                                         (rounded up), no attention term: the top
+                                         layer of a token-wise chunk, the first
+                                         claimed layer of a layer-wise request (each
+                                         further claim completes the layer below and
+                                         adds a K/V-only one).  Set it to 1000 x the
+                                         K/V-projection share of a layer's linear
+                                         FLOPs                                       */
 } cf_plan_opts;
 
 typedef struct cf_split {

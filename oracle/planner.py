@@ -60,6 +60,8 @@ class PlanOpts:
     kv_bytes_per_token_layer: int
     force_mode: int = -1            # -1: by l_delta; 0 token-wise; 1 layer-wise
     io_key: int = KEY_REMAINING_COST
+    kv_only_permille: int = 0       # > 0: the last recomputed layer of a request costs only
+                                    # its K/V projection, this many permille of alpha*t
 
 
 def ceil_div(a, b):
@@ -69,6 +71,12 @@ def ceil_div(a, b):
 def compute_cost(cm, n_layers, t, p0):
     pairs = t * p0 + t * (t + 1) // 2
     return n_layers * (cm.f_c + cm.alpha * t + cm.beta * ceil_div(pairs, 1024))
+
+
+def kv_only_cost(cm, permille, t):
+    """The last recomputed layer of a request stops after its K/V write (nothing downstream
+    reads its attention or MLP output): fixed part plus a fraction of the linear part."""
+    return cm.f_c + (cm.alpha * permille * t + 999) // 1000
 
 
 def io_cost(cm, n_bytes):
@@ -90,12 +98,22 @@ def unit_costs(cm, opts, n, mode):
         c = opts.chunk_tokens
         for u in range(ceil_div(n, c)):
             t = min((u + 1) * c, n) - u * c
-            a.append(compute_cost(cm, opts.n_layers, t, u * c))
+            if opts.kv_only_permille > 0:
+                # all layers but the top one in full, the top one K/V only
+                a.append(compute_cost(cm, opts.n_layers - 1, t, u * c) +
+                         kv_only_cost(cm, opts.kv_only_permille, t))
+            else:
+                a.append(compute_cost(cm, opts.n_layers, t, u * c))
             b.append(io_cost(cm, t * opts.n_layers * opts.kv_bytes_per_token_layer))
             tok.append(t)
     else:
-        for _ in range(opts.n_layers):
-            a.append(compute_cost(cm, 1, n, 0))
+        for l in range(opts.n_layers):
+            # claiming layer l turns layer l-1 from K/V-only into a full layer and adds a
+            # K/V-only layer l: the first layer costs K/V only, every further one a full layer
+            if opts.kv_only_permille > 0 and l == 0:
+                a.append(kv_only_cost(cm, opts.kv_only_permille, n))
+            else:
+                a.append(compute_cost(cm, 1, n, 0))
             b.append(io_cost(cm, n * opts.kv_bytes_per_token_layer))
             tok.append(n)
     return a, b, tok

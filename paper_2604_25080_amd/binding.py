@@ -37,7 +37,8 @@ class cf_cost_model(C.Structure):
 
 class cf_plan_opts(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("chunk_tokens", "l_delta", "n_layers",
-                                         "kv_bytes_per_token_layer", "force_mode", "io_key")]
+                                         "kv_bytes_per_token_layer", "force_mode", "io_key",
+                                         "kv_only_permille")]
 
 
 class cf_split(C.Structure):
@@ -175,9 +176,9 @@ def cost_model(f_c, alpha, beta, f_io, gamma, s_c=0, s_io=0):
 
 
 def plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode=-1,
-              io_key=CF_KEY_REMAINING_COST):
+              io_key=CF_KEY_REMAINING_COST, kv_only_permille=0):
     return cf_plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode,
-                        io_key)
+                        io_key, kv_only_permille)
 
 
 def restore_plan(cost, opts, n_ctx, trace_cap=0):

@@ -33,6 +33,12 @@ int64_t layer_pass_cost(const cf_cost_model& cm, int64_t layers, int64_t t, int6
     return layers * (cm.f_c + cm.alpha * t + cm.beta * cf::ceil_div(pairs, 1024));
 }
 
+// The last recomputed layer of a request stops after its K/V write: fixed part plus
+// kv_only_permille / 1000 of the linear part, no attention.
+int64_t kv_only_cost(const cf_cost_model& cm, int64_t permille, int64_t t) {
+    return cm.f_c + (cm.alpha * permille * t + 999) / 1000;
+}
+
 int64_t load_cost(const cf_cost_model& cm, int64_t bytes) {
     // bytes*gamma can exceed 2^63 only for absurd inputs; use 128-bit to be exact
     __int128 num = (__int128)bytes * cm.gamma;
@@ -56,13 +62,19 @@ Units make_units(const cf_cost_model& cm, const cf_plan_opts& o, int n, int mode
         int c = o.chunk_tokens;
         for (int64_t s = 0; s < n; s += c) {
             int64_t t = (s + c <= n) ? c : n - s;
-            u.a_prefix.push_back(u.a_prefix.back() + layer_pass_cost(cm, o.n_layers, t, s));
+            int64_t a = o.kv_only_permille > 0
+                            ? layer_pass_cost(cm, o.n_layers - 1, t, s) + kv_only_cost(cm, o.kv_only_permille, t)
+                            : layer_pass_cost(cm, o.n_layers, t, s);
+            u.a_prefix.push_back(u.a_prefix.back() + a);
             u.b.push_back(load_cost(cm, t * o.n_layers * (int64_t)o.kv_bytes_per_token_layer));
             u.tok_prefix.push_back(u.tok_prefix.back() + t * o.n_layers);
         }
     } else {
         for (int l = 0; l < o.n_layers; ++l) {
-            u.a_prefix.push_back(u.a_prefix.back() + layer_pass_cost(cm, 1, n, 0));
+            // claiming layer l makes layer l-1 a full layer and adds a K/V-only layer l
+            int64_t a = (o.kv_only_permille > 0 && l == 0) ? kv_only_cost(cm, o.kv_only_permille, n)
+                                                           : layer_pass_cost(cm, 1, n, 0);
+            u.a_prefix.push_back(u.a_prefix.back() + a);
             u.b.push_back(load_cost(cm, (int64_t)n * o.kv_bytes_per_token_layer));
             u.tok_prefix.push_back(u.tok_prefix.back() + n);
         }
@@ -77,6 +89,8 @@ int check(const cf_cost_model* cm, const cf_plan_opts* o, int32_t B, const int32
     if (o->chunk_tokens <= 0 || o->n_layers <= 0 || o->kv_bytes_per_token_layer <= 0)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: chunk_tokens, n_layers and KV bytes must be > 0",
                         who);
+    if (o->kv_only_permille < 0 || o->kv_only_permille > 1000)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: kv_only_permille %d not in 0..1000", who, o->kv_only_permille);
     if (o->io_key < 0 || o->io_key > CF_KEY_MARGINAL || o->force_mode < -1 || o->force_mode > 1)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: bad io_key or force_mode", who);
     if (cm->f_c < 0 || cm->alpha < 0 || cm->beta < 0 || cm->f_io < 0 || cm->gamma < 0 ||

@@ -19,8 +19,9 @@ def both_cost(d):
     return P.CostModel(**d), cf.cost_model(**d)
 
 
-def both_opts(chunk, l_delta, n_layers, kvb, mode=-1, key=0):
-    return P.PlanOpts(chunk, l_delta, n_layers, kvb, mode, key), cf.plan_opts(chunk, l_delta, n_layers, kvb, mode, key)
+def both_opts(chunk, l_delta, n_layers, kvb, mode=-1, key=0, kv_only=0):
+    return (P.PlanOpts(chunk, l_delta, n_layers, kvb, mode, key, kv_only),
+            cf.plan_opts(chunk, l_delta, n_layers, kvb, mode, key, kv_only))
 
 
 # ------------------------------------------------------------------ C-ABI surface
@@ -36,7 +37,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_cost_model) == 56
-    assert ctypes.sizeof(cf.cf_plan_opts) == 24
+    assert ctypes.sizeof(cf.cf_plan_opts) == 28
     assert ctypes.sizeof(cf.cf_split) == 12
     assert ctypes.sizeof(cf.cf_plan_stats) == 32
     assert ctypes.sizeof(cf.cf_model_desc) == 40
@@ -61,7 +62,7 @@ def test_planner_matches_oracle_on_random_batches():
         chunk = 16 * int(rng.integers(1, 40))
         oo, co = both_opts(chunk, int(rng.choice([0, 300, 2000, 10 ** 6])), int(rng.integers(1, 40)),
                            int(rng.choice([512, 4096, 1024])), int(rng.integers(-1, 2)),
-                           int(rng.integers(0, 3)))
+                           int(rng.integers(0, 3)), int(rng.choice([0, 0, 115, 98, 1000])))
         n_ctx = [int(rng.integers(0, 6000)) for _ in range(int(rng.integers(1, 12)))]
         otrace = []
         osplits, ostats = P.plan(ocm, oo, n_ctx, trace=otrace)

@@ -89,11 +89,42 @@ def test_single_request_matches_brute_force_exactly():
         cm = rand_cm(rng, startups=trial % 2 == 1)
         mode = int(rng.integers(0, 2))
         opts = P.PlanOpts(16 * int(rng.integers(1, 5)), 0, int(rng.integers(1, 9)),
-                          int(rng.choice([512, 4096])), mode)
+                          int(rng.choice([512, 4096])), mode,
+                          kv_only_permille=int(rng.choice([0, 115, 1000])))
         n = int(rng.integers(1, 16 * 40))
         _, st = P.plan(cm, opts, [n])
         best, _ = P.brute_force(cm, opts, [n])
         assert st["makespan"] == best, (trial, cm, opts, n)
+
+
+def test_last_recomputed_layer_costs_only_its_kv_projection():
+    """With kv_only_permille set, a request's LAST recomputed layer is priced f_c + alpha*t*p/1000
+    (no attention).  By hand: token-wise chunk = L-1 full layers + one K/V-only layer; layer-wise
+    c claimed layers = c-1 full + one K/V-only, whichever c (each claim completes the layer below
+    it); permille 1000 with beta = 0 is the old pricing; the plan never recomputes less."""
+    cm = P.CostModel(f_c=7, alpha=1000, beta=13, f_io=5, gamma=10 ** 6)
+    full = lambda t, p0: 7 + 1000 * t + 13 * -(-(t * p0 + t * (t + 1) // 2) // 1024)
+    kvo = lambda t, p: 7 + -(-(1000 * p * t) // 1000)
+    o = P.PlanOpts(32, 0, 5, 4096, P.TOKEN_WISE, kv_only_permille=115)
+    a, b, tok = P.unit_costs(cm, o, 80, P.TOKEN_WISE)
+    assert a == [4 * full(32, 0) + kvo(32, 115), 4 * full(32, 32) + kvo(32, 115), 4 * full(16, 64) + kvo(16, 115)]
+    a, b, tok = P.unit_costs(cm, o, 80, P.LAYER_WISE)
+    assert a == [kvo(80, 115)] + [full(80, 0)] * 4
+    for c in range(1, 6):
+        assert sum(a[:c]) == (c - 1) * full(80, 0) + kvo(80, 115)
+    flat = P.CostModel(f_c=7, alpha=1000, beta=0, f_io=5, gamma=10 ** 6)
+    for mode in (P.TOKEN_WISE, P.LAYER_WISE):
+        old = P.unit_costs(flat, P.PlanOpts(32, 0, 5, 4096, mode), 80, mode)
+        new = P.unit_costs(flat, P.PlanOpts(32, 0, 5, 4096, mode, kv_only_permille=1000), 80, mode)
+        assert old == new
+    rng = np.random.default_rng(8)
+    for _ in range(100):
+        cmr = rand_cm(rng)
+        n_ctx = [int(rng.integers(1, 3000)) for _ in range(int(rng.integers(1, 6)))]
+        mode = int(rng.integers(0, 2))
+        s0, _ = P.plan(cmr, P.PlanOpts(64, 0, 8, 4096, mode), n_ctx)
+        s1, _ = P.plan(cmr, P.PlanOpts(64, 0, 8, 4096, mode, kv_only_permille=115), n_ctx)
+        assert sum(k * c for _, k, c in s1) >= sum(k * c for _, k, c in s0)
 
 
 def test_tiny_batches_shared_model_full_chunks_match_brute_force():
