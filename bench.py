@@ -64,7 +64,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--plan", default="planner",
                     help="planner | all_recompute | all_load | cut=<L> (layer cut for every request)")
@@ -182,10 +182,26 @@ def main():
         m2.s_c += cf.prefill_cost(cm, shape.n_layers, batch.n_ctx, batch.n_new)
         return m2
 
+    # Measured guard: the two streams slow each other down, and where recompute buys little (a
+    # TP shard: I/O is ~18x cheaper per token) the hybrid's small saving can be less than that
+    # slow-down.  One warm-up step therefore runs the all-load extreme, and from then on the
+    # hybrid is kept only while its last measured TTFT beats the extreme's.
+    guard = {"all_load_ms": None, "hybrid_ms": None, "n_hybrid": 0, "all_load_steps": 0,
+             "probe": args.warmup >= 4}
+
     def make_plan():
         if args.plan == "planner":
             if batch.forced_splits:
                 return [(0, k, c) for k, c in batch.forced_splits], None
+            all_load = [(0, 0, L) for _ in batch.n_ctx]
+            if guard["probe"]:
+                guard["probe"] = False
+                return all_load, "probe"
+            # (the hybrid gets three steps of feedback before it is judged, by its best step)
+            if (guard["all_load_ms"] is not None and guard["n_hybrid"] >= 3 and
+                    guard["all_load_ms"] < 0.99 * guard["hybrid_ms"]):
+                guard["all_load_steps"] += 1
+                return all_load, None
             splits, stats, _ = cf.restore_plan(plan_model(), opts, batch.n_ctx)
             return splits, stats
         if args.plan == "per_request":
@@ -211,7 +227,12 @@ def main():
     def step():
         splits, stats = make_plan()
         logits, tm = sess.restore(reqs, splits, want_logits=not stage)
+        if stats == "probe":
+            guard["all_load_ms"] = tm["total_ms"]
+            return splits, None, tm
         if stats is not None:
+            guard["n_hybrid"] += 1
+            guard["hybrid_ms"] = min(guard["hybrid_ms"] or tm["total_ms"], tm["total_ms"])
             # closed loop: correct the cost model by what the two streams actually took (they
             # slow each other down when they overlap, which calibration in isolation cannot see)
             # The plan's t_comp is when the compute stream would finish ALL its work, the
@@ -314,7 +335,7 @@ def main():
         "all_recompute_pass": {"ms": tm_full["compute_ms"],
                                "tflops": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9,
                                "frac_of_mfma_peak": tm_full["recompute_flops"] / tm_full["compute_ms"] / 1e9 / peak},
-        "planner": {"cost_model_ps": cost, "l_delta": l_delta,
+        "planner": {"cost_model_ps": cost, "l_delta": l_delta, "all_load_guard_steps": guard["all_load_steps"],
                     "cost_model_after_feedback_ps": dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io,
                                                          gamma=cm.gamma, s_c=cm.s_c, s_io=cm.s_io),
                     "predicted_ms": None if stats is None else stats["makespan"] / 1e9},
