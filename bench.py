@@ -75,6 +75,8 @@ def main():
                     help="direct: load kernel reading pinned host memory; staged: DMA + scatter")
     ap.add_argument("--load-workgroups", type=int, default=0,
                     help="resident workgroups of the direct load kernel (0: library default)")
+    ap.add_argument("--no-guard", action="store_true",
+                    help="planner mode: never fall back to all-load (skip the probe step)")
     ap.add_argument("--stage", default="",
                     help="b:e -- restore only layers [b, e), one pipeline stage's share, recomputing from "
                          "boundary activations captured at layer b (no logits; value = the stage's tokens/s)")
@@ -187,7 +189,7 @@ def main():
     # slow-down.  One warm-up step therefore runs the all-load extreme, and from then on the
     # hybrid is kept only while its last measured TTFT beats the extreme's.
     guard = {"all_load_ms": None, "hybrid_ms": None, "n_hybrid": 0, "all_load_steps": 0,
-             "probe": args.warmup >= 4}
+             "probe": args.warmup >= 4 and not args.no_guard}
 
     def make_plan():
         if args.plan == "planner":
