@@ -238,8 +238,8 @@ int cf_workspace_bytes(const cf_model_desc* desc, const cf_ctx_opts* opts, size_
 /* compute_stream / copy_stream: hipStream_t handles (as void*), default
  * priority, distinct for overlap.  workspace: device memory of at least
  * cf_workspace_bytes, 256-byte aligned, owned by the caller and borrowed
- * until cf_ctx_destroy.  Allocates small pinned host buffers and the RoPE
- * table upload; no other device allocation.                                 */
+ * until cf_ctx_destroy.  Creates one more stream and its events, allocates
+ * small pinned host buffers and uploads the RoPE table; no device allocation. */
 int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weights, const cf_ctx_opts* opts,
                   void* workspace, size_t workspace_bytes, void* compute_stream,
                   void* copy_stream, cf_ctx** out);
@@ -251,8 +251,10 @@ typedef struct cf_request {
     const int32_t* ctx_tokens;     /* host int32[n_ctx]; only [0,k_tokens) is read */
     int32_t n_ctx;
     int32_t n_new;
-    const void* host_kv;           /* PINNED host block (layout above); may be NULL
-                                      iff the split loads nothing                  */
+    const void* host_kv;           /* host block (layout above); pinned, device-mapped
+                                      memory (hipHostMalloc) selects the direct load
+                                      path, pageable memory the staged one; may be
+                                      NULL iff the split loads nothing             */
     const int32_t* new_tokens;     /* host int32[n_new]                            */
     const float* boundary_h;       /* host float[n_ctx][d_model] (pinned for speed):
                                       the hidden states entering the stage's first
@@ -265,9 +267,12 @@ typedef struct cf_request {
 
 typedef struct cf_timing {
     float restore_ms;     /* call start -> both streams done with restoration    */
-    float compute_ms;     /* recompute phase on the compute stream               */
-    float copy_ms;        /* load+scatter phase on the copy stream               */
-    float suffix_ms;      /* new-token prefill + logits after the join           */
+    float compute_ms;     /* call start -> end of the last recomputed layer on the
+                             compute stream (pipelined join: the new-turn rows of
+                             the layers up to there included)                    */
+    float copy_ms;        /* call start -> last loaded cell in place (copy stream) */
+    float suffix_ms;      /* total_ms - restore_ms: what the new-turn prefill and
+                             the logits add after restoration                    */
     float total_ms;       /* call start -> logits ready (batch TTFT)             */
     double recompute_flops; /* algorithmic: linear layers + causal pairs needed  */
     double suffix_flops;
