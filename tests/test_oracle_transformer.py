@@ -114,10 +114,15 @@ def test_attention_matches_torch_sdpa():
 
 
 def test_kv_size_formula_matches_the_paper_example():
-    # Sec. 2: 2*L*H*d*N elements; Qwen3-8B-like (36 layers, 8 KV heads, hd 128),
-    # 16-bit, ~20k tokens is quoted as about 2.8 GB.
-    n_bytes = 2 * 36 * 8 * 128 * 20000 * 2
-    assert 2.7e9 < n_bytes < 3.0e9
+    # Sec. 2: 2*L*H*d*N elements; the paper states the resulting size for a named model
+    # (tests/golden/kv_size_examples.txt); the formula must land on it to the stated digits.
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "kv_size_examples.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert rows
+    for name, layers, kvh, hd, eb, toks, gb in rows:
+        n_bytes = 2 * int(layers) * int(kvh) * int(hd) * int(toks) * int(eb)
+        assert abs(n_bytes / 1e9 - float(gb)) <= 0.15, (name, n_bytes)
     s = SHAPES["8b"]
     assert s.kv_bytes_per_token_layer * s.n_layers == 2 * s.n_layers * s.n_kv_heads * s.head_dim * 2
 
