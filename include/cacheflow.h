@@ -167,6 +167,65 @@ int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int32_t B, cons
 int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t n_max,
                       int32_t* l_delta);
 
+/* ------------------------------------------------- run-time scheduling steps
+ * The two decisions of Alg. 1 taken against actual progress instead of
+ * simulated clocks (Sec. 3.3: after each chunk the scheduler updates the
+ * remaining cost of every request and re-ranks).  cf_restore_dynamic calls
+ * them whenever one of its engines runs dry; they are pure host integer code.
+ * State of request i: p_comp[i] = its next unit for the compute engine
+ * (units below it are recomputed or being recomputed), p_io[i] = its next unit
+ * for the I/O channel (units above it are loaded or being loaded); the request
+ * is live while p_comp[i] <= p_io[i].  Units and their costs are those of
+ * cf_restore_plan (chunks of C tokens, or layers).  p_comp in [0, units],
+ * p_io in [-1, units-1], else CF_ERR_INVALID_ARG.
+ *   compute_closed (host uint8[B], may be NULL = none): nonzero = the compute
+ *                   engine can take no further unit of request i (a
+ *                   layer-wise batch that has run its last layer K/V-only)
+ *   io_backlog_ps : predicted time the I/O channel still needs for units it
+ *                   has already claimed
+ *   compute_busy_ps : predicted time left of the compute step that is running
+ *   scale_*_permille : measured / predicted time of the compute steps and of
+ *                   the loads seen so far in this call (1000 = as modelled);
+ *                   every unit cost is multiplied by its scale (rounded down)
+ * Both follow one rule: an engine takes a unit only if its own finish time
+ * with it is no later than the time the OTHER engine would need for
+ * everything still unclaimed -- taking it then cannot delay the end.
+ *
+ * cf_dynamic_io_pick: the live request whose far-end unit the channel would
+ * load next has the largest key `opts->io_key` (default: recomputation still
+ * ahead of it; ties to the longer context, then the lower index).  Its load
+ * cost b (layer-wise: summed over all live layer-wise requests, which are
+ * loaded layer by layer together) passes iff
+ *   io_backlog + b <= compute_busy + sum of a over the unclaimed units of
+ *                     requests that are not closed,
+ * or if the request is closed.  *pick = that request, or -1 if none is live
+ * or the unit is better left to the compute engine for now.                  */
+int cf_dynamic_io_pick(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                       const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
+                       const uint8_t* compute_closed, int64_t io_backlog_ps,
+                       int64_t compute_busy_ps, int32_t scale_c_permille,
+                       int32_t scale_io_permille, int32_t* pick);
+
+/* cf_dynamic_claim: which of the live, not closed requests' next units the
+ * compute engine takes for its next step (one step = those units run together,
+ * layer-major).  With R = io_backlog + sum of the load costs b of all unclaimed
+ * units (when the channel would be done on its own), candidates are ranked by
+ * recompute cost per load cost saved (a/b ascending; ties to the lower index)
+ * and taken greedily while  A + a <= R - Bs  (A, Bs: recompute and load cost
+ * of what the step already holds).  Token-wise requests are candidates one by
+ * one; all open layer-wise requests form ONE candidate (they advance through
+ * the layers as a packed batch), a = sum a_i, b = sum b_i.
+ *   take[i] (host int32[B]) : 0 not taken; 1 taken; 2 (layer-wise only) taken
+ *                   as the group's last layer -- the same test fails for the
+ *                   group's following layer (or there is none), so the
+ *                   executor stops this one after its K/V write
+ *   step_ps (may be NULL)   : A, the predicted duration of the step          */
+int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                     const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
+                     const uint8_t* compute_closed, int64_t io_backlog_ps,
+                     int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
+                     int64_t* step_ps);
+
 /* --------------------------------------------------------------- page table
  * Paged KV cache bookkeeping (the serving substrate of Sec. 4.1).  Policy is
  * part of the contract: an allocation takes the ceil(n/16) lowest-numbered
@@ -296,6 +355,49 @@ typedef struct cf_timing {
  * max(sum k_i + sum n_new) must not exceed the context's max_tokens.         */
 int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
                      const cf_split* splits, float* logits_out, cf_timing* timing);
+
+typedef struct cf_dynamic_stats {
+    int32_t compute_steps;      /* steps the compute engine ran                    */
+    int32_t compute_units;      /* units it claimed (chunks, or request-layers)    */
+    int32_t io_units;           /* load launches (one per claimed I/O unit)        */
+    int32_t scale_c_permille;   /* measured / predicted at the end of the call     */
+    int32_t scale_io_permille;
+    int32_t reserved;
+    double compute_gap_ms;      /* compute stream idle between steps (host decides
+                                   the next step only when the last one is done)   */
+} cf_dynamic_stats;
+
+/* Restore a batch WITHOUT a precomputed split: the two engines claim units at
+ * run time (Sec. 3.3, progressive chunk-level scheduling).  The I/O channel
+ * keeps one unit in flight plus as many more as it takes to have about 2 ms
+ * of predicted work queued (at most 4), each picked by cf_dynamic_io_pick when
+ * a slot frees up; the compute engine asks cf_dynamic_claim each time its
+ * previous step has completed (HIP events, polled by the calling thread) and
+ * runs the units it gets as one packed step: the claimed chunks of token-wise
+ * requests through all layers, and the next layer of the layer-wise requests,
+ * whose hidden states stay in the workspace from step to step.  When every
+ * unit is claimed and both streams have drained, the new-turn prefill and the
+ * logits follow (sequential join).
+ *   cost, opts : the cost model seeds the predictions; the ratios measured /
+ *                predicted are tracked inside the call.  opts->chunk_tokens
+ *                must be a multiple of 16 (page size); modes by
+ *                opts->force_mode / l_delta as in cf_restore_plan.
+ *   reqs       : as for cf_restore_batch; every request with n_ctx > 0 needs
+ *                ctx_tokens and pinned, device-mapped host_kv (the direct
+ *                load path is the only one used here).
+ *   splits_out : host cf_split[B], the split that resulted (token-wise:
+ *                k = chunks recomputed x C, cut = L; layer-wise: k = n_ctx,
+ *                cut = layers recomputed); the restored cache and the logits
+ *                are those of cf_restore_batch under these splits up to the
+ *                order of floating-point summation (chunks are recomputed
+ *                one step at a time, over the pages of the chunks before).
+ *   logits_out, timing : as for cf_restore_batch.  stats may be NULL.
+ * The context must cover the whole model (no cf_ctx_set_stage restriction).
+ * Rows: (tokens of all layer-wise requests) + (token-wise requests x C) and
+ * sum n_new must each fit max_tokens.  Blocking.                              */
+int cf_restore_dynamic(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
+                       const cf_cost_model* cost, const cf_plan_opts* opts, float* logits_out,
+                       cf_split* splits_out, cf_timing* timing, cf_dynamic_stats* stats);
 
 /* Copy a request's first n_ctx tokens of KV from its pages to a host block
  * of cf_host_kv_bytes(n_ctx) bytes in the host layout (whole pages; the

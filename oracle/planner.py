@@ -26,6 +26,8 @@ notes of this repository):
  * I/O priority ties go to the longer context, then to the lower index.
 """
 from dataclasses import dataclass
+from fractions import Fraction
+from functools import cmp_to_key
 from itertools import product
 
 TOKEN_WISE = 0
@@ -283,3 +285,221 @@ def cost_feedback(cm, pred_comp, meas_comp, pred_io, meas_io):
         out.gamma = max(1, scale(cm.gamma, meas_io, pred_io))
         out.s_io = scale(cm.s_io, meas_io, pred_io)
     return out
+
+
+# --------------------------------------------------------------------------
+# Run-time scheduling (Sec. 3.3: the scheduler works progressively, chunk by
+# chunk, and re-ranks after every processed chunk).  The two decisions below
+# are what an executor asks whenever one of its engines runs dry; costs are
+# the cost model's, multiplied by the ratios measured/predicted seen so far
+# (permille, products rounded down per unit).  The paper gives no mechanism;
+# the reading taken here: an engine takes a unit only if its own finish time
+# with it is no later than the time the other engine would need for everything
+# still unclaimed, so that taking it cannot delay the end of the restoration.
+
+def _scaled_units(cm, opts, n_ctx, scale_c, scale_io):
+    out = []
+    for n in n_ctx:
+        mode = request_mode(opts, n)
+        a, b, tok = unit_costs(cm, opts, n, mode)
+        out.append((mode, [x * scale_c // 1000 for x in a], [x * scale_io // 1000 for x in b], a, tok, b))
+    return out
+
+
+def _io_candidate(opts, n_ctx, units, p_comp, p_io):
+    """The live request with the largest I/O priority key (Sec. 3.3), ties to the longer
+    context, then the lower index; None if no request is live."""
+    best, best_key = None, None
+    for i, n in enumerate(n_ctx):
+        if p_comp[i] > p_io[i]:
+            continue
+        mode, _, _, a_raw, tok, _ = units[i]
+        if opts.io_key == KEY_REMAINING_COST:
+            key = Fraction(sum(a_raw[p_comp[i]:p_io[i] + 1]))
+        elif opts.io_key == KEY_REMAINING_CELLS:
+            per = opts.n_layers if mode == TOKEN_WISE else 1
+            key = Fraction(sum(tok[p_comp[i]:p_io[i] + 1]) * per)
+        else:
+            key = Fraction(a_raw[p_io[i]], units[i][5][p_io[i]])
+        if best is None or (key, n) > best_key:
+            best, best_key = i, (key, n)
+    return best
+
+
+def io_pick(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, compute_busy=0,
+            scale_c=1000, scale_io=1000):
+    """Request whose far-end unit the I/O channel loads next, or -1 (none live, or the unit
+    is better left to the compute engine): the candidate passes iff
+    io_backlog + b <= compute_busy + (recompute cost of every unclaimed unit of requests the
+    compute engine has not closed), or if its request is closed.  Layer-wise requests are
+    loaded one layer of all of them at a time, so b sums over the live layer-wise ones."""
+    closed = closed or [False] * len(n_ctx)
+    units = _scaled_units(cm, opts, n_ctx, scale_c, scale_io)
+    best = _io_candidate(opts, n_ctx, units, p_comp, p_io)
+    if best is None:
+        return -1
+    if closed[best]:
+        return best
+    c_rem = compute_busy
+    for i in range(len(n_ctx)):
+        if not closed[i]:
+            c_rem += sum(units[i][1][p_comp[i]:p_io[i] + 1])
+    if units[best][0] == LAYER_WISE:
+        b = sum(units[i][2][p_io[i]] for i in range(len(n_ctx))
+                if p_comp[i] <= p_io[i] and units[i][0] == LAYER_WISE)
+    else:
+        b = units[best][2][p_io[best]]
+    return best if io_backlog + b <= c_rem else -1
+
+
+def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scale_c=1000,
+                  scale_io=1000):
+    """Which live, open requests' next units the compute engine takes for its next step.
+
+    R = io_backlog + load cost of every unclaimed unit: the time the I/O channel needs if
+    compute takes nothing.  Candidates: each open token-wise request's unit p_comp[i]; all
+    open layer-wise requests together as one candidate (they advance as a packed batch).
+    Ranked by recompute cost per load cost (ascending, ties by index), a candidate (a, b) is
+    taken if  A + a <= R - Bs  with A, Bs the sums over those already taken: the step ends
+    no later than the channel would finish what the step so far leaves to it.
+    Returns (take, A): take[i] in {0, 1, 2}; 2 marks layer-wise requests whose group should
+    stop this layer after its K/V write because the test fails for the group's next layer."""
+    b_req = len(n_ctx)
+    closed = closed or [False] * b_req
+    units = _scaled_units(cm, opts, n_ctx, scale_c, scale_io)
+    live = [i for i in range(b_req) if p_comp[i] <= p_io[i]]
+    r_total = io_backlog + sum(sum(units[i][2][p_comp[i]:p_io[i] + 1]) for i in live)
+    open_ = [i for i in live if not closed[i]]
+    group = [i for i in open_ if units[i][0] == LAYER_WISE]
+    cands = [(units[i][1][p_comp[i]], units[i][2][p_comp[i]], i, False)
+             for i in open_ if units[i][0] == TOKEN_WISE]
+    if group:
+        cands.append((sum(units[i][1][p_comp[i]] for i in group),
+                      sum(units[i][2][p_comp[i]] for i in group), group[0], True))
+
+    def order(x, y):
+        lhs, rhs = x[0] * y[1], y[0] * x[1]       # a_x/b_x against a_y/b_y
+        if lhs != rhs:
+            return -1 if lhs < rhs else 1
+        return (x[2] > y[2]) - (x[2] < y[2])
+
+    cands.sort(key=cmp_to_key(order))
+    take = [0] * b_req
+    a_sum = b_sum = 0
+    group_taken = False
+    for a, b, first, is_group in cands:
+        if a_sum + a <= r_total - b_sum:
+            a_sum += a
+            b_sum += b
+            if is_group:
+                group_taken = True
+            else:
+                take[first] = 1
+    if group_taken:
+        more = all(p_comp[i] + 1 <= p_io[i] for i in group)
+        if more:
+            more = a_sum + sum(units[i][1][p_comp[i] + 1] for i in group) <= r_total - b_sum
+        for i in group:
+            take[i] = 1 if more else 2
+    return take, a_sum
+
+
+def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max_depth=4):
+    """Event-driven model of an executor that schedules at run time with `io_pick` and
+    `dynamic_claim`: the I/O channel holds one claimed unit plus more while less than
+    `lookahead` of predicted work is queued (at most `max_depth`); the compute engine asks
+    for a step whenever it is idle and the state has changed.  Durations come from
+    `true_cm` (default: the model itself), predictions from `cm` times the ratios
+    measured/predicted so far.  A step lasts the sum of its units' true costs.
+    Returns (splits, makespan, n_steps)."""
+    true_cm = true_cm or cm
+    b_req = len(n_ctx)
+    modes = [request_mode(opts, n) for n in n_ctx]
+    pred = [unit_costs(cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
+    true = [unit_costs(true_cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
+    p_comp = [0] * b_req
+    p_io = [len(pred[i][0]) - 1 for i in range(b_req)]
+    closed = [False] * b_req
+    group = [i for i in range(b_req) if modes[i] == LAYER_WISE and n_ctx[i] > 0]
+    now = 0
+    io_queue = []            # (true duration, predicted) of claimed loads, oldest first
+    io_head_done = 0         # when the load at the head of the queue completes
+    io_pred_done = 0
+    io_busy_from = None
+    step_end, step_start, step_pred = None, 0, 0
+    c_pred_done = c_true_done = 0
+    scale_c = scale_io = 1000
+    n_steps = 0
+    ask = True
+    force_io = False
+
+    def clamp(num, den):
+        return min(4000, max(250, (num * 1000 + den // 2) // den))
+
+    while True:
+        progressed = False
+        while len(io_queue) < max_depth:
+            backlog = sum(d * scale_io // 1000 for _, d in io_queue)
+            if io_queue and backlog >= lookahead:
+                break
+            busy = max(0, step_pred - (now - step_start)) if step_end is not None else 0
+            if force_io:
+                busy = 1 << 62
+            force_io = False
+            i = io_pick(cm, opts, n_ctx, p_comp, p_io, closed, backlog, busy, scale_c, scale_io)
+            if i < 0:
+                break
+            members = group if modes[i] == LAYER_WISE else [i]
+            u = p_io[i]
+            d_true = sum(true[j][1][u] for j in members)
+            d_pred = sum(pred[j][1][u] for j in members)
+            for j in members:
+                p_io[j] -= 1
+            if not io_queue:
+                io_head_done = now + d_true
+            if io_busy_from is None:
+                io_busy_from = now
+            io_queue.append((d_true, d_pred))
+            ask = progressed = True
+        if step_end is None and ask:
+            ask = False
+            backlog = sum(d * scale_io // 1000 for _, d in io_queue)
+            take, a_pred = dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed, backlog, scale_c, scale_io)
+            dur = 0
+            for i in range(b_req):
+                if take[i]:
+                    dur += true[i][0][p_comp[i]]
+                    p_comp[i] += 1
+                    if take[i] == 2:
+                        closed[i] = True
+            if any(take):
+                step_start, step_end, step_pred = now, now + dur, a_pred
+                c_true_done += dur
+                n_steps += 1
+                progressed = True
+        events = ([io_head_done] if io_queue else []) + ([step_end] if step_end is not None else [])
+        if not events:
+            if all(p_comp[i] > p_io[i] for i in range(b_req)):
+                break
+            if not progressed:
+                if force_io:
+                    raise AssertionError("scheduler stalled with live requests")
+                force_io = True
+            continue
+        now = min(events)
+        if io_queue and io_head_done == now:
+            _, d_pred = io_queue.pop(0)
+            io_pred_done += d_pred
+            if io_queue:
+                io_head_done = now + io_queue[0][0]
+            if io_pred_done > 0 and now > io_busy_from:
+                scale_io = clamp(now - io_busy_from, io_pred_done)
+            ask = True
+        if step_end is not None and step_end == now:
+            step_end = None
+            c_pred_done += step_pred
+            if c_pred_done > 0:
+                scale_c = clamp(c_true_done, c_pred_done)
+            ask = True
+    splits = [_split_of(opts, n_ctx[i], modes[i], p_comp[i]) for i in range(b_req)]
+    return splits, now, n_steps

@@ -92,6 +92,15 @@ class cf_timing(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class cf_dynamic_stats(C.Structure):
+    _fields_ = [("compute_steps", C.c_int32), ("compute_units", C.c_int32), ("io_units", C.c_int32),
+                ("scale_c_permille", C.c_int32), ("scale_io_permille", C.c_int32),
+                ("reserved", C.c_int32), ("compute_gap_ms", C.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+
+
 class cf_kernel_stat(C.Structure):
     _fields_ = [("kernel", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double),
                 ("work", C.c_double)]
@@ -114,6 +123,12 @@ lib.cf_cost_feedback.argtypes = [_P(cf_cost_model), C.c_int64, C.c_int64, C.c_in
 lib.cf_prefill_cost.argtypes = [_P(cf_cost_model), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                 _P(C.c_int64)]
 lib.cf_derive_l_delta.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, _P(C.c_int32)]
+lib.cf_dynamic_io_pick.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                   C.c_int32, C.c_int32, _P(C.c_int32)]
+lib.cf_dynamic_claim.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                 C.c_int32, C.c_void_p, _P(C.c_int64)]
 lib.cf_cache_create.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                 _P(C.c_void_p)]
 lib.cf_cache_destroy.argtypes = [C.c_void_p]
@@ -140,6 +155,9 @@ lib.cf_ctx_set_stage.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
 lib.cf_ctx_capture_boundary.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
 lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request), _P(cf_split),
                                  C.c_void_p, _P(cf_timing)]
+lib.cf_restore_dynamic.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request),
+                                   _P(cf_cost_model), _P(cf_plan_opts), C.c_void_p, _P(cf_split),
+                                   _P(cf_timing), _P(cf_dynamic_stats)]
 lib.cf_offload.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]
 lib.cf_measure_h2d.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32,
                                _P(C.c_double)]
@@ -152,7 +170,7 @@ lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_v
                            _P(C.c_float)]
 
 EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", "cf_cost_feedback", "cf_prefill_cost",
-           "cf_derive_l_delta", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
+           "cf_derive_l_delta", "cf_dynamic_io_pick", "cf_dynamic_claim", "cf_restore_dynamic", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
            "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_ctx_set_stage", "cf_ctx_capture_boundary", "cf_restore_batch", "cf_offload",
@@ -229,6 +247,40 @@ def derive_l_delta(cost, opts, n_max):
     _check(lib.cf_derive_l_delta(C.byref(cost), C.byref(opts), n_max, C.byref(out)),
            "cf_derive_l_delta")
     return out.value
+
+
+def _closed(closed, b):
+    arr = np.zeros(max(b, 1), dtype=np.uint8)
+    if closed is not None:
+        arr[:b] = np.asarray(closed, dtype=np.uint8)
+    return arr
+
+
+def dynamic_io_pick(cost, opts, n_ctx, p_comp, p_io, closed=None, io_backlog_ps=0,
+                    compute_busy_ps=0, scale_c_permille=1000, scale_io_permille=1000):
+    """Request whose far-end unit the I/O channel loads next, or -1."""
+    n, pc, pio = _i32(n_ctx), _i32(p_comp), _i32(p_io)
+    cl = _closed(closed, len(n))
+    out = C.c_int32()
+    _check(lib.cf_dynamic_io_pick(C.byref(cost), C.byref(opts), len(n), n.ctypes.data,
+                                  pc.ctypes.data, pio.ctypes.data, cl.ctypes.data,
+                                  int(io_backlog_ps), int(compute_busy_ps), int(scale_c_permille),
+                                  int(scale_io_permille), C.byref(out)), "cf_dynamic_io_pick")
+    return out.value
+
+
+def dynamic_claim(cost, opts, n_ctx, p_comp, p_io, closed=None, io_backlog_ps=0,
+                  scale_c_permille=1000, scale_io_permille=1000):
+    """-> (take list, predicted step ps)"""
+    n, pc, pio = _i32(n_ctx), _i32(p_comp), _i32(p_io)
+    cl = _closed(closed, len(n))
+    take = np.zeros(max(len(n), 1), dtype=np.int32)
+    ps = C.c_int64()
+    _check(lib.cf_dynamic_claim(C.byref(cost), C.byref(opts), len(n), n.ctypes.data, pc.ctypes.data,
+                                pio.ctypes.data, cl.ctypes.data, int(io_backlog_ps),
+                                int(scale_c_permille), int(scale_io_permille), take.ctypes.data,
+                                C.byref(ps)), "cf_dynamic_claim")
+    return [int(t) for t in take[:len(n)]], ps.value
 
 
 # ---------------------------------------------------------------- page table
@@ -366,6 +418,27 @@ class Ctx:
         _check(lib.cf_restore_batch(self.handle, cache.handle, b, arr, sp, logits_ptr or None,
                                     C.byref(tm)), "cf_restore_batch")
         return tm.as_dict()
+
+    def restore_dynamic(self, cache, requests, cost, opts, logits_ptr):
+        """Run-time scheduled restore.  Returns (splits [(mode,k,cut)], timing dict, stats dict)."""
+        b = len(requests)
+        keep = []
+        arr = (cf_request * max(b, 1))()
+        for i, r in enumerate(requests):
+            ct = _i32(r["ctx_tokens"])
+            nt = _i32(r["new_tokens"])
+            keep += [ct, nt]
+            arr[i] = cf_request(r["req_id"], ct.ctypes.data if len(ct) else None, len(ct),
+                                len(nt), r.get("host_kv") or None,
+                                nt.ctypes.data if len(nt) else None, None)
+        sp = (cf_split * max(b, 1))()
+        tm = cf_timing()
+        st = cf_dynamic_stats()
+        _check(lib.cf_restore_dynamic(self.handle, cache.handle, b, arr, C.byref(cost), C.byref(opts),
+                                      logits_ptr or None, sp, C.byref(tm), C.byref(st)),
+               "cf_restore_dynamic")
+        return ([(sp[i].mode, sp[i].k_tokens, sp[i].layer_cut) for i in range(b)], tm.as_dict(),
+                st.as_dict())
 
     def offload(self, cache, req_id, n_ctx, host_ptr):
         _check(lib.cf_offload(self.handle, cache.handle, req_id, n_ctx, host_ptr), "cf_offload")

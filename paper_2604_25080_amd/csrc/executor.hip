@@ -8,8 +8,12 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
+#include <deque>
+#include <thread>
 #include <vector>
 
 #include "cf_common.h"
@@ -62,7 +66,9 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
                   + (size_t)(sizeof(AttnWork) + sizeof(AttnCombine)) *
                         (2 * ((size_t)o.max_tokens / ATTN_BLOCK_ROWS) + 4 * (size_t)o.max_batch +
                          4 * ((size_t)o.max_tokens / chunk + 2) + 2 * ATTN_MAX_PART_BLOCKS)
-                  + (size_t)sizeof(PageJob) * ((size_t)o.max_batch * m.n_layers * 2 + 4096) +
+                  + (size_t)sizeof(PageJob) * ((size_t)o.max_batch * m.n_layers * 2 + 4096)
+                  // run-time scheduling: one job per (chunk of >= 256 tokens, layer) of every request
+                  + (size_t)sizeof(PageJob) * (size_t)o.max_batch * ((size_t)o.max_positions / 256 + 2) * m.n_layers +
                   (size_t)8 * o.max_batch + (1 << 16);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
@@ -114,6 +120,7 @@ struct cf_ctx {
     double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
+    std::vector<hipEvent_t> dyn_events;   // run-time scheduler: loads in flight + the compute step
     std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
@@ -261,6 +268,8 @@ extern "C" void cf_ctx_destroy(cf_ctx* c) {
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
     }
     for (hipEvent_t e : c->ev_layer)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->dyn_events)
         if (e) (void)hipEventDestroy(e);
     for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.e0); c->prof_pool.push_back(r.e1); }
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
@@ -482,7 +491,10 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
     c->prof_end(cls, c->cs);
 }
 
-// Run layers [0, n_layers_max) of one packed phase on the compute stream.
+// Run layers [l_begin, n_layers_max) of one packed phase on the compute stream; the phase's
+// rows sit at rows row_base.. of the residual buffers.  l_begin > 0 resumes a phase whose
+// earlier layers ran in a previous call with the same row_base (its hidden states are still
+// in the workspace), so nothing is embedded.
 //
 // The residual stream h stays float.  O-proj and down-proj store their result into the
 // float buffer dl (plain stores out of the GEMM), and the next RMSNorm folds it in
@@ -498,7 +510,7 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 // A stage above layer 0 has no embedding to start from: its rows start from the boundary
 // activations the caller holds for them (copied into h ahead of the first layer).
 int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
-              const hipEvent_t* layer_ready, hipEvent_t ev_rec_done) {
+              const hipEvent_t* layer_ready, hipEvent_t ev_rec_done, int l_begin = 0, int row_base = 0) {
     const int layer0 = c->stage_begin;
     const cf_model_desc& m = c->m;
     int last_rec_layer = -1;
@@ -526,19 +538,23 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                      attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads);
     const bool any_new = ph.rec_rows() < ph.T;
 
-    if (layer0 == 0) {
+    float* const h_rows = c->h() + (size_t)row_base * d;
+    float* const dl_rows = c->dl() + (size_t)row_base * d;
+    if (l_begin > 0) {
+        // resumed phase: hidden states are in place
+    } else if (layer0 == 0) {
         c->prof_begin(CF_K_EMBED, (double)ph.T * d * (es + 4), c->cs);
-        launch_embed(c->cs, m.dtype, c->w.embed, d_ids, c->h(), ph.T, d);
+        launch_embed(c->cs, m.dtype, c->w.embed, d_ids, h_rows, ph.T, d);
         c->prof_end(CF_K_EMBED, c->cs);
     } else {
         for (size_t si = 0; si < ph.segs.size(); ++si) {
             const Segment& sg = ph.segs[si];
             if (sg.n_rows <= 0) continue;
-            CF_HIP(hipMemcpyAsync(c->h() + (size_t)sg.row0 * d, ph.seg_boundary[si],
+            CF_HIP(hipMemcpyAsync(h_rows + (size_t)sg.row0 * d, ph.seg_boundary[si],
                                   (size_t)sg.n_rows * d * sizeof(float), hipMemcpyHostToDevice, c->cs));
         }
     }
-    for (int l = 0; l < n_layers_max; ++l) {
+    for (int l = l_begin; l < n_layers_max; ++l) {
         const int Ta_rec = ph.rec_active(l, 0);    // recompute rows that need K/V in this layer
         const int Tn_rec = ph.rec_active(l, 1);    // ... and go on through the layer
         if (Ta_rec <= 0 && !any_new) break;
@@ -550,7 +566,7 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
             if (rows > c->capture_cap_rows)
                 return fail(CF_ERR_WORKSPACE, "cf_restore_batch: boundary capture needs %d rows, buffer holds %lld",
                             rows, (long long)c->capture_cap_rows);
-            launch_residual_rows(c->cs, c->capture_out, c->h(), l > 0 ? c->dl() : nullptr, rows, d);
+            launch_residual_rows(c->cs, c->capture_out, h_rows, l > 0 ? dl_rows : nullptr, rows, d);
             c->capture_out = nullptr;          // one shot
             c->capture_layer = -1;
         }
@@ -570,8 +586,8 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
             for (int ri = 0; ri < n_ranges; ++ri) {
                 const int x = ranges[ri][0], y = ranges[ri][1], ycont = ranges[ri][2];
                 const int Tc = y - x, Tr = ycont - x, xo = x - ci.r0;   // xo: row offset inside the chunk buffers
-                float* h = c->h() + (size_t)x * d;
-                float* dl = c->dl() + (size_t)x * d;
+                float* h = h_rows + (size_t)x * d;
+                float* dl = dl_rows + (size_t)x * d;
                 char* a_buf = (char*)c->a() + (size_t)xo * d * es;
                 float* qkv_buf = c->qkv() + (size_t)xo * qcols;
                 char* q_buf = (char*)c->q() + (size_t)xo * nq * es;
@@ -1082,6 +1098,498 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         timing->loaded_bytes = loaded_bytes;
         timing->recomputed_cells = rec_cells;
         timing->loaded_cells = loaded_cells;
+    }
+    return CF_OK;
+}
+
+// ------------------------------------------------------------------ run-time scheduling
+// cf_restore_dynamic: the two engines claim units while the call runs (Sec. 3.3).  The calling
+// thread is the scheduler: it polls completion events, keeps the copy stream a few units deep
+// and gives the compute stream one step at a time.
+namespace {
+
+struct DynUnitLoad {          // one I/O unit = one load-kernel launch
+    int job_first, n_jobs, n_vblocks;
+    size_t bytes;
+};
+
+double now_ms() {
+    using clk = std::chrono::steady_clock;
+    return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const cf_request* reqs,
+                                  const cf_cost_model* cost, const cf_plan_opts* opts,
+                                  float* logits_out, cf_split* splits_out, cf_timing* timing,
+                                  cf_dynamic_stats* stats) {
+    if (!c || !cache || !cost || !opts || B < 0 || (B > 0 && (!reqs || !splits_out)))
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: null argument");
+    const cf_model_desc& m = c->m;
+    if (cache->n_layers != m.n_layers || cache->n_kv_heads != m.n_kv_heads ||
+        cache->head_dim != m.head_dim || cache->dtype != m.dtype || !cache->pool)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: cache geometry does not match the model");
+    if (c->stage_begin != 0 || c->stage_end != m.n_layers)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: the context must cover the whole model");
+    if (B > c->opts.max_batch)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: batch %d > max_batch %d", B, c->opts.max_batch);
+    const int L = m.n_layers, C = opts->chunk_tokens;
+    const size_t es = elem_bytes(m.dtype), pb = cache->page_bytes;
+    if (C <= 0 || C % CF_PAGE_TOKENS != 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: chunk_tokens must be a positive multiple of %d",
+                    CF_PAGE_TOKENS);
+    if (opts->n_layers != L || opts->kv_bytes_per_token_layer != (int32_t)(pb / CF_PAGE_TOKENS))
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: plan options do not describe this model "
+                    "(n_layers %d, KV bytes per token and layer %d)", opts->n_layers, opts->kv_bytes_per_token_layer);
+    if (timing) std::memset(timing, 0, sizeof(*timing));
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    if (B == 0) return CF_OK;
+
+    // ---- validate, page tables, modes and unit counts
+    std::vector<int32_t> n_ctx(B), mode(B), n_units(B), p_comp(B, 0), p_io(B);
+    std::vector<int> pt_off(B), n_pages_req(B);
+    std::vector<const int32_t*> pt(B);
+    std::vector<const char*> host_dev(B, nullptr);
+    int total_pt = 0;
+    int64_t sum_new = 0, rows_lw = 0, n_tw = 0;
+    for (int i = 0; i < B; ++i) {
+        const cf_request& r = reqs[i];
+        if (r.n_ctx < 0 || r.n_new < 0 || (r.n_new > 0 && !r.new_tokens))
+            return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d has bad sizes", i);
+        int np = 0;
+        pt[i] = cache->table_of(r.req_id, &np);
+        if (!cache->has(r.req_id))
+            return fail(CF_ERR_UNKNOWN_REQUEST, "cf_restore_dynamic: request id %llu has no pages",
+                        (unsigned long long)r.req_id);
+        if ((int64_t)np * CF_PAGE_TOKENS < (int64_t)r.n_ctx + (logits_out ? r.n_new : 0))
+            return fail(CF_ERR_OUT_OF_PAGES, "cf_restore_dynamic: request %d holds %d pages, needs %d tokens",
+                        i, np, r.n_ctx + r.n_new);
+        if (r.n_ctx + r.n_new > c->opts.max_positions)
+            return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: request %d exceeds max_positions", i);
+        if (r.n_ctx > 0) {
+            if (!r.ctx_tokens || !r.host_kv)
+                return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d needs ctx_tokens and host_kv", i);
+            for (int t = 0; t < r.n_ctx; ++t)
+                if ((uint32_t)r.ctx_tokens[t] >= (uint32_t)m.vocab)
+                    return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d token %d out of vocab", i, t);
+            hipPointerAttribute_t at;
+            void* dp = nullptr;
+            if (hipPointerGetAttributes(&at, r.host_kv) != hipSuccess || at.type != hipMemoryTypeHost ||
+                hipHostGetDevicePointer(&dp, const_cast<void*>(r.host_kv), 0) != hipSuccess || !dp) {
+                (void)hipGetLastError();
+                return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d: host KV must be pinned, "
+                            "device-mapped memory", i);
+            }
+            host_dev[i] = (const char*)dp;
+            int np_ctx = (int)ceil_div(r.n_ctx, CF_PAGE_TOKENS);
+            if ((int64_t)np_ctx * (int64_t)(pb / 16) >= ((int64_t)1 << 31))
+                return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: request %d holds more than 32 GiB per layer", i);
+        }
+        if (logits_out) {
+            if (r.n_new <= 0)
+                return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d needs n_new > 0 for logits", i);
+            sum_new += r.n_new;
+            for (int t = 0; t < r.n_new; ++t)
+                if ((uint32_t)r.new_tokens[t] >= (uint32_t)m.vocab)
+                    return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d new token %d out of vocab", i, t);
+        }
+        n_ctx[i] = r.n_ctx;
+        mode[i] = (opts->force_mode == CF_TOKEN_WISE || opts->force_mode == CF_LAYER_WISE)
+                      ? opts->force_mode : (r.n_ctx >= opts->l_delta ? CF_TOKEN_WISE : CF_LAYER_WISE);
+        n_units[i] = r.n_ctx <= 0 ? 0 : (mode[i] == CF_TOKEN_WISE ? (int)ceil_div(r.n_ctx, C) : L);
+        p_io[i] = n_units[i] - 1;
+        if (r.n_ctx > 0 && mode[i] == CF_LAYER_WISE) rows_lw += r.n_ctx;
+        if (r.n_ctx > 0 && mode[i] == CF_TOKEN_WISE) ++n_tw;
+        pt_off[i] = total_pt;
+        n_pages_req[i] = np;
+        total_pt += np;
+    }
+    if (rows_lw + n_tw * C > c->opts.max_tokens || sum_new > c->opts.max_tokens)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: %lld layer-wise rows + %lld token-wise chunks of %d, "
+                    "or %lld new tokens, exceed max_tokens %d", (long long)rows_lw, (long long)n_tw, C,
+                    (long long)sum_new, c->opts.max_tokens);
+    // argument check of the scheduling calls once, so that later calls cannot fail
+    {
+        int32_t pick = -1;
+        int rc0 = cf_dynamic_io_pick(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), nullptr, 0, 0,
+                                     1000, 1000, &pick);
+        if (rc0) return rc0;
+    }
+
+    // ---- metadata written once: page tables, the jobs of every possible load unit, the packed
+    // rows of the layer-wise group and of the new-turn rows.  What follows is rewritten per step.
+    MetaWriter mw{c->meta_host, c->cv.meta_bytes};
+    {
+        std::vector<int32_t> all_pt(std::max(total_pt, 1));
+        for (int i = 0; i < B; ++i)
+            if (n_pages_req[i]) std::memcpy(&all_pt[pt_off[i]], pt[i], (size_t)n_pages_req[i] * 4);
+        mw.put(all_pt.data(), all_pt.size() * 4);
+    }
+    auto slot_of = [&](int i, int t) { return pt[i][t / CF_PAGE_TOKENS] * CF_PAGE_TOKENS + t % CF_PAGE_TOKENS; };
+    const int split_heads = (!c->simple_only && attention_mfma_supported(m.dtype, m.head_dim, m.n_q_heads, m.n_kv_heads))
+                                ? m.n_q_heads : 0;
+    const int hpb = split_heads ? attention_mfma_heads_per_block(m.n_q_heads, m.n_kv_heads) : 1;
+    auto add_segment = [&](Phase& ph, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
+                           std::vector<int32_t>& slot, int i, const int32_t* toks, int n_rows, int pos0,
+                           int layers, bool is_new) {
+        ph.segs.push_back(Segment{i, ph.T, n_rows, pos0, layers, is_new});
+        ph.seg_boundary.push_back(nullptr);
+        for (int t = 0; t < n_rows; ++t) {
+            ids.push_back(toks[t]);
+            pos.push_back(pos0 + t);
+            slot.push_back(slot_of(i, pos0 + t));
+        }
+        ph.T += n_rows;
+    };
+    auto finish_phase = [&](Phase& ph, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
+                            std::vector<int32_t>& slot) {
+        build_chunks(ph, c->cv.chunk_rows, pt_off, split_heads, hpb);
+        ph.off_ids = mw.put(ids.data(), ids.size() * 4);
+        ph.off_pos = mw.put(pos.data(), pos.size() * 4);
+        ph.off_slot = mw.put(slot.data(), slot.size() * 4);
+        ph.off_work = mw.put(ph.work.data(), ph.work.size() * sizeof(AttnWork));
+        ph.off_grp = mw.put(ph.groups.data(), ph.groups.size() * sizeof(AttnCombine));
+    };
+
+    // load units: token-wise request i, unit u = chunk u in all layers; layer-wise group, unit
+    // l = layer l of every layer-wise request
+    std::vector<PageJob> jobs;
+    std::vector<std::vector<DynUnitLoad>> tw_units(B);
+    std::vector<DynUnitLoad> lw_units;
+    std::vector<int> lw_members;
+    int64_t vec_per_page = (int64_t)(pb / 16);
+    auto add_job = [&](DynUnitLoad& ul, int i, int l, int lo, int hi) {
+        int np_ctx = (int)ceil_div(n_ctx[i], CF_PAGE_TOKENS);
+        int j = lo / CF_PAGE_TOKENS, j1 = (int)ceil_div(hi, CF_PAGE_TOKENS);
+        PageJob jb;
+        jb.staging_off = (int64_t)(uintptr_t)(host_dev[i] + ((size_t)l * np_ctx + j) * pb);
+        jb.layer = l;
+        jb.pt_off = pt_off[i];
+        jb.page_first = j;
+        jb.n_pages = j1 - j;
+        jb.tok_first = lo;
+        jb.tok_end = hi;
+        jb.block_first = ul.n_vblocks;
+        jb.pad = 0;
+        jobs.push_back(jb);
+        ++ul.n_jobs;
+        ul.n_vblocks += (int)ceil_div((int64_t)(j1 - j) * vec_per_page, PAGE_LOAD_UNIT_VECS);
+        ul.bytes += (size_t)(j1 - j) * pb;
+    };
+    for (int i = 0; i < B; ++i) {
+        if (n_units[i] == 0) continue;
+        if (mode[i] == CF_TOKEN_WISE) {
+            for (int u = 0; u < n_units[i]; ++u) {
+                DynUnitLoad ul{(int)jobs.size(), 0, 0, 0};
+                int lo = u * C, hi = std::min(n_ctx[i], lo + C);
+                for (int l = 0; l < L; ++l) add_job(ul, i, l, lo, hi);
+                tw_units[i].push_back(ul);
+            }
+        } else {
+            lw_members.push_back(i);
+        }
+    }
+    if (!lw_members.empty())
+        for (int l = 0; l < L; ++l) {
+            DynUnitLoad ul{(int)jobs.size(), 0, 0, 0};
+            for (int i : lw_members) add_job(ul, i, l, 0, n_ctx[i]);
+            lw_units.push_back(ul);
+        }
+    size_t off_jobs = mw.put(jobs.data(), jobs.size() * sizeof(PageJob));
+
+    Phase lw, suf;
+    {
+        std::vector<int32_t> ids, pos, slot;
+        for (int i : lw_members) add_segment(lw, ids, pos, slot, i, reqs[i].ctx_tokens, n_ctx[i], 0, L, false);
+        if (lw.T > 0) finish_phase(lw, ids, pos, slot);
+    }
+    std::vector<int32_t> last_rows;
+    if (logits_out) {
+        std::vector<int32_t> ids, pos, slot;
+        for (int i = 0; i < B; ++i) {
+            add_segment(suf, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, reqs[i].n_ctx, L, true);
+            last_rows.push_back(suf.T - 1);
+        }
+        finish_phase(suf, ids, pos, slot);
+    }
+    size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
+    c->last_rows = last_rows;
+    if (mw.overflow)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: batch metadata exceeds the context's limits "
+                    "(%zu load jobs)", jobs.size());
+    const size_t step_off = mw.off;      // per-step arrays start here, every step
+
+    // ---- events: one per load unit in flight, one for the compute step.  The copy stream is
+    // kept one unit deep, plus more while less than IO_LOOKAHEAD_PS of predicted work is queued
+    // (short units need the next launch queued behind them; long ones are claimed one at a time
+    // so that the claim is made as late as possible)
+    constexpr int IO_DEPTH = 4;
+    constexpr int64_t IO_LOOKAHEAD_PS = 2000000000;
+    while ((int)c->dyn_events.size() < IO_DEPTH + 1) {
+        hipEvent_t e = nullptr;
+        CF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c->dyn_events.push_back(e);
+    }
+    hipEvent_t ev_step = c->dyn_events[IO_DEPTH];
+
+    char* md = c->meta_dev();
+    CF_HIP(hipEventRecord(c->ev_start, c->cs));
+    CF_HIP(hipMemcpyAsync(md, c->meta_host, step_off, hipMemcpyHostToDevice, c->cs));
+    CF_HIP(hipEventRecord(c->ev_meta, c->cs));
+    CF_HIP(hipStreamWaitEvent(c->ps, c->ev_meta, 0));
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_elems = (int64_t)(pb / es);
+    g.layer_stride = g.page_elems * cache->n_pages;
+    double paced_bytes = 0;
+    if (c->throttle_gbs > 0) launch_pace_mark(c->ps, c->pace_dev());
+
+    // ---- the scheduling loop
+    // Layer-wise members share their pointers (the group moves as one).  `closed[i]`: the compute
+    // engine is done with request i for good (the group ran its last layer K/V-only, so there are
+    // no hidden states to go on from); the I/O channel takes what is left of it.
+    std::deque<int64_t> io_flight;                // predicted ps of the loads in flight, oldest first
+    int64_t io_issued = 0, io_retired = 0;        // event of load k: dyn_events[k % IO_DEPTH]
+    int64_t io_pred_done = 0;                     // predicted ps of the retired loads
+    double io_t_first = 0, io_t_last = 0;         // host clock: first issue, latest completion
+    int64_t c_pred_done = 0, step_pred = 0;
+    double c_meas_done_ms = 0, step_t0 = 0, gap_ms = 0, last_step_end = 0;
+    bool step_running = false, ask = true;        // ask: state changed since the last declined claim
+    bool force_io = false;
+    int scale_c = 1000, scale_io = 1000;
+    int n_steps = 0, n_cunits = 0;
+    int64_t loaded_bytes = 0;
+    int lw_layer = 0;                             // next layer of the layer-wise group
+    std::vector<uint8_t> closed(B, 0);
+    std::vector<int32_t> take(B);
+    auto any_live = [&]() {
+        for (int i = 0; i < B; ++i)
+            if (p_comp[i] <= p_io[i]) return true;
+        return false;
+    };
+    auto clamp_scale = [](double r) { return (int)std::min(4000.0, std::max(250.0, r * 1000.0 + 0.5)); };
+    auto unit_load_ps = [&](size_t bytes) {
+        __int128 num = (__int128)bytes * cost->gamma;
+        return cost->f_io + (int64_t)((num + (((__int128)1) << 20) - 1) >> 20);
+    };
+    CF_HIP(hipEventRecord(c->ev_comp, c->cs));    // stands if the compute engine claims nothing
+    // event state: 1 complete, 0 pending, -1 the runtime reports a failure
+    auto done = [](hipEvent_t e) {
+        hipError_t q = hipEventQuery(e);
+        if (q == hipSuccess) return 1;
+        (void)hipGetLastError();
+        return q == hipErrorNotReady ? 0 : -1;
+    };
+    double t_progress = now_ms();
+    constexpr double STALL_LIMIT_MS = 60000;      // no completion for this long: give up, do not spin for ever
+
+    while (true) {
+        bool progressed = false;
+        // retire finished loads (they complete in issue order)
+        while (!io_flight.empty()) {
+            int dn = done(c->dyn_events[io_retired % IO_DEPTH]);
+            if (dn < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed");
+            if (dn == 0) break;
+            io_t_last = now_ms();
+            io_pred_done += io_flight.front();
+            io_flight.pop_front();
+            ++io_retired;
+            if (io_pred_done > 0 && io_t_last > io_t_first)
+                scale_io = clamp_scale((io_t_last - io_t_first) * 1e9 / (double)io_pred_done);
+            progressed = ask = true;
+        }
+        // keep the copy stream fed
+        while ((int)io_flight.size() < IO_DEPTH) {
+            int64_t backlog = 0;
+            for (int64_t f : io_flight) backlog += (int64_t)((__int128)f * scale_io / 1000);
+            if (!io_flight.empty() && backlog >= IO_LOOKAHEAD_PS) break;
+            int64_t busy = 0;
+            if (step_running)
+                busy = std::max<int64_t>(0, step_pred - (int64_t)((now_ms() - step_t0) * 1e9));
+            // both engines idle and both declined (cannot happen with consistent costs): the channel takes it
+            if (force_io) busy = INT64_MAX / 4;
+            force_io = false;
+            int32_t pick = -1;
+            cf_dynamic_io_pick(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
+                               busy, scale_c, scale_io, &pick);
+            if (pick < 0) break;
+            const DynUnitLoad* ul;
+            if (mode[pick] == CF_TOKEN_WISE) {
+                ul = &tw_units[pick][p_io[pick]];
+                --p_io[pick];
+            } else {
+                ul = &lw_units[p_io[pick]];
+                for (int i : lw_members) --p_io[i];
+            }
+            if (io_issued == 0) io_t_first = now_ms();
+            c->prof_begin(CF_K_H2D_COPY, (double)ul->bytes, c->ps);
+            launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ul->job_first,
+                             ul->n_jobs, ul->n_vblocks, c->load_wgs, (const int32_t*)md, g);
+            if (c->throttle_gbs > 0) {
+                paced_bytes += (double)ul->bytes;
+                launch_pace_wait(c->ps, c->pace_dev(),
+                                 (unsigned long long)(paced_bytes / (c->throttle_gbs * 1e9) * c->wall_hz));
+            }
+            c->prof_end(CF_K_H2D_COPY, c->ps);
+            CF_HIP(hipEventRecord(c->dyn_events[io_issued % IO_DEPTH], c->ps));
+            io_flight.push_back(unit_load_ps(ul->bytes));
+            loaded_bytes += (int64_t)ul->bytes;
+            ++io_issued;
+            progressed = ask = true;
+        }
+        // compute engine: retire the step ...
+        int step_dn = step_running ? done(ev_step) : 0;
+        if (step_dn < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the compute stream failed");
+        if (step_dn > 0) {
+            last_step_end = now_ms();
+            c_meas_done_ms += last_step_end - step_t0;
+            c_pred_done += step_pred;
+            if (c_pred_done > 0) scale_c = clamp_scale(c_meas_done_ms * 1e9 / (double)c_pred_done);
+            step_running = false;
+            progressed = ask = true;
+        }
+        // ... and ask for the next one (again after every change of state while it is idle)
+        if (!step_running && ask) {
+            ask = false;
+            int64_t backlog = 0, pred = 0;
+            for (int64_t f : io_flight) backlog += (int64_t)((__int128)f * scale_io / 1000);
+            cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
+                             scale_c, scale_io, take.data(), &pred);
+            Phase step;
+            std::vector<int32_t> ids, pos, slot;
+            bool lw_take = false, lw_last = false;
+            for (int i = 0; i < B; ++i) {
+                if (!take[i]) continue;
+                if (mode[i] == CF_TOKEN_WISE) {
+                    int lo = p_comp[i] * C, hi = std::min(n_ctx[i], lo + C);
+                    add_segment(step, ids, pos, slot, i, reqs[i].ctx_tokens + lo, hi - lo, lo, L, false);
+                    ++p_comp[i];
+                    ++n_cunits;
+                } else {
+                    lw_take = true;
+                    lw_last = take[i] == 2;
+                }
+            }
+            if (step.T > 0 || lw_take) {
+                double t_launch = now_ms();
+                if (n_steps > 0) gap_ms += t_launch - last_step_end;
+                step_t0 = t_launch;
+                if (lw_take) {
+                    // layer lw_layer of the group: in full if the group goes on, else up to its K/V write
+                    for (Segment& sg : lw.segs) sg.layers = lw_layer + (lw_last ? 1 : 2);
+                    int rc2 = run_phase(c, cache, lw, lw_layer + 1, nullptr, nullptr, lw_layer, 0);
+                    if (rc2) return rc2;
+                    for (int i : lw_members) {
+                        ++p_comp[i];
+                        ++n_cunits;
+                        if (lw_last) closed[i] = 1;
+                    }
+                    ++lw_layer;
+                }
+                if (step.T > 0) {
+                    mw.off = step_off;
+                    finish_phase(step, ids, pos, slot);
+                    if (mw.overflow)
+                        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits");
+                    CF_HIP(hipMemcpyAsync(md + step_off, c->meta_host + step_off, mw.off - step_off,
+                                          hipMemcpyHostToDevice, c->cs));
+                    int rc2 = run_phase(c, cache, step, L, nullptr, nullptr, 0, lw.T);
+                    if (rc2) return rc2;
+                }
+                CF_HIP(hipEventRecord(ev_step, c->cs));
+                CF_HIP(hipEventRecord(c->ev_comp, c->cs));
+                step_running = true;
+                step_pred = pred;
+                ++n_steps;
+                progressed = true;
+            }
+        }
+        if (!step_running && io_flight.empty()) {
+            if (!any_live()) break;
+            if (!progressed) force_io = true;
+        }
+        if (progressed) {
+            t_progress = now_ms();
+        } else {
+            if (now_ms() - t_progress > STALL_LIMIT_MS)
+                return fail(CF_ERR_HIP, "cf_restore_dynamic: no unit completed within %.0f s", STALL_LIMIT_MS / 1e3);
+            std::this_thread::sleep_for(std::chrono::microseconds(20));
+        }
+    }
+
+    // ---- join, new-turn prefill, logits
+    CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
+    CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+    if (logits_out) {
+        int rc2 = run_phase(c, cache, suf, L, nullptr, nullptr);
+        if (rc2) return rc2;
+        launch_rmsnorm(c->cs, m.dtype, c->h(), c->dl(), c->w.final_norm, c->a_last(), B, m.d_model,
+                       m.rms_eps, (const int32_t*)(md + off_last));
+        gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
+    }
+    CF_HIP(hipEventRecord(c->ev_end, c->cs));
+    CF_HIP(hipGetLastError());
+    CF_HIP(hipStreamSynchronize(c->cs));
+    CF_HIP(hipStreamSynchronize(c->ps));
+    c->prof_collect();
+
+    // ---- what came out
+    const double lin = linear_flops_per_token_layer(m);
+    const double pair_fl = 4.0 * m.n_q_heads * m.head_dim;
+    const double qkv_fl = 2.0 * m.d_model * (double)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    double fr = 0, fs = 0;
+    int64_t rec_cells = 0, all_cells = 0;
+    for (int i = 0; i < B; ++i) {
+        cf_split& sp = splits_out[i];
+        sp.mode = mode[i];
+        all_cells += (int64_t)n_ctx[i] * L;
+        if (mode[i] == CF_TOKEN_WISE) {
+            sp.k_tokens = (int32_t)std::min<int64_t>((int64_t)p_comp[i] * C, n_ctx[i]);
+            sp.layer_cut = L;
+            double k = sp.k_tokens;
+            rec_cells += (int64_t)sp.k_tokens * L;
+            // chunk by chunk the same pairs as one pass over k tokens; the top layer is K/V only
+            fr += (L - 1) * (k * lin + pair_fl * (k * (k + 1) / 2)) + k * qkv_fl;
+        } else {
+            sp.k_tokens = n_ctx[i];
+            sp.layer_cut = p_comp[i];
+            double t = n_ctx[i];
+            rec_cells += (int64_t)n_ctx[i] * p_comp[i];
+            if (p_comp[i] > 0) fr += (p_comp[i] - 1) * (t * lin + pair_fl * (t * (t + 1) / 2)) + t * qkv_fl;
+        }
+        if (logits_out) {
+            double nn = reqs[i].n_new, p0 = n_ctx[i];
+            fs += (double)L * (nn * lin + pair_fl * (nn * p0 + nn * (nn + 1) / 2));
+        }
+    }
+    if (logits_out) fs += 2.0 * m.d_model * (double)m.vocab * B;
+    if (timing) {
+        float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
+        CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
+        CF_HIP(hipEventElapsedTime(&t_copy, c->ev_start, c->ev_copy));
+        CF_HIP(hipEventElapsedTime(&t_join, c->ev_start, c->ev_t0));
+        CF_HIP(hipEventElapsedTime(&t_end, c->ev_start, c->ev_end));
+        timing->compute_ms = t_comp;
+        timing->copy_ms = t_copy;
+        timing->restore_ms = std::max(t_join, std::max(t_comp, t_copy));
+        timing->suffix_ms = t_end - timing->restore_ms;
+        timing->total_ms = t_end;
+        timing->recompute_flops = fr;
+        timing->suffix_flops = fs;
+        timing->loaded_bytes = loaded_bytes;
+        timing->recomputed_cells = rec_cells;
+        timing->loaded_cells = all_cells - rec_cells;
+    }
+    if (stats) {
+        stats->compute_steps = n_steps;
+        stats->compute_units = n_cunits;
+        stats->io_units = (int32_t)io_issued;
+        stats->scale_c_permille = scale_c;
+        stats->scale_io_permille = scale_io;
+        stats->compute_gap_ms = gap_ms;
     }
     return CF_OK;
 }

@@ -101,6 +101,43 @@ int check(const cf_cost_model* cm, const cf_plan_opts* o, int32_t B, const int32
     return CF_OK;
 }
 
+// The I/O channel's candidate: the live request (p_comp <= p_io) with the largest key -- by
+// default the recomputation still ahead of it (Sec. 3.3); ties go to the longer context, then
+// to the lower index.  -1 if no request is live.
+int pick_io(const std::vector<Units>& req, const std::vector<int>& pc, const std::vector<int>& pio,
+            const int32_t* n_ctx, int io_key) {
+    int best = -1;
+    for (int i = 0; i < (int)req.size(); ++i) {
+        if (pc[i] > pio[i]) continue;
+        if (best < 0) { best = i; continue; }
+        bool gt, eq;
+        if (io_key == CF_KEY_MARGINAL) {
+            __int128 ki = (__int128)req[i].a(pio[i]) * req[best].b[pio[best]];
+            __int128 kb = (__int128)req[best].a(pio[best]) * req[i].b[pio[i]];
+            gt = ki > kb; eq = ki == kb;
+        } else {
+            const auto& pi = io_key == CF_KEY_REMAINING_COST ? req[i].a_prefix : req[i].tok_prefix;
+            const auto& pb = io_key == CF_KEY_REMAINING_COST ? req[best].a_prefix : req[best].tok_prefix;
+            int64_t ki = pi[pio[i] + 1] - pi[pc[i]];
+            int64_t kb = pb[pio[best] + 1] - pb[pc[best]];
+            gt = ki > kb; eq = ki == kb;
+        }
+        if (gt || (eq && n_ctx[i] > n_ctx[best])) best = i;
+    }
+    return best;
+}
+
+// Shared argument check of the run-time scheduling calls: pointers of every request must lie
+// in [0, units] x [-1, units-1].
+int check_pointers(const std::vector<Units>& req, const int32_t* p_comp, const int32_t* p_io,
+                   const char* who) {
+    for (int i = 0; i < (int)req.size(); ++i)
+        if (p_comp[i] < 0 || p_comp[i] > req[i].m() || p_io[i] < -1 || p_io[i] >= req[i].m())
+            return cf::fail(CF_ERR_INVALID_ARG, "%s: pointers of request %d outside its %d units", who, i,
+                            req[i].m());
+    return CF_OK;
+}
+
 }  // namespace
 
 extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
@@ -128,26 +165,7 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
     while (n_live > 0) {
         int ic = rr;
         while (!live(ic)) ic = (ic + 1 == B) ? 0 : ic + 1;
-        int best = -1;
-        for (int i = 0; i < B; ++i) {
-            if (!live(i)) continue;
-            if (best < 0) { best = i; continue; }
-            bool gt, eq;
-            if (opts->io_key == CF_KEY_MARGINAL) {
-                __int128 ki = (__int128)req[i].a(pio[i]) * req[best].b[pio[best]];
-                __int128 kb = (__int128)req[best].a(pio[best]) * req[i].b[pio[i]];
-                gt = ki > kb; eq = ki == kb;
-            } else {
-                const auto& pi = opts->io_key == CF_KEY_REMAINING_COST ? req[i].a_prefix
-                                                                        : req[i].tok_prefix;
-                const auto& pb = opts->io_key == CF_KEY_REMAINING_COST ? req[best].a_prefix
-                                                                        : req[best].tok_prefix;
-                int64_t ki = pi[pio[i] + 1] - pi[pc[i]];
-                int64_t kb = pb[pio[best] + 1] - pb[pc[best]];
-                gt = ki > kb; eq = ki == kb;
-            }
-            if (gt || (eq && n_ctx[i] > n_ctx[best])) best = i;
-        }
+        int best = pick_io(req, pc, pio, n_ctx, opts->io_key);
         int64_t fin_c = t_c + req[ic].a(pc[ic]);
         int64_t fin_io = t_io + req[best].b[pio[best]];
         cf_claim cl;
@@ -246,9 +264,6 @@ extern "C" int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* 
     return CF_OK;
 }
 
-// Closed-loop correction of the cost model from one executed batch: the compute-side
-// coefficients are scaled by measured/predicted compute time, the I/O-side ones by
-// measured/predicted I/O time (each clamped to [1/4, 4] per update).  This is how the
 // Compute-clock cost of the new-turn prefill of a batch (the recompute cost formula applied to
 // rows n_ctx[i] .. n_ctx[i]+n_new[i]-1 through n_layers layers).
 extern "C" int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int32_t B,
@@ -265,6 +280,9 @@ extern "C" int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int3
     return CF_OK;
 }
 
+// Closed-loop correction of the cost model from one executed batch: the compute-side
+// coefficients are scaled by measured/predicted compute time, the I/O-side ones by
+// measured/predicted I/O time (each clamped to [1/4, 4] per update).  This is how the
 // scheduler adapts to what calibration in isolation cannot see: the two engines slow each
 // other down when they run together (Sec. 3.3: priorities follow evolving resource
 // availability).  Integer arithmetic, round to nearest.
@@ -289,5 +307,142 @@ extern "C" int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t 
         cost->gamma = std::max<int64_t>(1, scale(cost->gamma, meas_io, pred_io));
         cost->s_io = scale(cost->s_io, meas_io, pred_io);
     }
+    return CF_OK;
+}
+
+// ---------------------------------------------------------------- run-time scheduling
+// The same two-pointer rule driven by actual progress instead of simulated clocks (Sec. 3.3,
+// the progressive chunk-level update): an executor asks these two functions whenever one of
+// its engines runs dry.  Costs come from the cost model, corrected by the ratios
+// measured/predicted the executor has observed so far in the call (in permille).  Each engine
+// takes a unit only if that does not push the end of the whole restoration out: with the
+// other engine's time-to-finish T_other (everything unclaimed counted on its side), a unit of
+// own cost x is taken iff (own busy time + x) <= T_other.
+
+namespace {
+
+struct DynState {
+    std::vector<Units> req;
+    int32_t scale_c, scale_io;
+    int64_t sc(int64_t v) const { return (int64_t)(((__int128)v * scale_c) / 1000); }
+    int64_t sio(int64_t v) const { return (int64_t)(((__int128)v * scale_io) / 1000); }
+};
+
+int dyn_setup(const char* who, const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+              const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io, int64_t t0, int64_t t1,
+              int32_t scale_c, int32_t scale_io, DynState* st) {
+    int rc = check(cost, opts, B, n_ctx, who);
+    if (rc) return rc;
+    if (B > 0 && (!p_comp || !p_io)) return cf::fail(CF_ERR_INVALID_ARG, "%s: null pointer array", who);
+    if (t0 < 0 || t1 < 0 || scale_c <= 0 || scale_io <= 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: times must be >= 0, scales > 0", who);
+    st->req.resize(B);
+    for (int i = 0; i < B; ++i) st->req[i] = make_units(*cost, *opts, n_ctx[i], mode_of(*opts, n_ctx[i]));
+    st->scale_c = scale_c;
+    st->scale_io = scale_io;
+    return check_pointers(st->req, p_comp, p_io, who);
+}
+
+}  // namespace
+
+extern "C" int cf_dynamic_io_pick(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                                  const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
+                                  const uint8_t* compute_closed, int64_t io_backlog_ps,
+                                  int64_t compute_busy_ps, int32_t scale_c_permille,
+                                  int32_t scale_io_permille, int32_t* pick) {
+    DynState st;
+    int rc = dyn_setup("cf_dynamic_io_pick", cost, opts, B, n_ctx, p_comp, p_io, io_backlog_ps,
+                       compute_busy_ps, scale_c_permille, scale_io_permille, &st);
+    if (rc) return rc;
+    if (!pick) return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_io_pick: null pick");
+    std::vector<int> pc(p_comp, p_comp + B), pio(p_io, p_io + B);
+    int best = pick_io(st.req, pc, pio, n_ctx, opts->io_key);
+    *pick = best;
+    if (best < 0) return CF_OK;
+    // units of a request the compute engine has closed are the channel's in any case
+    if (compute_closed && compute_closed[best]) return CF_OK;
+    // C: when the compute engine would be done if the channel took nothing more
+    int64_t Crem = compute_busy_ps;
+    for (int i = 0; i < B; ++i) {
+        if (compute_closed && compute_closed[i]) continue;
+        for (int u = pc[i]; u <= pio[i]; ++u) Crem += st.sc(st.req[i].a(u));
+    }
+    // the candidate: the far-end unit of `best`; layer-wise requests move together, so the
+    // same layer of every open layer-wise request comes with it
+    int64_t b = 0;
+    if (st.req[best].mode == CF_LAYER_WISE) {
+        for (int i = 0; i < B; ++i)
+            if (pc[i] <= pio[i] && st.req[i].mode == CF_LAYER_WISE) b += st.sio(st.req[i].b[pio[i]]);
+    } else {
+        b = st.sio(st.req[best].b[pio[best]]);
+    }
+    if (io_backlog_ps + b > Crem) *pick = -1;      // the compute engine gets there sooner
+    return CF_OK;
+}
+
+extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
+                                const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
+                                const uint8_t* compute_closed, int64_t io_backlog_ps,
+                                int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
+                                int64_t* step_ps) {
+    DynState st;
+    int rc = dyn_setup("cf_dynamic_claim", cost, opts, B, n_ctx, p_comp, p_io, io_backlog_ps, 0,
+                       scale_c_permille, scale_io_permille, &st);
+    if (rc) return rc;
+    if (B > 0 && !take) return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: null take");
+    const std::vector<Units>& req = st.req;
+
+    // R: when the I/O channel would be done if the compute engine took nothing more
+    int64_t R = io_backlog_ps;
+    for (int i = 0; i < B; ++i)
+        for (int u = p_comp[i]; u <= p_io[i]; ++u) R += st.sio(req[i].b[u]);
+
+    // candidates: the next unit of every open token-wise request, and the next layer of all
+    // open layer-wise requests together (they move through the layers as one packed batch)
+    struct Item { int first; bool group; int64_t a, b; };
+    std::vector<Item> items;
+    Item grp{-1, true, 0, 0};
+    int64_t a_next = 0;                  // the group's unit after this one
+    bool has_next = true;
+    for (int i = 0; i < B; ++i) {
+        take[i] = 0;
+        if (p_comp[i] > p_io[i] || (compute_closed && compute_closed[i])) continue;
+        if (req[i].mode == CF_TOKEN_WISE) {
+            items.push_back(Item{i, false, st.sc(req[i].a(p_comp[i])), st.sio(req[i].b[p_comp[i]])});
+        } else {
+            if (grp.first < 0) grp.first = i;
+            grp.a += st.sc(req[i].a(p_comp[i]));
+            grp.b += st.sio(req[i].b[p_comp[i]]);
+            if (p_comp[i] + 1 <= p_io[i]) a_next += st.sc(req[i].a(p_comp[i] + 1));
+            else has_next = false;
+        }
+    }
+    if (grp.first >= 0) items.push_back(grp);
+    // cheapest recomputation per unit of I/O time saved first (a1/b1 < a2/b2), then by index
+    std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) {
+        __int128 l = (__int128)x.a * y.b, r = (__int128)y.a * x.b;
+        if (l != r) return l < r;
+        return x.first < y.first;
+    });
+    // a candidate is taken if the step, with it, still ends no later than the channel would
+    // need for everything the step so far leaves to it
+    int64_t A = 0, Bs = 0;
+    bool grp_taken = false;
+    for (const Item& it : items) {
+        if (A + it.a > R - Bs) continue;
+        A += it.a;
+        Bs += it.b;
+        if (it.group) grp_taken = true;
+        else take[it.first] = 1;
+    }
+    if (grp_taken) {
+        // 1: go through the whole layer (the next one looks worth taking too); 2: stop after
+        // the K/V write, this is the group's last recomputed layer
+        bool more = has_next && A + a_next <= R - Bs;
+        for (int i = 0; i < B; ++i)
+            if (p_comp[i] <= p_io[i] && req[i].mode == CF_LAYER_WISE && !(compute_closed && compute_closed[i]))
+                take[i] = more ? 1 : 2;
+    }
+    if (step_ps) *step_ps = A;
     return CF_OK;
 }

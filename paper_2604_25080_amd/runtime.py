@@ -123,6 +123,17 @@ class Session:
                                     self.logits.data_ptr() if want_logits else 0)
         return (self.logits[:len(requests)] if want_logits else None), tm
 
+    def restore_dynamic(self, requests, cost, opts, want_logits=True):
+        """Restore without a precomputed split: the engines claim units at run time.
+        Returns (logits or None, splits [(mode,k,cut)], timing dict, stats dict)."""
+        torch.cuda.current_stream(self.device).synchronize()
+        reqs = [dict(req_id=r["req_id"], ctx_tokens=r["ctx_tokens"], new_tokens=r["new_tokens"],
+                     host_kv=r["host_kv"].data_ptr() if r.get("host_kv") is not None else 0)
+                for r in requests]
+        splits, tm, st = self.ctx.restore_dynamic(self.cache, reqs, cost, opts,
+                                                  self.logits.data_ptr() if want_logits else 0)
+        return (self.logits[:len(requests)] if want_logits else None), splits, tm, st
+
     # -------------------------------------------------------------- introspection
     def read_pages(self, req_id, n_tokens):
         """Raw page bytes of a request: uint8 numpy [L, n_pages_req, page_bytes]."""

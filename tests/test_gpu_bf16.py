@@ -32,7 +32,9 @@ def build(shape_name, seed, n_req, n_lo, n_hi, m_lo, m_hi, chunk_rows, n_pages=N
     return b, refs, sess, host
 
 
-def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pipelined=True, load_path=0):
+def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pipelined=True, load_path=0,
+                        dynamic=None):
+    # dynamic = (cost model, plan options): scheduled at run time, checked against the splits that resulted
     sess.ctx.set_kernel_set(simple_only)
     sess.ctx.set_pipelined_join(pipelined)
     sess.ctx.set_load_path(load_path)
@@ -50,7 +52,12 @@ def restore_and_compare(b, refs, sess, host, splits, seed, simple_only=False, pi
             sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
             assert sess.cache.page_table(1 + i) == opt.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
             reqs.append(dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=host[i]))
-        logits, tm = sess.restore(reqs, [(0, k, c) for k, c in splits])
+        if dynamic is None:
+            logits, tm = sess.restore(reqs, [(0, k, c) for k, c in splits])
+        else:
+            logits, got, tm, st = sess.restore_dynamic(reqs, *dynamic)
+            splits = [(k, c) for _, k, c in got]
+            tm = dict(tm, splits=got, stats=st)
         worst_kv = worst_logit = 0.0
         for i in range(len(b.n_ctx)):
             n, m = b.n_ctx[i], b.n_new[i]
@@ -250,3 +257,34 @@ def test_captured_boundary_reproduces_the_full_prefill_bit_for_bit(mini):
         sess.ctx.set_stage(0, L)
         for i in range(B):
             sess.cache.free(1 + i)
+
+
+def test_mini_bf16_run_time_scheduling(mini):
+    """No split is given: the two engines claim chunks / layers while the call runs.  Whatever
+    split results, the restored cache and the logits must be the oracle's."""
+    import paper_2604_25080_amd as cf
+    b, refs, sess, host = mini
+    L = b.shape.n_layers
+    kvb = b.shape.kv_bytes_per_token_layer
+    tables = {
+        "recompute": dict(f_c=1000, alpha=1000, beta=10, f_io=10 ** 12, gamma=10 ** 12),
+        "load": dict(f_c=10 ** 12, alpha=10 ** 12, beta=10 ** 9, f_io=1000, gamma=1000),
+        "race": dict(f_c=20_000_000, alpha=60_000, beta=20_000, f_io=10_000_000, gamma=30_000_000),
+    }
+    seed = 60
+    for mode, l_delta, chunk in ((0, 0, 64), (1, 0, 64), (-1, 400, 128), (0, 0, 256)):
+        for kind in ("recompute", "load", "race", "race"):
+            seed += 1
+            dyn = (cf.cost_model(**tables[kind]), cf.plan_opts(chunk, l_delta, L, kvb, mode, 0, 150))
+            out, wkv, wlg, tm = restore_and_compare(b, refs, sess, host, None, seed=seed, dynamic=dyn)
+            splits, st = tm["splits"], tm["stats"]
+            print(f"mode {mode} chunk {chunk} {kind}: splits {splits} steps {st['compute_steps']} "
+                  f"loads {st['io_units']} KV err {wkv:.3g}")
+            assert tm["recomputed_cells"] + tm["loaded_cells"] == sum(b.n_ctx) * L
+            for (m, k, c), n in zip(splits, b.n_ctx):
+                assert m == (mode if mode >= 0 else (0 if n >= l_delta else 1))
+                assert (c == L and (k % chunk == 0 or k == n)) if m == 0 else k == n
+            if kind == "recompute":
+                assert tm["loaded_cells"] == 0
+            if kind == "load":
+                assert tm["recomputed_cells"] == 0

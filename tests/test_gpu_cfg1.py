@@ -39,7 +39,9 @@ def fragment(sess, oracle_pt, seed):
             oracle_pt.release(1000 + op[1])
 
 
-def run_and_check(env, splits, seed=3, check_logits=True):
+def run_and_check(env, splits, seed=3, check_logits=True, dynamic=None):
+    """`dynamic` = (cost model, plan options): no splits are given, the library schedules at run
+    time and reports the splits that resulted; everything is then checked against those."""
     b, refs, ws, sess, host = env
     sess.pool.fill_(0xFF)                       # NaN pattern: every owned slot must be overwritten
     opt = PageTable(N_PAGES)
@@ -54,7 +56,12 @@ def run_and_check(env, splits, seed=3, check_logits=True):
             assert sess.cache.page_table(rid) == opt.alloc(rid, b.n_ctx[i] + b.n_new[i])
             reqs.append(dict(req_id=rid, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i],
                              host_kv=host[i]))
-        logits, tm = sess.restore(reqs, [(0, k, c) for k, c in splits])
+        if dynamic is None:
+            logits, tm = sess.restore(reqs, [(0, k, c) for k, c in splits])
+        else:
+            logits, got_splits, tm, st = sess.restore_dynamic(reqs, *dynamic)
+            splits = [(k, c) for _, k, c in got_splits]
+            tm = dict(tm, splits=got_splits, stats=st)
         for i in range(len(b.n_ctx)):
             n, m = b.n_ctx[i], b.n_new[i]
             raw = sess.read_pages(1 + i, n + m)
@@ -275,3 +282,79 @@ def test_cfg1_degenerate_batches(env):
     finally:
         for i in range(len(cases)):
             sess.cache.free(1 + i)
+
+
+# ------------------------------------------------------------ run-time scheduling
+def dyn_args(shape, kind, mode, l_delta=0, chunk=16):
+    import paper_2604_25080_amd as cf
+    tables = {
+        # loads look ruinous: the compute engine takes every unit, the channel declines all
+        "recompute": dict(f_c=1000, alpha=1000, beta=10, f_io=10 ** 12, gamma=10 ** 12),
+        # recomputation looks ruinous: the channel takes every unit
+        "load": dict(f_c=10 ** 12, alpha=10 ** 12, beta=10 ** 9, f_io=1000, gamma=1000),
+        # the same order of magnitude as this tiny model really shows: a race, any split is legal
+        "race": dict(f_c=25_000_000, alpha=300_000, beta=100_000, f_io=15_000_000, gamma=40_000_000),
+    }
+    return (cf.cost_model(**tables[kind]),
+            cf.plan_opts(chunk, l_delta, shape.n_layers, shape.kv_bytes_per_token_layer, mode))
+
+
+@pytest.mark.parametrize("mode", [0, 1, -1])
+def test_cfg1_run_time_scheduling_restores_the_same_cache(env, mode):
+    b = env[0]
+    L = b.shape.n_layers
+    total = sum(b.n_ctx) * L
+    # mode -1 with l_delta 100: request 0 (128 tokens) token-wise, request 1 (64) layer-wise
+    for seed, kind in enumerate(("recompute", "load", "race", "race")):
+        tm = run_and_check(env, None, seed=30 + seed, dynamic=dyn_args(b.shape, kind, mode, l_delta=100))
+        splits, st = tm["splits"], tm["stats"]
+        assert tm["recomputed_cells"] + tm["loaded_cells"] == total
+        for (m, k, c), n in zip(splits, b.n_ctx):
+            assert m == (mode if mode >= 0 else (0 if n >= 100 else 1))
+            assert (k % 16 == 0 or k == n) and 0 <= k <= n and 0 <= c <= L
+            assert c == L if m == 0 else k == n
+        rec = sum(k * c if m == 0 else n * c for (m, k, c), n in zip(splits, b.n_ctx))
+        assert tm["recomputed_cells"] == rec
+        if kind == "recompute":
+            assert tm["loaded_cells"] == 0 and st["io_units"] == 0
+        if kind == "load":
+            assert tm["recomputed_cells"] == 0 and st["compute_steps"] == 0
+        assert (st["compute_steps"] == 0) == (st["compute_units"] == 0)
+
+
+def test_cfg1_run_time_scheduling_chunk_sizes_throttle_and_errors(env):
+    import paper_2604_25080_amd as cf
+    b, refs, ws, sess, host = env
+    # larger chunks (ragged last chunk of request 1: 64 = 48 + 16), throttled link
+    run_and_check(env, None, seed=40, dynamic=dyn_args(b.shape, "race", 0, chunk=48))
+    sess.ctx.set_link_throttle(0.05)
+    try:
+        tm = run_and_check(env, None, seed=41, dynamic=dyn_args(b.shape, "race", 0, chunk=32))
+        assert tm["copy_ms"] >= 0.9 * tm["loaded_bytes"] / 0.05e9 * 1e3
+    finally:
+        sess.ctx.set_link_throttle(0.0)
+    # argument errors come back as codes
+    sess.cache.alloc(1, b.n_ctx[0] + b.n_new[0])
+    r = dict(req_id=1, ctx_tokens=b.ctx_tokens[0], new_tokens=b.new_tokens[0], host_kv=host[0])
+    try:
+        cost, opts = dyn_args(b.shape, "race", 0, chunk=24)          # not a multiple of the page size
+        with pytest.raises(cf.CfError) as e:
+            sess.restore_dynamic([r], cost, opts)
+        assert e.value.status == cf.CF_ERR_INVALID_ARG
+        cost, opts = dyn_args(b.shape, "race", 0)
+        pageable = torch.from_numpy(host[0].numpy().copy())
+        with pytest.raises(cf.CfError) as e:
+            sess.restore_dynamic([dict(r, host_kv=pageable)], cost, opts)
+        assert e.value.status == cf.CF_ERR_INVALID_ARG
+        with pytest.raises(cf.CfError) as e:
+            sess.restore_dynamic([dict(r, req_id=77)], cost, opts)
+        assert e.value.status == cf.CF_ERR_UNKNOWN_REQUEST
+        sess.ctx.set_stage(1, 2)
+        with pytest.raises(cf.CfError):
+            sess.restore_dynamic([r], cost, opts)
+        sess.ctx.set_stage(0, b.shape.n_layers)
+        logits, splits, tm, st = sess.restore_dynamic([], cost, opts)
+        assert splits == [] and tm["loaded_cells"] == 0
+    finally:
+        sess.ctx.set_stage(0, b.shape.n_layers)
+        sess.cache.free(1)

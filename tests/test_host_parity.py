@@ -43,6 +43,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_model_desc) == 40
     assert ctypes.sizeof(cf.cf_request) == 48
     assert ctypes.sizeof(cf.cf_timing) == 64
+    assert ctypes.sizeof(cf.cf_dynamic_stats) == 32
 
 
 def test_status_strings():
@@ -146,6 +147,45 @@ def test_cost_feedback_matches_oracle_and_balances_a_contended_plan():
         t_c, t_io = P.split_times(true, opts_o, n_ctx, units)          # what "really" happens
         cf.cost_feedback(model, st["t_comp"], t_c, st["t_io"], t_io)
     assert abs(t_c - t_io) < 0.1 * max(t_c, t_io)
+
+
+def test_run_time_scheduling_calls_match_oracle_on_random_states():
+    rng = np.random.default_rng(44)
+    n_cases = 0
+    for it in range(400):
+        d = dict(f_c=int(rng.integers(0, 50_000_000)), alpha=int(rng.integers(100_000, 2_000_000)),
+                 beta=int(rng.integers(0, 60_000)), f_io=int(rng.integers(0, 20_000_000)),
+                 gamma=int(rng.integers(5_000_000, 900_000_000)))
+        ocm, ccm = both_cost(d)
+        mode = int(rng.integers(-1, 2))
+        key = int(rng.integers(0, 3))
+        opts_o, opts_c = both_opts(int(rng.choice([16, 64, 512])), int(rng.integers(0, 3000)),
+                                   int(rng.integers(1, 9)), 4096, mode, key, int(rng.integers(0, 400)))
+        b = int(rng.integers(1, 7))
+        n = [int(x) for x in rng.integers(0, 4000, size=b)]
+        m = [len(P.unit_costs(ocm, opts_o, x, P.request_mode(opts_o, x))[0]) for x in n]
+        pc = [int(rng.integers(0, mi + 1)) for mi in m]
+        pio = [int(rng.integers(-1, mi)) if mi else -1 for mi in m]
+        closed = [bool(rng.integers(0, 4) == 0) for _ in range(b)]
+        backlog = int(rng.integers(0, 3 * 10 ** 10))
+        busy = int(rng.integers(0, 10 ** 10))
+        sc, sio = int(rng.integers(250, 4001)), int(rng.integers(250, 4001))
+        want_take, want_a = P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio)
+        got_take, got_a = cf.dynamic_claim(ccm, opts_c, n, pc, pio, closed, backlog, sc, sio)
+        assert (got_take, got_a) == (want_take, want_a), (it, n, pc, pio)
+        want = P.io_pick(ocm, opts_o, n, pc, pio, closed, backlog, busy, sc, sio)
+        got = cf.dynamic_io_pick(ccm, opts_c, n, pc, pio, closed, backlog, busy, sc, sio)
+        assert got == want, (it, n, pc, pio)
+        n_cases += any(want_take) + (want >= 0)
+    assert n_cases > 200         # the states are not all trivial
+    cm = cf.cost_model(**hand_cost_model("balanced"))
+    with pytest.raises(cf.CfError) as e:
+        cf.dynamic_claim(cm, cf.plan_opts(512, 0, 32, 4096), [1000], [3], [1], None, 0)    # 2 units only
+    assert e.value.status == cf.CF_ERR_INVALID_ARG
+    with pytest.raises(cf.CfError):
+        cf.dynamic_io_pick(cm, cf.plan_opts(512, 0, 32, 4096), [1000], [0], [1], None, -1, 0)
+    with pytest.raises(cf.CfError):
+        cf.dynamic_claim(cm, cf.plan_opts(512, 0, 32, 4096), [1000], [0], [1], None, 0, 0, 1000)
 
 
 def test_planner_rejects_bad_arguments():

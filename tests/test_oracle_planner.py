@@ -267,3 +267,113 @@ def test_baseline_plans():
     opts = P.PlanOpts(512, 0, 32, 4096)
     assert P.all_recompute(opts, [5, 7]) == [(0, 5, 32), (0, 7, 32)]
     assert P.all_load(opts, [5, 7]) == [(0, 0, 32), (0, 0, 32)]
+
+
+# ------------------------------------------------ run-time scheduling (Sec. 3.3)
+def test_dynamic_claim_hand_cases():
+    # uniform costs: one token-wise request of 4 chunks, a = 2048 * alpha-ish each, b fixed
+    cm = P.CostModel(f_c=0, alpha=10, beta=0, f_io=0, gamma=1 << 20)     # a = L*10*t, b = bytes
+    opts = P.PlanOpts(16, 0, 2, 1, P.TOKEN_WISE)                         # unit: 16 tokens, 2 layers
+    a, b, _ = P.unit_costs(cm, opts, 64, P.TOKEN_WISE)
+    assert a == [320] * 4 and b == [32] * 4
+    # the channel alone needs 4*32 = 128 < 320: compute takes nothing
+    assert P.dynamic_claim(cm, opts, [64], [0], [3]) == ([0], 0)
+    # with a backlog of 192 the channel needs 320: a step of 320 ends no later -> taken
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=192) == ([1], 320)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=191) == ([0], 0)
+    # loads that turn out 3x slower than modelled tip the same state over
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], scale_io=3000) == ([1], 320)
+    # two requests: each unit taken shortens what is left to the channel, the second does not fit
+    take, a_sum = P.dynamic_claim(cm, opts, [64, 64], [0, 0], [3, 3], io_backlog=100)
+    assert (take, a_sum) == ([1, 0], 320)       # R = 100 + 256; 320 <= 356, then 640 > 356 - 32
+    # a finished request is never a candidate
+    assert P.dynamic_claim(cm, opts, [64, 64], [4, 0], [3, 3], io_backlog=10 ** 6)[0] == [0, 1]
+
+
+def test_dynamic_claim_layer_wise_group_and_last_layer_mark():
+    cm = P.CostModel(f_c=0, alpha=10, beta=0, f_io=0, gamma=1 << 20)
+    opts = P.PlanOpts(16, 0, 4, 1, P.LAYER_WISE)            # units: 4 layers over all tokens
+    n = [32, 16]                                            # a per layer 320 / 160, b 32 / 16
+    # plenty of backlog: the group takes layer 0 and expects to take layer 1 too
+    assert P.dynamic_claim(cm, opts, n, [0, 0], [3, 3], io_backlog=10 ** 6) == ([1, 1], 480)
+    # room for exactly one layer: R = 480 + 4*48 = 672; 480 <= 672, next 960 > 672 - 48
+    assert P.dynamic_claim(cm, opts, n, [0, 0], [3, 3], io_backlog=480) == ([2, 2], 480)
+    # the last unclaimed layer of the group is always marked as its last
+    assert P.dynamic_claim(cm, opts, n, [3, 3], [3, 3], io_backlog=10 ** 6)[0] == [2, 2]
+    # closed requests are not offered to the compute engine, whatever the backlog
+    assert P.dynamic_claim(cm, opts, n, [1, 1], [3, 3], closed=[True, True], io_backlog=10 ** 9) == ([0, 0], 0)
+
+
+def test_io_pick_declines_when_compute_gets_there_first():
+    cm = P.CostModel(f_c=0, alpha=10, beta=0, f_io=0, gamma=1 << 20)
+    opts = P.PlanOpts(16, 0, 2, 1, P.TOKEN_WISE)            # a = 320, b = 32 per unit
+    # longest remaining recomputation first (Sec. 3.3), ties to the longer context
+    assert P.io_pick(cm, opts, [64, 128], [0, 0], [3, 7]) == 1
+    assert P.io_pick(cm, opts, [64, 128], [0, 4], [3, 7]) == 1     # equal remaining: longer context
+    assert P.io_pick(cm, opts, [64, 128], [0, 5], [3, 7]) == 0
+    assert P.io_pick(cm, opts, [64, 128], [4, 8], [3, 7]) == -1    # nothing live
+    # one unit left, costs 320 to recompute: the channel takes it unless its backlog is longer
+    assert P.io_pick(cm, opts, [64], [3], [3], io_backlog=288) == 0
+    assert P.io_pick(cm, opts, [64], [3], [3], io_backlog=289) == -1
+    assert P.io_pick(cm, opts, [64], [3], [3], io_backlog=289, compute_busy=1) == 0
+    assert P.io_pick(cm, opts, [64], [3], [3], closed=[True], io_backlog=10 ** 9) == 0
+    # never both decline: whatever the state, with the compute engine idle one of them takes a unit
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        cm = rand_cm(rng)
+        mode = int(rng.integers(-1, 2))
+        opts = P.PlanOpts(64, 600, 4, 4096, mode, kv_only_permille=int(rng.integers(0, 300)))
+        n = [int(x) for x in rng.integers(1, 1500, size=int(rng.integers(1, 5)))]
+        m = [len(P.unit_costs(cm, opts, x, P.request_mode(opts, x))[0]) for x in n]
+        pc = [int(rng.integers(0, mi + 1)) for mi in m]
+        pio = [int(rng.integers(pc[i] - 1, m[i])) for i in range(len(n))]
+        if opts.force_mode != P.TOKEN_WISE:           # layer-wise requests share their pointers
+            lw = [i for i in range(len(n)) if P.request_mode(opts, n[i]) == P.LAYER_WISE]
+            for i in lw:
+                pc[i], pio[i] = pc[lw[0]], max(pio[lw[0]], pc[lw[0]] - 1)
+        if all(pc[i] > pio[i] for i in range(len(n))):
+            continue
+        backlog = int(rng.integers(0, 10 ** 10))
+        sc, sio = int(rng.integers(250, 4001)), int(rng.integers(250, 4001))
+        take, _ = P.dynamic_claim(cm, opts, n, pc, pio, None, backlog, sc, sio)
+        pick = P.io_pick(cm, opts, n, pc, pio, None, backlog, 0, sc, sio)
+        assert any(take) or pick >= 0
+
+
+@pytest.mark.parametrize("kind", ["mi355x_like", "balanced", "slow_io", "uniform"])
+@pytest.mark.parametrize("mode,n_ctx", [(P.TOKEN_WISE, [9000, 5000, 16000, 2100]),
+                                        (P.LAYER_WISE, [4096, 3000, 1000]),
+                                        (-1, [16384, 9000, 1500, 800])])
+def test_simulated_run_time_scheduling_tracks_the_static_plan_and_adapts(kind, mode, n_ctx):
+    cm = cm_of(kind)
+    opts = P.PlanOpts(512, 2048, 32, 4096, mode, kv_only_permille=120)
+    splits, st = P.plan(cm, opts, n_ctx)
+    dsplits, makespan, n_steps = P.simulate_dynamic(cm, opts, n_ctx)
+    for (m, k, c), n in zip(dsplits, n_ctx):              # a valid split for every request
+        assert 0 <= k <= n and 0 <= c <= 32 and (k == n if m == P.LAYER_WISE else c == 32)
+    # the world behaves as modelled: deciding at run time costs at most a few percent
+    assert makespan <= 1.03 * st["makespan"]
+    # compute really runs 1.5x slower than modelled: the static split is stuck with its plan,
+    # the run-time scheduler sees the slow steps and leaves more to the channel
+    slow = P.CostModel(cm.f_c * 3 // 2, cm.alpha * 3 // 2, cm.beta * 3 // 2, cm.f_io, cm.gamma)
+    units = [(-(-k // 512) if m == P.TOKEN_WISE else c) for m, k, c in splits]
+    t_c, t_io = P.split_times(slow, opts, n_ctx, units, [s[0] for s in splits])
+    _, makespan_slow, _ = P.simulate_dynamic(cm, opts, n_ctx, true_cm=slow)
+    assert makespan_slow <= max(t_c, t_io)
+    # and it never does worse than the better of the two extremes by more than one step
+    all_io = sum(sum(P.unit_costs(slow, opts, n, P.request_mode(opts, n))[1]) for n in n_ctx)
+    assert makespan_slow <= 1.05 * all_io
+
+
+def test_simulated_run_time_scheduling_against_brute_force():
+    rng = np.random.default_rng(31)
+    for _ in range(25):
+        cm = rand_cm(rng, overheads=False)
+        opts = P.PlanOpts(64, 0, 3, 4096, P.TOKEN_WISE)
+        n_ctx = [int(x) for x in rng.integers(64, 400, size=2)]
+        best, _ = P.brute_force(cm, opts, n_ctx)
+        _, makespan, _ = P.simulate_dynamic(cm, opts, n_ctx, lookahead=0)
+        costs = [P.unit_costs(cm, opts, n, P.TOKEN_WISE) for n in n_ctx]
+        biggest = max(max(a + b) for a, b, _ in costs)
+        # list scheduling: within one (largest) unit per engine of the optimum
+        assert makespan <= best + 2 * biggest
