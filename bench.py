@@ -67,7 +67,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--plan", default="planner",
-                    help="planner | all_recompute | all_load | cut=<L> (layer cut for every request)")
+                    help="planner | dynamic (claims at run time, no precomputed split) | per_request | "
+                         "all_recompute | all_load | cut=<L> (layer cut for every request)")
+    ap.add_argument("--step-cap-ms", type=float, default=0.0, help="dynamic: cap of a compute step (0: library default)")
+    ap.add_argument("--claim-order", choices=["cheapest", "shortest"], default="cheapest",
+                    help="dynamic: order of the compute engine's candidates")
+    ap.add_argument("--model-skew", default="1:1",
+                    help="c:io -- multiply the calibrated compute / load costs by these before planning "
+                         "(a deliberately wrong cost model, to see what each scheduler makes of it)")
+    ap.add_argument("--no-feedback", action="store_true",
+                    help="planner: do not correct the cost model from measured steps")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink context lengths (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-rows", type=int, default=0)
@@ -173,6 +182,12 @@ def main():
     l_delta = cf.derive_l_delta(cm, opts, 32768)
     opts.l_delta = l_delta
     log(f"[bench] H2D {h2d_gbs:.1f} GB/s; cost model {cost}; L_delta {l_delta}")
+    skew_c, skew_io = (float(x) for x in args.model_skew.split(":"))
+    if (skew_c, skew_io) != (1.0, 1.0):
+        for f in ("f_c", "alpha", "beta", "s_c"):
+            setattr(cm, f, int(getattr(cm, f) * skew_c))
+        for f in ("f_io", "gamma", "s_io"):
+            setattr(cm, f, int(getattr(cm, f) * skew_io))
 
     def plan_model():
         """The cost table the planner sees: with the pipelined join the new-turn prefill shares
@@ -226,7 +241,17 @@ def main():
     gemm_kernels = ["gemm_qkv", "gemm_oproj", "gemm_gate_up", "gemm_down", "gemm_lm_head"]
     prof_kernels = gemm_kernels + ["attention", "h2d_copy", "page_scatter"]
 
+    dyn_stats = []
+
     def step():
+        if args.plan == "dynamic":
+            # no plan: the engines claim units while the call runs; the cost model only seeds
+            # the predictions (no start-ups: they are not per-unit costs)
+            _, splits, tm, st = sess.restore_dynamic(reqs, cm, opts, want_logits=True,
+                                                     step_cap_ps=int(args.step_cap_ms * 1e9),
+                                                     order={"cheapest": 0, "shortest": 1}[args.claim_order])
+            dyn_stats.append(st)
+            return splits, None, tm
         splits, stats = make_plan()
         logits, tm = sess.restore(reqs, splits, want_logits=not stage)
         if stats == "probe":
@@ -244,8 +269,9 @@ def main():
             # when the compute stream finishes well after the copy stream, its end is the
             # measurement.
             meas_comp = tm["total_ms"] if tm["total_ms"] > 1.02 * tm["copy_ms"] else tm["compute_ms"]
-            cf.cost_feedback(cm, stats["t_comp"], int(meas_comp * 1e9), stats["t_io"],
-                             int(tm["copy_ms"] * 1e9))
+            if not args.no_feedback:
+                cf.cost_feedback(cm, stats["t_comp"], int(meas_comp * 1e9), stats["t_io"],
+                                 int(tm["copy_ms"] * 1e9))
         return splits, stats, tm
 
     # HIP events bracket every launch of a profiled kernel class and cost stream time, so the
@@ -257,10 +283,11 @@ def main():
     sess.ctx.profile_read(reset=True)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
-    tms = []
+    tms, all_splits = [], []
     for _ in range(args.steps):
         splits, stats, tm = step()
         tms.append(tm)
+        all_splits.append(splits)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
     prof = sess.ctx.profile_read(reset=True)
@@ -309,6 +336,7 @@ def main():
     all_gemm_fl = sum(prof_all[k]["work"] for k in gemm_kernels)
     copy_gbs = loaded_bytes / (copy_ms * 1e-3) / 1e9 if copy_ms > 0 and loaded_bytes else 0.0
 
+    seq_join = args.sequential_join or args.plan == "dynamic"   # run-time scheduling joins before the new turn
     out = {
         "metric": "restored tokens/s", "value": sum_ctx * args.steps / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -319,7 +347,7 @@ def main():
                                + (f"stage layers [{stage[0]},{stage[1]}) of {shape.n_layers} from boundary activations, "
                                   if stage else "") +
                                
-                               f"{'sequential' if args.sequential_join else 'pipelined'} join",
+                               f"{'sequential' if seq_join else 'pipelined'} join",
                    "n_ctx": batch.n_ctx, "splits": [list(s) for s in splits]},
         "ttft_ms": ttft_ms, "restore_ms": restore_ms, "compute_stream_ms": compute_ms,
         "copy_stream_ms": copy_ms, "suffix_ms": suffix_ms,
@@ -327,9 +355,9 @@ def main():
         # the compute stream runs the recompute AND (pipelined join) the new-turn prefill
         "recompute": {"tokens": int(sum(s[1] for s in splits if s[2] > 0)),
                       "compute_stream_tflops": (rec_flops + suf_flops) / (max(compute_ms, ttft_ms - 0.0) * 1e-3) / 1e12
-                      if not args.sequential_join else rec_flops / (compute_ms * 1e-3) / 1e12,
+                      if not seq_join else rec_flops / (compute_ms * 1e-3) / 1e12,
                       "frac_of_mfma_peak": ((rec_flops + suf_flops) / (ttft_ms * 1e-3) / 1e12 / peak)
-                      if not args.sequential_join else rec_flops / (compute_ms * 1e-3) / 1e12 / peak,
+                      if not seq_join else rec_flops / (compute_ms * 1e-3) / 1e12 / peak,
                       "all_gemm_tflops": all_gemm_fl / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else 0.0},
         "copy": {"bytes": int(loaded_bytes), "GB/s": copy_gbs, "h2d_measured_GB/s": h2d_gbs,
                  "frac_of_measured_h2d": copy_gbs / h2d_gbs if h2d_gbs else 0.0,
@@ -341,6 +369,11 @@ def main():
                     "cost_model_after_feedback_ps": dict(f_c=cm.f_c, alpha=cm.alpha, beta=cm.beta, f_io=cm.f_io,
                                                          gamma=cm.gamma, s_c=cm.s_c, s_io=cm.s_io),
                     "predicted_ms": None if stats is None else stats["makespan"] / 1e9},
+        "dynamic": None if not dyn_stats else dict(
+            dyn_stats[-1],
+            # what the static planner would have fixed in advance from the same cost model
+            static_plan_splits=[list(x) for x in cf.restore_plan(plan_model(), opts, batch.n_ctx)[0]],
+            recomputed_tokens_per_step=[int(sum(x[1] for x in sp if x[2] > 0)) for sp in all_splits]),
         "kernels": kernels,
         "roofline": roofline,
     }

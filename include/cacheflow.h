@@ -206,23 +206,38 @@ int cf_dynamic_io_pick(const cf_cost_model* cost, const cf_plan_opts* opts, int3
                        int64_t compute_busy_ps, int32_t scale_c_permille,
                        int32_t scale_io_permille, int32_t* pick);
 
+enum cf_claim_order {
+    CF_ORDER_CHEAPEST = 0,   /* least recompute cost per load cost saved (a/b) first   */
+    CF_ORDER_SHORTEST = 1    /* least recomputation still ahead of the request first  */
+};
+
 /* cf_dynamic_claim: which of the live, not closed requests' next units the
  * compute engine takes for its next step (one step = those units run together,
  * layer-major).  With R = io_backlog + sum of the load costs b of all unclaimed
  * units (when the channel would be done on its own), candidates are ranked by
- * recompute cost per load cost saved (a/b ascending; ties to the lower index)
- * and taken greedily while  A + a <= R - Bs  (A, Bs: recompute and load cost
- * of what the step already holds).  Token-wise requests are candidates one by
+ * `order` (cf_claim_order; ties to the lower index) and taken greedily -- until
+ * the step has reached step_cap_ps, if that is > 0 (a step always gets a first
+ * unit) -- while  A + a + compute_later_ps <= R - Bs  (A, Bs: recompute and
+ * load cost of what the step already holds; A starts at step_fixed_ps, the
+ * predicted cost of work the step carries in any case, such as the new-turn
+ * prefill of requests that are already restored; compute_later_ps is work the
+ * compute engine must do after this step whatever it takes now, such as the
+ * new-turn prefill of the other requests).  Token-wise requests are candidates one by
  * one; all open layer-wise requests form ONE candidate (they advance through
  * the layers as a packed batch), a = sum a_i, b = sum b_i.
  *   take[i] (host int32[B]) : 0 not taken; 1 taken; 2 (layer-wise only) taken
  *                   as the group's last layer -- the same test fails for the
  *                   group's following layer (or there is none), so the
  *                   executor stops this one after its K/V write
- *   step_ps (may be NULL)   : A, the predicted duration of the step          */
+ *   step_ps (may be NULL)   : predicted duration of the step: step_fixed_ps +
+ *                   the units taken, the layer-wise ones at what the step
+ *                   really runs (the whole layer for 1, its K/V projection
+ *                   for 2; unit prices charge a layer's attention and MLP to
+ *                   the following unit)                                      */
 int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
                      const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
-                     const uint8_t* compute_closed, int64_t io_backlog_ps,
+                     const uint8_t* compute_closed, int64_t io_backlog_ps, int64_t step_fixed_ps,
+                     int64_t compute_later_ps, int64_t step_cap_ps, int32_t order,
                      int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
                      int64_t* step_ps);
 
@@ -357,15 +372,24 @@ int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* 
                      const cf_split* splits, float* logits_out, cf_timing* timing);
 
 typedef struct cf_dynamic_stats {
-    int32_t compute_steps;      /* steps the compute engine ran                    */
+    int32_t compute_steps;      /* steps the compute engine ran (new-turn ones too) */
     int32_t compute_units;      /* units it claimed (chunks, or request-layers)    */
     int32_t io_units;           /* load launches (one per claimed I/O unit)        */
     int32_t scale_c_permille;   /* measured / predicted at the end of the call     */
     int32_t scale_io_permille;
-    int32_t reserved;
+    int32_t planned_tail;       /* 1: the call ended with the planned tail (see below) */
     double compute_gap_ms;      /* compute stream idle between steps (host decides
                                    the next step only when the last one is done)   */
 } cf_dynamic_stats;
+
+typedef struct cf_dynamic_opts {
+    int64_t step_cap_ps;        /* a compute step stops taking units once its predicted
+                                   duration reaches this (0: no cap); shorter steps decide
+                                   later and finish requests one after the other, longer
+                                   ones run larger GEMMs                              */
+    int32_t order;              /* cf_claim_order of the compute engine's candidates  */
+    int32_t reserved;
+} cf_dynamic_opts;
 
 /* Restore a batch WITHOUT a precomputed split: the two engines claim units at
  * run time (Sec. 3.3, progressive chunk-level scheduling).  The I/O channel
@@ -375,11 +399,18 @@ typedef struct cf_dynamic_stats {
  * previous step has completed (HIP events, polled by the calling thread) and
  * runs the units it gets as one packed step: the claimed chunks of token-wise
  * requests through all layers, and the next layer of the layer-wise requests,
- * whose hidden states stay in the workspace from step to step.  When every
- * unit is claimed and both streams have drained, the new-turn prefill and the
- * logits follow (sequential join).
+ * whose hidden states stay in the workspace from step to step.  A request
+ * whose cache is complete (pointers crossed, its loads landed) has its
+ * new-turn rows prefilled in the very next step, beside whatever that step
+ * recomputes.  Once the compute engine, idle, declines every unit that is
+ * left, the rest of the schedule is known and is laid out like a planned
+ * restore (the planned tail): the channel loads all unclaimed cells layer by
+ * layer from the bottom, and the new turn of every request not yet prefilled
+ * runs beside those loads, its attention in layer l waiting for layer l only.
+ * The logits follow when the last request is through.
  *   cost, opts : the cost model seeds the predictions; the ratios measured /
- *                predicted are tracked inside the call.  opts->chunk_tokens
+ *                predicted are tracked inside the call and carried over to
+ *                the context's next call (they start at 1).  opts->chunk_tokens
  *                must be a multiple of 16 (page size); modes by
  *                opts->force_mode / l_delta as in cf_restore_plan.
  *   reqs       : as for cf_restore_batch; every request with n_ctx > 0 needs
@@ -391,13 +422,16 @@ typedef struct cf_dynamic_stats {
  *                are those of cf_restore_batch under these splits up to the
  *                order of floating-point summation (chunks are recomputed
  *                one step at a time, over the pages of the chunks before).
+ *   dyn        : may be NULL = {0, CF_ORDER_CHEAPEST}.
  *   logits_out, timing : as for cf_restore_batch.  stats may be NULL.
  * The context must cover the whole model (no cf_ctx_set_stage restriction).
- * Rows: (tokens of all layer-wise requests) + (token-wise requests x C) and
- * sum n_new must each fit max_tokens.  Blocking.                              */
+ * Rows: (tokens of all layer-wise requests) + (token-wise requests x C) +
+ * sum n_new must fit max_tokens.  timing->compute_ms marks the end of the last
+ * step that recomputed anything.  Blocking.                                   */
 int cf_restore_dynamic(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* reqs,
-                       const cf_cost_model* cost, const cf_plan_opts* opts, float* logits_out,
-                       cf_split* splits_out, cf_timing* timing, cf_dynamic_stats* stats);
+                       const cf_cost_model* cost, const cf_plan_opts* opts,
+                       const cf_dynamic_opts* dyn, float* logits_out, cf_split* splits_out,
+                       cf_timing* timing, cf_dynamic_stats* stats);
 
 /* Copy a request's first n_ctx tokens of KV from its pages to a host block
  * of cf_host_kv_bytes(n_ctx) bytes in the host layout (whole pages; the

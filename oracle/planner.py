@@ -352,18 +352,30 @@ def io_pick(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, compute_bu
     return best if io_backlog + b <= c_rem else -1
 
 
+ORDER_CHEAPEST = 0     # least recompute cost per load cost saved first
+ORDER_SHORTEST = 1     # least recomputation still ahead of the request first
+
+
 def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scale_c=1000,
-                  scale_io=1000):
+                  scale_io=1000, step_fixed=0, step_cap=0, order=ORDER_CHEAPEST, compute_later=0):
     """Which live, open requests' next units the compute engine takes for its next step.
 
     R = io_backlog + load cost of every unclaimed unit: the time the I/O channel needs if
     compute takes nothing.  Candidates: each open token-wise request's unit p_comp[i]; all
     open layer-wise requests together as one candidate (they advance as a packed batch).
-    Ranked by recompute cost per load cost (ascending, ties by index), a candidate (a, b) is
-    taken if  A + a <= R - Bs  with A, Bs the sums over those already taken: the step ends
-    no later than the channel would finish what the step so far leaves to it.
-    Returns (take, A): take[i] in {0, 1, 2}; 2 marks layer-wise requests whose group should
-    stop this layer after its K/V write because the test fails for the group's next layer."""
+    Ranked by `order` (recompute cost per load cost, or the recomputation the request still
+    has ahead of it; ascending, ties by index), a candidate (a, b) is taken if
+    A + a <= R - Bs  with A, Bs the sums over those already taken: the step ends no later
+    than the channel would finish what the step so far leaves to it.  With step_cap > 0 the
+    step takes no further candidate once A has reached the cap (the first one always goes in).
+    A starts at `step_fixed`, the cost of work the step carries in any case; `compute_later`
+    is work the compute engine has to do after this step whatever it takes now, and counts
+    against what the step may take: the test is  A + a + compute_later <= R - Bs.
+    Returns (take, step cost): take[i] in {0, 1, 2}; 2 marks layer-wise requests whose group
+    should stop this layer after its K/V write because the test fails for the group's next
+    layer.  The step cost counts the group's layer at what the step really runs -- the whole
+    layer (1) or its K/V projection (2) -- whereas the unit prices used for the decision charge
+    a layer's attention and MLP to the following unit."""
     b_req = len(n_ctx)
     closed = closed or [False] * b_req
     units = _scaled_units(cm, opts, n_ctx, scale_c, scale_io)
@@ -371,24 +383,34 @@ def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scal
     r_total = io_backlog + sum(sum(units[i][2][p_comp[i]:p_io[i] + 1]) for i in live)
     open_ = [i for i in live if not closed[i]]
     group = [i for i in open_ if units[i][0] == LAYER_WISE]
-    cands = [(units[i][1][p_comp[i]], units[i][2][p_comp[i]], i, False)
+    def ahead(i):       # unscaled recomputation between the pointers
+        return sum(units[i][3][p_comp[i]:p_io[i] + 1])
+
+    cands = [(units[i][1][p_comp[i]], units[i][2][p_comp[i]], i, False, ahead(i))
              for i in open_ if units[i][0] == TOKEN_WISE]
     if group:
         cands.append((sum(units[i][1][p_comp[i]] for i in group),
-                      sum(units[i][2][p_comp[i]] for i in group), group[0], True))
+                      sum(units[i][2][p_comp[i]] for i in group), group[0], True,
+                      sum(ahead(i) for i in group)))
 
-    def order(x, y):
-        lhs, rhs = x[0] * y[1], y[0] * x[1]       # a_x/b_x against a_y/b_y
-        if lhs != rhs:
-            return -1 if lhs < rhs else 1
+    def before(x, y):
+        if order == ORDER_SHORTEST:
+            if x[4] != y[4]:
+                return -1 if x[4] < y[4] else 1
+        else:
+            lhs, rhs = x[0] * y[1], y[0] * x[1]       # a_x/b_x against a_y/b_y
+            if lhs != rhs:
+                return -1 if lhs < rhs else 1
         return (x[2] > y[2]) - (x[2] < y[2])
 
-    cands.sort(key=cmp_to_key(order))
+    cands.sort(key=cmp_to_key(before))
     take = [0] * b_req
-    a_sum = b_sum = 0
+    a_sum, b_sum = step_fixed, 0
     group_taken = False
-    for a, b, first, is_group in cands:
-        if a_sum + a <= r_total - b_sum:
+    for a, b, first, is_group, _ in cands:
+        if step_cap > 0 and a_sum >= step_cap and a_sum > step_fixed:
+            break
+        if a_sum + a + compute_later <= r_total - b_sum:
             a_sum += a
             b_sum += b
             if is_group:
@@ -398,13 +420,20 @@ def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scal
     if group_taken:
         more = all(p_comp[i] + 1 <= p_io[i] for i in group)
         if more:
-            more = a_sum + sum(units[i][1][p_comp[i] + 1] for i in group) <= r_total - b_sum
+            more = a_sum + sum(units[i][1][p_comp[i] + 1] for i in group) + compute_later <= r_total - b_sum
         for i in group:
             take[i] = 1 if more else 2
+        ran = 0
+        for i in group:
+            full = compute_cost(cm, 1, n_ctx[i], 0)
+            kv = kv_only_cost(cm, opts.kv_only_permille, n_ctx[i]) if opts.kv_only_permille > 0 else full
+            ran += (full if more else kv) * scale_c // 1000
+        a_sum += ran - sum(units[i][1][p_comp[i]] for i in group)
     return take, a_sum
 
 
-def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max_depth=4):
+def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max_depth=4,
+                     step_cap=0, order=ORDER_CHEAPEST):
     """Event-driven model of an executor that schedules at run time with `io_pick` and
     `dynamic_claim`: the I/O channel holds one claimed unit plus more while less than
     `lookahead` of predicted work is queued (at most `max_depth`); the compute engine asks
@@ -464,7 +493,8 @@ def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max
         if step_end is None and ask:
             ask = False
             backlog = sum(d * scale_io // 1000 for _, d in io_queue)
-            take, a_pred = dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed, backlog, scale_c, scale_io)
+            take, a_pred = dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed, backlog, scale_c, scale_io,
+                                         0, step_cap, order)
             dur = 0
             for i in range(b_req):
                 if take[i]:

@@ -13,6 +13,7 @@
 #include <cstdint>
 #include <cstring>
 #include <deque>
+#include <functional>
 #include <thread>
 #include <vector>
 
@@ -121,6 +122,7 @@ struct cf_ctx {
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
     std::vector<hipEvent_t> dyn_events;   // run-time scheduler: loads in flight + the compute step
+    int dyn_scale_c = 1000, dyn_scale_io = 1000;   // measured/predicted ratios carried from call to call
     std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
@@ -494,7 +496,8 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 // Run layers [l_begin, n_layers_max) of one packed phase on the compute stream; the phase's
 // rows sit at rows row_base.. of the residual buffers.  l_begin > 0 resumes a phase whose
 // earlier layers ran in a previous call with the same row_base (its hidden states are still
-// in the workspace), so nothing is embedded.
+// in the workspace), so nothing is embedded.  `between_layers` (may be null) is called before
+// every layer is enqueued; a negative result aborts.
 //
 // The residual stream h stays float.  O-proj and down-proj store their result into the
 // float buffer dl (plain stores out of the GEMM), and the next RMSNorm folds it in
@@ -510,7 +513,8 @@ void gemm(cf_ctx* c, int cls, const void* A, const void* W, const void* W2, floa
 // A stage above layer 0 has no embedding to start from: its rows start from the boundary
 // activations the caller holds for them (copied into h ahead of the first layer).
 int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
-              const hipEvent_t* layer_ready, hipEvent_t ev_rec_done, int l_begin = 0, int row_base = 0) {
+              const hipEvent_t* layer_ready, hipEvent_t ev_rec_done, int l_begin = 0, int row_base = 0,
+              const std::function<int()>* between_layers = nullptr) {
     const int layer0 = c->stage_begin;
     const cf_model_desc& m = c->m;
     int last_rec_layer = -1;
@@ -555,6 +559,8 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
         }
     }
     for (int l = l_begin; l < n_layers_max; ++l) {
+        if (between_layers && (*between_layers)() < 0)
+            return fail(CF_ERR_HIP, "the copy stream failed while a compute step was being enqueued");
         const int Ta_rec = ph.rec_active(l, 0);    // recompute rows that need K/V in this layer
         const int Tn_rec = ph.rec_active(l, 1);    // ... and go on through the layer
         if (Ta_rec <= 0 && !any_new) break;
@@ -1122,8 +1128,8 @@ double now_ms() {
 
 extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const cf_request* reqs,
                                   const cf_cost_model* cost, const cf_plan_opts* opts,
-                                  float* logits_out, cf_split* splits_out, cf_timing* timing,
-                                  cf_dynamic_stats* stats) {
+                                  const cf_dynamic_opts* dyn, float* logits_out, cf_split* splits_out,
+                                  cf_timing* timing, cf_dynamic_stats* stats) {
     if (!c || !cache || !cost || !opts || B < 0 || (B > 0 && (!reqs || !splits_out)))
         return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: null argument");
     const cf_model_desc& m = c->m;
@@ -1136,6 +1142,10 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: batch %d > max_batch %d", B, c->opts.max_batch);
     const int L = m.n_layers, C = opts->chunk_tokens;
     const size_t es = elem_bytes(m.dtype), pb = cache->page_bytes;
+    const int64_t step_cap = dyn ? dyn->step_cap_ps : 0;
+    const int32_t order = dyn ? dyn->order : CF_ORDER_CHEAPEST;
+    if (dyn && (dyn->step_cap_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST)))
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: bad step cap or claim order");
     if (C <= 0 || C % CF_PAGE_TOKENS != 0)
         return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: chunk_tokens must be a positive multiple of %d",
                     CF_PAGE_TOKENS);
@@ -1205,9 +1215,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         n_pages_req[i] = np;
         total_pt += np;
     }
-    if (rows_lw + n_tw * C > c->opts.max_tokens || sum_new > c->opts.max_tokens)
-        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: %lld layer-wise rows + %lld token-wise chunks of %d, "
-                    "or %lld new tokens, exceed max_tokens %d", (long long)rows_lw, (long long)n_tw, C,
+    if (rows_lw + n_tw * C + sum_new > c->opts.max_tokens)
+        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: %lld layer-wise rows + %lld token-wise chunks of %d + "
+                    "%lld new tokens exceed max_tokens %d", (long long)rows_lw, (long long)n_tw, C,
                     (long long)sum_new, c->opts.max_tokens);
     // argument check of the scheduling calls once, so that later calls cannot fail
     {
@@ -1298,23 +1308,13 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         }
     size_t off_jobs = mw.put(jobs.data(), jobs.size() * sizeof(PageJob));
 
-    Phase lw, suf;
+    Phase lw;
     {
         std::vector<int32_t> ids, pos, slot;
         for (int i : lw_members) add_segment(lw, ids, pos, slot, i, reqs[i].ctx_tokens, n_ctx[i], 0, L, false);
         if (lw.T > 0) finish_phase(lw, ids, pos, slot);
     }
-    std::vector<int32_t> last_rows;
-    if (logits_out) {
-        std::vector<int32_t> ids, pos, slot;
-        for (int i = 0; i < B; ++i) {
-            add_segment(suf, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, reqs[i].n_ctx, L, true);
-            last_rows.push_back(suf.T - 1);
-        }
-        finish_phase(suf, ids, pos, slot);
-    }
-    size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
-    c->last_rows = last_rows;
+    c->last_rows.clear();                // no single packed phase holds the final rows of this call
     if (mw.overflow)
         return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: batch metadata exceeds the context's limits "
                     "(%zu load jobs)", jobs.size());
@@ -1322,10 +1322,10 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
 
     // ---- events: one per load unit in flight, one for the compute step.  The copy stream is
     // kept one unit deep, plus more while less than IO_LOOKAHEAD_PS of predicted work is queued
-    // (short units need the next launch queued behind them; long ones are claimed one at a time
+    // (short units need the next launches queued behind them; long ones are claimed one at a time
     // so that the claim is made as late as possible)
-    constexpr int IO_DEPTH = 4;
-    constexpr int64_t IO_LOOKAHEAD_PS = 2000000000;
+    constexpr int IO_DEPTH = 8;
+    constexpr int64_t IO_LOOKAHEAD_PS = 4000000000;
     while ((int)c->dyn_events.size() < IO_DEPTH + 1) {
         hipEvent_t e = nullptr;
         CF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -1347,34 +1347,40 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     if (c->throttle_gbs > 0) launch_pace_mark(c->ps, c->pace_dev());
 
     // ---- the scheduling loop
-    // Layer-wise members share their pointers (the group moves as one).  `closed[i]`: the compute
+    // Layer-wise members share their pointers (the group moves as one).  closed[i]: the compute
     // engine is done with request i for good (the group ran its last layer K/V-only, so there are
     // no hidden states to go on from); the I/O channel takes what is left of it.
-    std::deque<int64_t> io_flight;                // predicted ps of the loads in flight, oldest first
+    // A request whose cache is complete (pointers crossed, its loads landed, its last recompute
+    // step done) has its new-turn rows prefilled in the next compute step, beside whatever else
+    // that step recomputes: the new turn of early finishers overlaps the loads of the others.
+    struct Flight { int64_t pred_ps; int req; };  // req: the token-wise request, or -1 = layer-wise group
+    std::deque<Flight> io_flight;                 // loads in flight, oldest first
     int64_t io_issued = 0, io_retired = 0;        // event of load k: dyn_events[k % IO_DEPTH]
     int64_t io_pred_done = 0;                     // predicted ps of the retired loads
     double io_t_first = 0, io_t_last = 0;         // host clock: first issue, latest completion
     int64_t c_pred_done = 0, step_pred = 0;
     double c_meas_done_ms = 0, step_t0 = 0, gap_ms = 0, last_step_end = 0;
     bool step_running = false, ask = true;        // ask: state changed since the last declined claim
-    bool force_io = false;
-    int scale_c = 1000, scale_io = 1000;
+    bool force_io = false, tail_ran = false;
+    // the ratios measured / predicted start from what the previous call on this context saw
+    int scale_c = c->dyn_scale_c, scale_io = c->dyn_scale_io;
     int n_steps = 0, n_cunits = 0;
     int64_t loaded_bytes = 0;
     int lw_layer = 0;                             // next layer of the layer-wise group
     std::vector<uint8_t> closed(B, 0);
     std::vector<int32_t> take(B);
-    auto any_live = [&]() {
-        for (int i = 0; i < B; ++i)
-            if (p_comp[i] <= p_io[i]) return true;
-        return false;
-    };
+    std::vector<int> io_pending(B, 0);            // loads in flight that touch request i
+    std::vector<char> in_step(B, 0), prefilled(B, 0);
+    int n_prefilled = 0;
+    const bool want_new = logits_out != nullptr;
     auto clamp_scale = [](double r) { return (int)std::min(4000.0, std::max(250.0, r * 1000.0 + 0.5)); };
     auto unit_load_ps = [&](size_t bytes) {
         __int128 num = (__int128)bytes * cost->gamma;
         return cost->f_io + (int64_t)((num + (((__int128)1) << 20) - 1) >> 20);
     };
+    auto restored = [&](int i) { return p_comp[i] > p_io[i] && io_pending[i] == 0 && !in_step[i]; };
     CF_HIP(hipEventRecord(c->ev_comp, c->cs));    // stands if the compute engine claims nothing
+    CF_HIP(hipEventRecord(c->ev_copy, c->ps));    // stands if the channel loads nothing
     // event state: 1 complete, 0 pending, -1 the runtime reports a failure
     auto done = [](hipEvent_t e) {
         hipError_t q = hipEventQuery(e);
@@ -1385,25 +1391,29 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     double t_progress = now_ms();
     constexpr double STALL_LIMIT_MS = 60000;      // no completion for this long: give up, do not spin for ever
 
-    while (true) {
-        bool progressed = false;
-        // retire finished loads (they complete in issue order)
-        while (!io_flight.empty()) {
+    // The copy stream's side of the loop; also called between the layers of a step that is being
+    // enqueued, so that the channel does not run dry while the host is busy launching.
+    // Returns < 0 on failure, else whether anything changed.
+    auto pump_io = [&]() -> int {
+        int changed = 0;
+        while (!io_flight.empty()) {              // retire finished loads (they complete in issue order)
             int dn = done(c->dyn_events[io_retired % IO_DEPTH]);
-            if (dn < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed");
+            if (dn < 0) return -1;
             if (dn == 0) break;
             io_t_last = now_ms();
-            io_pred_done += io_flight.front();
+            io_pred_done += io_flight.front().pred_ps;
+            int r = io_flight.front().req;
+            if (r >= 0) --io_pending[r];
+            else for (int i : lw_members) --io_pending[i];
             io_flight.pop_front();
             ++io_retired;
             if (io_pred_done > 0 && io_t_last > io_t_first)
                 scale_io = clamp_scale((io_t_last - io_t_first) * 1e9 / (double)io_pred_done);
-            progressed = ask = true;
+            changed = 1;
         }
-        // keep the copy stream fed
         while ((int)io_flight.size() < IO_DEPTH) {
             int64_t backlog = 0;
-            for (int64_t f : io_flight) backlog += (int64_t)((__int128)f * scale_io / 1000);
+            for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * scale_io / 1000);
             if (!io_flight.empty() && backlog >= IO_LOOKAHEAD_PS) break;
             int64_t busy = 0;
             if (step_running)
@@ -1416,12 +1426,16 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                                busy, scale_c, scale_io, &pick);
             if (pick < 0) break;
             const DynUnitLoad* ul;
+            int who;
             if (mode[pick] == CF_TOKEN_WISE) {
                 ul = &tw_units[pick][p_io[pick]];
                 --p_io[pick];
+                ++io_pending[pick];
+                who = pick;
             } else {
                 ul = &lw_units[p_io[pick]];
-                for (int i : lw_members) --p_io[i];
+                for (int i : lw_members) { --p_io[i]; ++io_pending[i]; }
+                who = -1;
             }
             if (io_issued == 0) io_t_first = now_ms();
             c->prof_begin(CF_K_H2D_COPY, (double)ul->bytes, c->ps);
@@ -1433,12 +1447,119 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                                  (unsigned long long)(paced_bytes / (c->throttle_gbs * 1e9) * c->wall_hz));
             }
             c->prof_end(CF_K_H2D_COPY, c->ps);
-            CF_HIP(hipEventRecord(c->dyn_events[io_issued % IO_DEPTH], c->ps));
-            io_flight.push_back(unit_load_ps(ul->bytes));
+            if (hipEventRecord(c->dyn_events[io_issued % IO_DEPTH], c->ps) != hipSuccess ||
+                hipEventRecord(c->ev_copy, c->ps) != hipSuccess)       // the latest record stands
+                return -1;
+            io_flight.push_back(Flight{unit_load_ps(ul->bytes), who});
             loaded_bytes += (int64_t)ul->bytes;
             ++io_issued;
-            progressed = ask = true;
+            changed = 1;
         }
+        return changed;
+    };
+    std::function<int()> between_layers = [&]() { return pump_io() < 0 ? -1 : 0; };
+
+    // The planned tail.  Once the compute engine will take nothing more, the schedule is known,
+    // so the rest is laid out like a planned restore: the channel gets every unclaimed cell,
+    // layer by layer from the bottom with an event per layer, and the new turn of every request
+    // not yet prefilled is enqueued right away (behind the running step, if there is one); its
+    // attention in layer l waits for that layer's event only.  `fresh`: requests known to be
+    // restored already (merged into the list of all that are not prefilled).
+    auto launch_tail = [&](std::vector<int> fresh, int64_t pred_ps, bool behind_step) -> int {
+        Phase step;
+        std::vector<int32_t> ids, pos, slot, last_idx;
+        std::vector<PageJob> tjobs;
+        std::vector<DynUnitLoad> tlayers(L, DynUnitLoad{0, 0, 0, 0});
+        jobs.swap(tjobs);                         // add_job appends to `jobs`
+        for (int l = 0; l < L; ++l) {
+            tlayers[l].job_first = (int)jobs.size();
+            for (int i = 0; i < B; ++i) {
+                if (p_comp[i] > p_io[i]) continue;
+                if (mode[i] == CF_TOKEN_WISE)
+                    add_job(tlayers[l], i, l, p_comp[i] * C, std::min(n_ctx[i], (p_io[i] + 1) * C));
+                else if (l >= p_comp[i] && l <= p_io[i])
+                    add_job(tlayers[l], i, l, 0, n_ctx[i]);
+            }
+        }
+        jobs.swap(tjobs);
+        for (int i = 0; i < B; ++i) {
+            if (p_comp[i] <= p_io[i]) p_io[i] = p_comp[i] - 1;     // claimed by the channel
+            if (prefilled[i]) continue;
+            add_segment(step, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, n_ctx[i], L, true);
+            last_idx.push_back(step.T - 1);
+            fresh.push_back(i);
+        }
+        std::sort(fresh.begin(), fresh.end());    // = every request not prefilled, in segment order
+        fresh.erase(std::unique(fresh.begin(), fresh.end()), fresh.end());
+        // metadata: behind a running step its arrays are still in use (the copy of them may not
+        // even have left the pinned mirror yet), so the tail's go after them
+        if (!behind_step) mw.off = step_off;
+        const size_t off_tjobs = mw.put(tjobs.data(), tjobs.size() * sizeof(PageJob));
+        const size_t off_rows = mw.off;
+        finish_phase(step, ids, pos, slot);
+        const size_t off_idx = mw.put(last_idx.data(), last_idx.size() * 4);
+        if (mw.overflow)
+            return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits");
+        // the jobs travel on the copy stream (it must not wait for the running step), the new
+        // turn's arrays on the compute stream
+        if (off_rows > off_tjobs)
+            CF_HIP(hipMemcpyAsync(md + off_tjobs, c->meta_host + off_tjobs, off_rows - off_tjobs,
+                                  hipMemcpyHostToDevice, c->ps));
+        CF_HIP(hipMemcpyAsync(md + off_rows, c->meta_host + off_rows, mw.off - off_rows,
+                              hipMemcpyHostToDevice, c->cs));
+        std::vector<hipEvent_t> ready(L);
+        for (int l = 0; l < L; ++l) {
+            const DynUnitLoad& tl = tlayers[l];
+            if (tl.n_jobs > 0) {
+                c->prof_begin(CF_K_H2D_COPY, (double)tl.bytes, c->ps);
+                launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs) + tl.job_first,
+                                 tl.n_jobs, tl.n_vblocks, c->load_wgs, (const int32_t*)md, g);
+                if (c->throttle_gbs > 0) {
+                    paced_bytes += (double)tl.bytes;
+                    launch_pace_wait(c->ps, c->pace_dev(),
+                                     (unsigned long long)(paced_bytes / (c->throttle_gbs * 1e9) * c->wall_hz));
+                }
+                c->prof_end(CF_K_H2D_COPY, c->ps);
+                loaded_bytes += (int64_t)tl.bytes;
+                ++io_issued;
+            }
+            // behind everything the copy stream was given so far, units in flight included
+            CF_HIP(hipEventRecord(c->ev_layer[l], c->ps));
+            ready[l] = c->ev_layer[l];
+        }
+        CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+        if (!behind_step) {
+            double t_launch = now_ms();
+            if (n_steps > 0) gap_ms += t_launch - last_step_end;
+            step_t0 = t_launch;
+            step_pred = 0;
+            ++n_steps;
+        }
+        step_pred += pred_ps;
+        step_running = true;
+        int rc2 = run_phase(c, cache, step, L, ready.data(), nullptr, 0, lw.T, nullptr);
+        if (rc2) return rc2;
+        // final norm of every request's last row into its LM-head slot (last_idx[k] belongs to
+        // fresh[k]); the last layer's down-proj result is still pending in dl
+        for (size_t k = 0; k < fresh.size(); ++k) {
+            int i = fresh[k];
+            launch_rmsnorm(c->cs, m.dtype, c->h() + (size_t)lw.T * m.d_model,
+                           c->dl() + (size_t)lw.T * m.d_model, c->w.final_norm,
+                           (char*)c->a_last() + (size_t)i * m.d_model * es, 1, m.d_model, m.rms_eps,
+                           (const int32_t*)(md + off_idx) + k);
+            prefilled[i] = 1;
+            ++n_prefilled;
+        }
+        CF_HIP(hipEventRecord(ev_step, c->cs));   // the running step, if any, now ends here
+        tail_ran = true;
+        return CF_OK;
+    };
+
+    while (true) {
+        bool progressed = false;
+        int pio_rc = pump_io();
+        if (pio_rc < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed");
+        if (pio_rc > 0) progressed = ask = true;
         // compute engine: retire the step ...
         int step_dn = step_running ? done(ev_step) : 0;
         if (step_dn < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the compute stream failed");
@@ -1448,20 +1569,46 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             c_pred_done += step_pred;
             if (c_pred_done > 0) scale_c = clamp_scale(c_meas_done_ms * 1e9 / (double)c_pred_done);
             step_running = false;
+            std::fill(in_step.begin(), in_step.end(), 0);
             progressed = ask = true;
         }
         // ... and ask for the next one (again after every change of state while it is idle)
         if (!step_running && ask) {
             ask = false;
+            // new-turn rows of the requests that are completely restored by now
+            // (and the cost of the new turns that are still to come: the compute engine has that
+            // work ahead of it whatever it takes now)
+            std::vector<int> fresh;
+            int64_t fixed = 0, later = 0;
+            if (want_new)
+                for (int i = 0; i < B; ++i) {
+                    if (prefilled[i]) continue;
+                    int64_t ps = 0;
+                    cf_prefill_cost(cost, L, 1, &n_ctx[i], &reqs[i].n_new, &ps);
+                    ps = (int64_t)((__int128)ps * scale_c / 1000);
+                    if (restored(i)) { fresh.push_back(i); fixed += ps; }
+                    else later += ps;
+                }
             int64_t backlog = 0, pred = 0;
-            for (int64_t f : io_flight) backlog += (int64_t)((__int128)f * scale_io / 1000);
+            for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * scale_io / 1000);
             cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
-                             scale_c, scale_io, take.data(), &pred);
+                             fixed, later, step_cap, order, scale_c, scale_io, take.data(), &pred);
             Phase step;
-            std::vector<int32_t> ids, pos, slot;
-            bool lw_take = false, lw_last = false;
+            std::vector<int32_t> ids, pos, slot, last_idx;
+            bool lw_take = false, lw_last = false, any_rec = false, any_live = false;
+            for (int i = 0; i < B; ++i) {
+                any_rec |= take[i] != 0;
+                any_live |= p_comp[i] <= p_io[i];
+            }
+            if (!any_rec && any_live && want_new) {
+                // idle and nothing worth taking: the rest is the channel's
+                int rc2 = launch_tail(fresh, fixed + later, false);
+                if (rc2) return rc2;
+                continue;
+            }
             for (int i = 0; i < B; ++i) {
                 if (!take[i]) continue;
+                in_step[i] = 1;
                 if (mode[i] == CF_TOKEN_WISE) {
                     int lo = p_comp[i] * C, hi = std::min(n_ctx[i], lo + C);
                     add_segment(step, ids, pos, slot, i, reqs[i].ctx_tokens + lo, hi - lo, lo, L, false);
@@ -1472,14 +1619,20 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                     lw_last = take[i] == 2;
                 }
             }
+            for (int i : fresh) {               // packed after the recompute rows
+                add_segment(step, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, n_ctx[i], L, true);
+                last_idx.push_back(step.T - 1);
+            }
             if (step.T > 0 || lw_take) {
                 double t_launch = now_ms();
                 if (n_steps > 0) gap_ms += t_launch - last_step_end;
                 step_t0 = t_launch;
+                step_pred = pred;
+                step_running = true;            // pump_io (between layers) sees the step as running
                 if (lw_take) {
                     // layer lw_layer of the group: in full if the group goes on, else up to its K/V write
                     for (Segment& sg : lw.segs) sg.layers = lw_layer + (lw_last ? 1 : 2);
-                    int rc2 = run_phase(c, cache, lw, lw_layer + 1, nullptr, nullptr, lw_layer, 0);
+                    int rc2 = run_phase(c, cache, lw, lw_layer + 1, nullptr, nullptr, lw_layer, 0, &between_layers);
                     if (rc2) return rc2;
                     for (int i : lw_members) {
                         ++p_comp[i];
@@ -1491,24 +1644,58 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 if (step.T > 0) {
                     mw.off = step_off;
                     finish_phase(step, ids, pos, slot);
+                    size_t off_idx = mw.put(last_idx.data(), last_idx.size() * 4);
                     if (mw.overflow)
                         return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits");
                     CF_HIP(hipMemcpyAsync(md + step_off, c->meta_host + step_off, mw.off - step_off,
                                           hipMemcpyHostToDevice, c->cs));
-                    int rc2 = run_phase(c, cache, step, L, nullptr, nullptr, 0, lw.T);
+                    int rc2 = run_phase(c, cache, step, L, nullptr, nullptr, 0, lw.T, &between_layers);
                     if (rc2) return rc2;
+                    // final norm of each fresh request's last row into its slot of the LM-head input
+                    // (the last layer's down-proj result is still pending in dl)
+                    for (size_t k = 0; k < fresh.size(); ++k) {
+                        int i = fresh[k];
+                        launch_rmsnorm(c->cs, m.dtype, c->h() + (size_t)lw.T * m.d_model,
+                                       c->dl() + (size_t)lw.T * m.d_model, c->w.final_norm,
+                                       (char*)c->a_last() + (size_t)i * m.d_model * es, 1, m.d_model, m.rms_eps,
+                                       (const int32_t*)(md + off_idx) + k);
+                        prefilled[i] = 1;
+                        ++n_prefilled;
+                    }
                 }
                 CF_HIP(hipEventRecord(ev_step, c->cs));
-                CF_HIP(hipEventRecord(c->ev_comp, c->cs));
-                step_running = true;
-                step_pred = pred;
+                if (any_rec) CF_HIP(hipEventRecord(c->ev_comp, c->cs));
                 ++n_steps;
                 progressed = true;
+                // Will there be anything to take when this step is over?  Ask for the state it
+                // leaves behind, with the step's own duration counted as work still ahead (the
+                // channel keeps loading meanwhile).  If not, this was the last recompute step:
+                // the rest is planned now and enqueued behind it, so that neither stream waits
+                // for the host to notice the step's end.
+                if (any_rec && want_new) {
+                    bool live_left = false;
+                    for (int i = 0; i < B; ++i) live_left |= p_comp[i] <= p_io[i];
+                    if (live_left) {
+                        int64_t later_all = later;       // new turns not in this step
+                        std::vector<int32_t> take2(B, 0);
+                        cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(),
+                                         backlog, 0, later_all + pred, 0, order, scale_c, scale_io, take2.data(),
+                                         nullptr);
+                        bool any2 = false;
+                        for (int i = 0; i < B; ++i) any2 |= take2[i] != 0;
+                        if (!any2) {
+                            int rc3 = launch_tail({}, later_all, true);
+                            if (rc3) return rc3;
+                        }
+                    }
+                }
             }
         }
         if (!step_running && io_flight.empty()) {
-            if (!any_live()) break;
-            if (!progressed) force_io = true;
+            bool live = false;
+            for (int i = 0; i < B; ++i) live |= p_comp[i] <= p_io[i];
+            if (!live && (!want_new || n_prefilled == B)) break;
+            if (live && !progressed) force_io = true;
         }
         if (progressed) {
             t_progress = now_ms();
@@ -1519,17 +1706,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         }
     }
 
-    // ---- join, new-turn prefill, logits
-    CF_HIP(hipEventRecord(c->ev_copy, c->ps));
-    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
-    CF_HIP(hipEventRecord(c->ev_t0, c->cs));
-    if (logits_out) {
-        int rc2 = run_phase(c, cache, suf, L, nullptr, nullptr);
-        if (rc2) return rc2;
-        launch_rmsnorm(c->cs, m.dtype, c->h(), c->dl(), c->w.final_norm, c->a_last(), B, m.d_model,
-                       m.rms_eps, (const int32_t*)(md + off_last));
+    // ---- every cache is complete and every new turn prefilled: first-token logits
+    if (logits_out)
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
-    }
     CF_HIP(hipEventRecord(c->ev_end, c->cs));
     CF_HIP(hipGetLastError());
     CF_HIP(hipStreamSynchronize(c->cs));
@@ -1567,14 +1746,13 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     }
     if (logits_out) fs += 2.0 * m.d_model * (double)m.vocab * B;
     if (timing) {
-        float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
+        float t_comp = 0, t_copy = 0, t_end = 0;
         CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
         CF_HIP(hipEventElapsedTime(&t_copy, c->ev_start, c->ev_copy));
-        CF_HIP(hipEventElapsedTime(&t_join, c->ev_start, c->ev_t0));
         CF_HIP(hipEventElapsedTime(&t_end, c->ev_start, c->ev_end));
-        timing->compute_ms = t_comp;
+        timing->compute_ms = t_comp;      // end of the last step that recomputed anything
         timing->copy_ms = t_copy;
-        timing->restore_ms = std::max(t_join, std::max(t_comp, t_copy));
+        timing->restore_ms = std::max(t_comp, t_copy);
         timing->suffix_ms = t_end - timing->restore_ms;
         timing->total_ms = t_end;
         timing->recompute_flops = fr;
@@ -1590,7 +1768,10 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         stats->scale_c_permille = scale_c;
         stats->scale_io_permille = scale_io;
         stats->compute_gap_ms = gap_ms;
+        stats->planned_tail = tail_ran ? 1 : 0;
     }
+    c->dyn_scale_c = scale_c;
+    c->dyn_scale_io = scale_io;
     return CF_OK;
 }
 

@@ -383,13 +383,17 @@ extern "C" int cf_dynamic_io_pick(const cf_cost_model* cost, const cf_plan_opts*
 extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
                                 const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
                                 const uint8_t* compute_closed, int64_t io_backlog_ps,
+                                int64_t step_fixed_ps, int64_t compute_later_ps, int64_t step_cap_ps,
+                                int32_t order,
                                 int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
                                 int64_t* step_ps) {
     DynState st;
-    int rc = dyn_setup("cf_dynamic_claim", cost, opts, B, n_ctx, p_comp, p_io, io_backlog_ps, 0,
+    int rc = dyn_setup("cf_dynamic_claim", cost, opts, B, n_ctx, p_comp, p_io, io_backlog_ps, step_fixed_ps,
                        scale_c_permille, scale_io_permille, &st);
     if (rc) return rc;
     if (B > 0 && !take) return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: null take");
+    if (step_cap_ps < 0 || compute_later_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST))
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: bad step cap, later work or order");
     const std::vector<Units>& req = st.req;
 
     // R: when the I/O channel would be done if the compute engine took nothing more
@@ -399,37 +403,53 @@ extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* o
 
     // candidates: the next unit of every open token-wise request, and the next layer of all
     // open layer-wise requests together (they move through the layers as one packed batch)
-    struct Item { int first; bool group; int64_t a, b; };
+    struct Item { int first; bool group; int64_t a, b, rem; };   // rem: recomputation still ahead of it
     std::vector<Item> items;
-    Item grp{-1, true, 0, 0};
+    Item grp{-1, true, 0, 0, 0};
     int64_t a_next = 0;                  // the group's unit after this one
+    int64_t grp_full = 0, grp_kv = 0;    // what the group's layer costs to run in full / up to its K/V write
     bool has_next = true;
     for (int i = 0; i < B; ++i) {
         take[i] = 0;
         if (p_comp[i] > p_io[i] || (compute_closed && compute_closed[i])) continue;
         if (req[i].mode == CF_TOKEN_WISE) {
-            items.push_back(Item{i, false, st.sc(req[i].a(p_comp[i])), st.sio(req[i].b[p_comp[i]])});
+            items.push_back(Item{i, false, st.sc(req[i].a(p_comp[i])), st.sio(req[i].b[p_comp[i]]),
+                                 req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[p_comp[i]]});
         } else {
             if (grp.first < 0) grp.first = i;
+            grp.rem += req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[p_comp[i]];
             grp.a += st.sc(req[i].a(p_comp[i]));
             grp.b += st.sio(req[i].b[p_comp[i]]);
+            int64_t full = layer_pass_cost(*cost, 1, n_ctx[i], 0);
+            grp_full += st.sc(full);
+            grp_kv += st.sc(opts->kv_only_permille > 0 ? kv_only_cost(*cost, opts->kv_only_permille, n_ctx[i]) : full);
             if (p_comp[i] + 1 <= p_io[i]) a_next += st.sc(req[i].a(p_comp[i] + 1));
             else has_next = false;
         }
     }
     if (grp.first >= 0) items.push_back(grp);
-    // cheapest recomputation per unit of I/O time saved first (a1/b1 < a2/b2), then by index
-    std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) {
-        __int128 l = (__int128)x.a * y.b, r = (__int128)y.a * x.b;
-        if (l != r) return l < r;
+    // CHEAPEST: least recomputation per unit of I/O time saved first (a1/b1 < a2/b2);
+    // SHORTEST: least recomputation still ahead first, so that requests finish one after the
+    // other and their new turns can start while the channel works on the long ones; then by index
+    std::stable_sort(items.begin(), items.end(), [order](const Item& x, const Item& y) {
+        if (order == CF_ORDER_SHORTEST) {
+            if (x.rem != y.rem) return x.rem < y.rem;
+        } else {
+            __int128 l = (__int128)x.a * y.b, r = (__int128)y.a * x.b;
+            if (l != r) return l < r;
+        }
         return x.first < y.first;
     });
-    // a candidate is taken if the step, with it, still ends no later than the channel would
-    // need for everything the step so far leaves to it
-    int64_t A = 0, Bs = 0;
+    // a candidate is taken if the step, with it -- and with compute_later_ps of work the
+    // compute engine has to do after the step in any case -- still ends no later than the
+    // channel would need for everything the step so far leaves to it
+    // (the step starts out with step_fixed_ps of work it carries in any case)
+    int64_t A = step_fixed_ps, Bs = 0;
     bool grp_taken = false;
     for (const Item& it : items) {
-        if (A + it.a > R - Bs) continue;
+        // a capped step stops growing once it is long enough (it always gets its first unit)
+        if (step_cap_ps > 0 && A >= step_cap_ps && A > step_fixed_ps) break;
+        if (A + it.a + compute_later_ps > R - Bs) continue;
         A += it.a;
         Bs += it.b;
         if (it.group) grp_taken = true;
@@ -438,10 +458,13 @@ extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* o
     if (grp_taken) {
         // 1: go through the whole layer (the next one looks worth taking too); 2: stop after
         // the K/V write, this is the group's last recomputed layer
-        bool more = has_next && A + a_next <= R - Bs;
+        bool more = has_next && A + a_next + compute_later_ps <= R - Bs;
         for (int i = 0; i < B; ++i)
             if (p_comp[i] <= p_io[i] && req[i].mode == CF_LAYER_WISE && !(compute_closed && compute_closed[i]))
                 take[i] = more ? 1 : 2;
+        // unit prices charge a layer's attention and MLP to the NEXT layer's unit; the step
+        // itself runs this layer in full (1) or up to its K/V write (2)
+        A += (more ? grp_full : grp_kv) - grp.a;
     }
     if (step_ps) *step_ps = A;
     return CF_OK;

@@ -123,7 +123,7 @@ class Session:
                                     self.logits.data_ptr() if want_logits else 0)
         return (self.logits[:len(requests)] if want_logits else None), tm
 
-    def restore_dynamic(self, requests, cost, opts, want_logits=True):
+    def restore_dynamic(self, requests, cost, opts, want_logits=True, step_cap_ps=0, order=0):
         """Restore without a precomputed split: the engines claim units at run time.
         Returns (logits or None, splits [(mode,k,cut)], timing dict, stats dict)."""
         torch.cuda.current_stream(self.device).synchronize()
@@ -131,7 +131,8 @@ class Session:
                      host_kv=r["host_kv"].data_ptr() if r.get("host_kv") is not None else 0)
                 for r in requests]
         splits, tm, st = self.ctx.restore_dynamic(self.cache, reqs, cost, opts,
-                                                  self.logits.data_ptr() if want_logits else 0)
+                                                  self.logits.data_ptr() if want_logits else 0,
+                                                  step_cap_ps, order)
         return (self.logits[:len(requests)] if want_logits else None), splits, tm, st
 
     # -------------------------------------------------------------- introspection

@@ -318,8 +318,8 @@ def test_cfg1_run_time_scheduling_restores_the_same_cache(env, mode):
         if kind == "recompute":
             assert tm["loaded_cells"] == 0 and st["io_units"] == 0
         if kind == "load":
-            assert tm["recomputed_cells"] == 0 and st["compute_steps"] == 0
-        assert (st["compute_steps"] == 0) == (st["compute_units"] == 0)
+            assert tm["recomputed_cells"] == 0 and st["compute_units"] == 0
+        assert st["compute_steps"] >= 1          # the new turn, at the least
 
 
 def test_cfg1_run_time_scheduling_chunk_sizes_throttle_and_errors(env):

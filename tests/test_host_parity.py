@@ -44,6 +44,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_request) == 48
     assert ctypes.sizeof(cf.cf_timing) == 64
     assert ctypes.sizeof(cf.cf_dynamic_stats) == 32
+    assert ctypes.sizeof(cf.cf_dynamic_opts) == 16
 
 
 def test_status_strings():
@@ -170,8 +171,12 @@ def test_run_time_scheduling_calls_match_oracle_on_random_states():
         backlog = int(rng.integers(0, 3 * 10 ** 10))
         busy = int(rng.integers(0, 10 ** 10))
         sc, sio = int(rng.integers(250, 4001)), int(rng.integers(250, 4001))
-        want_take, want_a = P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio)
-        got_take, got_a = cf.dynamic_claim(ccm, opts_c, n, pc, pio, closed, backlog, sc, sio)
+        fixed = int(rng.integers(0, 2) * rng.integers(0, 10 ** 10))
+        cap = int(rng.integers(0, 2) * rng.integers(0, 10 ** 10))
+        order = int(rng.integers(0, 2))
+        later = int(rng.integers(0, 2) * rng.integers(0, 10 ** 10))
+        want_take, want_a = P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later)
+        got_take, got_a = cf.dynamic_claim(ccm, opts_c, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later)
         assert (got_take, got_a) == (want_take, want_a), (it, n, pc, pio)
         want = P.io_pick(ocm, opts_o, n, pc, pio, closed, backlog, busy, sc, sio)
         got = cf.dynamic_io_pick(ccm, opts_c, n, pc, pio, closed, backlog, busy, sc, sio)

@@ -288,6 +288,41 @@ def test_dynamic_claim_hand_cases():
     assert (take, a_sum) == ([1, 0], 320)       # R = 100 + 256; 320 <= 356, then 640 > 356 - 32
     # a finished request is never a candidate
     assert P.dynamic_claim(cm, opts, [64, 64], [4, 0], [3, 3], io_backlog=10 ** 6)[0] == [0, 1]
+    # work the step carries anyway counts against what it can take on top
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=192, step_fixed=1) == ([0], 1)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=200, step_fixed=8) == ([1], 328)
+    # so does work that waits for the compute engine after the step, without lengthening the step
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=200, compute_later=8) == ([1], 320)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=200, compute_later=9) == ([0], 0)
+
+
+def test_dynamic_claim_step_cap_and_shortest_first_order():
+    cm = P.CostModel(f_c=0, alpha=10, beta=0, f_io=0, gamma=1 << 20)
+    opts = P.PlanOpts(16, 0, 2, 1, P.TOKEN_WISE)            # a = 320, b = 32 per full chunk
+    n = [64, 32, 48]                                        # 4, 2 and 3 chunks
+    big = 10 ** 6
+    # no cap: every live request's next chunk goes into the step
+    assert P.dynamic_claim(cm, opts, n, [0, 0, 0], [3, 1, 2], io_backlog=big) == ([1, 1, 1], 960)
+    # capped at one chunk's worth: the step stops after its first candidate -- by index under
+    # the cost-ratio order (all equal here), the request with least ahead of it under the other
+    assert P.dynamic_claim(cm, opts, n, [0, 0, 0], [3, 1, 2], io_backlog=big, step_cap=320) == ([1, 0, 0], 320)
+    assert P.dynamic_claim(cm, opts, n, [0, 0, 0], [3, 1, 2], io_backlog=big, step_cap=320,
+                           order=P.ORDER_SHORTEST) == ([0, 1, 0], 320)
+    assert P.dynamic_claim(cm, opts, n, [0, 0, 0], [3, 1, 2], io_backlog=big, step_cap=321,
+                           order=P.ORDER_SHORTEST) == ([0, 1, 1], 640)
+    # the cap never starves a step: work it carries anyway does not count as its first unit
+    assert P.dynamic_claim(cm, opts, n, [0, 0, 0], [3, 1, 2], io_backlog=big, step_fixed=500,
+                           step_cap=320)[0] == [1, 0, 0]
+    # shortest first finishes requests one after the other
+    pc, pio = [0, 0, 0], [3, 1, 2]
+    finished = []
+    for _ in range(9):
+        take, _ = P.dynamic_claim(cm, opts, n, pc, pio, io_backlog=big, step_cap=320, order=P.ORDER_SHORTEST)
+        i = take.index(1)
+        pc[i] += 1
+        if pc[i] > pio[i]:
+            finished.append(i)
+    assert finished == [1, 2, 0]
 
 
 def test_dynamic_claim_layer_wise_group_and_last_layer_mark():
@@ -300,6 +335,13 @@ def test_dynamic_claim_layer_wise_group_and_last_layer_mark():
     assert P.dynamic_claim(cm, opts, n, [0, 0], [3, 3], io_backlog=480) == ([2, 2], 480)
     # the last unclaimed layer of the group is always marked as its last
     assert P.dynamic_claim(cm, opts, n, [3, 3], [3, 3], io_backlog=10 ** 6)[0] == [2, 2]
+    # with a K/V-only price for a request's last layer (here 1/4 of the linear part): layer 0 is
+    # priced 80 + 40, the step that runs it in full is reported at 320 + 160
+    kvo = P.PlanOpts(16, 0, 4, 1, P.LAYER_WISE, kv_only_permille=250)
+    assert P.dynamic_claim(cm, kvo, n, [0, 0], [3, 3], io_backlog=10 ** 6) == ([1, 1], 480)
+    # ... and a last layer further up is priced in full (it completes the layer below) but runs
+    # only its K/V projection
+    assert P.dynamic_claim(cm, kvo, n, [3, 3], [3, 3], io_backlog=10 ** 6) == ([2, 2], 120)
     # closed requests are not offered to the compute engine, whatever the backlog
     assert P.dynamic_claim(cm, opts, n, [1, 1], [3, 3], closed=[True, True], io_backlog=10 ** 9) == ([0, 0], 0)
 
@@ -363,6 +405,10 @@ def test_simulated_run_time_scheduling_tracks_the_static_plan_and_adapts(kind, m
     # and it never does worse than the better of the two extremes by more than one step
     all_io = sum(sum(P.unit_costs(slow, opts, n, P.request_mode(opts, n))[1]) for n in n_ctx)
     assert makespan_slow <= 1.05 * all_io
+    # short steps that finish the short requests first: a different order of the same work
+    _, capped, n_capped = P.simulate_dynamic(cm, opts, n_ctx, step_cap=st["makespan"] // 20,
+                                             order=P.ORDER_SHORTEST)
+    assert capped <= 1.06 * st["makespan"] and n_capped >= n_steps
 
 
 def test_simulated_run_time_scheduling_against_brute_force():
