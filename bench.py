@@ -65,7 +65,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--config", default="cfg2",
+                    help="cfg1 .. cfg5, or sweep:<B>:<n>[:<mode>] = B requests of n tokens on the 8B shape "
+                         "(mode 0 token-wise, 1 layer-wise, default by L_delta)")
     ap.add_argument("--plan", default="planner",
                     help="planner | dynamic (claims at run time, no precomputed split) | per_request | "
                          "all_recompute | all_load | cut=<L> (layer cut for every request)")

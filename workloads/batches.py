@@ -39,9 +39,21 @@ def make_batch(config, scale=1.0, vocab=None):
     """Build the batch of one configuration.  `scale` < 1 shrinks every
     context length (kept >= 1 page) for bounded parity cases; the length
     *distribution* is unchanged."""
-    cfg = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}[config]
-    rng = np.random.default_rng(1000 + cfg)
-    if cfg == 1:
+    if config.startswith("sweep:"):
+        # "sweep:<B>:<n>[:<mode>]": B requests of exactly n context tokens on the 8B shape, 128
+        # new tokens each (length / batch-size sweeps and the token-wise vs layer-wise crossover)
+        f = config.split(":")
+        b_req, n = int(f[1]), int(f[2])
+        cfg = 6
+        rng = np.random.default_rng(1000 + 97 * b_req + n)
+        shape_name, n_ctx, n_new = "8b", [n] * b_req, [128] * b_req
+        chunk, forced, mode = 512, [], int(f[3]) if len(f) > 3 else -1
+    else:
+        cfg = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}[config]
+        rng = np.random.default_rng(1000 + cfg)
+    if cfg == 6:
+        pass
+    elif cfg == 1:
         shape_name, n_ctx, n_new = "tiny", [128, 64], [16, 16]
         chunk, forced, mode = 16, [(64, 2), (32, 2)], 0
     elif cfg == 2:
