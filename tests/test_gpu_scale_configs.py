@@ -197,6 +197,53 @@ def check_hybrid_restore(b, sess, ws, reqs):
     return splits
 
 
+def check_run_time_scheduled_restore(b, sess, reqs, l_delta):
+    """cf_restore_dynamic on the full batch (token-wise above l_delta, layer-wise below, or the
+    configuration's forced mode): loaded cells are the host block's bytes; recomputed cells --
+    chunk by chunk or layer by layer, in steps -- are compared with the single-pass prefill that
+    made the host block: bit for bit where that holds, else to within two bf16 ulps of the cell
+    on at least 99.9 % of the cells and a quarter of the tensor's spread everywhere."""
+    import paper_2604_25080_amd as cf
+    shape, L, B = b.shape, b.shape.n_layers, len(b.n_ctx)
+    opts = cf.plan_opts(b.chunk_tokens, l_delta, L, shape.kv_bytes_per_token_layer, b.forced_mode)
+    for kind in ("startup", "balanced", "slow_io"):
+        cm = cf.cost_model(**hand_cost_model(kind))
+        sess.pool.fill_(0xFF)
+        logits, splits, tm, st = sess.restore_dynamic(reqs, cm, opts)
+        if tm["recomputed_cells"] > 0 and tm["loaded_cells"] > 0:
+            break
+    print(f"{b.config} run-time scheduling, cost table '{kind}': {st}, splits {splits[:6]}{' ...' if B > 6 else ''}")
+    assert tm["recomputed_cells"] > 0 and tm["loaded_cells"] > 0, "no hand cost table gave a hybrid"
+    assert tm["loaded_cells"] + tm["recomputed_cells"] == sum(b.n_ctx) * L
+    n_exact = n_cmp = 0
+    for i in range(B):
+        n, (mode, kk, cc) = b.n_ctx[i], splits[i]
+        want_mode = b.forced_mode if b.forced_mode >= 0 else (0 if n >= l_delta else 1)
+        assert mode == want_mode and 0 <= kk <= n and 0 <= cc <= L
+        got = sess.read_pages(1 + i, n)
+        ref = reqs[i]["host_kv"].numpy()[:sess.host_kv_bytes(n)].reshape(L, -1, sess.page_bytes)
+        for l in sorted({0, 1, L // 2, L - 1}):
+            gk, gv = decode_pages(shape, got[l:l + 1], n)
+            rk, rv = decode_pages(shape, ref[l:l + 1], n)
+            lo = kk if l < cc else 0                       # cells [lo, n) of this layer were loaded
+            assert np.array_equal(gk[0, lo:], rk[0, lo:]) and np.array_equal(gv[0, lo:], rv[0, lo:]), \
+                f"{b.config} request {i} layer {l}: loaded cells differ from the host block"
+            for g, r, nm in ((gk[0, :lo], rk[0, :lo], "K"), (gv[0, :lo], rv[0, :lo], "V")):
+                if lo == 0:
+                    continue
+                assert np.isfinite(g).all(), f"{b.config} request {i} layer {l} {nm}: unwritten slot"
+                n_cmp += 1
+                if np.array_equal(g, r):
+                    n_exact += 1
+                    continue
+                d = np.abs(g - r)
+                ulp = np.maximum(np.abs(r), 1.0) * 2.0 ** -7
+                assert (d <= 2 * ulp).mean() >= 0.999 and d.max() <= 0.25 * r.std() + 0.05, \
+                    f"{b.config} request {i} layer {l} {nm}: max diff {d.max()}, within 2 ulp {(d <= 2 * ulp).mean()}"
+        del got
+    print(f"{b.config}: {n_exact} of {n_cmp} recomputed (request, layer, K|V) blocks bit-identical to the single pass")
+
+
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("config", ["cfg3", "cfg4"])
 def test_8b_configurations_at_full_size(config):
@@ -207,6 +254,7 @@ def test_8b_configurations_at_full_size(config):
         splits = check_hybrid_restore(b, sess, ws, reqs)
         if config == "cfg3":
             assert splits[0][1] == b.n_ctx[0] and 0 < splits[0][2] < b.shape.n_layers   # layer-wise
+        check_run_time_scheduled_restore(b, sess, reqs, l_delta=4096)
     finally:
         release(b, sess)
         for r in reqs:
@@ -238,5 +286,6 @@ def test_tp_shard_configuration_5_at_full_size():
                 assert gr <= 1.3 * rr + 1e-4 and gm <= 1.6 * rm + 1e-3, \
                     f"layer {l} {nm}: rms {gr} max {gm} vs noise floor {rr} / {rm}"
         check_hybrid_restore(b, sess, ws, reqs)
+        check_run_time_scheduled_restore(b, sess, reqs, l_delta=16384)
     finally:
         release(b, sess)
