@@ -323,7 +323,9 @@ def main():
                                "write_bytes": float(f[3]), "bytes": float(f[2]) + float(f[3])}
         roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "gemm_gate_up (MFMA GEMM, SiLU*mul epilogue)",
                     "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                    "traffic": traffic, "launches": dom["launches"], "avg_launch_ms": avg_ms,
+                    # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size)
+                    "traffic": None if traffic is None else traffic["bytes"], "traffic_detail": traffic,
+                    "launches": dom["launches"], "avg_launch_ms": avg_ms,
                     "flops_per_launch": dom["work"] / dom["launches"]}
     kernels = {}      # from the one extra step after the timed region, every class profiled
     for k in prof_kernels:

@@ -1937,7 +1937,7 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
         for (int i = 0; i < p.n_req && rc == CF_OK; ++i) {
             rc = cf_cache_alloc(cache, base_id + i, p.n_tok);
             if (rc == CF_OK) ++made;
-            rq[i] = cf_request{base_id + i, toks.data(), p.n_tok, 0, host_buf, nullptr};
+            rq[i] = cf_request{base_id + i, toks.data(), p.n_tok, 0, host_buf, nullptr, nullptr};
             sp[i] = cf_split{CF_TOKEN_WISE, p.k, L};
         }
         if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, tm);  // warm-up
