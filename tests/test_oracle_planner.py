@@ -423,3 +423,13 @@ def test_simulated_run_time_scheduling_against_brute_force():
         biggest = max(max(a + b) for a, b, _ in costs)
         # list scheduling: within one (largest) unit per engine of the optimum
         assert makespan <= best + 2 * biggest
+
+
+def test_sweep_batches_are_what_their_name_says():
+    from workloads import make_batch
+    b = make_batch("sweep:4:2048:1")
+    assert b.n_ctx == [2048] * 4 and b.n_new == [128] * 4 and b.forced_mode == 1 and b.shape.name == "8b"
+    assert all(len(t) == 2048 and t.max() < b.shape.vocab for t in b.ctx_tokens)
+    assert make_batch("sweep:1:512").forced_mode == -1
+    # seeded: the same name gives the same tokens
+    assert np.array_equal(make_batch("sweep:4:2048:1").ctx_tokens[3], b.ctx_tokens[3])
