@@ -1345,6 +1345,15 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     g.layer_stride = g.page_elems * cache->n_pages;
     double paced_bytes = 0;
     if (c->throttle_gbs > 0) launch_pace_mark(c->ps, c->pace_dev());
+    // an error once work is enqueued: let both streams drain before the caller gets control back
+    // (its buffers are in use until then)
+    auto bail = [&](int code) {
+        (void)hipStreamSynchronize(c->cs);
+        (void)hipStreamSynchronize(c->ps);
+        (void)hipGetLastError();
+        c->prof_collect();
+        return code;
+    };
 
     // ---- the scheduling loop
     // Layer-wise members share their pointers (the group moves as one).  closed[i]: the compute
@@ -1499,7 +1508,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         finish_phase(step, ids, pos, slot);
         const size_t off_idx = mw.put(last_idx.data(), last_idx.size() * 4);
         if (mw.overflow)
-            return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits");
+            return bail(fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits"));
         // the jobs travel on the copy stream (it must not wait for the running step), the new
         // turn's arrays on the compute stream
         if (off_rows > off_tjobs)
@@ -1538,7 +1547,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         step_pred += pred_ps;
         step_running = true;
         int rc2 = run_phase(c, cache, step, L, ready.data(), nullptr, 0, lw.T, nullptr);
-        if (rc2) return rc2;
+        if (rc2) return bail(rc2);
         // final norm of every request's last row into its LM-head slot (last_idx[k] belongs to
         // fresh[k]); the last layer's down-proj result is still pending in dl
         for (size_t k = 0; k < fresh.size(); ++k) {
@@ -1558,11 +1567,11 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     while (true) {
         bool progressed = false;
         int pio_rc = pump_io();
-        if (pio_rc < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed");
+        if (pio_rc < 0) return bail(fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed"));
         if (pio_rc > 0) progressed = ask = true;
         // compute engine: retire the step ...
         int step_dn = step_running ? done(ev_step) : 0;
-        if (step_dn < 0) return fail(CF_ERR_HIP, "cf_restore_dynamic: the compute stream failed");
+        if (step_dn < 0) return bail(fail(CF_ERR_HIP, "cf_restore_dynamic: the compute stream failed"));
         if (step_dn > 0) {
             last_step_end = now_ms();
             c_meas_done_ms += last_step_end - step_t0;
@@ -1603,7 +1612,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             if (!any_rec && any_live && want_new) {
                 // idle and nothing worth taking: the rest is the channel's
                 int rc2 = launch_tail(fresh, fixed + later, false);
-                if (rc2) return rc2;
+                if (rc2) return bail(rc2);
                 continue;
             }
             for (int i = 0; i < B; ++i) {
@@ -1633,7 +1642,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                     // layer lw_layer of the group: in full if the group goes on, else up to its K/V write
                     for (Segment& sg : lw.segs) sg.layers = lw_layer + (lw_last ? 1 : 2);
                     int rc2 = run_phase(c, cache, lw, lw_layer + 1, nullptr, nullptr, lw_layer, 0, &between_layers);
-                    if (rc2) return rc2;
+                    if (rc2) return bail(rc2);
                     for (int i : lw_members) {
                         ++p_comp[i];
                         ++n_cunits;
@@ -1646,11 +1655,11 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                     finish_phase(step, ids, pos, slot);
                     size_t off_idx = mw.put(last_idx.data(), last_idx.size() * 4);
                     if (mw.overflow)
-                        return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits");
+                        return bail(fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: step metadata exceeds the context's limits"));
                     CF_HIP(hipMemcpyAsync(md + step_off, c->meta_host + step_off, mw.off - step_off,
                                           hipMemcpyHostToDevice, c->cs));
                     int rc2 = run_phase(c, cache, step, L, nullptr, nullptr, 0, lw.T, &between_layers);
-                    if (rc2) return rc2;
+                    if (rc2) return bail(rc2);
                     // final norm of each fresh request's last row into its slot of the LM-head input
                     // (the last layer's down-proj result is still pending in dl)
                     for (size_t k = 0; k < fresh.size(); ++k) {
@@ -1685,7 +1694,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                         for (int i = 0; i < B; ++i) any2 |= take2[i] != 0;
                         if (!any2) {
                             int rc3 = launch_tail({}, later_all, true);
-                            if (rc3) return rc3;
+                            if (rc3) return bail(rc3);
                         }
                     }
                 }
@@ -1701,7 +1710,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             t_progress = now_ms();
         } else {
             if (now_ms() - t_progress > STALL_LIMIT_MS)
-                return fail(CF_ERR_HIP, "cf_restore_dynamic: no unit completed within %.0f s", STALL_LIMIT_MS / 1e3);
+                return bail(fail(CF_ERR_HIP, "cf_restore_dynamic: no unit completed within %.0f s", STALL_LIMIT_MS / 1e3));
             std::this_thread::sleep_for(std::chrono::microseconds(20));
         }
     }
