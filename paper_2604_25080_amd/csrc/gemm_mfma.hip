@@ -5,7 +5,8 @@
 //
 // Tiling: 256x256 block tile, 4 wavefronts (2x2), each a 128x128 wave tile =
 // 4x4 MFMA 32x32x16 fragments (256 accumulator registers per lane); problems
-// too small to fill the chip with such tiles use 128x128 block tiles instead.  K is
+// too small to fill the chip with such tiles use 128x128 or 64x64 block tiles instead (the
+// latter with four K-steps of operands in flight per workgroup).  K is
 // walked in steps of BK = 64 through a double-buffered LDS tile; the next
 // K-step is fetched from global memory into registers while the current one
 // is multiplied, then written to the other LDS buffer.  LDS rows are
@@ -242,6 +243,46 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
 #undef CF_BIG_FETCH_B
 #undef CF_BIG_STASH_A
 #undef CF_BIG_STASH_B
+    } else if (BM == 64 && (nk & 3) == 0) {
+        // The 64x64 tile is for launches with few rows against long K (the new turn of a small
+        // batch, a tensor-parallel shard's narrow projections): few workgroups, each walking K
+        // alone, so what counts is how many K-steps a workgroup has in flight.  Four register
+        // sets hold tiles kt+1 .. kt+4 (tile t lives in set t % 4): the set written to LDS in
+        // step kt was requested four steps earlier and is refilled with tile kt+5 right away
+        // (eight sets measured no faster).  Same MFMA order along K as every other tile shape,
+        // so the same bits.
+        u32x4_t ra0[LA], rb0[LB], ra1[LA], rb1[LB], ra2[LA], rb2[LB], ra3[LA], rb3[LB];
+        CF_FETCH_A(0, ra0); CF_FETCH_B(0, rb0);
+        CF_FETCH_A(1, ra1); CF_FETCH_B(1, rb1);
+        CF_FETCH_A(2, ra2); CF_FETCH_B(2, rb2);
+        CF_FETCH_A(3, ra3); CF_FETCH_B(3, rb3);
+        CF_STASH_A(smem, ra0); CF_STASH_B(smem, rb0);
+        CF_FETCH_A(4, ra0); CF_FETCH_B(4, rb0);
+        __syncthreads();
+        CF_READ_FRAGS(fa0, fb0, smem, 0);
+#define CF_RSTEP(KT, RA, RB)                                                                  \
+        {                                                                                     \
+            char* cur = smem + ((KT) & 1) * STAGE_BYTES;                                      \
+            char* nxt = smem + (((KT) + 1) & 1) * STAGE_BYTES;                                \
+            CF_READ_FRAGS(fa1, fb1, cur, 1);                                                  \
+            CF_MFMA(fa0, fb0);                                                                \
+            CF_READ_FRAGS(fa0, fb0, cur, 2);                                                  \
+            CF_MFMA(fa1, fb1);                                                                \
+            CF_READ_FRAGS(fa1, fb1, cur, 3);                                                  \
+            CF_STASH_A(nxt, RA); CF_STASH_B(nxt, RB);          /* tile KT+1 */                \
+            CF_MFMA(fa0, fb0);                                                                \
+            __syncthreads();                                                                  \
+            CF_READ_FRAGS(fa0, fb0, nxt, 0);                                                  \
+            CF_FETCH_A((KT) + 5, RA); CF_FETCH_B((KT) + 5, RB);                               \
+            CF_MFMA(fa1, fb1);                                                                \
+        }
+        for (int kt = 0; kt < nk; kt += 4) {
+            CF_RSTEP(kt, ra1, rb1)
+            CF_RSTEP(kt + 1, ra2, rb2)
+            CF_RSTEP(kt + 2, ra3, rb3)
+            CF_RSTEP(kt + 3, ra0, rb0)
+        }
+#undef CF_RSTEP
     } else {
         // Smaller tiles: tile kt+1 (fetched during the previous iteration) is written to the other
         // buffer during sub-step 2 and tile kt+2 fetched during sub-step 3; instruction order is

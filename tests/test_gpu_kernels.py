@@ -31,7 +31,7 @@ SHAPES_MNK = [(256, 256, 64), (300, 544, 512), (1000, 1408, 512), (129, 96, 1408
               (2048, 1280, 1024)]
 
 
-@pytest.mark.parametrize("impl", [3, 4, 1])
+@pytest.mark.parametrize("impl", [3, 4, 5, 1])
 @pytest.mark.parametrize("mnk", SHAPES_MNK)
 def test_gemm_epilogues_match_float64_matmul(sess, impl, mnk):
     import paper_2604_25080_amd as cf
@@ -60,6 +60,34 @@ def test_gemm_epilogues_match_float64_matmul(sess, impl, mnk):
     want = ref / (1.0 + np.exp(-ref)) * ref2
     got = from_bf16(Dt)
     assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -8 + 4 * tol)
+
+
+@pytest.mark.parametrize("mnk", [(300, 544, 512), (129, 4096, 1024), (16, 1280, 8192), (2048, 1280, 1024),
+                                 (600, 768, 1408)])
+def test_gemm_bits_do_not_depend_on_the_tile_shape(sess, mnk):
+    """Every output element is accumulated in the same order along K whatever the block tile
+    (256x256, 128x128, 64x64 with its deeper operand pipeline) and whatever else is in the
+    launch: hybrid == all-recompute == chunk-by-chunk restores rest on this."""
+    import paper_2604_25080_amd as cf
+    M, N, K = mnk
+    rng = np.random.default_rng(M + N + K)
+    A = dev_bf16(rng.normal(size=(M, K)).astype(np.float32))
+    W = dev_bf16((rng.normal(size=(N, K)) * 0.05).astype(np.float32))
+    outs = []
+    for impl in (3, 4, 5, 0):
+        if impl == 3 and (M < 256 or N < 256 or K % 128):
+            continue
+        Cf = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), 0, Cf.data_ptr(), 0, M, N, K, cf.EPI_STORE_F32, impl)
+        outs.append(Cf)
+    # a sub-range of the rows on its own gives the same bits for those rows
+    lo = M // 3
+    Cs = torch.full((M - lo, N), float("nan"), dtype=torch.float32, device="cuda")
+    sess.ctx.op_gemm(A[lo:].contiguous().data_ptr(), W.data_ptr(), 0, Cs.data_ptr(), 0, M - lo, N, K,
+                     cf.EPI_STORE_F32, 0)
+    for o in outs[1:]:
+        assert torch.equal(outs[0], o)
+    assert torch.equal(outs[0][lo:], Cs)
 
 
 def test_gemm_mfma_refuses_what_it_cannot_tile(sess):
