@@ -222,9 +222,9 @@ enum cf_claim_order {
  * predicted cost of work the step carries in any case, such as the new-turn
  * prefill of requests that are already restored; compute_later_ps is work the
  * compute engine must do after this step whatever it takes now, such as the
- * new-turn prefill of the other requests).  Token-wise requests are candidates one by
- * one; all open layer-wise requests form ONE candidate (they advance through
- * the layers as a packed batch), a = sum a_i, b = sum b_i.
+ * new-turn prefill of the other requests).  Token-wise requests are candidates
+ * one by one; all open layer-wise requests form ONE candidate (they advance
+ * through the layers as a packed batch), a = sum a_i, b = sum b_i.
  *   take[i] (host int32[B]) : 0 not taken; 1 taken; 2 (layer-wise only) taken
  *                   as the group's last layer -- the same test fails for the
  *                   group's following layer (or there is none), so the
