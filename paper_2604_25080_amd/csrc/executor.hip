@@ -1598,6 +1598,13 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                     if (restored(i)) { fresh.push_back(i); fixed += ps; }
                     else later += ps;
                 }
+            // every pass over the layers has a launch-bound floor, the cost model's compute
+            // start-up: this step pays it, and so does the new-turn pass that is still to come
+            {
+                const int64_t floor_ps = (int64_t)((__int128)cost->s_c * scale_c / 1000);
+                fixed += floor_ps;
+                if (later > 0) later += floor_ps;
+            }
             int64_t backlog = 0, pred = 0;
             for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * scale_io / 1000);
             cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
