@@ -60,6 +60,91 @@ def cpu_baseline(batch, n_tok=4096, n_layers=6):
     }
 
 
+class _ZeroWeights:
+    """Weight stand-in for a context that is only used to launch single kernels."""
+
+    def __init__(self, shape):
+        self.shape = shape
+
+    def storage(self, name, layer=-1):
+        import numpy as np
+        s = self.shape
+        dims = {"embed": (s.vocab, s.d_model), "lm_head": (s.vocab, s.d_model),
+                "wqkv": (s.qkv_cols, s.d_model), "wo": (s.d_model, s.n_q_heads * s.head_dim),
+                "w_gate": (s.d_ffn, s.d_model), "w_up": (s.d_ffn, s.d_model),
+                "w_down": (s.d_model, s.d_ffn)}[name]
+        return np.zeros(dims, dtype=np.uint16 if s.dtype == "bf16" else np.float32)
+
+    def norm_gain(self):
+        import numpy as np
+        return np.ones(self.shape.d_model, dtype=np.float32)
+
+
+def probe_gemm(a):
+    """--probe gemm: the four GEMMs of one decoder layer of the 8B shape at --rows rows through
+    cf_op_gemm, after a plain 1 GiB device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate
+    those counters.  For rocprofv3 (--kernel-trace --stats, or --pmc) runs."""
+    import torch
+    import paper_2604_25080_amd as cf
+    from paper_2604_25080_amd.runtime import Session
+    from workloads import SHAPES
+    copy_bytes = 1 << 30
+    big = SHAPES["8b"]
+    tiny = SHAPES["mini-bf16"].with_layers(1)        # only the context's streams and dtype are used
+    sess = Session(tiny, _ZeroWeights(tiny), max_batch=1, max_tokens=256, max_positions=256, n_pages=4)
+    dev = torch.device("cuda:0")
+    src = torch.zeros(copy_bytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)                                      # reference copy: reads and writes copy_bytes
+    torch.cuda.synchronize()
+    M, d = a.rows, big.d_model
+    gemms = [("gemm_qkv", big.qkv_cols, d, cf.EPI_STORE_F32),
+             ("gemm_oproj", d, big.n_q_heads * big.head_dim, cf.EPI_STORE_F32),
+             ("gemm_gate_up", big.d_ffn, d, cf.EPI_SILU_MUL), ("gemm_down", d, big.d_ffn, cf.EPI_STORE_F32)]
+    for name, N, K, epi in gemms:
+        A = torch.randn(M, K, device=dev).to(torch.bfloat16)
+        W = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+        W2 = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+        Cf = torch.zeros(M, N, dtype=torch.float32, device=dev)
+        Dt = torch.zeros(M, N, dtype=torch.bfloat16, device=dev)
+        torch.cuda.synchronize()
+        ms = sess.ctx.op_gemm(A.data_ptr(), W.data_ptr(), W2.data_ptr(), Cf.data_ptr(), Dt.data_ptr(),
+                              M, N, K, epi, 0, a.reps)
+        fl = 2.0 * M * N * K * (2 if epi == cf.EPI_SILU_MUL else 1)
+        in_bytes = (M * K + N * K * (2 if epi == cf.EPI_SILU_MUL else 1)) * 2
+        out_bytes = M * N * (2 if epi == cf.EPI_SILU_MUL else 4)
+        print(f"{name}: M={M} N={N} K={K} {ms:.4f} ms/launch {fl / ms / 1e9:.1f} TFLOP/s; "
+              f"algorithmic bytes in {in_bytes} out {out_bytes}; copy reference {copy_bytes} B each way",
+              flush=True)
+    sess.close()
+
+
+def probe_attention(a):
+    """--probe attention: causal self-attention of ONE request of --tokens tokens -- an
+    all-recompute restore of a two-layer model with the 8B widths -- so that the attention
+    kernel sees the benchmark's head geometry at a chosen context length."""
+    import numpy as np
+    from paper_2604_25080_amd.runtime import Session
+    from workloads import SHAPES, WeightSource
+    n = a.tokens
+    shape = SHAPES["8b"].with_layers(2).with_vocab(4096)
+    sess = Session(shape, WeightSource(shape, 5), max_batch=1, max_tokens=n + 128, max_positions=n + 256,
+                   n_pages=n // 16 + 64)
+    toks = np.random.default_rng(0).integers(0, 4096, size=n).astype(np.int32)
+    sess.cache.alloc(1, n + 128)
+    sess.ctx.profile(["attention"])
+    req = [dict(req_id=1, ctx_tokens=toks, new_tokens=toks[:128], host_kv=None)]
+    for _ in range(a.reps):
+        sess.restore(req, [(0, n, 2)], want_logits=False)
+    st = sess.ctx.profile_read()["attention"]
+    pairs = n * (n + 1) / 2
+    print(f"tokens {n}: {st['launches']} attention launches, {st['total_ms'] / st['launches']:.3f} ms each, "
+          f"{st['work'] / st['total_ms'] / 1e9:.1f} TFLOP/s "
+          f"({pairs * 4 * shape.n_q_heads * shape.head_dim / 1e12:.2f} TFLOP per launch: 4*Hq*hd per causal pair)",
+          flush=True)
+    sess.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,11 +180,21 @@ def main():
                     help="pace the copy stream to this many Gbit/s (emulates a slower storage tier; 0: off)")
     ap.add_argument("--sequential-join", action="store_true",
                     help="restore, wait for both streams, then prefill the new tokens (default: pipelined join)")
+    ap.add_argument("--probe", choices=["gemm", "attention"], default=None,
+                    help="run one kernel class alone (for rocprofv3 counter runs) instead of the benchmark: "
+                         "gemm = the layer GEMMs of the 8B shape at --rows rows; attention = one request of "
+                         "--tokens tokens")
+    ap.add_argument("--rows", type=int, default=10752)
+    ap.add_argument("--tokens", type=int, default=16384)
+    ap.add_argument("--reps", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
             f"--gpus {args.gpus} is not supported.")
         sys.exit(2)
+
+    if args.probe:
+        return probe_gemm(args) if args.probe == "gemm" else probe_attention(args)
 
     import numpy as np
     import torch

@@ -439,7 +439,8 @@ int cf_restore_dynamic(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request
  * manufactured for the large configurations).  Blocking.  If the block is
  * pinned, device-mapped memory a store kernel writes it over the host link in
  * one launch; otherwise (or with load path 1) pages are gathered into the
- * staging buffer and copied out layer by layer.  Same bytes either way.      */
+ * staging buffer and copied out layer by layer.  Same bytes either way
+ * (slots past n_ctx in the last page are written as zero).                  */
 int cf_offload(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv);
 
 /* Time a large pinned host->device copy on the copy stream: the bandwidth
@@ -539,6 +540,15 @@ int cf_ctx_set_link_throttle(cf_ctx* ctx, double gb_per_s);
  * the plain float-FMA kernels (the float32 path); 0 (default) uses the MFMA
  * kernels wherever they support the shape.  For kernel-vs-kernel GPU tests. */
 int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only);
+
+/* Test hook for the error path: the nth_check-th status check that
+ * cf_restore_batch makes AFTER it has started to enqueue work (1 = the first)
+ * reports a failure as if the HIP call had returned an error; the call then
+ * has to wait for all three streams before it returns CF_ERR_HIP, because the
+ * work already enqueued reads caller memory.  One shot: cleared by the next
+ * cf_restore_batch whether it fires or not.  0 switches it off.  Nothing on
+ * the GPU is made to fail.                                                  */
+int cf_ctx_inject_failure(cf_ctx* ctx, int32_t nth_check);
 
 /* One GEMM of the recompute path, exposed for parity tests and roofline
  * measurement: acc[M,N] = A[M,K] * W[N,K]^T with A, W (and W2) device arrays

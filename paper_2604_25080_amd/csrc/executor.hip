@@ -118,6 +118,7 @@ struct cf_ctx {
     int capture_layer = -1;               // next call: copy the rows entering this layer ...
     float* capture_out = nullptr;         // ... to this device array [rows][d]
     int64_t capture_cap_rows = 0;
+    int inject_fail_at = 0;           // > 0: that status check of the next call's enqueue part fails
     double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
@@ -333,6 +334,13 @@ extern "C" int cf_ctx_set_link_throttle(cf_ctx* ctx, double gb_per_s) {
 extern "C" int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only) {
     if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_set_kernel_set: null ctx");
     ctx->simple_only = simple_only != 0;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_inject_failure(cf_ctx* ctx, int32_t nth_check) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_inject_failure: null ctx");
+    if (nth_check < 0) return fail(CF_ERR_INVALID_ARG, "cf_ctx_inject_failure: nth_check must be >= 0");
+    ctx->inject_fail_at = nth_check;
     return CF_OK;
 }
 
@@ -664,6 +672,20 @@ double linear_flops_per_token_layer(const cf_model_desc& m) {
            6.0 * m.d_model * (double)m.d_ffn;
 }
 
+// index of the first request whose id already occurred earlier in the batch, or -1
+int first_repeated_id(const cf_request* reqs, int B) {
+    std::vector<uint64_t> ids(B);
+    for (int i = 0; i < B; ++i) ids[i] = reqs[i].req_id;
+    std::vector<uint64_t> sorted(ids);
+    std::sort(sorted.begin(), sorted.end());
+    auto it = std::adjacent_find(sorted.begin(), sorted.end());
+    if (it == sorted.end()) return -1;
+    int seen = 0;
+    for (int i = 0; i < B; ++i)
+        if (ids[i] == *it && seen++ == 1) return i;
+    return -1;
+}
+
 struct CopyOp {
     size_t dst_off;      // into staging
     const char* src;
@@ -751,6 +773,10 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         n_pages_req[i] = np;
         total_pt += np;
     }
+    if (int dup = first_repeated_id(reqs, B); dup >= 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: request %d repeats the id %llu of an earlier request "
+                    "of the batch (two segments would write the same pages)", dup,
+                    (unsigned long long)reqs[dup].req_id);
     if (sum_rec > c->opts.max_tokens || sum_new > c->opts.max_tokens)
         return fail(CF_ERR_WORKSPACE, "cf_restore_batch: %lld recompute / %lld new tokens > max_tokens %d",
                     (long long)sum_rec, (long long)sum_new, c->opts.max_tokens);
@@ -964,13 +990,36 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     if (mw.overflow)
         return fail(CF_ERR_WORKSPACE, "cf_restore_batch: batch metadata exceeds the context's limits");
 
+    // From here on work is in flight on three streams that reads caller memory (token ids went
+    // into the pinned metadata, but host KV blocks and boundary rows are read in place): every
+    // failure first waits for the streams, so that the caller may free its buffers on return.
+    int checks_done = 0;
+    auto bail = [&](int code) {
+        (void)hipStreamSynchronize(c->cs);
+        (void)hipStreamSynchronize(c->ps);
+        (void)hipStreamSynchronize(c->ss);
+        (void)hipGetLastError();
+        c->prof_collect();
+        c->capture_out = nullptr;
+        c->capture_layer = -1;
+        c->inject_fail_at = 0;
+        return code;
+    };
+#define CF_HIP_Q(call)                                                                        \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (c->inject_fail_at > 0 && ++checks_done == c->inject_fail_at) e_ = hipErrorUnknown; \
+        if (e_ != hipSuccess)                                                                 \
+            return bail(cf::fail(CF_ERR_HIP, "%s:%d %s -> %s", __FILE__, __LINE__, #call,     \
+                                 hipGetErrorString(e_)));                                     \
+    } while (0)
     // ---- enqueue
     char* md = c->meta_dev();
-    CF_HIP(hipEventRecord(c->ev_start, c->cs));
-    CF_HIP(hipMemcpyAsync(md, c->meta_host, mw.off, hipMemcpyHostToDevice, c->cs));
-    CF_HIP(hipEventRecord(c->ev_meta, c->cs));
-    CF_HIP(hipStreamWaitEvent(c->ps, c->ev_meta, 0));
-    CF_HIP(hipStreamWaitEvent(c->ss, c->ev_meta, 0));
+    CF_HIP_Q(hipEventRecord(c->ev_start, c->cs));
+    CF_HIP_Q(hipMemcpyAsync(md, c->meta_host, mw.off, hipMemcpyHostToDevice, c->cs));
+    CF_HIP_Q(hipEventRecord(c->ev_meta, c->cs));
+    CF_HIP_Q(hipStreamWaitEvent(c->ps, c->ev_meta, 0));
+    CF_HIP_Q(hipStreamWaitEvent(c->ss, c->ev_meta, 0));
 
     KvGeom g;
     g.n_kv_heads = m.n_kv_heads;
@@ -997,42 +1046,42 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         pace((double)ll.bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
         layer_loaded[ll.layer] = 1;
-        if (merged) CF_HIP(hipEventRecord(c->ev_layer[ll.layer], c->ps));
+        if (merged) CF_HIP_Q(hipEventRecord(c->ev_layer[ll.layer], c->ps));
     }
     // copy stream, staged path: fill a staging slot by DMA, then the scatter stream places its pages
     bool slot_used[N_STAGING_SLOTS] = {};
     int slot_idx = 0;
     for (const SlotPlan& sp : slots) {
-        if (slot_used[sp.slot]) CF_HIP(hipStreamWaitEvent(c->ps, c->ev_free[sp.slot], 0));
+        if (slot_used[sp.slot]) CF_HIP_Q(hipStreamWaitEvent(c->ps, c->ev_free[sp.slot], 0));
         double slot_bytes = 0;
         for (int k = 0; k < sp.n_ops; ++k) slot_bytes += (double)ops[sp.op_first + k].bytes;
         c->prof_begin(CF_K_H2D_COPY, slot_bytes, c->ps);
         for (int k = 0; k < sp.n_ops; ++k) {
             const CopyOp& op = ops[sp.op_first + k];
-            CF_HIP(hipMemcpyAsync(c->staging() + op.dst_off, op.src, op.bytes, hipMemcpyHostToDevice, c->ps));
+            CF_HIP_Q(hipMemcpyAsync(c->staging() + op.dst_off, op.src, op.bytes, hipMemcpyHostToDevice, c->ps));
         }
         pace(slot_bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
-        CF_HIP(hipEventRecord(c->ev_filled[sp.slot], c->ps));
-        CF_HIP(hipStreamWaitEvent(c->ss, c->ev_filled[sp.slot], 0));
+        CF_HIP_Q(hipEventRecord(c->ev_filled[sp.slot], c->ps));
+        CF_HIP_Q(hipStreamWaitEvent(c->ss, c->ev_filled[sp.slot], 0));
         c->prof_begin(CF_K_PAGE_SCATTER, 2.0 * slot_bytes, c->ss);
         launch_page_move(c->ss, m.dtype, c->staging(), cache->pool,
                          (const PageJob*)(md + off_jobs) + sp.job_first, sp.n_jobs, sp.n_blocks,
                          (const int32_t*)md, g, true);
         c->prof_end(CF_K_PAGE_SCATTER, c->ss);
-        CF_HIP(hipEventRecord(c->ev_free[sp.slot], c->ss));
+        CF_HIP_Q(hipEventRecord(c->ev_free[sp.slot], c->ss));
         slot_used[sp.slot] = true;
         if (merged)
             for (int l = 0; l < L; ++l)
                 if (layer_last_slot[l] == slot_idx) {
-                    CF_HIP(hipEventRecord(c->ev_layer[l], c->ss));
+                    CF_HIP_Q(hipEventRecord(c->ev_layer[l], c->ss));
                     layer_loaded[l] = 1;
                 }
         ++slot_idx;
     }
-    CF_HIP(hipEventRecord(c->ev_scat, c->ss));
-    CF_HIP(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
-    CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+    CF_HIP_Q(hipEventRecord(c->ev_scat, c->ss));
+    CF_HIP_Q(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
+    CF_HIP_Q(hipEventRecord(c->ev_copy, c->ps));
 
     // compute stream: layer-major over the batch
     int max_cut = 0;
@@ -1042,17 +1091,17 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         for (int l = 0; l < L; ++l)
             if (layer_loaded[l]) ready[l] = c->ev_layer[l];
         int rc2 = run_phase(c, cache, rec, L, ready.data(), c->ev_comp);
-        if (rc2) return rc2;
-        CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+        if (rc2) return bail(rc2);
+        CF_HIP_Q(hipEventRecord(c->ev_t0, c->cs));
     } else {
         int rc2 = run_phase(c, cache, rec, max_cut, nullptr, c->ev_comp);
-        if (rc2) return rc2;
+        if (rc2) return bail(rc2);
         // join, then the new-turn prefill
-        CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
-        CF_HIP(hipEventRecord(c->ev_t0, c->cs));
+        CF_HIP_Q(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
+        CF_HIP_Q(hipEventRecord(c->ev_t0, c->cs));
         if (logits_out) {
             rc2 = run_phase(c, cache, suf, L, nullptr, nullptr);
-            if (rc2) return rc2;
+            if (rc2) return bail(rc2);
         }
     }
     if (logits_out) {
@@ -1061,14 +1110,16 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                        m.rms_eps, (const int32_t*)(md + off_last));
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
     }
-    CF_HIP(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
-    CF_HIP(hipEventRecord(c->ev_end, c->cs));
-    CF_HIP(hipGetLastError());
-    CF_HIP(hipStreamSynchronize(c->cs));
-    CF_HIP(hipStreamSynchronize(c->ps));
-    CF_HIP(hipStreamSynchronize(c->ss));
+    CF_HIP_Q(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
+    CF_HIP_Q(hipEventRecord(c->ev_end, c->cs));
+    CF_HIP_Q(hipGetLastError());
+    CF_HIP_Q(hipStreamSynchronize(c->cs));
+    CF_HIP_Q(hipStreamSynchronize(c->ps));
+    CF_HIP_Q(hipStreamSynchronize(c->ss));
     c->prof_collect();
 
+#undef CF_HIP_Q
+    c->inject_fail_at = 0;
     if (timing) {
         float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
         CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
@@ -1215,6 +1266,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         n_pages_req[i] = np;
         total_pt += np;
     }
+    if (int dup = first_repeated_id(reqs, B); dup >= 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: request %d repeats the id %llu of an earlier request "
+                    "of the batch", dup, (unsigned long long)reqs[dup].req_id);
     if (rows_lw + n_tw * C + sum_new > c->opts.max_tokens)
         return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: %lld layer-wise rows + %lld token-wise chunks of %d + "
                     "%lld new tokens exceed max_tokens %d", (long long)rows_lw, (long long)n_tw, C,
@@ -1858,6 +1912,7 @@ extern "C" int cf_offload(cf_ctx* c, cf_cache* cache, uint64_t req_id, int32_t n
     }
     return CF_OK;
 }
+
 
 extern "C" int cf_measure_h2d(cf_ctx* c, const void* host_buf, void* dev_buf, size_t bytes,
                               int32_t reps, double* gb_per_s) {

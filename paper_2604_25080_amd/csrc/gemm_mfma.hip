@@ -14,8 +14,6 @@
 // row so that the 16-byte fragment reads of a wavefront spread over all banks.
 // Workgroups are renumbered so that the 32 workgroups resident on one XCD
 // (one L2) cover an 8x4 patch of tiles.
-#include <cstdlib>
-
 #include "kernels.h"
 #include "cacheflow.h"
 
@@ -46,7 +44,7 @@ template <int EPI, int BM, int BN, int NW>
 __global__ void __launch_bounds__(64 * NW)
 gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                  const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
-                 int N, int K, int tiles_m, int tiles_n, int map_mode, int group_m) {
+                 int N, int K, int tiles_m, int tiles_n) {
     extern __shared__ __align__(16) char smem[];
     constexpr bool SILU = (EPI == EPI_SILU_MUL);
     constexpr int BN_OUT = SILU ? BN / 2 : BN;    // output columns per block
@@ -63,8 +61,7 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     int bid = blockIdx.x;
     int per = nb >> 3, rem = nb & 7, xcd = bid & 7, idx = bid >> 3;
     int pid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    if (map_mode == 1) pid = bid;
-    const int GM = group_m;
+    constexpr int GM = 8;
     int in_group = GM * tiles_n;
     int first_m = (pid / in_group) * GM;
     int gsz = min(tiles_m - first_m, GM);
@@ -374,15 +371,8 @@ void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, fl
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
-    static int map_mode = -1, group_m = 8;
-    if (map_mode < 0) {
-        const char* e = getenv("CF_GEMM_MAP");
-        map_mode = e ? atoi(e) : 0;
-        const char* gme = getenv("CF_GEMM_GM");
-        group_m = gme ? atoi(gme) : 8;
-    }
     kern<<<tiles_m * tiles_n, 64 * NW, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf,
-                                             (bf16*)Dt, M, N, K, tiles_m, tiles_n, map_mode, group_m);
+                                             (bf16*)Dt, M, N, K, tiles_m, tiles_n);
 }
 
 int g_force_tile = 0;   // 0 = heuristic, 256 / 128 / 64 = forced (tuning hook)

@@ -470,10 +470,27 @@ page_store_kernel(const T* __restrict__ pool, const PageJob* __restrict__ jobs, 
             const T* src = layer_base + (int64_t)table[pg] * g.page_elems;
             val[u] = reinterpret_cast<const v4u*>(src)[v];
         }
+        // slots past the run's last token (the tail of a request's last page) go out as zero,
+        // whatever the pool holds there
+        const int64_t k_elems = (int64_t)g.n_kv_heads * CF_PAGE_TOKENS * g.head_dim;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             unsigned o = u * 256 + threadIdx.x;
-            if (base + o < job_vecs) __builtin_nontemporal_store(val[u], dst + o);
+            if (base + o >= job_vecs) continue;
+            unsigned pg = pg0 + (rem0 + o) / (unsigned)nvec;
+            int hi = job.tok_end - (job.page_first + (int)pg) * CF_PAGE_TOKENS;
+            if (hi < CF_PAGE_TOKENS) {
+                int64_t e = (int64_t)(rem0 + o - (pg - pg0) * (unsigned)nvec) * VE;
+                if (e < k_elems) {          // K part: the vector lies inside one slot row
+                    if ((int)((e / g.head_dim) % CF_PAGE_TOKENS) >= hi) val[u] = v4u{0, 0, 0, 0};
+                } else {                    // V part: VE consecutive slots of one column
+                    int s0 = (int)((e - k_elems) % CF_PAGE_TOKENS);
+                    T* sv = reinterpret_cast<T*>(&val[u]);
+                    for (int i = 0; i < VE; ++i)
+                        if (s0 + i >= hi) sv[i] = T{};
+                }
+            }
+            __builtin_nontemporal_store(val[u], dst + o);
         }
     }
 }

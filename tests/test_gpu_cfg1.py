@@ -242,6 +242,45 @@ def test_cfg1_error_paths_return_codes_not_faults(env):
         sess.cache.free(1)
 
 
+def test_cfg1_failure_after_enqueue_drains_the_streams_and_leaves_the_context_usable(env):
+    """An error reported after work was enqueued (forced from the host: nothing on the GPU
+    fails) must come back only when all three streams are idle -- the caller may free its host
+    blocks right away -- and the same context must then restore the batch correctly."""
+    import paper_2604_25080_amd as cf
+    b, refs, ws, sess, host = env
+    for nth in (1, 6, 11, 17):
+        for i in range(len(b.n_ctx)):
+            sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
+        try:
+            blocks = [h.clone().pin_memory() for h in host]
+            reqs = [dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=blocks[i])
+                    for i in range(len(b.n_ctx))]
+            sess.ctx.inject_failure(nth)
+            with pytest.raises(cf.CfError) as e:
+                sess.restore(reqs, [(0, k, c) for k, c in b.forced_splits])
+            assert e.value.status == cf.CF_ERR_HIP
+            for blk in blocks:                       # the call has returned: scribbling must be harmless
+                blk.fill_(0xFF)
+            del blocks, reqs
+        finally:
+            for i in range(len(b.n_ctx)):
+                sess.cache.free(1 + i)
+        run_and_check(env, b.forced_splits, seed=20 + nth)      # the hook is one shot; results are right again
+
+
+def test_cfg1_repeated_request_id_is_rejected(env):
+    import paper_2604_25080_amd as cf
+    b, refs, ws, sess, host = env
+    sess.cache.alloc(1, b.n_ctx[0] + b.n_new[0])
+    r = dict(req_id=1, ctx_tokens=b.ctx_tokens[0], new_tokens=b.new_tokens[0], host_kv=host[0])
+    try:
+        with pytest.raises(cf.CfError) as e:
+            sess.restore([r, dict(r)], [(0, 64, 2), (0, 32, 2)])
+        assert e.value.status == cf.CF_ERR_INVALID_ARG
+    finally:
+        sess.cache.free(1)
+
+
 def test_cfg1_degenerate_batches(env):
     """Empty batch; a request with no context at all (pure new-turn prefill); one new token;
     a context of one token; all in one batch with an ordinary request."""
