@@ -527,6 +527,27 @@ int cf_ctx_set_stage(cf_ctx* ctx, int32_t layer_begin, int32_t layer_end);
  * with CF_ERR_WORKSPACE if more than cap_rows rows are active.               */
 int cf_ctx_capture_boundary(cf_ctx* ctx, int32_t layer, float* dev_out, int64_t cap_rows);
 
+/* One-shot sampling of the residual stream for teacher-forced parity checks
+ * at sizes where the CPU cannot run the whole context (the scale plan's
+ * per-layer check: a layer's K/V cells, its attention half and its MLP half
+ * are recomputed on the CPU from the hidden state the GPU fed them, so errors
+ * do not accumulate over depth).  During the NEXT cf_restore_batch, for every
+ * layer l of the context's stage (l = 0 .. L-1, counted from the stage's
+ * first layer) the residual stream of the listed packed rows is copied
+ *   to dev_out[2l][j][0..d_model)    as it enters the layer, and
+ *   to dev_out[2l+1][j][0..d_model)  as it enters the layer's MLP half (input
+ *                                    plus the projected attention output);
+ * what leaves the last layer goes to dev_out[2L][j].  A listed row leaves a
+ * slot untouched where it is not active: a recompute row at or above its
+ * layer cut has no entry, and in its last recomputed layer, which stops after
+ * the K/V write, neither an MLP input nor (for l = L-1) a final state; only
+ * new-turn rows have all 2L+1 slots.
+ *   packed_rows : host int32[n_rows] (copied), packed row order as for
+ *                 cf_ctx_capture_boundary; n_rows <= 4096; 0 cancels
+ *   dev_out     : DEVICE float[2L+1][n_rows][d_model]
+ * With the sequential join only the recompute phase is sampled.             */
+int cf_ctx_capture_rows(cf_ctx* ctx, const int32_t* packed_rows, int32_t n_rows, float* dev_out);
+
 /* Emulation of a slower storage tier or link (the bandwidth ablation of the
  * paper's evaluation): with gb_per_s > 0 the copy stream of cf_restore_batch
  * is held after every transfer unit until the bytes moved so far would have

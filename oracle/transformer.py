@@ -242,12 +242,13 @@ def full_reference(shape, weights, ctx_tokens, new_tokens, dtype=np.float64, act
     return kv_ctx, kv_new, logits
 
 
-def layer_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
-                              v_cache, dtype=np.float64):
-    """Teacher-forced check of one layer on a few sampled rows: given the
-    rows' input hidden states and the layer's K/V cache for positions
-    0..max(positions) (which must already include the rows' own K/V), return
-    (k_rows, v_rows, h_out_rows)."""
+def attention_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
+                                  v_cache, dtype=np.float64):
+    """Attention half of one layer on a few sampled rows: given the rows' input
+    hidden states and the layer's K/V cache for positions 0..max(positions)
+    (which must already include the rows' own K/V), return (k_rows, v_rows,
+    h_mid_rows) with h_mid = h + attention(h) W_o, the residual stream that
+    enters the MLP half."""
     s = shape
     t = h_rows.shape[0]
     a = rmsnorm(h_rows, gain, s.rms_eps, dtype)
@@ -261,10 +262,40 @@ def layer_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
     v = qkv[:, nq + nk:].reshape(t, s.n_kv_heads, s.head_dim)
     o = causal_attention(q, k_cache, v_cache, positions, dtype)
     h = np.asarray(h_rows, dtype=dtype) + o.reshape(t, nq) @ lw["wo"].astype(dtype).T
-    u = rmsnorm(h, gain, s.rms_eps, dtype)
-    h = h + (silu(u @ lw["w_gate"].astype(dtype).T) *
-             (u @ lw["w_up"].astype(dtype).T)) @ lw["w_down"].astype(dtype).T
     return k, v, h
+
+
+def mlp_rows(shape, lw, gain, h_mid_rows, dtype=np.float64):
+    """MLP half of one layer on a few rows: h_mid + SwiGLU(RMSNorm(h_mid))."""
+    h = np.asarray(h_mid_rows, dtype=dtype)
+    u = rmsnorm(h, gain, shape.rms_eps, dtype)
+    return h + (silu(u @ lw["w_gate"].astype(dtype).T) *
+                (u @ lw["w_up"].astype(dtype).T)) @ lw["w_down"].astype(dtype).T
+
+
+def layer_rows_teacher_forced(shape, lw, gain, h_rows, positions, k_cache,
+                              v_cache, dtype=np.float64):
+    """Teacher-forced check of one layer on a few sampled rows: the attention
+    half followed by the MLP half.  Returns (k_rows, v_rows, h_out_rows)."""
+    k, v, h_mid = attention_rows_teacher_forced(shape, lw, gain, h_rows, positions,
+                                                k_cache, v_cache, dtype)
+    return k, v, mlp_rows(shape, lw, gain, h_mid, dtype)
+
+
+def kv_rows_teacher_forced(shape, lw, gain, h_rows, positions, dtype=np.float64):
+    """The K/V half of the teacher-forced check: the cache cells of one layer
+    for a few sampled rows, from the rows' input hidden states alone (K and V
+    of a token depend on nothing but its own hidden state and position):
+    RMSNorm, K/V projection, rotary turn of K.  Returns (k_rows, v_rows)."""
+    s = shape
+    t = h_rows.shape[0]
+    a = rmsnorm(h_rows, gain, s.rms_eps, dtype)
+    nq = s.n_q_heads * s.head_dim
+    nk = s.n_kv_heads * s.head_dim
+    kv = a @ lw["wqkv"][nq:].astype(dtype).T
+    k = rope(kv[:, :nk].reshape(t, s.n_kv_heads, s.head_dim), positions, s.rope_base, dtype)
+    v = kv[:, nk:].reshape(t, s.n_kv_heads, s.head_dim)
+    return k, v
 
 
 def kv_to_pages(shape, cache, n_tokens, page_tokens=16):

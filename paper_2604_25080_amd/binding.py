@@ -161,6 +161,7 @@ lib.cf_ctx_set_load_path.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
 lib.cf_ctx_set_link_throttle.argtypes = [C.c_void_p, C.c_double]
 lib.cf_ctx_set_stage.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
 lib.cf_ctx_capture_boundary.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
+lib.cf_ctx_capture_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
 lib.cf_restore_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request), _P(cf_split),
                                  C.c_void_p, _P(cf_timing)]
 lib.cf_restore_dynamic.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _P(cf_request),
@@ -182,7 +183,7 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", 
            "cf_derive_l_delta", "cf_dynamic_io_pick", "cf_dynamic_claim", "cf_restore_dynamic", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
-           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_ctx_set_stage", "cf_ctx_capture_boundary", "cf_restore_batch", "cf_offload",
+           "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_ctx_set_stage", "cf_ctx_capture_boundary", "cf_ctx_capture_rows", "cf_restore_batch", "cf_offload",
            "cf_ctx_inject_failure",
            "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
            "cf_ctx_profile_read", "cf_read_final_hidden"]
@@ -407,6 +408,13 @@ class Ctx:
         """One shot: the next restore_batch copies the rows entering `layer` to dev_ptr (float[cap_rows][d])."""
         _check(lib.cf_ctx_capture_boundary(self.handle, int(layer), dev_ptr, int(cap_rows)),
                "cf_ctx_capture_boundary")
+
+    def capture_rows(self, packed_rows, dev_ptr):
+        """One shot: the next restore_batch samples the residual stream of the listed packed rows
+        into dev_ptr (float[2L+1][n_rows][d]): slot 2l = entering layer l, 2l+1 = entering its MLP
+        half, 2L = leaving the last layer."""
+        rows = _i32(packed_rows)
+        _check(lib.cf_ctx_capture_rows(self.handle, rows.ctypes.data, len(rows), dev_ptr), "cf_ctx_capture_rows")
 
     def set_link_throttle(self, gb_per_s):
         """Pace the copy stream to gb_per_s GB/s (0: off)."""

@@ -9,6 +9,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <climits>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -36,7 +37,7 @@ constexpr int PAGE_MOVE_SPLIT = 4;       // blocks per page in the page mover
 constexpr int N_STAGING_SLOTS = 2;
 
 struct Carve {
-    size_t rope, h, dl, a, qkv, q, o, act, a_last, attn_part, staging, meta, total;
+    size_t rope, h, dl, a, qkv, q, o, act, a_last, h_last, attn_part, staging, meta, total;
     size_t staging_bytes, meta_bytes;
     int chunk_rows;
     size_t pace;
@@ -82,6 +83,7 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
     c->o = take((size_t)chunk * m.n_q_heads * m.head_dim * es);
     c->act = take((size_t)chunk * m.d_ffn * es);
     c->a_last = take((size_t)o.max_batch * m.d_model * es);
+    c->h_last = take((size_t)o.max_batch * m.d_model * 4);
     c->attn_part = take(attn_part_bytes(m.head_dim));
     c->staging = take(stg);
     c->meta = take(meta);
@@ -118,13 +120,16 @@ struct cf_ctx {
     int capture_layer = -1;               // next call: copy the rows entering this layer ...
     float* capture_out = nullptr;         // ... to this device array [rows][d]
     int64_t capture_cap_rows = 0;
+    std::vector<int32_t> caprows;         // next call: packed rows whose residual stream is sampled ...
+    float* caprows_out = nullptr;         // ... at every layer entry, to this device array [L+1][n][d]
+    const int32_t* caprows_dev = nullptr; // the row list in the call's device metadata
     int inject_fail_at = 0;           // > 0: that status check of the next call's enqueue part fails
     double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
     std::vector<hipEvent_t> dyn_events;   // run-time scheduler: loads in flight + the compute step
     int dyn_scale_c = 1000, dyn_scale_io = 1000;   // measured/predicted ratios carried from call to call
-    std::vector<int32_t> last_rows;   // packed row of each request's last new token, last call
+    int n_last = 0;                   // requests whose final hidden row the last call left in h_last
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
     struct ProfRec { int cls; double work; hipEvent_t e0, e1; };
@@ -172,6 +177,7 @@ struct cf_ctx {
     void* o() { return ws + cv.o; }
     void* act() { return ws + cv.act; }
     void* a_last() { return ws + cv.a_last; }
+    float* h_last() { return (float*)(ws + cv.h_last); }   // final hidden row of each request's last new token
     float* attn_part() { return (float*)(ws + cv.attn_part); }
     float2* rope() { return (float2*)(ws + cv.rope); }
     char* staging() { return ws + cv.staging; }
@@ -314,6 +320,16 @@ extern "C" int cf_ctx_capture_boundary(cf_ctx* ctx, int32_t layer, float* dev_ou
     ctx->capture_layer = layer;
     ctx->capture_out = dev_out;
     ctx->capture_cap_rows = cap_rows;
+    return CF_OK;
+}
+
+extern "C" int cf_ctx_capture_rows(cf_ctx* ctx, const int32_t* packed_rows, int32_t n_rows, float* dev_out) {
+    if (!ctx) return fail(CF_ERR_INVALID_ARG, "cf_ctx_capture_rows: null ctx");
+    if (n_rows < 0 || n_rows > 4096 || (n_rows > 0 && (!packed_rows || !dev_out)))
+        return fail(CF_ERR_INVALID_ARG, "cf_ctx_capture_rows: need 0 <= n_rows <= 4096 and non-null arrays");
+    if (ctx->m.d_model % 4 != 0) return fail(CF_ERR_UNSUPPORTED, "cf_ctx_capture_rows: d_model %% 4 != 0");
+    ctx->caprows.assign(packed_rows, packed_rows + n_rows);
+    ctx->caprows_out = n_rows > 0 ? dev_out : nullptr;
     return CF_OK;
 }
 
@@ -574,6 +590,10 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
         if (Ta_rec <= 0 && !any_new) break;
         const cf_layer_weights& lw = c->layers[layer0 + l];
         char* pool_layer = (char*)cache->pool + (size_t)(layer0 + l) * g.layer_stride * es;
+        if (c->caprows_out && c->caprows_dev && row_base == 0)
+            launch_residual_gather(c->cs, c->caprows_out + (size_t)(2 * l) * c->caprows.size() * d, h_rows,
+                                   l > 0 ? dl_rows : nullptr, c->caprows_dev, (int)c->caprows.size(), d,
+                                   0, Ta_rec, ph.rec_rows(), ph.T);
         if (c->capture_out && c->capture_layer == layer0 + l) {
             // boundary activations: the residual stream of the rows entering this layer
             int rows = any_new ? ph.T : Ta_rec;
@@ -654,6 +674,9 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                     c->prof_end(CF_K_ATTENTION, c->cs);
                 }
                 gemm(c, CF_K_GEMM_OPROJ, o_buf, lw.wo, nullptr, dl, nullptr, Tr, d, nq, EPI_STORE_F32);
+                if (c->caprows_out && c->caprows_dev && row_base == 0)     // the stream entering the MLP half
+                    launch_residual_gather(c->cs, c->caprows_out + (size_t)(2 * l + 1) * c->caprows.size() * d,
+                                           h_rows, dl_rows, c->caprows_dev, (int)c->caprows.size(), d, x, x + Tr, 0, 0);
                 c->prof_begin(CF_K_RMSNORM, (double)Tr * d * (12 + es), c->cs);
                 launch_rmsnorm(c->cs, m.dtype, h, dl, lw.mlp_norm, a_buf, Tr, d, m.rms_eps, nullptr);
                 c->prof_end(CF_K_RMSNORM, c->cs);
@@ -663,6 +686,11 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
         }
         if (l == last_rec_layer && ev_rec_done) CF_HIP(hipEventRecord(ev_rec_done, c->cs));
     }
+    if (c->caprows_out && c->caprows_dev && row_base == 0 && any_new && l_begin < n_layers_max)
+        // what leaves the last layer: only the new-turn rows ran it to the end
+        launch_residual_gather(c->cs, c->caprows_out + (size_t)(2 * n_layers_max) * c->caprows.size() * d, h_rows,
+                               dl_rows, c->caprows_dev, (int)c->caprows.size(), d, 0, 0, ph.rec_rows(), ph.T);
+    c->caprows_dev = nullptr;         // the first phase of a call is the one that is sampled
     return CF_OK;
 }
 
@@ -858,7 +886,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         return fail(CF_ERR_WORKSPACE, "cf_restore_batch: boundary capture buffer holds %lld rows, the call packs %d",
                     (long long)c->capture_cap_rows, std::max(rec.T, suf.T));
     size_t off_last = mw.put(last_rows.data(), last_rows.size() * 4);
-    c->last_rows = last_rows;
+    c->n_last = 0;
+    const size_t off_caprows = c->caprows_out ? mw.put(c->caprows.data(), c->caprows.size() * 4) : 0;
 
     // Load path.  Direct: a load kernel reads the pinned host block over the link and writes the
     // pages itself (needs device-mapped host memory).  Staged: DMA into staging slots, then a
@@ -1002,6 +1031,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         c->prof_collect();
         c->capture_out = nullptr;
         c->capture_layer = -1;
+        c->caprows_out = nullptr;
+        c->caprows_dev = nullptr;
         c->inject_fail_at = 0;
         return code;
     };
@@ -1083,6 +1114,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     CF_HIP_Q(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
     CF_HIP_Q(hipEventRecord(c->ev_copy, c->ps));
 
+    c->caprows_dev = c->caprows_out ? (const int32_t*)(md + off_caprows) : nullptr;
     // compute stream: layer-major over the batch
     int max_cut = 0;
     for (const Segment& sg : rec.segs) max_cut = std::max(max_cut, sg.layers);
@@ -1109,6 +1141,10 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         launch_rmsnorm(c->cs, m.dtype, c->h(), c->dl(), c->w.final_norm, c->a_last(), B, m.d_model,
                        m.rms_eps, (const int32_t*)(md + off_last));
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
+        // the rows the head saw, kept for cf_read_final_hidden
+        launch_residual_gather(c->cs, c->h_last(), c->h(), c->dl(), (const int32_t*)(md + off_last), B, m.d_model,
+                               0, INT32_MAX, 0, 0);
+        c->n_last = B;
     }
     CF_HIP_Q(hipStreamWaitEvent(c->cs, c->ev_copy, 0));
     CF_HIP_Q(hipEventRecord(c->ev_end, c->cs));
@@ -1120,6 +1156,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
 
 #undef CF_HIP_Q
     c->inject_fail_at = 0;
+    c->caprows_out = nullptr;         // one shot
+    c->caprows_dev = nullptr;
     if (timing) {
         float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
         CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
@@ -1368,7 +1406,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         for (int i : lw_members) add_segment(lw, ids, pos, slot, i, reqs[i].ctx_tokens, n_ctx[i], 0, L, false);
         if (lw.T > 0) finish_phase(lw, ids, pos, slot);
     }
-    c->last_rows.clear();                // no single packed phase holds the final rows of this call
+    c->n_last = 0;
     if (mw.overflow)
         return fail(CF_ERR_WORKSPACE, "cf_restore_dynamic: batch metadata exceeds the context's limits "
                     "(%zu load jobs)", jobs.size());
@@ -1380,9 +1418,12 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     // so that the claim is made as late as possible)
     constexpr int IO_DEPTH = 8;
     constexpr int64_t IO_LOOKAHEAD_PS = 4000000000;
-    while ((int)c->dyn_events.size() < IO_DEPTH + 1) {
+    // events [0, IO_DEPTH): end of the load in that slot; [IO_DEPTH]: the compute step;
+    // (IO_DEPTH, 2 IO_DEPTH]: start of the load in that slot (its duration is read on the GPU's
+    // clock: the host sees completions late whenever it is busy enqueuing a step)
+    while ((int)c->dyn_events.size() < 2 * IO_DEPTH + 1) {
         hipEvent_t e = nullptr;
-        CF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        CF_HIP(hipEventCreate(&e));
         c->dyn_events.push_back(e);
     }
     hipEvent_t ev_step = c->dyn_events[IO_DEPTH];
@@ -1416,11 +1457,11 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     // A request whose cache is complete (pointers crossed, its loads landed, its last recompute
     // step done) has its new-turn rows prefilled in the next compute step, beside whatever else
     // that step recomputes: the new turn of early finishers overlaps the loads of the others.
-    struct Flight { int64_t pred_ps; int req; };  // req: the token-wise request, or -1 = layer-wise group
+    struct Flight { int64_t pred_ps; int req; double t_issue; };  // req: the token-wise request, or -1 = layer-wise group
     std::deque<Flight> io_flight;                 // loads in flight, oldest first
     int64_t io_issued = 0, io_retired = 0;        // event of load k: dyn_events[k % IO_DEPTH]
     int64_t io_pred_done = 0;                     // predicted ps of the retired loads
-    double io_t_first = 0, io_t_last = 0;         // host clock: first issue, latest completion
+    double io_t_last = 0, io_busy_ms = 0;         // host clock: latest completion; time the channel was busy
     int64_t c_pred_done = 0, step_pred = 0;
     double c_meas_done_ms = 0, step_t0 = 0, gap_ms = 0, last_step_end = 0;
     bool step_running = false, ask = true;        // ask: state changed since the last declined claim
@@ -1463,6 +1504,15 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             int dn = done(c->dyn_events[io_retired % IO_DEPTH]);
             if (dn < 0) return -1;
             if (dn == 0) break;
+            // what the channel spent on this load, on the GPU's clock (idle gaps between claims
+            // are not load time, and the host may notice a completion late)
+            float load_ms = 0;
+            if (hipEventElapsedTime(&load_ms, c->dyn_events[IO_DEPTH + 1 + io_retired % IO_DEPTH],
+                                    c->dyn_events[io_retired % IO_DEPTH]) != hipSuccess) {
+                (void)hipGetLastError();
+                load_ms = (float)(now_ms() - std::max(io_flight.front().t_issue, io_t_last));
+            }
+            io_busy_ms += load_ms;
             io_t_last = now_ms();
             io_pred_done += io_flight.front().pred_ps;
             int r = io_flight.front().req;
@@ -1470,8 +1520,8 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             else for (int i : lw_members) --io_pending[i];
             io_flight.pop_front();
             ++io_retired;
-            if (io_pred_done > 0 && io_t_last > io_t_first)
-                scale_io = clamp_scale((io_t_last - io_t_first) * 1e9 / (double)io_pred_done);
+            if (io_pred_done > 0 && io_busy_ms > 0)
+                scale_io = clamp_scale(io_busy_ms * 1e9 / (double)io_pred_done);
             changed = 1;
         }
         while ((int)io_flight.size() < IO_DEPTH) {
@@ -1500,8 +1550,8 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 for (int i : lw_members) { --p_io[i]; ++io_pending[i]; }
                 who = -1;
             }
-            if (io_issued == 0) io_t_first = now_ms();
             c->prof_begin(CF_K_H2D_COPY, (double)ul->bytes, c->ps);
+            if (hipEventRecord(c->dyn_events[IO_DEPTH + 1 + io_issued % IO_DEPTH], c->ps) != hipSuccess) return -1;
             launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ul->job_first,
                              ul->n_jobs, ul->n_vblocks, c->load_wgs, (const int32_t*)md, g);
             if (c->throttle_gbs > 0) {
@@ -1513,7 +1563,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             if (hipEventRecord(c->dyn_events[io_issued % IO_DEPTH], c->ps) != hipSuccess ||
                 hipEventRecord(c->ev_copy, c->ps) != hipSuccess)       // the latest record stands
                 return -1;
-            io_flight.push_back(Flight{unit_load_ps(ul->bytes), who});
+            io_flight.push_back(Flight{unit_load_ps(ul->bytes), who, now_ms()});
             loaded_bytes += (int64_t)ul->bytes;
             ++io_issued;
             changed = 1;
@@ -1610,6 +1660,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                            c->dl() + (size_t)lw.T * m.d_model, c->w.final_norm,
                            (char*)c->a_last() + (size_t)i * m.d_model * es, 1, m.d_model, m.rms_eps,
                            (const int32_t*)(md + off_idx) + k);
+            launch_residual_gather(c->cs, c->h_last() + (size_t)i * m.d_model, c->h() + (size_t)lw.T * m.d_model,
+                                   c->dl() + (size_t)lw.T * m.d_model, (const int32_t*)(md + off_idx) + k, 1,
+                                   m.d_model, 0, INT32_MAX, 0, 0);
             prefilled[i] = 1;
             ++n_prefilled;
         }
@@ -1729,6 +1782,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                                        c->dl() + (size_t)lw.T * m.d_model, c->w.final_norm,
                                        (char*)c->a_last() + (size_t)i * m.d_model * es, 1, m.d_model, m.rms_eps,
                                        (const int32_t*)(md + off_idx) + k);
+                        launch_residual_gather(c->cs, c->h_last() + (size_t)i * m.d_model,
+                                               c->h() + (size_t)lw.T * m.d_model, c->dl() + (size_t)lw.T * m.d_model,
+                                               (const int32_t*)(md + off_idx) + k, 1, m.d_model, 0, INT32_MAX, 0, 0);
                         prefilled[i] = 1;
                         ++n_prefilled;
                     }
@@ -1777,8 +1833,10 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     }
 
     // ---- every cache is complete and every new turn prefilled: first-token logits
-    if (logits_out)
+    if (logits_out) {
         gemm(c, CF_K_GEMM_LM_HEAD, c->a_last(), c->w.lm_head, nullptr, logits_out, nullptr, B, m.vocab, m.d_model, EPI_STORE_F32);
+        c->n_last = B;
+    }
     CF_HIP(hipEventRecord(c->ev_end, c->cs));
     CF_HIP(hipGetLastError());
     CF_HIP(hipStreamSynchronize(c->cs));
@@ -2066,16 +2124,9 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
 
 extern "C" int cf_read_final_hidden(cf_ctx* c, int32_t B, float* out_host) {
     if (!c || !out_host || B <= 0) return fail(CF_ERR_INVALID_ARG, "cf_read_final_hidden: bad argument");
-    if ((int)c->last_rows.size() != B)
-        return fail(CF_ERR_INVALID_ARG, "cf_read_final_hidden: last cf_restore_batch had %zu requests with logits",
-                    c->last_rows.size());
-    int d = c->m.d_model;
-    std::vector<float> hrow(d), drow(d);
-    for (int i = 0; i < B; ++i) {
-        size_t off = (size_t)c->last_rows[i] * d;
-        CF_HIP(hipMemcpy(hrow.data(), c->h() + off, (size_t)d * 4, hipMemcpyDeviceToHost));
-        CF_HIP(hipMemcpy(drow.data(), c->dl() + off, (size_t)d * 4, hipMemcpyDeviceToHost));
-        for (int j = 0; j < d; ++j) out_host[(size_t)i * d + j] = hrow[j] + drow[j];
-    }
+    if (c->n_last != B)
+        return fail(CF_ERR_INVALID_ARG, "cf_read_final_hidden: the last restore call produced logits for %d requests",
+                    c->n_last);
+    CF_HIP(hipMemcpy(out_host, c->h_last(), (size_t)B * c->m.d_model * sizeof(float), hipMemcpyDeviceToHost));
     return CF_OK;
 }

@@ -95,6 +95,10 @@ void launch_page_load(hipStream_t s, int dtype, void* pool, const PageJob* jobs,
                       int n_units, int n_workgroups, const int32_t* page_tables, KvGeom g);
 // out[T][d] = h (+ dl when non-null): the residual stream of packed rows entering a layer (d % 4 == 0)
 void launch_residual_rows(hipStream_t s, float* out, const float* h, const float* dl, int T, int d);
+// out[j][d] = h[idx[j]] (+ dl[idx[j]] when non-null) for j < n; a listed row is skipped unless it
+// lies in [a0, a1) or [b0, b1) (d % 4 == 0)
+void launch_residual_gather(hipStream_t s, float* out, const float* h, const float* dl, const int32_t* idx,
+                            int n, int d, int a0, int a1, int b0, int b1);
 // copy-stream pacing: mark stores the wall clock at *t0 (device, 8 bytes), wait holds the stream
 // until `ticks` wall-clock ticks have passed since the mark (bounded spin)
 void launch_pace_mark(hipStream_t s, void* t0);

@@ -538,6 +538,29 @@ residual_rows_kernel(float* __restrict__ out, const float* __restrict__ h, const
     reinterpret_cast<float4*>(out)[i] = a;
 }
 
+// out[j] = h[idx[j]] (+ dl[idx[j]]) for the listed rows that lie in [a0, a1) or [b0, b1);
+// others are skipped
+__global__ void __launch_bounds__(256)
+residual_gather_kernel(float* __restrict__ out, const float* __restrict__ h, const float* __restrict__ dl,
+                       const int32_t* __restrict__ idx, int d4, int a0, int a1, int b0, int b1) {
+    int r = idx[blockIdx.x];
+    if (!((r >= a0 && r < a1) || (r >= b0 && r < b1))) return;
+    const float4* hr = reinterpret_cast<const float4*>(h) + (int64_t)r * d4;
+    const float4* dr = dl ? reinterpret_cast<const float4*>(dl) + (int64_t)r * d4 : nullptr;
+    float4* o = reinterpret_cast<float4*>(out) + (int64_t)blockIdx.x * d4;
+    for (int i = threadIdx.x; i < d4; i += 256) {
+        float4 a = hr[i];
+        if (dr) { float4 b = dr[i]; a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+        o[i] = a;
+    }
+}
+
+void launch_residual_gather(hipStream_t s, float* out, const float* h, const float* dl, const int32_t* idx,
+                            int n, int d, int a0, int a1, int b0, int b1) {
+    if (n <= 0) return;
+    residual_gather_kernel<<<n, 256, 0, s>>>(out, h, dl, idx, d / 4, a0, a1, b0, b1);
+}
+
 void launch_residual_rows(hipStream_t s, float* out, const float* h, const float* dl, int T, int d) {
     int64_t n4 = (int64_t)T * d / 4;
     if (n4 <= 0) return;

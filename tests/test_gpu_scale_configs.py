@@ -28,7 +28,7 @@ from oracle import transformer as T
 from oracle.pagetable import PageTable
 from workloads import WeightSource, hand_cost_model, make_batch
 
-from gpu_util import decode_pages, kv_tolerance_ok
+from gpu_util import decode_pages, kv_tolerance_ok, teacher_forced_layer_checks, teacher_forced_samples
 
 pytestmark = pytest.mark.gpu
 
@@ -73,10 +73,30 @@ def build(config):
         sess.cache.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
         assert sess.cache.page_table(1 + i) == opt.alloc(1 + i, b.n_ctx[i] + b.n_new[i])
         reqs.append(dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i], host_kv=None))
+    # hidden rows entering every layer, sampled in the longest, the shortest and the first request
+    picked = sorted({0, int(np.argmax(b.n_ctx)), int(np.argmin(b.n_ctx))})
+    rows, rows_req, rows_pos = teacher_forced_samples(b.n_ctx, picked)
+    if len(rows) < 64:       # a single request: add evenly spaced positions
+        more = np.setdiff1d(np.linspace(0, b.n_ctx[0] - 1, 48).astype(np.int64), rows_pos)
+        rows = np.concatenate([rows, more.astype(np.int32)])
+        rows_req, rows_pos = np.concatenate([rows_req, np.zeros(len(more), dtype=np.int64)]), np.concatenate([rows_pos, more])
+    hid = torch.full((2 * shape.n_layers + 1, len(rows), shape.d_model), float("nan"), dtype=torch.float32, device="cuda")
+    sess.ctx.capture_rows(rows, hid.data_ptr())
     sess.restore(reqs, [(0, n, shape.n_layers) for n in b.n_ctx], want_logits=False)
+    sess.teacher = (hid.cpu().numpy(), rows_req, rows_pos)
+    del hid
     for i in range(B):
         reqs[i]["host_kv"] = sess.offload(1 + i, b.n_ctx[i])
     return b, sess, ws, reqs
+
+
+def check_teacher_forced(b, sess, ws, reqs, out_layers):
+    """K/V cells of the sampled rows at EVERY layer and the layer output rows at `out_layers`,
+    element by element against the unrounded oracle fed with the GPU's own hidden rows."""
+    hid, rows_req, rows_pos = sess.teacher
+    assert len(rows_req) >= 64
+    return teacher_forced_layer_checks(b.shape, ws, sess, b.n_ctx, [r["host_kv"] for r in reqs], hid, rows_req,
+                                       rows_pos, out_layers=set(out_layers), label=b.config)
 
 
 def release(b, sess):
@@ -197,12 +217,17 @@ def check_hybrid_restore(b, sess, ws, reqs):
     return splits
 
 
-def check_run_time_scheduled_restore(b, sess, reqs, l_delta):
+def check_run_time_scheduled_restore(b, sess, ws, reqs, l_delta):
     """cf_restore_dynamic on the full batch (token-wise above l_delta, layer-wise below, or the
     configuration's forced mode): loaded cells are the host block's bytes; recomputed cells --
     chunk by chunk or layer by layer, in steps -- are compared with the single-pass prefill that
-    made the host block: bit for bit where that holds, else to within two bf16 ulps of the cell
-    on at least 99.9 % of the cells and a quarter of the tensor's spread everywhere."""
+    made the host block: bit for bit where that holds (layer 0 always: no attention feeds it),
+    else to within two bf16 ulps of the cell on at least 97 % of the cells and a quarter of the
+    tensor's spread everywhere -- a second net only: the attention of a step splits its key ranges
+    by how many rows the step holds, so the summation order, and with it the last bits of every
+    later layer, depends on how many steps the schedule took.  The element-wise statements about
+    this path are the loaded cells (bytes), layer 0 (bits), the logits (oracle head on the final
+    hidden rows) and the small shapes, where the oracle runs the whole batch."""
     import paper_2604_25080_amd as cf
     shape, L, B = b.shape, b.shape.n_layers, len(b.n_ctx)
     opts = cf.plan_opts(b.chunk_tokens, l_delta, L, shape.kv_bytes_per_token_layer, b.forced_mode)
@@ -238,10 +263,17 @@ def check_run_time_scheduled_restore(b, sess, reqs, l_delta):
                     continue
                 d = np.abs(g - r)
                 ulp = np.maximum(np.abs(r), 1.0) * 2.0 ** -7
-                assert (d <= 2 * ulp).mean() >= 0.999 and d.max() <= 0.25 * r.std() + 0.05, \
+                assert l > 0, f"{b.config} request {i} layer 0 {nm}: recomputed cells differ from the single pass"
+                assert (d <= 2 * ulp).mean() >= 0.97 and d.max() <= 0.25 * r.std() + 0.05, \
                     f"{b.config} request {i} layer {l} {nm}: max diff {d.max()}, within 2 ulp {(d <= 2 * ulp).mean()}"
         del got
     print(f"{b.config}: {n_exact} of {n_cmp} recomputed (request, layer, K|V) blocks bit-identical to the single pass")
+    hid = sess.ctx.read_final_hidden(B)
+    out = logits.cpu().numpy()
+    for i in sorted({0, B - 1}):
+        ref = T.logits_last(shape, ws, hid[i].astype(np.float64), act="bf16")
+        err = np.abs(out[i] - ref).max()
+        assert err <= 2e-2, f"{b.config} request {i}: run-time scheduled logits max abs err {err}"
 
 
 @pytest.mark.timeout(900)
@@ -251,10 +283,13 @@ def test_8b_configurations_at_full_size(config):
     try:
         longest = int(np.argmax(b.n_ctx))
         check_layers_0_and_1(b, sess, ws, reqs, longest)
+        L = b.shape.n_layers
+        check_teacher_forced(b, sess, ws, reqs, out_layers=(0, 1, L // 2, L - 2) if config == "cfg3"
+                             else (0, 1, 2, L // 2 - 1, L // 2, L - 3, L - 2))
         splits = check_hybrid_restore(b, sess, ws, reqs)
         if config == "cfg3":
             assert splits[0][1] == b.n_ctx[0] and 0 < splits[0][2] < b.shape.n_layers   # layer-wise
-        check_run_time_scheduled_restore(b, sess, reqs, l_delta=4096)
+        check_run_time_scheduled_restore(b, sess, ws, reqs, l_delta=4096)
     finally:
         release(b, sess)
         for r in reqs:
@@ -285,7 +320,8 @@ def test_tp_shard_configuration_5_at_full_size():
                     print(f"cfg5 layer {l} {nm}: gpu rms {gr:.5f} max {gm:.5f}; bf16 cpu rms {rr:.5f} max {rm:.5f}")
                 assert gr <= 1.3 * rr + 1e-4 and gm <= 1.6 * rm + 1e-3, \
                     f"layer {l} {nm}: rms {gr} max {gm} vs noise floor {rr} / {rm}"
+        check_teacher_forced(b, sess, ws, reqs, out_layers=(0, 1, 2, L // 2 - 1, L // 2, L - 3, L - 2))
         check_hybrid_restore(b, sess, ws, reqs)
-        check_run_time_scheduled_restore(b, sess, reqs, l_delta=16384)
+        check_run_time_scheduled_restore(b, sess, ws, reqs, l_delta=16384)
     finally:
         release(b, sess)

@@ -286,6 +286,23 @@ def test_teacher_forced_rows_match_full_layer():
     np.testing.assert_allclose(kr, kv.k[l][rows], rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(vr, kv.v[l][rows], rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(hr, h_out[rows], rtol=1e-10, atol=1e-12)
+    # the two halves on their own: with a zero down-projection a layer's output IS the residual
+    # stream after its attention half, and the MLP half of that stream is what the full layer adds
+    lw0 = dict(ws.layer_f32(l))
+    lw0["w_down"] = np.zeros_like(lw0["w_down"])
+    h_mid_full, _, _ = T.layer_forward(shape, lw0, ws.norm_gain(), h_in[l], np.arange(len(toks)), None, None)
+    _, _, h_mid = T.attention_rows_teacher_forced(shape, ws.layer_f32(l), ws.norm_gain(), h_in[l][rows], rows,
+                                                  kv.k[l], kv.v[l])
+    np.testing.assert_allclose(h_mid, h_mid_full[rows], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(T.mlp_rows(shape, ws.layer_f32(l), ws.norm_gain(), h_mid_full[rows]), h_out[rows],
+                               rtol=1e-10, atol=1e-12)
+    assert np.abs(h_mid - h_out[rows]).max() > 1e-3          # the MLP half is not a no-op here
+    # the K/V-only form agrees with the full prefill at every layer (not with itself: the
+    # prefill computes the cells inside layer_forward, batched over all tokens)
+    for l in range(shape.n_layers):
+        k2, v2 = T.kv_rows_teacher_forced(shape, ws.layer_f32(l), ws.norm_gain(), h_in[l][rows], rows)
+        np.testing.assert_allclose(k2, kv.k[l][rows], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(v2, kv.v[l][rows], rtol=1e-10, atol=1e-12)
 
 
 def test_kv_to_pages_layout():
