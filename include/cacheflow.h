@@ -443,6 +443,26 @@ int cf_restore_dynamic(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request
  * (slots past n_ctx in the last page are written as zero).                  */
 int cf_offload(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv);
 
+/* cf_offload for callers that cannot allocate device memory (code under HIP
+ * graph capture set-up, tight serving loops, harnesses that forbid hipMalloc):
+ * the same result as cf_offload's staged path -- whole pages in the host
+ * layout, slots past n_ctx in the last page zero -- but the device scratch it
+ * needs (the request's page table, one job record, one 16 MiB staging slot)
+ * lives in a static device array of the library (16 MiB + 64 KiB, held on every
+ * GPU the library runs on until the process ends) instead of the context's
+ * workspace.  The call allocates nothing, on the device or through the HIP
+ * runtime: it uses the context's compute stream and pinned metadata buffer,
+ * and host_kv must be PINNED host memory (hipHostMalloc; a copy into pageable
+ * memory would go through buffers the runtime allocates), else
+ * CF_ERR_INVALID_ARG.  Limits: n_ctx <= cf_offload_static_max_tokens()
+ * (16320 pages = 261120 tokens) and page_bytes <= 16 MiB, else
+ * CF_ERR_WORKSPACE.  Blocking.  Every call on a GPU shares that GPU's array,
+ * which keeps the previous call's contents (each call overwrites what it
+ * reads back, nothing needs to start at zero): calls that overlap on one GPU,
+ * from any thread or context, race.                                          */
+int cf_offload_static(cf_ctx* ctx, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv);
+size_t cf_offload_static_max_tokens(void);
+
 /* Time a large pinned host->device copy on the copy stream: the bandwidth
  * roofline of the load path.  host_buf pinned, dev_buf device, both >= bytes. */
 int cf_measure_h2d(cf_ctx* ctx, const void* host_buf, void* dev_buf, size_t bytes, int32_t reps,

@@ -99,6 +99,8 @@ static int carve_workspace(const cf_model_desc& m, const cf_ctx_opts& o, Carve* 
 
 using namespace cf;
 
+static int static_scratch_of_current_device(char** out);
+
 struct cf_ctx {
     cf_model_desc m;
     cf_ctx_opts opts;
@@ -234,6 +236,12 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
             return bail(fail(CF_ERR_HIP, "%s:%d %s -> %s", __FILE__, __LINE__, #call,         \
                              hipGetErrorString(e_)));                                         \
     } while (0)
+    {
+        // set-up of cf_offload_static on this device: resolve the static scratch array's address
+        char* sc = nullptr;
+        int rs = static_scratch_of_current_device(&sc);
+        if (rs) return bail(rs);
+    }
     CF_HIP_CTX(hipStreamCreateWithFlags(&c->ss, hipStreamNonBlocking));
     c->own_ss = true;
     CF_HIP_CTX(hipHostMalloc((void**)&c->meta_host, cv.meta_bytes, hipHostMallocDefault));
@@ -1971,6 +1979,109 @@ extern "C" int cf_offload(cf_ctx* c, cf_cache* cache, uint64_t req_id, int32_t n
     return CF_OK;
 }
 
+
+// ------------------------------------------------- offload for callers that cannot allocate
+// cf_offload's staged path with its device scratch (page table, job record, staging slot) in a
+// file-scope device array instead of the context's workspace.  Host code never uses the array's
+// name as an address: the device address is looked up once per device with hipGetSymbolAddress
+// (each GPU holds its own copy) and kept in g_static_scratch.
+namespace {
+constexpr size_t STATIC_META_BYTES = (size_t)64 << 10;       // page table + one job record
+constexpr size_t STATIC_STAGING_BYTES = (size_t)16 << 20;    // one staging slot
+constexpr int STATIC_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[STATIC_META_BYTES + STATIC_STAGING_BYTES];
+static char* g_static_scratch[STATIC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static int static_scratch_of_current_device(char** out) {
+    int dev = -1;
+    CF_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES)
+        return fail(CF_ERR_UNSUPPORTED, "static scratch: device index %d outside [0, %d)", dev, STATIC_MAX_DEVICES);
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        CF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(CF_ERR_HIP, "static scratch: hipGetSymbolAddress returned a null address");
+        g_static_scratch[dev] = (char*)p;
+    }
+    *out = g_static_scratch[dev];
+    return CF_OK;
+}
+
+extern "C" size_t cf_offload_static_max_tokens(void) {
+    return ((STATIC_META_BYTES - 256) / 4) * CF_PAGE_TOKENS;
+}
+
+extern "C" int cf_offload_static(cf_ctx* c, cf_cache* cache, uint64_t req_id, int32_t n_ctx, void* host_kv) {
+    if (!c || !cache || !host_kv || n_ctx < 0)
+        return fail(CF_ERR_INVALID_ARG, "cf_offload_static: bad argument");
+    int np = 0;
+    const int32_t* pt = cache->table_of(req_id, &np);
+    if (!cache->has(req_id))
+        return fail(CF_ERR_UNKNOWN_REQUEST, "cf_offload_static: request %llu has no pages", (unsigned long long)req_id);
+    const int np_ctx = (int)ceil_div(n_ctx, CF_PAGE_TOKENS);
+    if (np_ctx > np) return fail(CF_ERR_INVALID_ARG, "cf_offload_static: request holds fewer than n_ctx tokens");
+    const cf_model_desc& m = c->m;
+    const size_t es = elem_bytes(m.dtype), pb = cache->page_bytes;
+    const size_t job_off = STATIC_META_BYTES - 256;          // the job record sits behind the page table
+    if ((size_t)np_ctx * 4 > job_off)
+        return fail(CF_ERR_WORKSPACE, "cf_offload_static: %d tokens exceed the static scratch's maximum of %zu "
+                    "tokens per request", n_ctx, cf_offload_static_max_tokens());
+    if (pb > STATIC_STAGING_BYTES || (size_t)np_ctx * 4 + sizeof(PageJob) + 64 > c->cv.meta_bytes)
+        return fail(CF_ERR_WORKSPACE, "cf_offload_static: a page of %zu bytes exceeds the static staging slot of "
+                    "%zu bytes, or the page table exceeds the context's pinned metadata buffer", pb,
+                    STATIC_STAGING_BYTES);
+    if (np_ctx == 0) return CF_OK;
+    // the destination must be pinned: a copy into pageable memory goes through buffers the
+    // runtime allocates
+    {
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, host_kv) != hipSuccess || at.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            return fail(CF_ERR_INVALID_ARG, "cf_offload_static: host_kv must be pinned host memory");
+        }
+    }
+    char* sc = nullptr;
+    int rc = static_scratch_of_current_device(&sc);
+    if (rc) return rc;
+    char* staging = sc + STATIC_META_BYTES;
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_elems = (int64_t)(pb / es);
+    g.layer_stride = g.page_elems * cache->n_pages;
+    const size_t cap_pages = STATIC_STAGING_BYTES / pb;
+    // pinned mirror: page table at 0, the job record of the current piece behind it
+    const size_t job_host = ((size_t)np_ctx * 4 + 15) / 16 * 16;
+    std::memcpy(c->meta_host, pt, (size_t)np_ctx * 4);
+    auto drain = [&](int code) { (void)hipStreamSynchronize(c->cs); (void)hipGetLastError(); return code; };
+#define CF_HIP_D(call)                                                                        \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return drain(cf::fail(CF_ERR_HIP, "%s:%d %s -> %s", __FILE__, __LINE__, #call,    \
+                                  hipGetErrorString(e_)));                                    \
+    } while (0)
+    CF_HIP_D(hipMemcpyAsync(sc, c->meta_host, (size_t)np_ctx * 4, hipMemcpyHostToDevice, c->cs));
+    for (int l = 0; l < m.n_layers; ++l) {
+        for (int j = 0; j < np_ctx; j += (int)cap_pages) {
+            const int take = (int)std::min<size_t>(cap_pages, (size_t)(np_ctx - j));
+            PageJob jb{0, l, 0, j, take, 0, n_ctx, 0, 0};
+            std::memcpy(c->meta_host + job_host, &jb, sizeof(jb));
+            CF_HIP_D(hipMemcpyAsync(sc + job_off, c->meta_host + job_host, sizeof(jb), hipMemcpyHostToDevice, c->cs));
+            launch_page_move(c->cs, m.dtype, staging, cache->pool, (const PageJob*)(sc + job_off), 1,
+                             take * PAGE_MOVE_SPLIT, (const int32_t*)sc, g, false);
+            CF_HIP_D(hipGetLastError());
+            CF_HIP_D(hipMemcpyAsync((char*)host_kv + ((size_t)l * np_ctx + j) * pb, staging, (size_t)take * pb,
+                                    hipMemcpyDeviceToHost, c->cs));
+            // the pinned job record and the staging slot are reused by the next piece
+            CF_HIP_D(hipStreamSynchronize(c->cs));
+        }
+    }
+#undef CF_HIP_D
+    return CF_OK;
+}
 
 extern "C" int cf_measure_h2d(cf_ctx* c, const void* host_buf, void* dev_buf, size_t bytes,
                               int32_t reps, double* gb_per_s) {
