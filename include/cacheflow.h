@@ -162,6 +162,99 @@ int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t meas_comp, 
 int cf_prefill_cost(const cf_cost_model* cost, int32_t n_layers, int32_t B, const int32_t* n_ctx,
                     const int32_t* n_new, int64_t* out_ps);
 
+struct cf_model_desc;
+
+/* ------------------------------------------------------- planning policy
+ * cf_restore_plan is Algorithm 1 and nothing else.  What a serving loop needs
+ * around it -- the new turn's prefill on the compute clock, the K/V-only
+ * price of a request's last recomputed layer, the slow-down the two engines
+ * cause each other (Sec. 3.3: contention on shared resources), and the check
+ * that the hybrid actually beats the two extremes of Sec. 4.1 (recompute
+ * everything / load everything) -- is cf_plan_batch; cf_plan_feedback closes
+ * the loop after the batch has run.  Pure host integer code.                */
+
+/* Contention between the engines: while both run, every compute cost counts
+ * comp_permille / 1000 of its isolated value and every load cost io_permille
+ * / 1000 (1000 = no interference; rounded to nearest per coefficient).      */
+typedef struct cf_overlap_model {
+    int32_t comp_permille, io_permille;
+} cf_overlap_model;
+
+typedef struct cf_batch_plan_opts {
+    int32_t chunk_tokens;      /* C (Sec. 3.1), > 0                                  */
+    int32_t l_delta;           /* token-wise iff n_ctx >= l_delta (Alg. 1)           */
+    int32_t force_mode;        /* -1 use l_delta; else a cf_mode for all             */
+    int32_t io_key;            /* cf_io_key                                          */
+    int32_t pipelined_join;    /* nonzero: the new-turn rows ride along with the
+                                  recompute pass (cf_ctx_set_pipelined_join), so their
+                                  cost starts the compute clock and only one layer of
+                                  it is left when the last load lands; zero: the new
+                                  turn runs after both engines are done               */
+    int32_t stage_layers;      /* 0: the whole model; else the number of layers of the
+                                  pipeline stage that is planned (cf_ctx_set_stage)   */
+} cf_batch_plan_opts;
+
+enum cf_plan_kind { CF_PLAN_HYBRID = 0, CF_PLAN_ALL_LOAD = 1, CF_PLAN_ALL_RECOMPUTE = 2 };
+
+typedef struct cf_batch_plan {
+    int32_t kind;              /* cf_plan_kind of the splits returned                 */
+    int32_t kv_only_permille;  /* K/V projection's share of a layer's linear FLOPs    */
+    int32_t pipelined_join;    /* copied from the options (cf_plan_feedback reads it)  */
+    int32_t reserved;
+    int64_t prefill_ps;        /* isolated cost of the new-turn prefill               */
+    int64_t t_comp, t_io;      /* predicted busy time of each engine under the plan
+                                  returned (contention applied iff kind == hybrid;
+                                  t_comp includes the prefill with the pipelined join) */
+    int64_t ttft;              /* predicted time to the first token of the plan       */
+    int64_t ttft_hybrid, ttft_all_load, ttft_all_recompute;   /* the three candidates */
+} cf_batch_plan;
+
+/* Plan a batch for cf_restore_batch.  n_new: host int32[B] or NULL (no new
+ * turn).  Steps, all in integers:
+ *  1. kv_only_permille = round(1000 * 2d(Hq+2Hkv)hd / linear FLOPs of a layer);
+ *  2. prefill = sum_i cost of n_new[i] tokens from position n_ctx[i] through
+ *     all layers (the recompute formula);
+ *  3. hybrid candidate: Algorithm 1 under the cost model with the compute
+ *     coefficients (f_c, alpha, beta, s_c, and the prefill) scaled by
+ *     comp_permille and the load coefficients (f_io, gamma, s_io) by
+ *     io_permille; with the pipelined join its compute clock starts at the
+ *     scaled s_c + prefill;
+ *  4. the extremes under the unscaled model: all-load (every unit loaded) and
+ *     all-recompute (every unit recomputed);
+ *  5. times of a candidate with start-up s, new-turn cost p, compute clock c
+ *     at the end of its claims (0: none) and channel time t_io, nt = s + p
+ *     (0 if p = 0) being the new turn as a pass of its own:
+ *       pipelined join : t_comp = c (claims on top of s + p) or nt;
+ *                        ttft = max(t_comp, t_io + p / L) -- one layer of the
+ *                        new turn is left when the last load lands;
+ *       sequential join: t_comp = c; ttft = max(c, t_io) + nt;
+ *  6. the candidate with the smallest ttft is returned (ties: hybrid, then
+ *     all-load); a hybrid that recomputes nothing or loads nothing is one of
+ *     the extremes and is reported as such.
+ * out_splits: host cf_split[B]; info may be NULL.                           */
+int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* overlap,
+                  const struct cf_model_desc* desc, const cf_batch_plan_opts* opts, int32_t B,
+                  const int32_t* n_ctx, const int32_t* n_new, cf_split* out_splits,
+                  cf_batch_plan* info);
+
+/* Closed loop after the batch has run (Sec. 3.3: scheduling follows evolving
+ * resource availability).  meas_*_ps are cf_timing.compute_ms / copy_ms /
+ * total_ms / compute_wait_ms of the call in picoseconds; the time the compute
+ * stream waited for loads is taken off its measurement (it would otherwise
+ * read as slow compute, move work to the channel and make the wait longer).  The compute measurement is
+ * meas_compute_ps, except under the pipelined join when the call ended more
+ * than 2 % after the copy stream did (the compute stream was the last to
+ * finish, new turn included): then it is meas_total_ps.  A hybrid ran both engines side by side, so its ratios
+ * measured / predicted correct the overlap model (each ratio clamped to
+ * [1/4, 4] per call, the factors to [500, 8000]); an extreme ran one engine
+ * alone, so its ratio corrects that engine's coefficients of the cost model
+ * (as cf_cost_feedback does), and the overlap factors move an eighth of the
+ * way back to 1000: an extreme teaches nothing about contention, and one bad
+ * sample must not rule the hybrid out for good.                             */
+int cf_plan_feedback(cf_cost_model* cost, cf_overlap_model* overlap, const cf_batch_plan* info,
+                     int64_t meas_compute_ps, int64_t meas_copy_ps, int64_t meas_total_ps,
+                     int64_t meas_wait_ps);
+
 /* L_delta = min{N : T_token(N) <= T_layer(N)} (Sec. 3.1, adaptive strategy)
  * searched on multiples of chunk_tokens up to n_max; n_max + C if none.     */
 int cf_derive_l_delta(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t n_max,
@@ -348,6 +441,10 @@ typedef struct cf_timing {
     float suffix_ms;      /* total_ms - restore_ms: what the new-turn prefill and
                              the logits add after restoration                    */
     float total_ms;       /* call start -> logits ready (batch TTFT)             */
+    float compute_wait_ms;/* of that, time the compute stream stood still waiting
+                             for loaded KV (pipelined join: the new-turn attention
+                             of a layer waits for that layer's loads); a compute
+                             stream that ends late because it WAITED is not slow  */
     double recompute_flops; /* algorithmic: linear layers + causal pairs needed  */
     double suffix_flops;
     int64_t loaded_bytes; /* KV bytes that crossed the host link                 */
@@ -479,6 +576,16 @@ int cf_measure_h2d(cf_ctx* ctx, const void* host_buf, void* dev_buf, size_t byte
 int cf_calibrate(cf_ctx* ctx, cf_cache* cache, void* host_buf, size_t host_bytes,
                  cf_cost_model* out);
 
+/* First estimate of the overlap model (Sec. 3.3, contention): one batch in
+ * which one scratch request is recomputed in full while another is loaded in
+ * full, both of min(8192, ctx limits) tokens, timed against what `cost` (from
+ * cf_calibrate on the same context) predicts for each alone.  The load is
+ * short beside the recompute, so the compute factor is a rough figure;
+ * cf_plan_feedback refines both from real batches.  Needs free pages for twice
+ * that many tokens; host_buf as for cf_calibrate.                            */
+int cf_calibrate_overlap(cf_ctx* ctx, cf_cache* cache, void* host_buf, size_t host_bytes,
+                         const cf_cost_model* cost, cf_overlap_model* out);
+
 /* Per-kernel timing inside cf_restore_batch, from HIP event pairs recorded
  * around each selected launch on the stream it is launched on.             */
 enum cf_kernel {
@@ -601,7 +708,10 @@ int cf_ctx_inject_failure(cf_ctx* ctx, int32_t nth_check);
  * impl 0 = what cf_restore_batch would pick, 1 = plain FMA kernel, 2 = MFMA
  * kernel with its own tile choice, 3 / 4 / 5 = MFMA kernel forced to 256x256 /
  * 128x128 / 64x64 block tiles (epi 3 has no 64x64 tile and takes 128x128;
- * CF_ERR_UNSUPPORTED if MFMA does not take the shape).  Runs `reps`
+ * CF_ERR_UNSUPPORTED if MFMA does not take the shape), 6 = 256x256 tiles
+ * whose last partial round of tiles is covered by 128x128 tiles in the same
+ * launch wherever the tile count allows it (what impl 0 picks for large
+ * problems; the plain 256x256 launch otherwise).  Runs `reps`
  * times on the compute stream, blocks, and returns the mean time per run
  * from HIP events in *avg_ms (may be NULL).                                 */
 int cf_op_gemm(cf_ctx* ctx, const void* A, const void* W, const void* W2, float* Cf, void* Dt,

@@ -288,6 +288,116 @@ def cost_feedback(cm, pred_comp, meas_comp, pred_io, meas_io):
 
 
 # --------------------------------------------------------------------------
+# Planning policy around Algorithm 1 (Sec. 3.3 names contention on shared
+# resources and adaptation to evolving availability; Sec. 4.1 names the two
+# extremes a hybrid has to beat: recompute everything, load everything).  The
+# paper gives no formulas for these; the reading taken: while both engines run,
+# every compute cost counts comp_permille/1000 and every load cost
+# io_permille/1000 of its isolated value; the new turn's prefill is priced with
+# the recompute formula and, under a per-layer pipelined join, rides on the
+# compute clock with one layer of it left when the last load lands; the plan
+# returned is the candidate (hybrid / all-load / all-recompute) with the
+# smallest predicted time to first token.
+
+PLAN_HYBRID, PLAN_ALL_LOAD, PLAN_ALL_RECOMPUTE = 0, 1, 2
+
+
+def _permille(v, p):
+    return (v * p + 500) // 1000
+
+
+def kv_share_permille(d_model, n_q_heads, n_kv_heads, head_dim, d_ffn):
+    """K/V-projection share of one layer's linear FLOPs, in permille, rounded to nearest."""
+    qkv = 2 * d_model * (n_q_heads + 2 * n_kv_heads) * head_dim
+    lin = qkv + 2 * n_q_heads * head_dim * d_model + 6 * d_model * d_ffn
+    return (1000 * qkv + lin // 2) // lin
+
+
+def plan_batch(cm, overlap, model, chunk_tokens, l_delta, force_mode, io_key, pipelined_join, n_ctx,
+               n_new=None, stage_layers=0):
+    """overlap = (comp_permille, io_permille); model = (n_layers, d_model, n_q_heads, n_kv_heads,
+    head_dim, d_ffn, elem_bytes).  Returns (splits, info dict)."""
+    n_layers, d_model, hq, hkv, hd, ffn, esz = model
+    comp_pm, io_pm = overlap
+    L = stage_layers if stage_layers > 0 else n_layers
+    opts = PlanOpts(chunk_tokens, l_delta, L, 2 * hkv * hd * esz, force_mode, io_key,
+                    kv_share_permille(d_model, hq, hkv, hd, ffn))
+    base = CostModel(cm.f_c, cm.alpha, cm.beta, cm.f_io, cm.gamma, cm.s_c, cm.s_io)
+    if stage_layers > 0:
+        base.s_c = cm.s_c * L // n_layers
+    pre = 0
+    if n_new is not None and stage_layers == 0:
+        pre = prefill_cost(base, L, n_ctx, n_new)
+
+    def times(s_c, p, comp, t_io):
+        nt = s_c + p if p > 0 else 0
+        if pipelined_join:
+            t_comp = comp if comp > 0 else nt
+            return t_comp, max(t_comp, t_io + p // L)
+        return comp, max(comp, t_io) + nt
+
+    # hybrid: Algorithm 1 under contention
+    hy = CostModel(_permille(base.f_c, comp_pm), max(1 if base.alpha > 0 else 0, _permille(base.alpha, comp_pm)),
+                   _permille(base.beta, comp_pm), _permille(base.f_io, io_pm),
+                   max(1 if base.gamma > 0 else 0, _permille(base.gamma, io_pm)), _permille(base.s_c, comp_pm),
+                   _permille(base.s_io, io_pm))
+    pre_h = _permille(pre, comp_pm)
+    run = CostModel(hy.f_c, hy.alpha, hy.beta, hy.f_io, hy.gamma, hy.s_c + (pre_h if pipelined_join else 0), hy.s_io)
+    sp_h, st_h = plan(run, opts, n_ctx)
+    recomputes = any(k > 0 and c > 0 for _, k, c in sp_h)
+    loads = any(n > 0 and (k < n or c < L) for (_, k, c), n in zip(sp_h, n_ctx))
+    th = times(hy.s_c, pre_h, st_h["t_comp"], st_h["t_io"])
+    # the extremes, each engine alone, under the isolated costs
+    modes = [request_mode(opts, n) for n in n_ctx]
+    n_units = [len(unit_costs(base, opts, n, m)[0]) for n, m in zip(n_ctx, modes)]
+    _, l_io = split_times(base, opts, n_ctx, [0] * len(n_ctx), modes)
+    r_c, _ = split_times(base, opts, n_ctx, n_units, modes)
+    tl = times(base.s_c, pre, 0, l_io)
+    tr = times(base.s_c, pre, (r_c + (pre if pipelined_join else 0)) if r_c > 0 else 0, 0)
+    sp_l = [(m, 0, L) if m == TOKEN_WISE else (m, n, 0) for m, n in zip(modes, n_ctx)]
+    sp_r = [(m, n, L) for m, n in zip(modes, n_ctx)]
+    kind = PLAN_HYBRID if (recomputes and loads) else (PLAN_ALL_LOAD if not recomputes else PLAN_ALL_RECOMPUTE)
+    best = (th, tl, tr)[kind][1]
+    if tl[1] < best:
+        kind, best = PLAN_ALL_LOAD, tl[1]
+    if tr[1] < best:
+        kind, best = PLAN_ALL_RECOMPUTE, tr[1]
+    info = dict(kind=kind, kv_only_permille=opts.kv_only_permille, pipelined_join=1 if pipelined_join else 0,
+                prefill_ps=pre, t_comp=(th, tl, tr)[kind][0], t_io=(st_h["t_io"], l_io, 0)[kind], ttft=best,
+                ttft_hybrid=th[1], ttft_all_load=tl[1], ttft_all_recompute=tr[1])
+    return (sp_h, sp_l, sp_r)[kind], info
+
+
+def plan_feedback(cm, overlap, info, meas_compute, meas_copy, meas_total, meas_wait=0):
+    """-> (cost model, overlap) after an executed batch.  A hybrid's ratios measured/predicted
+    correct the overlap factors (ratio clamped to [1/4, 4], factors to [500, 8000]); an extreme's
+    ratio corrects the coefficients of the engine that ran alone (cost_feedback) and lets the
+    overlap factors relax towards 1000."""
+    def ratio(v, num, den):
+        if num > 4 * den:
+            num, den = 4, 1
+        if 4 * num < den:
+            num, den = 1, 4
+        return (v * num + den // 2) // den
+    meas_comp = meas_total if (info["pipelined_join"] and meas_total * 100 > meas_copy * 102) else meas_compute
+    meas_comp = max(0, meas_comp - meas_wait)     # time the compute stream stood waiting for loads is not compute
+    comp_pm, io_pm = overlap
+    if info["kind"] == PLAN_HYBRID:
+        if info["t_comp"] > 0 and meas_comp > 0:
+            comp_pm = min(8000, max(500, ratio(comp_pm, meas_comp, info["t_comp"])))
+        if info["t_io"] > 0 and meas_copy > 0:
+            io_pm = min(8000, max(500, ratio(io_pm, meas_copy, info["t_io"])))
+        return cm, (comp_pm, io_pm)
+    # an extreme teaches nothing about contention: what was learned ages, an eighth of the way
+    # back to 1000 per such batch
+    relax = lambda pm: pm - (pm - 1000) // 8 if pm >= 1000 else pm + (1000 - pm) // 8
+    overlap = (relax(comp_pm), relax(io_pm))
+    if info["kind"] == PLAN_ALL_LOAD:
+        return cost_feedback(cm, 0, 0, info["t_io"], meas_copy), overlap
+    return cost_feedback(cm, info["t_comp"], meas_comp, 0, 0), overlap
+
+
+# --------------------------------------------------------------------------
 # Run-time scheduling (Sec. 3.3: the scheduler works progressively, chunk by
 # chunk, and re-ranks after every processed chunk).  The two decisions below
 # are what an executor asks whenever one of its engines runs dry; costs are

@@ -83,7 +83,7 @@ class cf_request(C.Structure):
 
 class cf_timing(C.Structure):
     _fields_ = [("restore_ms", C.c_float), ("compute_ms", C.c_float), ("copy_ms", C.c_float),
-                ("suffix_ms", C.c_float), ("total_ms", C.c_float),
+                ("suffix_ms", C.c_float), ("total_ms", C.c_float), ("compute_wait_ms", C.c_float),
                 ("recompute_flops", C.c_double), ("suffix_flops", C.c_double),
                 ("loaded_bytes", C.c_int64), ("recomputed_cells", C.c_int64),
                 ("loaded_cells", C.c_int64)]
@@ -99,6 +99,28 @@ class cf_dynamic_stats(C.Structure):
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class cf_overlap_model(C.Structure):
+    _fields_ = [("comp_permille", C.c_int32), ("io_permille", C.c_int32)]
+
+
+class cf_batch_plan_opts(C.Structure):
+    _fields_ = [("chunk_tokens", C.c_int32), ("l_delta", C.c_int32), ("force_mode", C.c_int32),
+                ("io_key", C.c_int32), ("pipelined_join", C.c_int32), ("stage_layers", C.c_int32)]
+
+
+class cf_batch_plan(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("kv_only_permille", C.c_int32), ("pipelined_join", C.c_int32),
+                ("reserved", C.c_int32), ("prefill_ps", C.c_int64), ("t_comp", C.c_int64), ("t_io", C.c_int64),
+                ("ttft", C.c_int64), ("ttft_hybrid", C.c_int64), ("ttft_all_load", C.c_int64),
+                ("ttft_all_recompute", C.c_int64)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+PLAN_HYBRID, PLAN_ALL_LOAD, PLAN_ALL_RECOMPUTE = 0, 1, 2
 
 
 class cf_dynamic_opts(C.Structure):
@@ -129,6 +151,12 @@ lib.cf_plan_eval.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c
 lib.cf_cost_feedback.argtypes = [_P(cf_cost_model), C.c_int64, C.c_int64, C.c_int64, C.c_int64]
 lib.cf_prefill_cost.argtypes = [_P(cf_cost_model), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                 _P(C.c_int64)]
+lib.cf_plan_batch.argtypes = [_P(cf_cost_model), _P(cf_overlap_model), _P(cf_model_desc), _P(cf_batch_plan_opts),
+                              C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, _P(cf_batch_plan)]
+lib.cf_plan_feedback.argtypes = [_P(cf_cost_model), _P(cf_overlap_model), _P(cf_batch_plan), C.c_int64,
+                                 C.c_int64, C.c_int64, C.c_int64]
+lib.cf_calibrate_overlap.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, _P(cf_cost_model),
+                                     _P(cf_overlap_model)]
 lib.cf_derive_l_delta.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, _P(C.c_int32)]
 lib.cf_dynamic_io_pick.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
@@ -183,6 +211,7 @@ lib.cf_op_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_v
                            _P(C.c_float)]
 
 EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", "cf_cost_feedback", "cf_prefill_cost",
+           "cf_plan_batch", "cf_plan_feedback", "cf_calibrate_overlap",
            "cf_derive_l_delta", "cf_dynamic_io_pick", "cf_dynamic_claim", "cf_restore_dynamic", "cf_cache_create", "cf_cache_destroy", "cf_cache_n_pages",
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
@@ -228,6 +257,36 @@ def restore_plan(cost, opts, n_ctx, trace_cap=0):
               n_claims=stats.n_claims)
     tr = [(trace[i].engine, trace[i].request, trace[i].unit) for i in range(stats.n_trace)]
     return out, st, tr
+
+
+def overlap_model(comp_permille=1000, io_permille=1000):
+    return cf_overlap_model(int(comp_permille), int(io_permille))
+
+
+def batch_plan_opts(chunk_tokens, l_delta, force_mode=-1, io_key=0, pipelined_join=True, stage_layers=0):
+    return cf_batch_plan_opts(int(chunk_tokens), int(l_delta), int(force_mode), int(io_key),
+                              int(bool(pipelined_join)), int(stage_layers))
+
+
+def plan_batch(cost, overlap, desc, opts, n_ctx, n_new=None):
+    """-> (splits [(mode,k,cut)], cf_batch_plan): the planning policy around Algorithm 1."""
+    n = _i32(n_ctx)
+    m = _i32(n_new) if n_new is not None else None
+    b = len(n)
+    splits = (cf_split * max(b, 1))()
+    info = cf_batch_plan()
+    _check(lib.cf_plan_batch(C.byref(cost), C.byref(overlap), C.byref(desc), C.byref(opts), b, n.ctypes.data,
+                             m.ctypes.data if m is not None else None, splits, C.byref(info)), "cf_plan_batch")
+    return [(splits[i].mode, splits[i].k_tokens, splits[i].layer_cut) for i in range(b)], info
+
+
+def plan_feedback(cost, overlap, info, timing):
+    """Closed loop after a batch (modifies cost / overlap in place).  timing: the dict returned by
+    restore_batch (milliseconds -> picoseconds is the only conversion made here)."""
+    ps = lambda ms: int(round(ms * 1e9))
+    _check(lib.cf_plan_feedback(C.byref(cost), C.byref(overlap), C.byref(info), ps(timing["compute_ms"]),
+                                ps(timing["copy_ms"]), ps(timing["total_ms"]), ps(timing["compute_wait_ms"])),
+           "cf_plan_feedback")
 
 
 def plan_eval(cost, opts, n_ctx, splits):
@@ -487,6 +546,12 @@ class Ctx:
         _check(lib.cf_calibrate(self.handle, cache.handle, host_ptr, host_bytes, C.byref(cm)),
                "cf_calibrate")
         return cm
+
+    def calibrate_overlap(self, cache, host_ptr, host_bytes, cost):
+        ov = cf_overlap_model()
+        _check(lib.cf_calibrate_overlap(self.handle, cache.handle, host_ptr, host_bytes, C.byref(cost),
+                                        C.byref(ov)), "cf_calibrate_overlap")
+        return ov
 
     def profile(self, kernel_names):
         mask = 0

@@ -129,6 +129,8 @@ struct cf_ctx {
     double throttle_gbs = 0;          // > 0: the copy stream is paced to this many GB/s
     double wall_hz = 1e8;             // rate of the device's constant wall clock
     std::vector<hipEvent_t> ev_layer; // copy stream: loaded KV of layer l is in place
+    std::vector<hipEvent_t> ev_wait;  // compute stream: before / after its wait for layer l's loads (2 per layer)
+    std::vector<char> waited;         // layers whose wait was recorded in the current call
     std::vector<hipEvent_t> dyn_events;   // run-time scheduler: loads in flight + the compute step
     int dyn_scale_c = 1000, dyn_scale_io = 1000;   // measured/predicted ratios carried from call to call
     int n_last = 0;                   // requests whose final hidden row the last call left in h_last
@@ -255,6 +257,9 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
     c->ev_layer.assign(desc->n_layers, nullptr);
     for (int l = 0; l < desc->n_layers; ++l)
         CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming));
+    c->ev_wait.assign(2 * (size_t)desc->n_layers, nullptr);
+    for (hipEvent_t& e : c->ev_wait) CF_HIP_CTX(hipEventCreate(&e));
+    c->waited.assign(desc->n_layers, 0);
     // RoPE table: angles formed in double, rounded once to float.
     {
         int half = desc->head_dim / 2;
@@ -285,6 +290,8 @@ extern "C" void cf_ctx_destroy(cf_ctx* c) {
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
     }
     for (hipEvent_t e : c->ev_layer)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_wait)
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->dyn_events)
         if (e) (void)hipEventDestroy(e);
@@ -661,8 +668,17 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                     if (part == 0) { if (!with_rec) continue; w0 = 0; w1 = rec_items; g0 = 0; g1 = rec_groups; }
                     else { if (!with_new) continue; w0 = ci.n_work_rec; w1 = ci.n_work; g0 = ci.n_grp_rec; g1 = ci.n_grp; }
                     if (w1 <= w0) continue;
-                    if (part == 1 && layer_ready && layer_ready[l])
+                    if (part == 1 && layer_ready && layer_ready[l]) {
+                        // the stall of the compute stream on the copy stream is timed (first wait
+                        // of a layer: later chunks of the layer find the event complete)
+                        const bool timed = !c->waited[l] && row_base == 0;
+                        if (timed) CF_HIP(hipEventRecord(c->ev_wait[2 * l], c->cs));
                         CF_HIP(hipStreamWaitEvent(c->cs, layer_ready[l], 0));
+                        if (timed) {
+                            CF_HIP(hipEventRecord(c->ev_wait[2 * l + 1], c->cs));
+                            c->waited[l] = 1;
+                        }
+                    }
                     if (c->prof_on(CF_K_ATTENTION)) {
                         double pairs = 0;
                         for (int i = w0; i < w1; ++i) {
@@ -918,7 +934,6 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     }
     if (!direct && c->load_path == 2)
         return fail(CF_ERR_INVALID_ARG, "cf_restore_batch: the direct load path needs pinned, device-mapped host KV");
-
     // copy plan: runs of pages per (request, layer); staged path: packed into staging slots;
     // direct path: one launch per layer
     std::vector<CopyOp> ops;
@@ -1031,6 +1046,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     // into the pinned metadata, but host KV blocks and boundary rows are read in place): every
     // failure first waits for the streams, so that the caller may free its buffers on return.
     int checks_done = 0;
+    std::fill(c->waited.begin(), c->waited.end(), 0);
     auto bail = [&](int code) {
         (void)hipStreamSynchronize(c->cs);
         (void)hipStreamSynchronize(c->ps);
@@ -1166,6 +1182,14 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     c->inject_fail_at = 0;
     c->caprows_out = nullptr;         // one shot
     c->caprows_dev = nullptr;
+    float wait_ms = 0;
+    for (int l = 0; l < (int)c->waited.size(); ++l) {
+        if (!c->waited[l]) continue;
+        float w = 0;
+        if (hipEventElapsedTime(&w, c->ev_wait[2 * l], c->ev_wait[2 * l + 1]) == hipSuccess) wait_ms += w;
+        else (void)hipGetLastError();
+        c->waited[l] = 0;
+    }
     if (timing) {
         float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
         CF_HIP(hipEventElapsedTime(&t_comp, c->ev_start, c->ev_comp));
@@ -1179,6 +1203,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         timing->restore_ms = merged ? std::max(t_comp, t_copy) : std::max(t_join, std::max(t_comp, t_copy));
         timing->suffix_ms = t_end - timing->restore_ms;
         timing->total_ms = t_end;
+        timing->compute_wait_ms = wait_ms;
         double lin = linear_flops_per_token_layer(m);
         double pair = 4.0 * m.n_q_heads * m.head_dim;
         double fr = 0, fs = 0;
@@ -2107,11 +2132,11 @@ extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W
     if ((epi == EPI_SILU_MUL && !W2) || ((epi == EPI_STORE_F32 || epi == EPI_ADD_F32) && !Cf) ||
         ((epi == EPI_STORE_T || epi == EPI_SILU_MUL) && !Dt))
         return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: missing operand for this epilogue");
-    if (impl < 0 || impl > 5) return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: impl must be 0..5");
+    if (impl < 0 || impl > 6) return fail(CF_ERR_INVALID_ARG, "cf_op_gemm: impl must be 0..6");
     bool mfma_ok = gemm_mfma_supported(c->m.dtype, M, N, K, epi);
     if (impl >= 2 && !mfma_ok) return fail(CF_ERR_UNSUPPORTED, "cf_op_gemm: MFMA kernel does not take this problem");
     bool use_mfma = impl >= 2 || (impl == 0 && mfma_ok && !c->simple_only);
-    gemm_mfma_force_tile(impl == 3 ? 256 : impl == 4 ? 128 : impl == 5 ? 64 : 0);
+    gemm_mfma_force_tile(impl == 3 ? 256 : impl == 4 ? 128 : impl == 5 ? 64 : impl == 6 ? 257 : 0);
     struct Reset { ~Reset() { gemm_mfma_force_tile(0); } } reset_on_exit;
     CF_HIP(hipEventRecord(c->ev_t0, c->cs));
     for (int i = 0; i < reps; ++i) {
@@ -2230,6 +2255,53 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
     out->gamma = std::max<int64_t>(1, (int64_t)std::llround(gamma));
     out->s_c = (int64_t)std::llround(floor_c * L);
     out->s_io = (int64_t)std::llround(start_io);
+    return CF_OK;
+}
+
+// One overlapped probe: request A (t tokens) is recomputed in full while request B (t tokens) is
+// loaded in full; each engine's time is compared with what the cost model predicts for it alone.
+extern "C" int cf_calibrate_overlap(cf_ctx* c, cf_cache* cache, void* host_buf, size_t host_bytes,
+                                    const cf_cost_model* cost, cf_overlap_model* out) {
+    if (!c || !cache || !host_buf || !cost || !out)
+        return fail(CF_ERR_INVALID_ARG, "cf_calibrate_overlap: null argument");
+    const cf_model_desc& m = c->m;
+    if (c->stage_begin != 0 || c->stage_end != m.n_layers)
+        return fail(CF_ERR_INVALID_ARG, "cf_calibrate_overlap: calibrate on the whole model");
+    const int L = m.n_layers;
+    int t = std::min(std::min(c->opts.max_tokens, c->opts.max_positions), 8192) / 512 * 512;
+    if (t < 1024) return fail(CF_ERR_WORKSPACE, "cf_calibrate_overlap: context too small (needs >= 1024 tokens)");
+    if (c->opts.max_batch < 2) return fail(CF_ERR_WORKSPACE, "cf_calibrate_overlap: needs max_batch >= 2");
+    const size_t need_host = cf_host_kv_bytes(L, m.n_kv_heads, m.head_dim, m.dtype, t);
+    if (host_bytes < need_host)
+        return fail(CF_ERR_WORKSPACE, "cf_calibrate_overlap: host scratch %zu < %zu", host_bytes, need_host);
+    std::vector<int32_t> toks(t);
+    for (int i = 0; i < t; ++i) toks[i] = (int32_t)(((int64_t)i * 7919 + 13) % m.vocab);
+    const uint64_t id_a = 0xCA11B100ull, id_b = 0xCA11B101ull;
+    int rc = cf_cache_alloc(cache, id_a, t);
+    if (rc) return rc;
+    rc = cf_cache_alloc(cache, id_b, t);
+    if (rc) { cf_cache_free(cache, id_a); return rc; }
+    cf_request rq[2] = {cf_request{id_a, toks.data(), t, 0, nullptr, nullptr, nullptr},
+                        cf_request{id_b, toks.data(), t, 0, host_buf, nullptr, nullptr}};
+    cf_split sp[2] = {cf_split{CF_TOKEN_WISE, t, L}, cf_split{CF_TOKEN_WISE, 0, L}};
+    cf_timing tm;
+    rc = cf_restore_batch(c, cache, 2, rq, sp, nullptr, &tm);                 // warm-up
+    if (rc == CF_OK) rc = cf_restore_batch(c, cache, 2, rq, sp, nullptr, &tm);
+    cf_cache_free(cache, id_a);
+    cf_cache_free(cache, id_b);
+    if (rc) return rc;
+    // predictions for each engine alone (the executor stops the top layer after its K/V write,
+    // which the planner prices separately; this probe's figure is rough either way)
+    const double pairs = (double)t * ((double)t + 1) / 2 / 1024.0;
+    const double pred_c = (double)cost->s_c + (double)L * ((double)cost->f_c + (double)cost->alpha * t + (double)cost->beta * pairs);
+    const double pred_io = (double)cost->s_io + (double)cost->f_io * L + (double)cost->gamma * ((double)tm.loaded_bytes / 1048576.0);
+    const double meas_c = (double)tm.compute_ms * 1e9, meas_io = (double)tm.copy_ms * 1e9;
+    double f_io = pred_io > 0 ? meas_io / pred_io : 1.0;
+    // the compute stream is slowed only while the load runs beside it
+    double f_c = (meas_io > 0 && pred_c > 0) ? 1.0 + (meas_c - pred_c) / meas_io : 1.0;
+    auto clampf = [](double v) { return std::min(2.0, std::max(1.0, v)); };
+    out->comp_permille = (int32_t)std::llround(1000.0 * clampf(f_c));
+    out->io_permille = (int32_t)std::llround(1000.0 * clampf(f_io));
     return CF_OK;
 }
 

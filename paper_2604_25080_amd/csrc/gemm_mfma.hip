@@ -32,6 +32,14 @@ constexpr int N_STAGES = 2;
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & (NCH - 1); }
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+// two floats -> two bf16 (round to nearest even), low half = a
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) {
     uint32_t u = __float_as_uint(v);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -40,13 +48,17 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) {
 
 // BM x BN block tile (256x256 for large problems, 128x128 when that would leave CUs idle);
 // the 4 wavefronts form a 2x2 grid of (BM/2)x(BN/2) wave tiles.
+// `bid` of `nb` workgroups walk the tiles_m x tiles_n tiles whose origin is (m_off, n_off); M, N
+// are the bounds of the whole matrix.
 template <int EPI, int BM, int BN, int NW>
-__global__ void __launch_bounds__(64 * NW)
-gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
-                 const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
-                 int N, int K, int tiles_m, int tiles_n) {
-    extern __shared__ __align__(16) char smem[];
+__device__ __forceinline__ void
+gemm_mfma_body(char* smem, const bf16* __restrict__ A, const bf16* __restrict__ W,
+               const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
+               int N, int K, int tiles_m, int tiles_n, int m_off, int n_off, int bid, int nb) {
     constexpr bool SILU = (EPI == EPI_SILU_MUL);
+    // 16-bit outputs: the MFMAs take the W fragment as their first operand, which leaves the
+    // TRANSPOSED product in the accumulators (see the epilogue)
+    constexpr bool SWAP = (EPI == EPI_SILU_MUL || EPI == EPI_STORE_T);
     constexpr int BN_OUT = SILU ? BN / 2 : BN;    // output columns per block
     constexpr int WGN = NW / 2;                   // wavefront grid: 2 x WGN
     constexpr int NT = 64 * NW;                   // threads
@@ -57,17 +69,15 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     constexpr int LA = BM * NCH / NT, LB = BN * NCH / NT;     // 16-byte loads per thread
 
     // ---- workgroup -> tile: XCD-contiguous renumbering, then 8-row groups
-    int nb = tiles_m * tiles_n;
-    int bid = blockIdx.x;
     int per = nb >> 3, rem = nb & 7, xcd = bid & 7, idx = bid >> 3;
     int pid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    constexpr int GM = 8;
+    constexpr int GM = 8;             // = GROUP_M of the launcher
     int in_group = GM * tiles_n;
     int first_m = (pid / in_group) * GM;
     int gsz = min(tiles_m - first_m, GM);
     int tile_m = first_m + (pid % in_group) % gsz;
     int tile_n = (pid % in_group) / gsz;
-    int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+    int m0 = m_off + tile_m * BM, n0 = n_off + tile_n * BN_OUT;
     constexpr bool BIG = (BM == 256 && NW == 4);
     if constexpr (BIG) {
         // Edge tiles are shifted back inside the matrix (the host guarantees M >= BM and
@@ -163,7 +173,8 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
     _Pragma("unroll") for (int i = 0; i < FM; ++i)                                            \
         _Pragma("unroll") for (int j = 0; j < FN; ++j)                                        \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                              \
-                __builtin_bit_cast(bf16x8_t, FA[i]), __builtin_bit_cast(bf16x8_t, FB[j]), acc[i][j], 0, 0, 0);
+                __builtin_bit_cast(bf16x8_t, SWAP ? FB[j] : FA[i]),                           \
+                __builtin_bit_cast(bf16x8_t, SWAP ? FA[i] : FB[j]), acc[i][j], 0, 0, 0);
 
     u32x4_t fa0[FM], fb0[FN], fa1[FM], fb1[FN];
     if constexpr (BIG) {
@@ -314,57 +325,142 @@ gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
 #undef CF_MFMA
 
 #undef CF_B_BASE
-    // ---- epilogue.  Fragment (i,j), register r: row = 32i + 8(r/4) + 4(lane/32) + r%4,
-    // column = 32j + lane%32.
-    int col_l = lane & 31;
-    int row_l = 4 * (lane >> 5);
-    if (SILU) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN / 2; ++j) {
-                int gn = n0 + wn * (WN / 2) + j * 32 + col_l;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int gm = m0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
-                    if (gm < M && gn < N) {
-                        float g = acc[i][j][r], u = acc[i][j + FN / 2][r];
-                        // silu(g) * u with the hardware exp2 and reciprocal (each within 1 ulp;
-                        // the result is rounded to bf16 right after): a full-precision divide
-                        // here costs ~30 VALU cycles per output, 2 % of the whole kernel
-                        float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
-                        float v = g * __builtin_amdgcn_rcpf(1.0f + e) * u;
-                        Dt[(int64_t)gm * N + gn].x = f32_to_bf16_bits(v);
-                    }
-                }
-            }
-    } else {
+    // ---- epilogue.
+    // float outputs: fragment (i,j), register r = row 32i + 8(r/4) + 4(lane/32) + r%4, column
+    // 32j + lane%32: one store instruction writes two rows of 32 consecutive floats (whole
+    // 128-byte lines, which is what the memory system likes best for 4-byte elements).
+    // 16-bit outputs (SWAP): the accumulators hold the transposed product, register r = output
+    // row 32i + lane%32, column 32j + 8(r/4) + 4(lane/32) + r%4, so a lane owns runs of four
+    // consecutive columns of one row and stores them as one 8-byte vector -- a quarter of the
+    // store instructions and address arithmetic of a column-per-lane layout, whose 2-byte stores
+    // would fill only half a line per instruction anyway.
+    // The big tile lies wholly inside the matrix (shifted back at the edges): no bounds tests.
+    if constexpr (!SWAP) {
+        const int col_l = lane & 31, row_l = 4 * (lane >> 5);
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
-                int gn = n0 + wn * WN + j * 32 + col_l;
+                const int gn = n0 + wn * WN + j * 32 + col_l;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int gm = m0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
-                    if (gm < M && gn < N) {
-                        int64_t o = (int64_t)gm * N + gn;
-                        float v = acc[i][j][r];
-                        if (EPI == EPI_STORE_F32) Cf[o] = v;
-                        else if (EPI == EPI_ADD_F32) Cf[o] += v;
-                        else Dt[o].x = f32_to_bf16_bits(v);
+                    const int gm = m0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
+                    if (BIG || (gm < M && gn < N)) {
+                        const int64_t o = (int64_t)gm * N + gn;
+                        if (EPI == EPI_STORE_F32) Cf[o] = acc[i][j][r];
+                        else Cf[o] += acc[i][j][r];
                     }
                 }
             }
+    } else {
+        const int row_l = lane & 31, col_l = 4 * (lane >> 5);
+        const bool vec_ok = (N & 3) == 0;             // row starts stay 8-byte aligned
+        constexpr int FN_OUT = SILU ? FN / 2 : FN;
+        constexpr int WN_OUT = SILU ? WN / 2 : WN;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int gm = m0 + wm * WM + i * 32 + row_l;
+            if (!BIG && gm >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN_OUT; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int gn = n0 + wn * WN_OUT + j * 32 + 8 * q + col_l;
+                    const int64_t o = (int64_t)gm * N + gn;
+                    float v[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        float g = acc[i][j][4 * q + t];
+                        if (SILU) {
+                            // silu(g) * u with the hardware exp2 and reciprocal (each within 1 ulp;
+                            // the result is rounded to bf16 right after)
+                            float u = acc[i][j + FN / 2][4 * q + t];
+                            float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+                            g = g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+                        }
+                        v[t] = g;
+                    }
+                    if (BIG || (vec_ok && gn + 3 < N)) {
+                        uint2 pk;
+                        pk.x = pack_bf16x2(v[0], v[1]);
+                        pk.y = pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<uint2*>(Dt + o) = pk;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (gn + t < N) Dt[o + t].x = f32_to_bf16_bits(v[t]);
+                    }
+                }
+            }
+        }
     }
 }
 
 template <int EPI, int BM, int BN, int NW>
+__global__ void __launch_bounds__(64 * NW)
+gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                 const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
+                 int N, int K, int tiles_m, int tiles_n) {
+    extern __shared__ __align__(16) char smem[];
+    gemm_mfma_body<EPI, BM, BN, NW>(smem, A, W, W2, Cf, Dt, M, N, K, tiles_m, tiles_n, 0, 0,
+                                    (int)blockIdx.x, tiles_m * tiles_n);
+}
+
+// Big tiles with a quartered tail.  With one 256x256 tile per CU at a time, a launch whose tile
+// count is not a multiple of the CU count ends with a round in which most CUs idle for a whole
+// tile time (5152 tiles on 256 CUs: 20 rounds and 32 tiles).  Here the first n_big workgroups
+// take the big tiles in the usual order EXCEPT a rectangle at its end -- the last tail_cols
+// tile columns of the last 8-row group -- and the remaining workgroups cover that rectangle
+// with 128x128 tiles, four times as many and a quarter as long (done only when they fit one
+// round themselves: measured, more of them cost more than the idle round they replace).  The K
+// order of an output element does not depend on the tile shape, so the result bits are those
+// of any other tiling.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_mfma_tail_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                      const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt,
+                      int M, int N, int K, int tiles_m, int tiles_n, int n_big, int tail_m_off,
+                      int tail_n_off, int tail_tiles_m, int tail_tiles_n) {
+    extern __shared__ __align__(16) char smem[];
+    if ((int)blockIdx.x < n_big)
+        gemm_mfma_body<EPI, 256, 256, 4>(smem, A, W, W2, Cf, Dt, M, N, K, tiles_m, tiles_n, 0, 0,
+                                         (int)blockIdx.x, n_big);
+    else
+        gemm_mfma_body<EPI, 128, 128, 4>(smem, A, W, W2, Cf, Dt, M, N, K, tail_tiles_m, tail_tiles_n,
+                                         tail_m_off, tail_n_off, (int)blockIdx.x - n_big,
+                                         tail_tiles_m * tail_tiles_n);
+}
+
+constexpr int N_CUS = 256;            // MI355X
+constexpr int GROUP_M = 8;            // tile rows per group of the tile order (see the body)
+
+template <int EPI, int BM, int BN, int NW>
 void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
-                 int M, int N, int K) {
+                 int M, int N, int K, bool tail_ok = false) {
     constexpr int BN_OUT = (EPI == EPI_SILU_MUL) ? BN / 2 : BN;
     constexpr int LDS = N_STAGES * (BM + BN) * ROW_BYTES;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN_OUT - 1) / BN_OUT;
+    if constexpr (BM == 256 && NW == 4 && EPI != EPI_ADD_F32) {
+        // tail: the last nb % N_CUS tiles, rounded up to whole columns of the last row group
+        const int nb = tiles_m * tiles_n, tail = nb % N_CUS;
+        const int gsz = tiles_m - (tiles_m - 1) / GROUP_M * GROUP_M;       // rows of the last group
+        const int cols = (tail + gsz - 1) / gsz;
+        if (tail_ok && nb > N_CUS && tail > 0 && gsz * cols <= N_CUS / 4 && cols <= tiles_n) {
+            static bool configured = false;
+            auto kern = gemm_mfma_tail_kernel<EPI>;
+            if (!configured) {
+                (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+                configured = true;
+            }
+            constexpr int SBN_OUT = (EPI == EPI_SILU_MUL) ? 64 : 128;
+            const int m_off = (tiles_m - gsz) * BM, n_off = (tiles_n - cols) * BN_OUT;
+            const int tm = (M - m_off + 127) / 128, tn = (N - n_off + SBN_OUT - 1) / SBN_OUT;
+            const int n_big = nb - gsz * cols;
+            kern<<<n_big + tm * tn, 256, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf, (bf16*)Dt,
+                                                   M, N, K, tiles_m, tiles_n, n_big, m_off, n_off, tm, tn);
+            return;
+        }
+    }
     static bool configured = false;
     auto kern = gemm_mfma_kernel<EPI, BM, BN, NW>;
     if (!configured) {
@@ -375,7 +471,7 @@ void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, fl
                                              (bf16*)Dt, M, N, K, tiles_m, tiles_n);
 }
 
-int g_force_tile = 0;   // 0 = heuristic, 256 / 128 / 64 = forced (tuning hook)
+int g_force_tile = 0;   // 0 = heuristic; 256 / 128 / 64 = forced tile, 257 = 256 with the quartered tail
 int g_small_below = 160;   // 64x64 tiles when there are fewer 128x128 tiles than this
 
 template <int EPI>
@@ -388,7 +484,7 @@ void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* 
     int64_t need = EPI == EPI_SILU_MUL ? 200 : 256;
     bool big = (g_force_tile ? g_force_tile >= 256 : tiles256 >= need) && K % (2 * BK) == 0 &&
                M >= 256 && N >= BN_OUT256 && EPI != EPI_ADD_F32;
-    if (big) { launch_tile<EPI, 256, 256, 4>(s, A, W, W2, Cf, Dt, M, N, K); return; }
+    if (big) { launch_tile<EPI, 256, 256, 4>(s, A, W, W2, Cf, Dt, M, N, K, g_force_tile == 0 || g_force_tile == 257); return; }
     if constexpr (EPI != EPI_SILU_MUL) {
         // few rows against a narrow weight (a tensor-parallel shard's QKV projection): 128x128
         // tiles would leave most CUs idle, so quarter the tile.  The K order of every output

@@ -310,6 +310,181 @@ extern "C" int cf_cost_feedback(cf_cost_model* cost, int64_t pred_comp, int64_t 
     return CF_OK;
 }
 
+// ---------------------------------------------------------------- planning policy
+// cf_plan_batch: Algorithm 1 with the terms a serving loop has to add around it, and the check
+// against the two extremes; cf_plan_feedback: the closed loop.  Integer arithmetic throughout
+// (an oracle twin reproduces every number bit for bit).
+
+namespace {
+
+int64_t scale_permille(int64_t v, int64_t permille) {          // round to nearest
+    return (int64_t)(((__int128)v * permille + 500) / 1000);
+}
+
+int64_t ratio_scale(int64_t v, int64_t num, int64_t den) {     // v * num / den, ratio clamped to [1/4, 4]
+    if (num > 4 * den) { num = 4; den = 1; }
+    if (4 * num < den) { num = 1; den = 4; }
+    return (int64_t)(((__int128)v * num + den / 2) / den);
+}
+
+}  // namespace
+
+extern "C" int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* overlap,
+                             const cf_model_desc* desc, const cf_batch_plan_opts* bo, int32_t B,
+                             const int32_t* n_ctx, const int32_t* n_new, cf_split* out,
+                             cf_batch_plan* info) {
+    if (!cost || !overlap || !desc || !bo || B < 0 || (B > 0 && (!n_ctx || !out)))
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: null argument or negative batch");
+    if (desc->n_layers <= 0 || desc->d_model <= 0 || desc->n_q_heads <= 0 || desc->n_kv_heads <= 0 ||
+        desc->head_dim <= 0 || desc->d_ffn <= 0 || (desc->dtype != CF_F32 && desc->dtype != CF_BF16))
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: model descriptor has a non-positive field or bad dtype");
+    if (overlap->comp_permille < 500 || overlap->comp_permille > 8000 || overlap->io_permille < 500 ||
+        overlap->io_permille > 8000)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: overlap factors must lie in [500, 8000] permille");
+    if (bo->stage_layers < 0 || bo->stage_layers > desc->n_layers)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: stage_layers %d not in [0, %d]", bo->stage_layers,
+                        desc->n_layers);
+    const int L = bo->stage_layers > 0 ? bo->stage_layers : desc->n_layers;
+    // 1. the K/V projection's share of a layer's linear FLOPs
+    const int64_t d = desc->d_model, hd = desc->head_dim;
+    const int64_t qkv = 2 * d * (desc->n_q_heads + 2 * (int64_t)desc->n_kv_heads) * hd;
+    const int64_t lin = qkv + 2 * (int64_t)desc->n_q_heads * hd * d + 6 * d * (int64_t)desc->d_ffn;
+    cf_plan_opts po;
+    po.chunk_tokens = bo->chunk_tokens;
+    po.l_delta = bo->l_delta;
+    po.n_layers = L;
+    po.kv_bytes_per_token_layer = (int32_t)(2 * (int64_t)desc->n_kv_heads * hd * (int64_t)cf::elem_bytes(desc->dtype));
+    po.force_mode = bo->force_mode;
+    po.io_key = bo->io_key;
+    po.kv_only_permille = (int32_t)((1000 * qkv + lin / 2) / lin);
+    int rc = check(cost, &po, B, n_ctx, "cf_plan_batch");
+    if (rc) return rc;
+    // a stage pays its share of the per-pass start-up and has no new turn of its own
+    cf_cost_model base = *cost;
+    if (bo->stage_layers > 0) base.s_c = (int64_t)(((__int128)cost->s_c * L) / desc->n_layers);
+    // 2. the new turn
+    int64_t prefill = 0;
+    if (n_new && bo->stage_layers == 0)
+        for (int i = 0; i < B; ++i) {
+            if (n_new[i] < 0) return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: n_new[%d] < 0", i);
+            if (n_new[i] > 0) prefill += layer_pass_cost(base, L, n_new[i], n_ctx[i]);
+        }
+    const bool piped = bo->pipelined_join != 0;
+    // Times of a candidate x from its start-up s_c_x, its new-turn cost pre_x, the compute
+    // clock `comp` at the end of its claims (start-up included; 0 = claimed nothing) and its
+    // channel time t_io.  The new turn as a pass of its own costs nt = s_c_x + pre_x.
+    //   pipelined join : the new turn rides on the compute clock, which Algorithm 1 was started
+    //                    at s_c_x + pre_x for; one layer of it is left when the last load lands
+    //   sequential join: the new turn is a pass after both engines are done
+    struct Times { int64_t t_comp, ttft; };
+    auto times_of = [&](int64_t s_c_x, int64_t pre_x, int64_t comp, int64_t t_io) {
+        const int64_t nt = pre_x > 0 ? s_c_x + pre_x : 0;
+        Times t;
+        if (piped) {
+            t.t_comp = comp > 0 ? comp : nt;
+            t.ttft = std::max(t.t_comp, t_io + pre_x / L);
+        } else {
+            t.t_comp = comp;
+            t.ttft = std::max(comp, t_io) + nt;
+        }
+        return t;
+    };
+    // 3. the hybrid under contention
+    cf_cost_model hy = base;
+    hy.f_c = scale_permille(base.f_c, overlap->comp_permille);
+    hy.alpha = std::max<int64_t>(base.alpha > 0 ? 1 : 0, scale_permille(base.alpha, overlap->comp_permille));
+    hy.beta = scale_permille(base.beta, overlap->comp_permille);
+    hy.s_c = scale_permille(base.s_c, overlap->comp_permille);
+    hy.f_io = scale_permille(base.f_io, overlap->io_permille);
+    hy.gamma = std::max<int64_t>(base.gamma > 0 ? 1 : 0, scale_permille(base.gamma, overlap->io_permille));
+    hy.s_io = scale_permille(base.s_io, overlap->io_permille);
+    const int64_t prefill_hy = scale_permille(prefill, overlap->comp_permille);
+    cf_cost_model hy_plan = hy;
+    if (piped) hy_plan.s_c += prefill_hy;
+    std::vector<cf_split> sp_h(std::max(B, 1));
+    cf_plan_stats st_h;
+    rc = cf_restore_plan(&hy_plan, &po, B, n_ctx, sp_h.data(), &st_h, nullptr, 0);
+    if (rc) return rc;
+    bool recomputes = false, loads = false;
+    for (int i = 0; i < B; ++i) {
+        if (sp_h[i].k_tokens > 0 && sp_h[i].layer_cut > 0) recomputes = true;
+        if (n_ctx[i] > 0 && (sp_h[i].k_tokens < n_ctx[i] || sp_h[i].layer_cut < L)) loads = true;
+    }
+    const Times th = times_of(hy.s_c, prefill_hy, st_h.t_comp, st_h.t_io);
+    // 4. the extremes, each engine alone
+    std::vector<cf_split> sp_l(std::max(B, 1)), sp_r(std::max(B, 1));
+    for (int i = 0; i < B; ++i) {
+        const int mode = mode_of(po, n_ctx[i]);
+        sp_l[i] = mode == CF_TOKEN_WISE ? cf_split{mode, 0, L} : cf_split{mode, n_ctx[i], 0};
+        sp_r[i] = cf_split{mode, n_ctx[i], L};
+    }
+    int64_t l_c = 0, l_io = 0, r_c = 0, r_io = 0;
+    rc = cf_plan_eval(&base, &po, B, n_ctx, sp_l.data(), &l_c, &l_io);
+    if (rc) return rc;
+    rc = cf_plan_eval(&base, &po, B, n_ctx, sp_r.data(), &r_c, &r_io);
+    if (rc) return rc;
+    const Times tl = times_of(base.s_c, prefill, 0, l_io);
+    const Times tr = times_of(base.s_c, prefill, r_c > 0 ? r_c + (piped ? prefill : 0) : 0, 0);
+    const int64_t ttft_h = th.ttft, ttft_l = tl.ttft, ttft_r = tr.ttft;
+    // 5. / 6. the best candidate
+    int kind = CF_PLAN_HYBRID;
+    if (!recomputes) kind = CF_PLAN_ALL_LOAD;
+    else if (!loads) kind = CF_PLAN_ALL_RECOMPUTE;
+    int64_t best = kind == CF_PLAN_HYBRID ? ttft_h : (kind == CF_PLAN_ALL_LOAD ? ttft_l : ttft_r);
+    if (ttft_l < best) { kind = CF_PLAN_ALL_LOAD; best = ttft_l; }
+    if (ttft_r < best) { kind = CF_PLAN_ALL_RECOMPUTE; best = ttft_r; }
+    const std::vector<cf_split>& chosen = kind == CF_PLAN_HYBRID ? sp_h : (kind == CF_PLAN_ALL_LOAD ? sp_l : sp_r);
+    for (int i = 0; i < B; ++i) out[i] = chosen[i];
+    if (info) {
+        info->kind = kind;
+        info->kv_only_permille = po.kv_only_permille;
+        info->pipelined_join = piped ? 1 : 0;
+        info->reserved = 0;
+        info->prefill_ps = prefill;
+        const Times& tc = kind == CF_PLAN_HYBRID ? th : (kind == CF_PLAN_ALL_LOAD ? tl : tr);
+        info->t_comp = tc.t_comp;
+        info->t_io = kind == CF_PLAN_HYBRID ? st_h.t_io : (kind == CF_PLAN_ALL_LOAD ? l_io : 0);
+        info->ttft = best;
+        info->ttft_hybrid = ttft_h;
+        info->ttft_all_load = ttft_l;
+        info->ttft_all_recompute = ttft_r;
+    }
+    return CF_OK;
+}
+
+extern "C" int cf_plan_feedback(cf_cost_model* cost, cf_overlap_model* overlap, const cf_batch_plan* info,
+                                int64_t meas_compute_ps, int64_t meas_copy_ps, int64_t meas_total_ps,
+                                int64_t meas_wait_ps) {
+    if (!cost || !overlap || !info || meas_compute_ps < 0 || meas_copy_ps < 0 || meas_total_ps < 0 || meas_wait_ps < 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_feedback: bad argument");
+    if (info->kind < CF_PLAN_HYBRID || info->kind > CF_PLAN_ALL_RECOMPUTE)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_feedback: unknown plan kind %d", info->kind);
+    // the compute stream's end: with the pipelined join, the call's end when that came well
+    // after the copy stream's
+    // after the copy stream's, less the time it stood waiting for loads
+    const int64_t meas_end = (info->pipelined_join && (__int128)meas_total_ps * 100 > (__int128)meas_copy_ps * 102)
+                                 ? meas_total_ps : meas_compute_ps;
+    const int64_t meas_comp = std::max<int64_t>(0, meas_end - meas_wait_ps);
+    if (info->kind == CF_PLAN_HYBRID) {
+        if (info->t_comp > 0 && meas_comp > 0)
+            overlap->comp_permille = (int32_t)std::min<int64_t>(
+                8000, std::max<int64_t>(500, ratio_scale(overlap->comp_permille, meas_comp, info->t_comp)));
+        if (info->t_io > 0 && meas_copy_ps > 0)
+            overlap->io_permille = (int32_t)std::min<int64_t>(
+                8000, std::max<int64_t>(500, ratio_scale(overlap->io_permille, meas_copy_ps, info->t_io)));
+        return CF_OK;
+    }
+    // An extreme ran one engine alone: its ratio corrects that engine's own coefficients, and it
+    // teaches nothing about contention -- what was learned about that ages: the factors move an
+    // eighth of the way back to 1000, so that one bad sample cannot rule the hybrid out for good.
+    auto relax = [](int32_t pm) { return pm >= 1000 ? pm - (pm - 1000) / 8 : pm + (1000 - pm) / 8; };
+    overlap->comp_permille = relax(overlap->comp_permille);
+    overlap->io_permille = relax(overlap->io_permille);
+    if (info->kind == CF_PLAN_ALL_LOAD)
+        return cf_cost_feedback(cost, 0, 0, info->t_io, meas_copy_ps);
+    return cf_cost_feedback(cost, info->t_comp, meas_comp, 0, 0);
+}
+
 // ---------------------------------------------------------------- run-time scheduling
 // The same two-pointer rule driven by actual progress instead of simulated clocks (Sec. 3.3,
 // the progressive chunk-level update): an executor asks these two functions whenever one of

@@ -45,6 +45,9 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_timing) == 64
     assert ctypes.sizeof(cf.cf_dynamic_stats) == 32
     assert ctypes.sizeof(cf.cf_dynamic_opts) == 16
+    assert ctypes.sizeof(cf.cf_overlap_model) == 8
+    assert ctypes.sizeof(cf.cf_batch_plan_opts) == 24
+    assert ctypes.sizeof(cf.cf_batch_plan) == 72
 
 
 def test_status_strings():
@@ -148,6 +151,60 @@ def test_cost_feedback_matches_oracle_and_balances_a_contended_plan():
         t_c, t_io = P.split_times(true, opts_o, n_ctx, units)          # what "really" happens
         cf.cost_feedback(model, st["t_comp"], t_c, st["t_io"], t_io)
     assert abs(t_c - t_io) < 0.1 * max(t_c, t_io)
+
+
+def test_planning_policy_matches_oracle_on_random_batches_and_hand_cases():
+    """cf_plan_batch / cf_plan_feedback against their oracle twins: splits, plan kind, every
+    predicted time and the corrected models, bit for bit, over random cost tables, contention
+    factors, model widths, join modes, new turns and stages."""
+    from workloads import SHAPES
+    rng = np.random.default_rng(47)
+    kinds = [0, 0, 0]
+    for trial in range(600):
+        d = dict(f_c=int(rng.integers(0, 50_000_000)), alpha=int(rng.integers(1, 2_000_000)),
+                 beta=int(rng.integers(0, 60_000)), f_io=int(rng.integers(0, 20_000_000)),
+                 gamma=int(rng.integers(1_000_000, 900_000_000)), s_c=int(rng.integers(0, 10 ** 10)),
+                 s_io=int(rng.integers(0, 10 ** 9)))
+        if trial % 3 == 0:          # around the point where the three candidates are close
+            d = dict(hand_cost_model("startup"))
+            d["gamma"] = int(d["gamma"] * rng.uniform(0.3, 30))
+        ocm, ccm = both_cost(d)
+        sh = SHAPES[("8b", "70b-tp8", "mini-bf16", "tiny")[trial % 4]]
+        model = (sh.n_layers, sh.d_model, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn, sh.elem_bytes)
+        desc = cf.model_desc(sh)
+        ov = (int(rng.integers(500, 3000)), int(rng.integers(500, 3000))) if trial % 5 else (1000, 1000)
+        B = int(rng.integers(1, 7))
+        n_ctx = [int(x) for x in rng.integers(0, 6000, size=B)]
+        n_new = [int(x) for x in rng.integers(0, 300, size=B)] if trial % 4 else None
+        chunk = int(rng.choice([16, 256, 512]))
+        l_delta = int(rng.choice([0, 1024, 4096]))
+        mode, key, piped = int(rng.integers(-1, 2)), int(rng.integers(0, 3)), bool(rng.integers(0, 2))
+        stage = int(rng.integers(1, sh.n_layers + 1)) if trial % 7 == 0 else 0
+        want_sp, want = P.plan_batch(ocm, ov, model, chunk, l_delta, mode, key, piped, n_ctx, n_new, stage)
+        cov = cf.overlap_model(*ov)
+        got_sp, info = cf.plan_batch(ccm, cov, desc, cf.batch_plan_opts(chunk, l_delta, mode, key, piped, stage),
+                                     n_ctx, n_new)
+        assert got_sp == want_sp, (trial, got_sp, want_sp)
+        got = info.as_dict()
+        got.pop("reserved")
+        assert got == want, (trial, got, want)
+        kinds[want["kind"]] += 1
+        meas = [int(rng.integers(0, 4 * max(want["ttft"], 1))) for _ in range(3)]
+        meas.append(int(rng.integers(0, meas[0] + 1)) if trial % 2 else 0)
+        ocm2, ov2 = P.plan_feedback(ocm, ov, want, *meas)
+        cf.lib.cf_plan_feedback(ccm, cov, info, *meas)
+        assert (cov.comp_permille, cov.io_permille) == ov2
+        assert (ccm.f_c, ccm.alpha, ccm.beta, ccm.f_io, ccm.gamma, ccm.s_c, ccm.s_io) == \
+               (ocm2.f_c, ocm2.alpha, ocm2.beta, ocm2.f_io, ocm2.gamma, ocm2.s_c, ocm2.s_io)
+    assert min(kinds) >= 20, kinds          # all three outcomes occur
+    # argument errors are codes, not crashes
+    sh = SHAPES["8b"]
+    with pytest.raises(cf.CfError):
+        cf.plan_batch(cf.cost_model(**hand_cost_model("startup")), cf.overlap_model(100, 1000), cf.model_desc(sh),
+                      cf.batch_plan_opts(512, 0), [4096])
+    with pytest.raises(cf.CfError):
+        cf.plan_batch(cf.cost_model(**hand_cost_model("startup")), cf.overlap_model(), cf.model_desc(sh),
+                      cf.batch_plan_opts(512, 0, stage_layers=33), [4096])
 
 
 def test_run_time_scheduling_calls_match_oracle_on_random_states():

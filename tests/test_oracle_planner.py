@@ -433,3 +433,127 @@ def test_sweep_batches_are_what_their_name_says():
     assert make_batch("sweep:1:512").forced_mode == -1
     # seeded: the same name gives the same tokens
     assert np.array_equal(make_batch("sweep:4:2048:1").ctx_tokens[3], b.ctx_tokens[3])
+
+
+# ------------------------------------------------------------------ feedback and policy pins
+def test_cost_feedback_hand_values():
+    """Ratios measured/predicted scale each side; clamped to [1/4, 4]; round to nearest; alpha
+    and gamma never drop below 1; a side with no prediction or no measurement is left alone."""
+    cm = P.CostModel(f_c=7, alpha=1000, beta=10, f_io=9, gamma=2000, s_c=500, s_io=100)
+    out = P.cost_feedback(cm, 1_000_000, 1_200_000, 5_000, 5_000)           # compute 20 % slower
+    assert (out.f_c, out.alpha, out.beta, out.s_c) == (8, 1200, 12, 600)     # 7 * 1.2 = 8.4 -> 8
+    assert (out.f_io, out.gamma, out.s_io) == (9, 2000, 100)
+    out = P.cost_feedback(cm, 1_000, 9_000, 1_000, 100)                      # 9x and 0.1x: clamped
+    assert (out.f_c, out.alpha, out.beta, out.s_c) == (28, 4000, 40, 2000)
+    assert (out.f_io, out.gamma, out.s_io) == (2, 500, 25)                   # 9/4 = 2.25 -> 2
+    out = P.cost_feedback(cm, 2, 3, 2, 3)                                    # 1.5x: halves round up
+    assert (out.f_c, out.alpha, out.beta, out.s_c) == (11, 1500, 15, 750)    # 10.5 -> 11
+    tiny = P.CostModel(0, 1, 0, 0, 3, 0, 0)
+    out = P.cost_feedback(tiny, 4, 1, 4, 1)                                  # a quarter of 1 and of 3
+    assert (out.alpha, out.gamma) == (1, 1)
+    out = P.cost_feedback(cm, 0, 5, 7, 0)
+    assert out == cm
+
+
+def test_prefill_cost_hand_value():
+    """16 new tokens from position 2048 through 2 layers: 16*2048 + 16*17/2 = 32904 pairs =
+    33 blocks of 1024 -> per layer 10 + 3*16 + 1000*33 = 33058."""
+    cm = P.CostModel(f_c=10, alpha=3, beta=1000, f_io=0, gamma=1)
+    assert P.prefill_cost(cm, 2, [2048], [16]) == 66116
+    assert P.prefill_cost(cm, 2, [2048, 77], [16, 0]) == 66116              # no new turn, no cost
+    assert P.prefill_cost(cm, 2, [0], [1]) == 2 * (10 + 3 + 1000)            # one pair
+
+
+# A model small enough to price by hand: 2 layers, d 16, 2 query heads / 1 KV head of 8, FFN 16,
+# 2-byte elements.  K/V-projection share: 2*16*(2+2)*8 = 1024 of 1024 + 2*2*8*16 + 6*16*16 =
+# 3072 linear FLOPs -> 333 permille.  KV bytes per token and layer: 2*1*8*2 = 32.
+HAND_MODEL = (2, 16, 2, 1, 8, 16, 2)
+# alpha 1000 ps per token and layer, nothing else on the compute side; gamma = 20 * 2^20, i.e.
+# 20 ps per byte.  One request of 64 tokens, chunks of 16: four units, each
+#   a = 1 full layer (16000) + the top layer's K/V share ceil(1000*333*16/1000) = 5328 -> 21328
+#   b = 16 tokens * 2 layers * 32 B * 20 = 20480
+HAND_COST = P.CostModel(f_c=0, alpha=1000, beta=0, f_io=0, gamma=20 << 20)
+
+
+def test_policy_kv_share_of_the_8b_layer():
+    # 2*4096*6144 of 436207616 linear FLOPs = 11.54 %
+    assert P.kv_share_permille(4096, 32, 8, 128, 14336) == 115
+    assert P.kv_share_permille(16, 2, 1, 8, 16) == 333
+
+
+def test_policy_hybrid_without_contention_and_all_load_under_heavy_contention():
+    """No new turn.  Isolated costs: I/O takes unit 3 (20480 < 21328), compute unit 0, I/O unit 2
+    (40960 < 42656), compute unit 1: k = 32, t_comp 42656, t_io 40960 -- against 81920 for
+    loading everything and 85312 for recomputing everything.  With both engines twice as slow
+    side by side the same hybrid ends at 85312 and loses to loading everything."""
+    splits, info = P.plan_batch(HAND_COST, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64])
+    assert splits == [(0, 32, 2)]
+    assert info["kind"] == P.PLAN_HYBRID and info["kv_only_permille"] == 333
+    assert (info["t_comp"], info["t_io"], info["ttft"]) == (42656, 40960, 42656)
+    assert (info["ttft_hybrid"], info["ttft_all_load"], info["ttft_all_recompute"]) == (42656, 81920, 85312)
+    # contention 1.5x: a = 31992, b = 30720 -> t_comp 63984: still ahead of 81920
+    splits, info = P.plan_batch(HAND_COST, (1500, 1500), HAND_MODEL, 16, 0, 0, 0, True, [64])
+    assert splits == [(0, 32, 2)] and info["kind"] == P.PLAN_HYBRID and info["ttft"] == 63984
+    splits, info = P.plan_batch(HAND_COST, (2000, 2000), HAND_MODEL, 16, 0, 0, 0, True, [64])
+    assert splits == [(0, 0, 2)]
+    assert info["kind"] == P.PLAN_ALL_LOAD and info["ttft_hybrid"] == 85312 and info["ttft"] == 81920
+    assert (info["t_comp"], info["t_io"]) == (0, 81920)
+    # contention on the compute side only can make recomputing everything the plan when loads are dear
+    dear = P.CostModel(0, 1000, 0, 0, 200 << 20)             # b = 204800 per unit
+    splits, info = P.plan_batch(dear, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64])
+    assert splits == [(0, 64, 2)] and info["kind"] == P.PLAN_ALL_RECOMPUTE and info["ttft"] == 85312
+
+
+def test_policy_new_turn_on_the_compute_clock():
+    """16 new tokens behind the 64: prefill = 2 layers * 16 * 1000 = 32000.  Pipelined join: the
+    compute clock starts there, so I/O takes units 3 and 2 (20480, 40960 < 53328), compute unit 0
+    (53328 < 61440), I/O unit 1 (61440 < 74656): k = 16; one layer of the new turn (16000) is
+    left when the last load lands -> 77440.  Sequential join: the plan of the test above, then
+    the new turn as a pass of its own: 42656 + 32000."""
+    splits, info = P.plan_batch(HAND_COST, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64], [16])
+    assert splits == [(0, 16, 2)] and info["kind"] == P.PLAN_HYBRID and info["prefill_ps"] == 32000
+    assert (info["t_comp"], info["t_io"], info["ttft"]) == (53328, 61440, 77440)
+    assert (info["ttft_all_load"], info["ttft_all_recompute"]) == (97920, 117312)
+    splits, info = P.plan_batch(HAND_COST, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, False, [64], [16])
+    assert splits == [(0, 32, 2)]
+    assert (info["t_comp"], info["t_io"], info["ttft"]) == (42656, 40960, 74656)
+    assert (info["ttft_all_load"], info["ttft_all_recompute"]) == (113920, 117312)
+    # a start-up of 1000 is paid once by a pipelined pass, twice when the new turn runs on its own
+    su = P.CostModel(0, 1000, 0, 0, 20 << 20, s_c=1000)
+    _, info = P.plan_batch(su, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64], [16])
+    assert info["ttft_all_recompute"] == 1000 + 85312 + 32000
+    _, info = P.plan_batch(su, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, False, [64], [16])
+    assert info["ttft_all_recompute"] == (1000 + 85312) + (1000 + 32000)
+    # a pipeline stage of one of the two layers: half the start-up, no new turn of its own
+    _, info = P.plan_batch(su, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64], [16], stage_layers=1)
+    assert info["prefill_ps"] == 0 and info["ttft_all_recompute"] == 500 + 4 * 5328
+
+
+def test_policy_feedback_hand_values():
+    info = dict(kind=P.PLAN_HYBRID, pipelined_join=1, t_comp=53328, t_io=61440)
+    # the call ended well after the copy stream: its end is the compute measurement
+    cm, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 80000)
+    assert cm == HAND_COST and ov == (1500, 1000)            # 80000 / 53328 = 1.50015
+    # ... not with the sequential join, and not when both streams ended together
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), dict(info, pipelined_join=0), 60000, 61440, 80000)
+    assert ov == (1125, 1000)                                 # 60000 / 53328 = 1.1251
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 62000)
+    assert ov == (1125, 1000)
+    # time the compute stream stood waiting for loads is taken off: (80000 - 26672) / 53328 = 1
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 80000, 26672)
+    assert ov == (1000, 1000)
+    # ratios are clamped to 4 per call and the factors to [500, 8000]
+    _, ov = P.plan_feedback(HAND_COST, (1000, 3000), info, 533280, 614400, 533280)
+    assert ov == (4000, 8000)
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 53, 61, 53)
+    assert ov == (500, 500)
+    # an extreme corrects the coefficients of the engine that ran alone
+    cm, ov = P.plan_feedback(HAND_COST, (1200, 1300), dict(kind=P.PLAN_ALL_LOAD, pipelined_join=1, t_comp=0, t_io=81920),
+                             0, 98304, 98304)
+    assert ov == (1175, 1263) and cm.gamma == (20 << 20) * 6 // 5 and cm.alpha == 1000     # 200/8, 300/8 back
+    cm, ov = P.plan_feedback(HAND_COST, (1200, 1300), dict(kind=P.PLAN_ALL_RECOMPUTE, pipelined_join=1, t_comp=85312, t_io=0),
+                             85312, 0, 127968)
+    assert cm.alpha == 1500 and cm.gamma == 20 << 20 and ov == (1175, 1263)
+    _, ov = P.plan_feedback(HAND_COST, (600, 1000), dict(kind=P.PLAN_ALL_LOAD, pipelined_join=1, t_comp=0, t_io=81920),
+                            0, 81920, 81920)
+    assert ov == (650, 1000)
