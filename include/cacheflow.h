@@ -698,6 +698,14 @@ int cf_ctx_set_kernel_set(cf_ctx* ctx, int32_t simple_only);
  * the GPU is made to fail.                                                  */
 int cf_ctx_inject_failure(cf_ctx* ctx, int32_t nth_check);
 
+/* Test hook: force the block tile of every MFMA GEMM the library launches from
+ * now on, wherever the shape allows it (0 = the library's own choice, the
+ * default; 256 / 128 / 64 = that tile; 257 = 256 with the quartered tail).
+ * Process-wide.  The tile never changes a result bit; the hook exists so that
+ * small end-to-end tests can run on the tile the full-size runs take.
+ * cf_op_gemm sets and clears it for its own launches.                       */
+int cf_debug_force_gemm_tile(int32_t tile);
+
 /* One GEMM of the recompute path, exposed for parity tests and roofline
  * measurement: acc[M,N] = A[M,K] * W[N,K]^T with A, W (and W2) device arrays
  * in the context's model dtype, float accumulation, then the epilogue

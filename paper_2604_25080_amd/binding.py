@@ -200,6 +200,7 @@ lib.cf_offload_static.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32,
 lib.cf_offload_static_max_tokens.restype = C.c_size_t
 lib.cf_offload_static_max_tokens.argtypes = []
 lib.cf_ctx_inject_failure.argtypes = [C.c_void_p, C.c_int32]
+lib.cf_debug_force_gemm_tile.argtypes = [C.c_int32]
 lib.cf_measure_h2d.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32,
                                _P(C.c_double)]
 lib.cf_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, _P(cf_cost_model)]
@@ -216,7 +217,7 @@ EXPORTS = ["cf_status_str", "cf_last_error", "cf_restore_plan", "cf_plan_eval", 
            "cf_cache_n_free", "cf_cache_page_bytes", "cf_cache_alloc", "cf_cache_free",
            "cf_cache_page_table", "cf_host_kv_bytes", "cf_workspace_bytes", "cf_ctx_create",
            "cf_ctx_destroy", "cf_ctx_set_kernel_set", "cf_ctx_set_pipelined_join", "cf_ctx_set_load_path", "cf_ctx_set_link_throttle", "cf_ctx_set_stage", "cf_ctx_capture_boundary", "cf_ctx_capture_rows", "cf_restore_batch", "cf_offload",
-           "cf_offload_static", "cf_offload_static_max_tokens", "cf_ctx_inject_failure",
+           "cf_offload_static", "cf_offload_static_max_tokens", "cf_ctx_inject_failure", "cf_debug_force_gemm_tile",
            "cf_measure_h2d", "cf_op_gemm", "cf_calibrate", "cf_ctx_profile",
            "cf_ctx_profile_read", "cf_read_final_hidden"]
 

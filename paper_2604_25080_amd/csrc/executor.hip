@@ -2124,6 +2124,13 @@ extern "C" int cf_measure_h2d(cf_ctx* c, const void* host_buf, void* dev_buf, si
     return CF_OK;
 }
 
+extern "C" int cf_debug_force_gemm_tile(int32_t tile) {
+    if (tile != 0 && tile != 64 && tile != 128 && tile != 256 && tile != 257)
+        return fail(CF_ERR_INVALID_ARG, "cf_debug_force_gemm_tile: tile must be 0, 64, 128, 256 or 257");
+    gemm_mfma_force_tile(tile);
+    return CF_OK;
+}
+
 extern "C" int cf_op_gemm(cf_ctx* c, const void* A, const void* W, const void* W2, float* Cf,
                           void* Dt, int32_t M, int32_t N, int32_t K, int32_t epi, int32_t impl,
                           int32_t reps, float* avg_ms) {

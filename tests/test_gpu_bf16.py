@@ -218,6 +218,56 @@ def test_head_dim_64_bf16_model():
         sess.close()
 
 
+@pytest.mark.parametrize("shape_name", ["mini64-gqa2-bf16", "mini128-gqa3-bf16"])
+def test_remaining_head_geometries_of_the_attention_kernel(shape_name):
+    """head_dim 64 with an even query group (two heads of a KV group per workgroup) and head_dim
+    128 with an odd one (one head per workgroup): ragged lengths, hybrid splits, and -- few new
+    tokens over contexts of 2100..2900 tokens -- split key ranges with their combine pass; all
+    against the oracle, and against the plain kernels of the same library."""
+    b, refs, sess, host = build(shape_name, 14, 3, 60, 700, 3, 70, chunk_rows=256)
+    try:
+        L = b.shape.n_layers
+        fast, *_ = restore_and_compare(b, refs, sess, host, [(n, L) for n in b.n_ctx], seed=53)
+        slow, *_ = restore_and_compare(b, refs, sess, host, [(n, L) for n in b.n_ctx], seed=53, simple_only=True)
+        for i in fast:
+            assert np.abs(fast[i][0] - slow[i][0]).max() <= 2e-2 and np.abs(fast[i][2] - slow[i][2]).max() <= 2e-2
+        restore_and_compare(b, refs, sess, host, [((n // 2), 1) for n in b.n_ctx], seed=54)
+        restore_and_compare(b, refs, sess, host, [(n // 3 // 16 * 16, L) for n in b.n_ctx], seed=55)
+    finally:
+        sess.close()
+    b, refs, sess, host = build(shape_name, 15, 2, 2100, 2900, 3, 9, chunk_rows=1024, n_pages=1000)
+    try:
+        L = b.shape.n_layers
+        restore_and_compare(b, refs, sess, host, [(0, L) for n in b.n_ctx], seed=63)
+        restore_and_compare(b, refs, sess, host, [(n // 2 // 16 * 16, L) for n in b.n_ctx], seed=64)
+    finally:
+        sess.close()
+
+
+def test_small_shape_end_to_end_on_the_big_gemm_tile():
+    """The 256x256 GEMM tile (and its quartered tail) is what the full-size runs use; the small
+    shapes take the 128 / 64 tiles by themselves.  Forced here (the GEMMs whose shapes allow the
+    big tile: M >= 256, N >= 256, K a multiple of 128), one hybrid restore end to end against
+    the oracle -- and bit for bit against the tiles the heuristic picks."""
+    import paper_2604_25080_amd as cf
+    b, refs, sess, host = build("mini-bf16", 16, 3, 300, 700, 40, 150, chunk_rows=2048)
+    try:
+        L = b.shape.n_layers
+        splits = [(n // 2 // 16 * 16, L) for n in b.n_ctx]
+        ref_out, *_ = restore_and_compare(b, refs, sess, host, splits, seed=71)
+        for force in (256, 257):
+            cf.lib.cf_debug_force_gemm_tile(force)
+            try:
+                out, *_ = restore_and_compare(b, refs, sess, host, splits, seed=71)
+            finally:
+                cf.lib.cf_debug_force_gemm_tile(0)
+            for i in out:
+                assert np.array_equal(out[i][0], ref_out[i][0]) and np.array_equal(out[i][1], ref_out[i][1])
+                assert np.array_equal(out[i][2], ref_out[i][2])
+    finally:
+        sess.close()
+
+
 def test_stage_restore_from_boundary_activations(mini):
     """One pipeline stage's share (Sec. 3.2): the context is restricted to layers [b, e), recompute
     starts from the oracle's hidden states entering layer b, loads cover only the stage's layers

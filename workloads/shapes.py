@@ -53,6 +53,9 @@ SHAPES = {
     # small bf16 shapes for parity tests that span several tiles and ragged tails
     "mini-bf16": ModelShape("mini-bf16", 3, 512, 8, 2, 128, 1408, 2000, 500000.0, 1e-5, "bf16"),
     "mini64-bf16": ModelShape("mini64-bf16", 2, 256, 4, 4, 64, 688, 1000, 10000.0, 1e-5, "bf16"),
+    # head_dim 64 with two query heads per KV head, and head_dim 128 with three (an odd group)
+    "mini64-gqa2-bf16": ModelShape("mini64-gqa2-bf16", 2, 256, 4, 2, 64, 688, 1000, 10000.0, 1e-5, "bf16"),
+    "mini128-gqa3-bf16": ModelShape("mini128-gqa3-bf16", 2, 384, 3, 1, 128, 1024, 1000, 500000.0, 1e-5, "bf16"),
 }
 
 
