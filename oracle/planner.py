@@ -543,13 +543,15 @@ def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scal
 
 
 def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max_depth=4,
-                     step_cap=0, order=ORDER_CHEAPEST):
+                     step_cap=0, order=ORDER_CHEAPEST, trace=None):
     """Event-driven model of an executor that schedules at run time with `io_pick` and
     `dynamic_claim`: the I/O channel holds one claimed unit plus more while less than
     `lookahead` of predicted work is queued (at most `max_depth`); the compute engine asks
     for a step whenever it is idle and the state has changed.  Durations come from
     `true_cm` (default: the model itself), predictions from `cm` times the ratios
     measured/predicted so far.  A step lasts the sum of its units' true costs.
+    If `trace` is a list, every claim is appended to it as (time, engine, request, unit) with
+    engine 0 = compute, 1 = I/O (a layer-wise group's claim names its first member).
     Returns (splits, makespan, n_steps)."""
     true_cm = true_cm or cm
     b_req = len(n_ctx)
@@ -594,6 +596,8 @@ def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max
             d_pred = sum(pred[j][1][u] for j in members)
             for j in members:
                 p_io[j] -= 1
+            if trace is not None:
+                trace.append((now, 1, members[0], u))
             if not io_queue:
                 io_head_done = now + d_true
             if io_busy_from is None:
@@ -608,6 +612,8 @@ def simulate_dynamic(cm, opts, n_ctx, true_cm=None, lookahead=2_000_000_000, max
             dur = 0
             for i in range(b_req):
                 if take[i]:
+                    if trace is not None and (modes[i] == TOKEN_WISE or i == group[0]):
+                        trace.append((now, 0, i, p_comp[i]))
                     dur += true[i][0][p_comp[i]]
                     p_comp[i] += 1
                     if take[i] == 2:

@@ -557,3 +557,40 @@ def test_policy_feedback_hand_values():
     _, ov = P.plan_feedback(HAND_COST, (600, 1000), dict(kind=P.PLAN_ALL_LOAD, pipelined_join=1, t_comp=0, t_io=81920),
                             0, 81920, 81920)
     assert ov == (650, 1000)
+
+
+def test_simulated_run_time_scheduling_hand_traces():
+    """Two runs of the event-driven simulator traced by hand (true costs = the model's, so every
+    ratio measured/predicted stays 1000).
+    (1) One token-wise request of four 16-token chunks, recompute 32 per chunk, load 24 (units
+    of 10^6 ps).  t=0: the channel takes chunk 3 (0+24 <= 128 of recompute left) and chunk 2
+    (24+24 <= 96), declines chunk 1 (48+24 > 64); compute takes chunk 0 (32 <= 48 backlog + 48
+    unclaimed loads).  t=24: chunk 3 has landed; the channel declines chunk 1 again (24+24 > 8
+    left of the step + 32).  t=32: compute takes chunk 1 (32 <= 24 + 24).  t=48: chunk 2 has
+    landed.  t=64: done -- the split and the makespan of the static plan.
+    (2) Two layer-wise requests (32 and 16 tokens, 3 layers), loaded and recomputed as a group:
+    per layer recompute 32+16 = 48, load 24+12 = 36.  t=0: the channel takes layer 2 (36 <= 144)
+    and layer 1 (36+36 <= 96), declines layer 0 (72+36 > 48); compute takes layer 0 of the group
+    (48 <= 72 + 36) as its last layer (there is no layer left to go on to): both requests are
+    closed with cut 1.  Loads land at 36 and 72: makespan 72."""
+    M = 1_000_000
+    cm = P.CostModel(f_c=0, alpha=M, beta=0, f_io=0, gamma=1_536 * M)        # 24 M per 16 tokens x 2 x 512 B
+    opts = P.PlanOpts(chunk_tokens=16, l_delta=0, n_layers=2, kv_bytes_per_token_layer=512, force_mode=P.TOKEN_WISE)
+    assert P.unit_costs(cm, opts, 64, P.TOKEN_WISE)[:2] == ([32 * M] * 4, [24 * M] * 4)
+    tr = []
+    splits, makespan, n_steps = P.simulate_dynamic(cm, opts, [64], trace=tr)
+    assert tr == [(0, 1, 0, 3), (0, 1, 0, 2), (0, 0, 0, 0), (32 * M, 0, 0, 1)]
+    assert (splits, makespan, n_steps) == ([(P.TOKEN_WISE, 32, 2)], 64 * M, 2)
+    assert P.plan(cm, opts, [64])[0] == splits and P.plan(cm, opts, [64])[1]["makespan"] == makespan
+    opts = P.PlanOpts(chunk_tokens=16, l_delta=0, n_layers=3, kv_bytes_per_token_layer=512, force_mode=P.LAYER_WISE)
+    assert P.unit_costs(cm, opts, 32, P.LAYER_WISE)[:2] == ([32 * M] * 3, [24 * M] * 3)
+    assert P.unit_costs(cm, opts, 16, P.LAYER_WISE)[:2] == ([16 * M] * 3, [12 * M] * 3)
+    tr = []
+    splits, makespan, n_steps = P.simulate_dynamic(cm, opts, [32, 16], trace=tr)
+    assert tr == [(0, 1, 0, 2), (0, 1, 0, 1), (0, 0, 0, 0)]
+    assert (splits, makespan, n_steps) == ([(P.LAYER_WISE, 32, 1), (P.LAYER_WISE, 16, 1)], 72 * M, 1)
+    # a slower channel (48 per chunk) still takes chunks 3 and 2 at t=0 (48+48 <= 96, the test is
+    # "no later than"), compute chunks 0 and 1 (32 <= 96 + 96, then 32 <= 96 + 48); the loads
+    # land at 48 and 96: the channel, not compute, ends the restoration
+    assert tr == [(0, 1, 0, 3), (0, 1, 0, 2), (0, 0, 0, 0), (32 * M, 0, 0, 1)]
+    assert (splits, makespan, n_steps) == ([(P.TOKEN_WISE, 32, 2)], 96 * M, 2)
