@@ -592,5 +592,9 @@ def test_simulated_run_time_scheduling_hand_traces():
     # a slower channel (48 per chunk) still takes chunks 3 and 2 at t=0 (48+48 <= 96, the test is
     # "no later than"), compute chunks 0 and 1 (32 <= 96 + 96, then 32 <= 96 + 48); the loads
     # land at 48 and 96: the channel, not compute, ends the restoration
+    slow = P.CostModel(0, M, 0, 0, 3_072 * M)
+    opts = P.PlanOpts(16, 0, 2, 512, P.TOKEN_WISE)
+    tr = []
+    splits, makespan, n_steps = P.simulate_dynamic(slow, opts, [64], trace=tr)
     assert tr == [(0, 1, 0, 3), (0, 1, 0, 2), (0, 0, 0, 0), (32 * M, 0, 0, 1)]
     assert (splits, makespan, n_steps) == ([(P.TOKEN_WISE, 32, 2)], 96 * M, 2)
