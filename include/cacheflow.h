@@ -622,8 +622,12 @@ int cf_read_final_hidden(cf_ctx* ctx, int32_t B, float* out_host);
 int cf_ctx_set_pipelined_join(cf_ctx* ctx, int32_t on);
 
 /* Load path (the I/O side of Sec. 3.1's two pointers).  path 0 (default):
- * automatic -- the direct path whenever every request's host block is pinned,
- * device-mapped host memory, else the staged path.  path 2: direct -- a load
+ * automatic -- for pinned, device-mapped host blocks the direct path, in which
+ * runs of whole pages whose pool slots are consecutive and that are at least
+ * 4 MiB long go as single DMA transfers straight into the pool (no kernel, no
+ * compute unit taken from the GEMMs running beside the loads) and everything
+ * else -- scattered or short runs, partly loaded pages -- through the load
+ * kernel; the staged path for other host memory.  path 2: direct -- a load
  * kernel of n_workgroups resident workgroups (0 keeps the current value,
  * default 8, at most 1024) reads the host block over the host link and writes
  * the KV pages itself, one launch per layer; cf_restore_batch then fails with

@@ -744,10 +744,17 @@ struct CopyOp {
     size_t bytes;
 };
 
-struct LayerLoad {            // direct path: one load-kernel launch
+struct LayerLoad {            // direct path: the loads of one layer -- DMA transfers, then one load-kernel launch
     int layer, job_first, n_jobs, n_vblocks;
+    size_t bytes;             // all of the layer's loaded bytes (both kinds)
+    int dma_first, n_dma;
+};
+struct DmaOp {                // a run of whole pages that is contiguous in the pool: one transfer, no kernel
+    char* dst;
+    const char* src;
     size_t bytes;
 };
+constexpr size_t DMA_MIN_BYTES = (size_t)4 << 20;   // shorter transfers do not reach link speed
 struct SlotPlan {
     int slot;
     int op_first, n_ops;
@@ -940,6 +947,7 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     std::vector<PageJob> jobs;
     std::vector<SlotPlan> slots;
     std::vector<LayerLoad> layer_loads;
+    std::vector<DmaOp> dma_ops;
     int64_t loaded_bytes = 0, loaded_cells = 0, rec_cells = 0;
     std::vector<int> layer_last_slot(L, -1);   // slot (in issue order) holding a layer's last job
     {
@@ -973,7 +981,8 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
             for (int i : by_len)
                 for (int l = L - 1; l >= 0; --l) runs.emplace_back(i, l);
         }
-        for (auto [i, l] : runs) {
+        for (const auto& run : runs) {
+            const int i = run.first, l = run.second;
             const cf_request& r = reqs[i];
             const cf_split& s = splits[i];
             int np_ctx = (int)ceil_div(r.n_ctx, CF_PAGE_TOKENS);
@@ -987,21 +996,52 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                 if ((int64_t)(j1 - j) * (int64_t)(pb / 16) >= ((int64_t)1 << 31))
                     return fail(CF_ERR_WORKSPACE, "cf_restore_batch: request %d loads more than 32 GiB per layer", i);
                 if (layer_loads.empty() || layer_loads.back().layer != l)
-                    layer_loads.push_back(LayerLoad{l, (int)jobs.size(), 0, 0, 0});
+                    layer_loads.push_back(LayerLoad{l, (int)jobs.size(), 0, 0, 0, (int)dma_ops.size(), 0});
                 LayerLoad& ll = layer_loads.back();
-                PageJob jb;
-                jb.staging_off = (int64_t)(uintptr_t)(host_dev[i] + ((size_t)(Lb + l) * np_ctx + j) * pb);
-                jb.layer = Lb + l;
-                jb.pt_off = pt_off[i];
-                jb.page_first = j;
-                jb.n_pages = j1 - j;
-                jb.tok_first = lo;
-                jb.tok_end = hi;
-                jb.block_first = ll.n_vblocks;
-                jb.pad = 0;
-                jobs.push_back(jb);
-                ++ll.n_jobs;
-                ll.n_vblocks += (int)ceil_div((int64_t)(j1 - j) * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
+                const char* host_run = host_dev[i] + (size_t)(Lb + l) * np_ctx * pb;     // page 0 of this layer
+                auto kernel_job = [&](int ja, int jb) {      // pages [ja, jb) through the load kernel
+                    if (jb <= ja) return;
+                    PageJob job;
+                    job.staging_off = (int64_t)(uintptr_t)(host_run + (size_t)ja * pb);
+                    job.layer = Lb + l;
+                    job.pt_off = pt_off[i];
+                    job.page_first = ja;
+                    job.n_pages = jb - ja;
+                    job.tok_first = std::max(lo, ja * CF_PAGE_TOKENS);
+                    job.tok_end = std::min(hi, jb * CF_PAGE_TOKENS);
+                    job.block_first = ll.n_vblocks;
+                    job.pad = 0;
+                    jobs.push_back(job);
+                    ++ll.n_jobs;
+                    ll.n_vblocks += (int)ceil_div((int64_t)(jb - ja) * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
+                };
+                // Whole pages whose pool slots are consecutive (the usual case: the allocator hands
+                // out the lowest free ids in order) go as ONE DMA transfer straight into the pool --
+                // no kernel, no compute unit taken from the GEMMs running beside the loads -- when
+                // the transfer is long enough to reach link speed.  A first page that is only
+                // partly loaded (unaligned split) and a last page whose tail slots belong to the new
+                // turn go through the load kernel, which writes slot by slot; so do short or
+                // scattered runs.
+                const bool use_dma = c->load_path == 0;
+                int ja = j, jb = j1, kfirst = j;              // [kfirst, .) accumulates kernel pages
+                if (use_dma) {
+                    if (lo % CF_PAGE_TOKENS != 0) ++ja;
+                    if (hi % CF_PAGE_TOKENS != 0) --jb;
+                    for (int p0 = ja; p0 < jb;) {
+                        int p1 = p0 + 1;
+                        while (p1 < jb && pt[i][p1] == pt[i][p1 - 1] + 1) ++p1;
+                        const size_t seg = (size_t)(p1 - p0) * pb;
+                        if (seg >= DMA_MIN_BYTES) {
+                            kernel_job(kfirst, p0);
+                            kfirst = p1;
+                            char* dst = (char*)cache->pool + ((size_t)(Lb + l) * cache->n_pages + pt[i][p0]) * pb;
+                            dma_ops.push_back(DmaOp{dst, (const char*)reqs[i].host_kv + ((size_t)(Lb + l) * np_ctx + p0) * pb, seg});
+                            ++ll.n_dma;
+                        }
+                        p0 = p1;
+                    }
+                }
+                kernel_job(kfirst, j1);
                 ll.bytes += (size_t)(j1 - j) * pb;
                 loaded_bytes += (int64_t)(j1 - j) * pb;
                 continue;
@@ -1094,15 +1134,34 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     };
     if (c->throttle_gbs > 0) launch_pace_mark(c->ps, c->pace_dev());
     std::vector<char> layer_loaded(L, 0);
-    for (const LayerLoad& ll : layer_loads) {
+    std::vector<int> load_of_layer(L, -1);
+    for (size_t k = 0; k < layer_loads.size(); ++k) {
+        load_of_layer[layer_loads[k].layer] = (int)k;
+        layer_loaded[layer_loads[k].layer] = 1;
+    }
+    size_t loads_enqueued = 0;
+    auto enqueue_load = [&](const LayerLoad& ll) -> int {
         c->prof_begin(CF_K_H2D_COPY, (double)ll.bytes, c->ps);
+        for (int k = 0; k < ll.n_dma; ++k) {
+            const DmaOp& op = dma_ops[ll.dma_first + k];
+            if (hipMemcpyAsync(op.dst, op.src, op.bytes, hipMemcpyHostToDevice, c->ps) != hipSuccess) return -1;
+        }
         launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ll.job_first,
                          ll.n_jobs, ll.n_vblocks, c->load_wgs, (const int32_t*)md, g);
         pace((double)ll.bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
-        layer_loaded[ll.layer] = 1;
-        if (merged) CF_HIP_Q(hipEventRecord(c->ev_layer[ll.layer], c->ps));
-    }
+        if (merged && hipEventRecord(c->ev_layer[ll.layer], c->ps) != hipSuccess) return -1;
+        return 0;
+    };
+    // Sequential join: everything is enqueued here, from the top layer down.  Pipelined join: the
+    // loads of layer l are enqueued just before the compute stream's layer l (see below), so that
+    // the host, which issues a transfer per (request, layer), never holds the compute stream back;
+    // the copy stream still runs far ahead of it (enqueuing a layer takes microseconds, executing
+    // it milliseconds).
+    if (!merged)
+        for (; loads_enqueued < layer_loads.size(); ++loads_enqueued)
+            if (enqueue_load(layer_loads[loads_enqueued]) < 0)
+                return bail(fail(CF_ERR_HIP, "cf_restore_batch: enqueuing a load failed"));
     // copy stream, staged path: fill a staging slot by DMA, then the scatter stream places its pages
     bool slot_used[N_STAGING_SLOTS] = {};
     int slot_idx = 0;
@@ -1134,9 +1193,15 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                 }
         ++slot_idx;
     }
-    CF_HIP_Q(hipEventRecord(c->ev_scat, c->ss));
-    CF_HIP_Q(hipStreamWaitEvent(c->ps, c->ev_scat, 0));
-    CF_HIP_Q(hipEventRecord(c->ev_copy, c->ps));
+    // the end of the copy stream's work: after the scatter stream's last placement
+    auto close_copy_stream = [&]() -> int {
+        if (hipEventRecord(c->ev_scat, c->ss) != hipSuccess || hipStreamWaitEvent(c->ps, c->ev_scat, 0) != hipSuccess ||
+            hipEventRecord(c->ev_copy, c->ps) != hipSuccess)
+            return -1;
+        return 0;
+    };
+    if (!merged && close_copy_stream() < 0)
+        return bail(fail(CF_ERR_HIP, "cf_restore_batch: recording the end of the copy stream failed"));
 
     c->caprows_dev = c->caprows_out ? (const int32_t*)(md + off_caprows) : nullptr;
     // compute stream: layer-major over the batch
@@ -1146,8 +1211,23 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         std::vector<hipEvent_t> ready(L, nullptr);
         for (int l = 0; l < L; ++l)
             if (layer_loaded[l]) ready[l] = c->ev_layer[l];
-        int rc2 = run_phase(c, cache, rec, L, ready.data(), c->ev_comp);
+        // direct path: layer l's loads go onto the copy stream right before layer l's kernels go
+        // onto the compute stream (the event of a layer is recorded before anything waits for it)
+        int next_layer = 0;
+        const std::function<int()> feed_copy_stream = [&]() -> int {
+            const int l = next_layer++;
+            if (l < L && load_of_layer[l] >= 0) {
+                if (enqueue_load(layer_loads[load_of_layer[l]]) < 0) return -1;
+                ++loads_enqueued;
+            }
+            return 0;
+        };
+        int rc2 = run_phase(c, cache, rec, L, ready.data(), c->ev_comp, 0, 0, &feed_copy_stream);
         if (rc2) return bail(rc2);
+        while (next_layer < L)
+            if (feed_copy_stream() < 0) return bail(fail(CF_ERR_HIP, "cf_restore_batch: enqueuing a load failed"));
+        if (close_copy_stream() < 0)
+            return bail(fail(CF_ERR_HIP, "cf_restore_batch: recording the end of the copy stream failed"));
         CF_HIP_Q(hipEventRecord(c->ev_t0, c->cs));
     } else {
         int rc2 = run_phase(c, cache, rec, max_cut, nullptr, c->ev_comp);
@@ -2213,7 +2293,12 @@ extern "C" int cf_calibrate(cf_ctx* c, cf_cache* cache, void* host_buf, size_t h
             sp[i] = cf_split{CF_TOKEN_WISE, p.k, L};
         }
         if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, tm);  // warm-up
+        // the faster of two timed runs: a one-off stall (clock ramp, a first transfer) would
+        // otherwise end up in a coefficient
+        cf_timing t2;
         if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, tm);
+        if (rc == CF_OK) rc = cf_restore_batch(c, cache, p.n_req, rq.data(), sp.data(), nullptr, &t2);
+        if (rc == CF_OK && (p.k > 0 ? t2.compute_ms < tm->compute_ms : t2.copy_ms < tm->copy_ms)) *tm = t2;
         for (int i = 0; i < made; ++i) cf_cache_free(cache, base_id + i);
         return rc;
     };
