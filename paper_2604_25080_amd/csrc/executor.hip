@@ -645,11 +645,19 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                 c->prof_begin(CF_K_RMSNORM, (double)Tc * d * (4 + es), c->cs);
                 launch_rmsnorm(c->cs, m.dtype, h, l > 0 ? dl : nullptr, lw.attn_norm, a_buf, Tc, d, m.rms_eps, nullptr);
                 c->prof_end(CF_K_RMSNORM, c->cs);
-                gemm(c, CF_K_GEMM_QKV, a_buf, lw.wqkv, nullptr, qkv_buf, nullptr, Tc, qcols, d, EPI_STORE_F32);
-                c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
-                launch_rope_write(c->cs, m.dtype, qkv_buf, d_pos + x, d_slot + x, c->rope(), q_buf, pool_layer,
-                                  Tc, m.n_q_heads, g);
-                c->prof_end(CF_K_ROPE_WRITE, c->cs);
+                if (!c->simple_only && gemm_mfma_qkv_rope_supported(m.dtype, Tc, qcols, d, m.head_dim)) {
+                    // RoPE and the page write happen on the accumulators of the QKV projection
+                    const RopeEpilogue re{d_pos + x, d_slot + x, c->rope(), pool_layer, m.n_q_heads, g};
+                    c->prof_begin(CF_K_GEMM_QKV, 2.0 * Tc * (double)qcols * d, c->cs);
+                    launch_gemm_mfma_qkv_rope(c->cs, a_buf, lw.wqkv, q_buf, Tc, qcols, d, re);
+                    c->prof_end(CF_K_GEMM_QKV, c->cs);
+                } else {
+                    gemm(c, CF_K_GEMM_QKV, a_buf, lw.wqkv, nullptr, qkv_buf, nullptr, Tc, qcols, d, EPI_STORE_F32);
+                    c->prof_begin(CF_K_ROPE_WRITE, (double)Tc * qcols * (4 + es), c->cs);
+                    launch_rope_write(c->cs, m.dtype, qkv_buf, d_pos + x, d_slot + x, c->rope(), q_buf, pool_layer,
+                                      Tc, m.n_q_heads, g);
+                    c->prof_end(CF_K_ROPE_WRITE, c->cs);
+                }
                 if (Tr <= 0) continue;
                 // attention work items (row0 is relative to the chunk): recompute items lead, new-turn
                 // items trail.  Recompute rows run first; the new-turn rows also read this layer's

@@ -1,7 +1,9 @@
 // bf16 GEMM on CDNA4 matrix cores for the linear layers of recompute:
 //   acc[M,N] = A[M,K] * W[N,K]^T   (both operands K-contiguous, float accumulate)
 // with the layer's epilogue fused: float store (QKV), float residual add
-// (O-proj, down-proj), bf16 store, or SiLU(gate)*up -> bf16 (gate/up pair).
+// (O-proj, down-proj), bf16 store, SiLU(gate)*up -> bf16 (gate/up pair), or -- for the QKV
+// projection on the big tile -- RoPE on the accumulators with Q stored as bf16 and K/V written
+// straight into their page slots.
 //
 // Tiling: 256x256 block tile, 4 wavefronts (2x2), each a 128x128 wave tile =
 // 4x4 MFMA 32x32x16 fragments (256 accumulator registers per lane); problems
@@ -15,6 +17,7 @@
 // Workgroups are renumbered so that the 32 workgroups resident on one XCD
 // (one L2) cover an 8x4 patch of tiles.
 #include "kernels.h"
+#include "rope.h"
 #include "cacheflow.h"
 
 namespace cf {
@@ -54,11 +57,13 @@ template <int EPI, int BM, int BN, int NW>
 __device__ __forceinline__ void
 gemm_mfma_body(char* smem, const bf16* __restrict__ A, const bf16* __restrict__ W,
                const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
-               int N, int K, int tiles_m, int tiles_n, int m_off, int n_off, int bid, int nb) {
+               int N, int K, int tiles_m, int tiles_n, int m_off, int n_off, int bid, int nb,
+               const RopeEpilogue& rope) {
     constexpr bool SILU = (EPI == EPI_SILU_MUL);
+    constexpr bool ROPE = (EPI == EPI_QKV_ROPE128 || EPI == EPI_QKV_ROPE64);
     // 16-bit outputs: the MFMAs take the W fragment as their first operand, which leaves the
     // TRANSPOSED product in the accumulators (see the epilogue)
-    constexpr bool SWAP = (EPI == EPI_SILU_MUL || EPI == EPI_STORE_T);
+    constexpr bool SWAP = (EPI == EPI_SILU_MUL || EPI == EPI_STORE_T || ROPE);
     constexpr int BN_OUT = SILU ? BN / 2 : BN;    // output columns per block
     constexpr int WGN = NW / 2;                   // wavefront grid: 2 x WGN
     constexpr int NT = 64 * NW;                   // threads
@@ -352,6 +357,95 @@ gemm_mfma_body(char* smem, const bf16* __restrict__ A, const bf16* __restrict__ 
                     }
                 }
             }
+    } else if constexpr (ROPE) {
+        // QKV projection (big tile only, N a multiple of the tile): a wave tile spans whole
+        // heads, and both elements (j, j + head_dim/2) of a rotation pair sit in the same lane,
+        // HALF_F fragments apart.  Per row the lane looks up the position (angle) and the page
+        // slot; whether a head is Q, K or V is the same for the whole wavefront.
+        static_assert(BIG, "the fused QKV epilogue exists for the 256x256 tile only");
+        constexpr int HD = (EPI == EPI_QKV_ROPE128) ? 128 : 64;
+        constexpr int HALF_F = HD / 64;               // fragments per half head
+        static_assert(WN % HD == 0 && FN % (2 * HALF_F) == 0, "wave tile must span whole heads");
+        const int row_l = lane & 31, col_l = 4 * (lane >> 5);
+        const int nq = rope.n_q_heads * HD, nkv = rope.g.n_kv_heads * HD;
+        bf16* pool = (bf16*)rope.pool_layer;
+        // Loads first, and ahead of the stores they could alias with as far as the compiler
+        // knows: the rows' positions and slots up front, then the angles of row group i + 1
+        // while row group i is rotated and stored (one wavefront per SIMD: nothing else hides
+        // the latency of a load that waits behind a store).
+        int rpos[FM], rslot[FM];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int gm = m0 + wm * WM + i * 32 + row_l;
+            rpos[i] = rope.pos[gm];
+            rslot[i] = rope.slot[gm];
+        }
+        constexpr int NTAB = HALF_F * 8;              // float4 loads per row: 16 * HALF_F (cos, sin) pairs
+        constexpr int FH = 2 * HALF_F;                // fragments per head
+#define CF_LOAD_ANGLES(I, T)                                                                  \
+        {                                                                                     \
+            const float2* cs_ = rope.cos_sin + (int64_t)rpos[I] * (HD / 2) + col_l;           \
+            _Pragma("unroll") for (int u = 0; u < HALF_F * 4; ++u) {                          \
+                T[2 * u] = *reinterpret_cast<const float4*>(cs_ + 8 * u);                     \
+                T[2 * u + 1] = *reinterpret_cast<const float4*>(cs_ + 8 * u + 2);             \
+            }                                                                                 \
+        }
+        // Head by head; Q, K or V is decided once per head, outside the row loop, so that each
+        // branch is straight-line code over the four row groups.
+#pragma unroll
+        for (int hh = 0; hh < WN / HD; ++hh) {
+            // first column of this head (the same for every lane: kept in a scalar register)
+            const int hc = __builtin_amdgcn_readfirstlane(n0 + wn * WN + hh * HD);
+            if (hc < nq + nkv) {
+                float4 tab[2][NTAB];
+                CF_LOAD_ANGLES(0, tab[0]);
+#pragma unroll
+                for (int i = 0; i < FM; ++i) {
+                    if (i + 1 < FM) CF_LOAD_ANGLES(i + 1, tab[(i + 1) & 1]);
+                    const float4* tb = tab[i & 1];
+                    const int gm = m0 + wm * WM + i * 32 + row_l;
+                    // Q row of the packed query buffer, or the K row [head][slot][HD] of the page
+                    bf16* dst = hc < nq ? Dt + (int64_t)gm * nq + hc
+                                        : pool + (int64_t)(rslot[i] / CF_PAGE_TOKENS) * rope.g.page_elems +
+                                              ((int64_t)((hc - nq) / HD) * CF_PAGE_TOKENS + rslot[i] % CF_PAGE_TOKENS) * HD;
+#pragma unroll
+                    for (int jj = 0; jj < HALF_F; ++jj)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int cj = jj * 32 + 8 * q + col_l;        // pair index, multiple of 4
+                            const float4 t0 = tb[2 * (jj * 4 + q)], t1 = tb[2 * (jj * 4 + q) + 1];
+                            const float2 cc[4] = {{t0.x, t0.y}, {t0.z, t0.w}, {t1.x, t1.y}, {t1.z, t1.w}};
+                            float y1[4], y2[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                rope_rotate(acc[i][hh * FH + jj][4 * q + t],
+                                            acc[i][hh * FH + HALF_F + jj][4 * q + t], cc[t], y1[t], y2[t]);
+                            uint2 lo, hi;
+                            lo.x = pack_bf16x2(y1[0], y1[1]); lo.y = pack_bf16x2(y1[2], y1[3]);
+                            hi.x = pack_bf16x2(y2[0], y2[1]); hi.y = pack_bf16x2(y2[2], y2[3]);
+                            *reinterpret_cast<uint2*>(dst + cj) = lo;
+                            *reinterpret_cast<uint2*>(dst + cj + HD / 2) = hi;
+                        }
+                }
+            } else {
+                // V, stored transposed in the page: [head][HD][slot]; the 32 rows of a fragment
+                // are mostly consecutive slots, so a store instruction still fills 32-byte runs
+#pragma unroll
+                for (int i = 0; i < FM; ++i) {
+                    bf16* dst = pool + (int64_t)(rslot[i] / CF_PAGE_TOKENS) * rope.g.page_elems +
+                                (int64_t)rope.g.n_kv_heads * CF_PAGE_TOKENS * HD +
+                                (int64_t)((hc - nq - nkv) / HD) * HD * CF_PAGE_TOKENS + rslot[i] % CF_PAGE_TOKENS;
+#pragma unroll
+                    for (int j = 0; j < FH; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int col = j * 32 + 8 * (r >> 2) + col_l + (r & 3);
+                            dst[col * CF_PAGE_TOKENS].x = f32_to_bf16_bits(acc[i][hh * FH + j][r]);
+                        }
+                }
+            }
+        }
+#undef CF_LOAD_ANGLES
     } else {
         const int row_l = lane & 31, col_l = 4 * (lane >> 5);
         const bool vec_ok = (N & 3) == 0;             // row starts stay 8-byte aligned
@@ -400,10 +494,10 @@ template <int EPI, int BM, int BN, int NW>
 __global__ void __launch_bounds__(64 * NW)
 gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                  const bf16* __restrict__ W2, float* __restrict__ Cf, bf16* __restrict__ Dt, int M,
-                 int N, int K, int tiles_m, int tiles_n) {
+                 int N, int K, int tiles_m, int tiles_n, RopeEpilogue rope) {
     extern __shared__ __align__(16) char smem[];
     gemm_mfma_body<EPI, BM, BN, NW>(smem, A, W, W2, Cf, Dt, M, N, K, tiles_m, tiles_n, 0, 0,
-                                    (int)blockIdx.x, tiles_m * tiles_n);
+                                    (int)blockIdx.x, tiles_m * tiles_n, rope);
 }
 
 // Big tiles with a quartered tail.  With one 256x256 tile per CU at a time, a launch whose tile
@@ -422,13 +516,14 @@ gemm_mfma_tail_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                       int M, int N, int K, int tiles_m, int tiles_n, int n_big, int tail_m_off,
                       int tail_n_off, int tail_tiles_m, int tail_tiles_n) {
     extern __shared__ __align__(16) char smem[];
+    const RopeEpilogue none{};
     if ((int)blockIdx.x < n_big)
         gemm_mfma_body<EPI, 256, 256, 4>(smem, A, W, W2, Cf, Dt, M, N, K, tiles_m, tiles_n, 0, 0,
-                                         (int)blockIdx.x, n_big);
+                                         (int)blockIdx.x, n_big, none);
     else
         gemm_mfma_body<EPI, 128, 128, 4>(smem, A, W, W2, Cf, Dt, M, N, K, tail_tiles_m, tail_tiles_n,
                                          tail_m_off, tail_n_off, (int)blockIdx.x - n_big,
-                                         tail_tiles_m * tail_tiles_n);
+                                         tail_tiles_m * tail_tiles_n, none);
 }
 
 constexpr int N_CUS = 256;            // MI355X
@@ -436,11 +531,11 @@ constexpr int GROUP_M = 8;            // tile rows per group of the tile order (
 
 template <int EPI, int BM, int BN, int NW>
 void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf, void* Dt,
-                 int M, int N, int K, bool tail_ok = false) {
+                 int M, int N, int K, bool tail_ok = false, const RopeEpilogue& rope = RopeEpilogue{}) {
     constexpr int BN_OUT = (EPI == EPI_SILU_MUL) ? BN / 2 : BN;
     constexpr int LDS = N_STAGES * (BM + BN) * ROW_BYTES;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN_OUT - 1) / BN_OUT;
-    if constexpr (BM == 256 && NW == 4 && EPI != EPI_ADD_F32) {
+    if constexpr (BM == 256 && NW == 4 && EPI != EPI_ADD_F32 && EPI != EPI_QKV_ROPE128 && EPI != EPI_QKV_ROPE64) {
         // tail: the last nb % N_CUS tiles, rounded up to whole columns of the last row group
         const int nb = tiles_m * tiles_n, tail = nb % N_CUS;
         const int gsz = tiles_m - (tiles_m - 1) / GROUP_M * GROUP_M;       // rows of the last group
@@ -468,7 +563,7 @@ void launch_tile(hipStream_t s, const void* A, const void* W, const void* W2, fl
         configured = true;
     }
     kern<<<tiles_m * tiles_n, 64 * NW, LDS, s>>>((const bf16*)A, (const bf16*)W, (const bf16*)W2, Cf,
-                                             (bf16*)Dt, M, N, K, tiles_m, tiles_n);
+                                             (bf16*)Dt, M, N, K, tiles_m, tiles_n, rope);
 }
 
 int g_force_tile = 0;   // 0 = heuristic; 256 / 128 / 64 = forced tile, 257 = 256 with the quartered tail
@@ -499,6 +594,23 @@ void launch(hipStream_t s, const void* A, const void* W, const void* W2, float* 
 }  // namespace
 
 void gemm_mfma_force_tile(int t) { g_force_tile = t; }
+
+bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int head_dim) {
+    // the shapes for which the float-output QKV GEMM would take the big tile anyway, with whole
+    // tiles along N (no shifted edge tile: head boundaries stay on wave-tile boundaries)
+    const int64_t tiles256 = (int64_t)((M + 255) / 256) * (N / 256);
+    const bool big = g_force_tile ? g_force_tile >= 256 : tiles256 >= 256;
+    return dtype == CF_BF16 && (head_dim == 128 || head_dim == 64) && big && M >= 256 && N >= 256 &&
+           N % 256 == 0 && K >= 2 * BK && K % (2 * BK) == 0;
+}
+
+void launch_gemm_mfma_qkv_rope(hipStream_t s, const void* A, const void* Wqkv, void* q_out, int M,
+                               int N, int K, const RopeEpilogue& rope) {
+    if (rope.g.head_dim == 128)
+        launch_tile<EPI_QKV_ROPE128, 256, 256, 4>(s, A, Wqkv, nullptr, nullptr, q_out, M, N, K, false, rope);
+    else
+        launch_tile<EPI_QKV_ROPE64, 256, 256, 4>(s, A, Wqkv, nullptr, nullptr, q_out, M, N, K, false, rope);
+}
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K, int epi) {
     (void)epi;

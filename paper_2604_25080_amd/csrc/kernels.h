@@ -16,7 +16,10 @@ enum Epilogue {
     EPI_STORE_F32 = 0,  // C[m,n] = acc                     (float out)
     EPI_ADD_F32 = 1,    // C[m,n] += acc                    (float residual stream)
     EPI_STORE_T = 2,    // D[m,n] = (T)acc                  (model dtype out)
-    EPI_SILU_MUL = 3    // D[m,n] = (T)(silu(acc) * acc2)   acc2 from second weight W2
+    EPI_SILU_MUL = 3,   // D[m,n] = (T)(silu(acc) * acc2)   acc2 from second weight W2
+    // QKV projection with RoPE and the paged K/V write done on the accumulators (head_dim 128 / 64)
+    EPI_QKV_ROPE128 = 4,
+    EPI_QKV_ROPE64 = 5
 };
 
 // One q-block of attention work: rows [row0, row0+n_rows) of the packed query
@@ -73,6 +76,24 @@ bool gemm_mfma_supported(int dtype, int M, int N, int K, int epi);
 void gemm_mfma_force_tile(int tile);   // 0 = heuristic, 256 or 128 = forced (tuning)
 void launch_gemm_mfma(hipStream_t s, const void* A, const void* W, const void* W2, float* Cf,
                       void* Dt, int M, int N, int K, int epi);
+// What the QKV projection needs to finish its own output: per packed row its absolute position
+// (the RoPE angle) and pool slot (page * CF_PAGE_TOKENS + slot in page), the angle table
+// [position][head_dim / 2] of (cos, sin), and the layer's slice of the page pool.
+struct RopeEpilogue {
+    const int32_t* pos;
+    const int32_t* slot;
+    const float2* cos_sin;
+    void* pool_layer;
+    int n_q_heads;
+    KvGeom g;
+};
+// true if the MFMA GEMM can take the QKV projection [M, N = (Hq + 2 Hkv) * head_dim] with RoPE
+// and the page write in its epilogue (the 256x256 tile, whose wave tile spans whole heads)
+bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int head_dim);
+// q_out[M][Hq * head_dim] = rotated Q; rotated K and V go to the rows' page slots.  Same bits as
+// the float-output GEMM followed by launch_rope_write.
+void launch_gemm_mfma_qkv_rope(hipStream_t s, const void* A, const void* Wqkv, void* q_out, int M,
+                               int N, int K, const RopeEpilogue& rope);
 void launch_rope_write(hipStream_t s, int dtype, const float* qkv, const int32_t* pos,
                        const int32_t* slot, const float2* cos_sin, void* q_out, void* pool_layer,
                        int T, int n_q_heads, KvGeom g);

@@ -4,6 +4,7 @@
 // kernels are tested against on the GPU; the page mover, norm, embed and RoPE
 // kernels serve every configuration.
 #include "kernels.h"
+#include "rope.h"
 #include "cacheflow.h"
 
 namespace cf {
@@ -203,8 +204,8 @@ rope_write_kernel(const float* __restrict__ qkv, const int32_t* __restrict__ pos
         int head = i / half, j = i % half;
         float2 c = cs[j];
         float x1 = row[head * hd + j], x2 = row[head * hd + j + half];
-        float y1 = x1 * c.x - x2 * c.y;
-        float y2 = x2 * c.x + x1 * c.y;
+        float y1, y2;
+        rope_rotate(x1, x2, c, y1, y2);
         if (head < n_q_heads) {
             T* dst = q_out + (int64_t)t * nq + head * hd;
             dst[j] = from_f32<T>(y1);

@@ -244,13 +244,18 @@ def test_remaining_head_geometries_of_the_attention_kernel(shape_name):
         sess.close()
 
 
-def test_small_shape_end_to_end_on_the_big_gemm_tile():
+@pytest.mark.parametrize("shape_name", ["mini-bf16", "mini64-gqa2-bf16"])
+def test_small_shape_end_to_end_on_the_big_gemm_tile(shape_name):
     """The 256x256 GEMM tile (and its quartered tail) is what the full-size runs use; the small
     shapes take the 128 / 64 tiles by themselves.  Forced here (the GEMMs whose shapes allow the
     big tile: M >= 256, N >= 256, K a multiple of 128), one hybrid restore end to end against
-    the oracle -- and bit for bit against the tiles the heuristic picks."""
+    the oracle -- and bit for bit against the tiles the heuristic picks.  On the big tile the QKV
+    projection rotates and writes Q, K and V in its own epilogue (head_dim 128 and 64: a wave
+    tile of one head, and of two heads with K and V heads side by side in one block tile); on
+    the small tiles a separate kernel does, so the bit comparison also holds the two against
+    each other."""
     import paper_2604_25080_amd as cf
-    b, refs, sess, host = build("mini-bf16", 16, 3, 300, 700, 40, 150, chunk_rows=2048)
+    b, refs, sess, host = build(shape_name, 16, 3, 300, 700, 40, 150, chunk_rows=2048)
     try:
         L = b.shape.n_layers
         splits = [(n // 2 // 16 * 16, L) for n in b.n_ctx]
