@@ -277,6 +277,7 @@ class Bench:
         self.cost = sess.ctx.calibrate(sess.cache, scratch.data_ptr(), scratch.numel())
         self.overlap = sess.ctx.calibrate_overlap(sess.cache, scratch.data_ptr(), scratch.numel(), self.cost)
         self.cost0 = self.cost_dict()
+        self.dyn_seeded = False
         opts = cf.plan_opts(512, 0, self.shape.n_layers, self.shape.kv_bytes_per_token_layer, -1)
         self.l_delta = cf.derive_l_delta(self.cost, opts, 32768)
         self.kv_only = cf.plan_batch(self.cost, self.overlap, self.desc, cf.batch_plan_opts(512, 0), [512])[1].kv_only_permille
@@ -294,7 +295,19 @@ class Bench:
         if plan == "dynamic":
             opts = cf.plan_opts(batch.chunk_tokens, self.l_delta, L, self.shape.kv_bytes_per_token_layer,
                                 batch.forced_mode, kv_only_permille=self.kv_only)
-            _, splits, tm, st = sess.restore_dynamic(reqs, self.cost, opts, want_logits=True)
+            cost = self.cost
+            if args.model_skew:       # a deliberately wrong cost table in front of the run-time scheduler
+                fc, fio = (float(x) for x in args.model_skew.split(":"))
+                cost = cf.cost_model(**{k: int(getattr(self.cost, k) * (fc if k in ("f_c", "alpha", "beta", "s_c") else fio))
+                                        for k in ("f_c", "alpha", "beta", "f_io", "gamma", "s_c", "s_io")})
+            _, splits, tm, st = sess.restore_dynamic(reqs, cost, opts, want_logits=True,
+                                                     step_cap_ps=int(args.step_cap_ms * 1e9),
+                                                     units_per_request=args.units_per_request,
+                                                     overlap=None if self.dyn_seeded else self.overlap)
+            self.dyn_seeded = True    # from here on the context's own measured ratios carry over
+            log(f"[bench]   {batch.config} run-time: comp {tm['compute_ms']:.1f} (waited {tm['compute_wait_ms']:.1f}) "
+                f"copy {tm['copy_ms']:.1f} ttft {tm['total_ms']:.1f} ms; recomputed "
+                f"{sum(s_[1] for s_ in splits if s_[2] > 0)} tokens; {st}")
             return splits, dict(kind="run-time", stats=st), tm
         info = None
         if plan == "planner" and batch.forced_splits:
@@ -434,6 +447,13 @@ def main():
     ap.add_argument("--plan", default="planner",
                     help="planner | dynamic (claims at run time, no precomputed split) | per_request | "
                          "all_recompute | all_load | cut=<L> (layer cut for every request)")
+    ap.add_argument("--step-cap-ms", type=float, default=0.0,
+                    help="--plan dynamic: a compute step stops taking units at this predicted duration (0: no cap)")
+    ap.add_argument("--units-per-request", type=int, default=0,
+                    help="--plan dynamic: most consecutive chunks of one request in a step (0: no limit)")
+    ap.add_argument("--model-skew", default="",
+                    help="--plan dynamic: c:io -- multiply the calibrated compute / load costs by these factors "
+                         "before the run-time scheduler sees them (a wrong cost model)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the short runs of the other configurations and plans after the timed region")

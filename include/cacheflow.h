@@ -304,21 +304,34 @@ enum cf_claim_order {
     CF_ORDER_SHORTEST = 1    /* least recomputation still ahead of the request first  */
 };
 
-/* cf_dynamic_claim: which of the live, not closed requests' next units the
- * compute engine takes for its next step (one step = those units run together,
+/* cf_dynamic_claim: which units of the live, not closed requests the compute
+ * engine takes for its next step (one step = those units run together,
  * layer-major).  With R = io_backlog + sum of the load costs b of all unclaimed
- * units (when the channel would be done on its own), candidates are ranked by
- * `order` (cf_claim_order; ties to the lower index) and taken greedily -- until
- * the step has reached step_cap_ps, if that is > 0 (a step always gets a first
- * unit) -- while  A + a + compute_later_ps <= R - Bs  (A, Bs: recompute and
- * load cost of what the step already holds; A starts at step_fixed_ps, the
- * predicted cost of work the step carries in any case, such as the new-turn
- * prefill of requests that are already restored; compute_later_ps is work the
- * compute engine must do after this step whatever it takes now, such as the
- * new-turn prefill of the other requests).  Token-wise requests are candidates
- * one by one; all open layer-wise requests form ONE candidate (they advance
- * through the layers as a packed batch), a = sum a_i, b = sum b_i.
- *   take[i] (host int32[B]) : 0 not taken; 1 taken; 2 (layer-wise only) taken
+ * units (when the channel would be done on its own), the candidates are the
+ * next unit of every open token-wise request -- the unit behind those the step
+ * already holds of it, while it holds fewer than max_units of that request
+ * (0: no limit) -- and ALL open layer-wise requests as ONE candidate, once per
+ * step (they advance through the layers as a packed batch, one layer per
+ * step; a = sum a_i, b = sum b_i).  Ranked by `order` (cf_claim_order; ties to
+ * the lower index), the best candidate is taken if
+ *        A + a + compute_later_ps <= R - Bs
+ * (A, Bs: recompute and load cost of what the step already holds; A starts at
+ * step_fixed_ps, the predicted cost of work the step carries in any case, such
+ * as the new-turn prefill of requests that are already restored;
+ * compute_later_ps is work the compute engine must do after this step whatever
+ * it takes now, such as the new-turn prefill of the other requests); a request
+ * whose candidate fails is out for this step.  This repeats until no candidate
+ * is left or the step has reached step_cap_ps, if that is > 0 (a step always
+ * gets a first unit).
+ * Contention: scale_io_permille prices the channel while the compute engine
+ * recomputes beside it, io_alone_permille (> 0) the channel when the compute
+ * engine takes nothing.  What was chosen is given back (all take[i] = 0,
+ * *step_ps = step_fixed_ps) unless it pays for the slowdown it causes:
+ *   max(A + compute_later_ps, R - Bs)
+ *        < max(step_fixed_ps + compute_later_ps, R at the scale io_alone_permille).
+ * io_alone_permille = 0 skips the test.
+ *   take[i] (host int32[B]) : token-wise: number of consecutive units taken,
+ *                   from p_comp[i] on; layer-wise: 0 not taken, 1 taken, 2 taken
  *                   as the group's last layer -- the same test fails for the
  *                   group's following layer (or there is none), so the
  *                   executor stops this one after its K/V write
@@ -331,8 +344,8 @@ int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* opts, int32_
                      const int32_t* n_ctx, const int32_t* p_comp, const int32_t* p_io,
                      const uint8_t* compute_closed, int64_t io_backlog_ps, int64_t step_fixed_ps,
                      int64_t compute_later_ps, int64_t step_cap_ps, int32_t order,
-                     int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
-                     int64_t* step_ps);
+                     int32_t scale_c_permille, int32_t scale_io_permille, int32_t max_units,
+                     int32_t io_alone_permille, int32_t* take, int64_t* step_ps);
 
 /* --------------------------------------------------------------- page table
  * Paged KV cache bookkeeping (the serving substrate of Sec. 4.1).  Policy is
@@ -471,10 +484,16 @@ int cf_restore_batch(cf_ctx* ctx, cf_cache* cache, int32_t B, const cf_request* 
 typedef struct cf_dynamic_stats {
     int32_t compute_steps;      /* steps the compute engine ran (new-turn ones too) */
     int32_t compute_units;      /* units it claimed (chunks, or request-layers)    */
-    int32_t io_units;           /* load launches (one per claimed I/O unit)        */
-    int32_t scale_c_permille;   /* measured / predicted at the end of the call     */
-    int32_t scale_io_permille;
+    int32_t io_units;           /* loads the channel claimed (each one launch or a
+                                   group of transfers), the planned tail's layers
+                                   included                                        */
+    int32_t scale_c_permille;   /* measured / predicted at the end of the call:
+                                   compute engine,                                 */
+    int32_t scale_io_permille;  /* channel beside a recomputing compute engine,    */
+    int32_t scale_io_alone_permille;   /* channel on its own                       */
     int32_t planned_tail;       /* 1: the call ended with the planned tail (see below) */
+    int32_t last_step_merged;   /* 1: the last recompute step carried the planned
+                                   tail and every outstanding new turn itself      */
     double compute_gap_ms;      /* compute stream idle between steps (host decides
                                    the next step only when the last one is done)   */
 } cf_dynamic_stats;
@@ -485,7 +504,17 @@ typedef struct cf_dynamic_opts {
                                    later and finish requests one after the other, longer
                                    ones run larger GEMMs                              */
     int32_t order;              /* cf_claim_order of the compute engine's candidates  */
-    int32_t reserved;
+    int32_t units_per_request;  /* most consecutive units of one token-wise request a
+                                   step may take (0: no limit; 1: a step holds one chunk
+                                   of each request it takes)                          */
+    int32_t overlap_comp_permille;   /* cf_overlap_model of the machine (cf_calibrate_overlap,
+                                   cf_plan_feedback).  If either is > 0 the context's ratios */
+    int32_t overlap_io_permille;     /* measured / predicted restart in this call: the two
+                                   engines' side-by-side ratios from these factors (0 reads
+                                   as 1000), the channel's own from 1000.  Both 0: the ratios
+                                   carry on from the context's previous call (a new context
+                                   starts at 1000).  Pass them with a new or changed cost
+                                   model, leave them 0 while the same one stays in use.   */
 } cf_dynamic_opts;
 
 /* Restore a batch WITHOUT a precomputed split: the two engines claim units at
@@ -506,8 +535,10 @@ typedef struct cf_dynamic_opts {
  * runs beside those loads, its attention in layer l waiting for layer l only.
  * The logits follow when the last request is through.
  *   cost, opts : the cost model seeds the predictions; the ratios measured /
- *                predicted are tracked inside the call and carried over to
- *                the context's next call (they start at 1).  opts->chunk_tokens
+ *                predicted are tracked inside the call -- the compute engine's,
+ *                the channel's while a recompute step runs beside it, and the
+ *                channel's on its own -- and carried over to the context's
+ *                next call (see cf_dynamic_opts).  opts->chunk_tokens
  *                must be a multiple of 16 (page size); modes by
  *                opts->force_mode / l_delta as in cf_restore_plan.
  *   reqs       : as for cf_restore_batch; every request with n_ctx > 0 needs
@@ -519,7 +550,7 @@ typedef struct cf_dynamic_opts {
  *                are those of cf_restore_batch under these splits up to the
  *                order of floating-point summation (chunks are recomputed
  *                one step at a time, over the pages of the chunks before).
- *   dyn        : may be NULL = {0, CF_ORDER_CHEAPEST}.
+ *   dyn        : may be NULL = {0, CF_ORDER_CHEAPEST, 0, 0, 0}.
  *   logits_out, timing : as for cf_restore_batch.  stats may be NULL.
  * The context must cover the whole model (no cf_ctx_set_stage restriction).
  * Rows: (tokens of all layer-wise requests) + (token-wise requests x C) +

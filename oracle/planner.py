@@ -467,25 +467,41 @@ ORDER_SHORTEST = 1     # least recomputation still ahead of the request first
 
 
 def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scale_c=1000,
-                  scale_io=1000, step_fixed=0, step_cap=0, order=ORDER_CHEAPEST, compute_later=0):
+                  scale_io=1000, step_fixed=0, step_cap=0, order=ORDER_CHEAPEST, compute_later=0,
+                  max_units=1, io_alone=0):
     """Which live, open requests' next units the compute engine takes for its next step.
 
     R = io_backlog + load cost of every unclaimed unit: the time the I/O channel needs if
-    compute takes nothing.  Candidates: each open token-wise request's unit p_comp[i]; all
-    open layer-wise requests together as one candidate (they advance as a packed batch).
-    Ranked by `order` (recompute cost per load cost, or the recomputation the request still
-    has ahead of it; ascending, ties by index), a candidate (a, b) is taken if
-    A + a <= R - Bs  with A, Bs the sums over those already taken: the step ends no later
-    than the channel would finish what the step so far leaves to it.  With step_cap > 0 the
-    step takes no further candidate once A has reached the cap (the first one always goes in).
-    A starts at `step_fixed`, the cost of work the step carries in any case; `compute_later`
-    is work the compute engine has to do after this step whatever it takes now, and counts
-    against what the step may take: the test is  A + a + compute_later <= R - Bs.
-    Returns (take, step cost): take[i] in {0, 1, 2}; 2 marks layer-wise requests whose group
-    should stop this layer after its K/V write because the test fails for the group's next
-    layer.  The step cost counts the group's layer at what the step really runs -- the whole
-    layer (1) or its K/V projection (2) -- whereas the unit prices used for the decision charge
-    a layer's attention and MLP to the following unit."""
+    compute takes nothing.  Candidates: each open token-wise request's next unit -- the unit
+    behind the ones the step already holds of it, as long as the step holds fewer than
+    `max_units` of that request (0: no limit) -- and all open layer-wise requests together as
+    one candidate, once per step (they advance as a packed batch, one layer per step).
+    The candidates are ranked by `order` (recompute cost per load cost, or the recomputation
+    the request still has ahead of it; ascending, ties by index) and the first in rank with
+        A + a + compute_later <= R - Bs
+    is taken (A, Bs: recompute and load cost of what the step holds; A starts at
+    `step_fixed`, the cost of work the step carries in any case; `compute_later` is work the
+    compute engine has to do after this step whatever it takes now): the step, and what
+    follows it, end no later than the channel would finish what the step leaves to it.  A
+    request whose candidate fails is out for this step (its later units cost no less).  This
+    repeats until no candidate passes or, with step_cap > 0, A has reached the cap (the first
+    unit always goes in).
+
+    Contention (Sec. 3.3, evolving resource availability): scale_io prices the channel while
+    the compute engine recomputes beside it; `io_alone` > 0 is the channel's scale when the
+    compute engine takes nothing.  Nothing is taken (take all 0) unless recomputing pays for
+    the slowdown it causes:  max(A* + compute_later, R - Bs*) < max(step_fixed +
+    compute_later, R_alone), with R_alone = R at the scale io_alone and A*, Bs* the totals of
+    everything the same rule would take from this state without step_cap and max_units, the
+    layer-wise group layer after layer (a capped step is the first of several: what counts
+    is where the engine ends up, not what one step holds).
+
+    Returns (take, step cost): take[i] = units taken of token-wise request i; for layer-wise
+    requests 1 or 2, 2 marking that the group should stop this layer after its K/V write
+    because the test fails for the group's next layer.  The step cost counts the group's layer
+    at what the step really runs -- the whole layer (1) or its K/V projection (2) -- whereas the
+    unit prices used for the decision charge a layer's attention and MLP to the following
+    unit."""
     b_req = len(n_ctx)
     closed = closed or [False] * b_req
     units = _scaled_units(cm, opts, n_ctx, scale_c, scale_io)
@@ -493,15 +509,10 @@ def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scal
     r_total = io_backlog + sum(sum(units[i][2][p_comp[i]:p_io[i] + 1]) for i in live)
     open_ = [i for i in live if not closed[i]]
     group = [i for i in open_ if units[i][0] == LAYER_WISE]
-    def ahead(i):       # unscaled recomputation between the pointers
-        return sum(units[i][3][p_comp[i]:p_io[i] + 1])
+    front = list(p_comp)                       # next unit of each token-wise request
 
-    cands = [(units[i][1][p_comp[i]], units[i][2][p_comp[i]], i, False, ahead(i))
-             for i in open_ if units[i][0] == TOKEN_WISE]
-    if group:
-        cands.append((sum(units[i][1][p_comp[i]] for i in group),
-                      sum(units[i][2][p_comp[i]] for i in group), group[0], True,
-                      sum(ahead(i) for i in group)))
+    def ahead(i):       # unscaled recomputation between the pointers
+        return sum(units[i][3][front[i]:p_io[i] + 1])
 
     def before(x, y):
         if order == ORDER_SHORTEST:
@@ -513,20 +524,54 @@ def dynamic_claim(cm, opts, n_ctx, p_comp, p_io, closed=None, io_backlog=0, scal
                 return -1 if lhs < rhs else 1
         return (x[2] > y[2]) - (x[2] < y[2])
 
-    cands.sort(key=cmp_to_key(before))
-    take = [0] * b_req
-    a_sum, b_sum = step_fixed, 0
-    group_taken = False
-    for a, b, first, is_group, _ in cands:
-        if step_cap > 0 and a_sum >= step_cap and a_sum > step_fixed:
-            break
-        if a_sum + a + compute_later <= r_total - b_sum:
-            a_sum += a
-            b_sum += b
-            if is_group:
-                group_taken = True
+    def greedy(cap, limit, group_depth):
+        """One pass of the rule.  group_depth: how many layers of the layer-wise group a pass may
+        take (a step runs one; the contention test looks at everything the engine would take)."""
+        nonlocal front
+        front = list(p_comp)
+        take = [0] * b_req
+        a_sum, b_sum = step_fixed, 0
+        out = set()                            # requests (or the group's first member) that failed
+        g_taken = 0
+        g_open = bool(group)
+        while True:
+            if cap > 0 and a_sum >= cap and a_sum > step_fixed:
+                break
+            cands = [(units[i][1][front[i]], units[i][2][front[i]], i, False, ahead(i))
+                     for i in open_ if units[i][0] == TOKEN_WISE and i not in out and front[i] <= p_io[i]
+                     and (limit <= 0 or take[i] < limit)]
+            if g_open and g_taken < group_depth and all(p_comp[i] + g_taken <= p_io[i] for i in group):
+                cands.append((sum(units[i][1][p_comp[i] + g_taken] for i in group),
+                              sum(units[i][2][p_comp[i] + g_taken] for i in group), group[0], True,
+                              sum(sum(units[i][3][p_comp[i] + g_taken:p_io[i] + 1]) for i in group)))
+            if not cands:
+                break
+            cands.sort(key=cmp_to_key(before))
+            a, b, first, is_group, _ = cands[0]
+            if a_sum + a + compute_later <= r_total - b_sum:
+                a_sum += a
+                b_sum += b
+                if is_group:
+                    g_taken += 1
+                else:
+                    take[first] += 1
+                    front[first] += 1
+            elif is_group:
+                g_open = False
             else:
-                take[first] = 1
+                out.add(first)
+        return take, a_sum, b_sum, g_taken
+
+    if io_alone > 0:
+        # everything the compute engine would take from here on, steps and unit limits aside
+        _, a_all, b_all, g_all = greedy(0, 0, 1 << 30)
+        if a_all > step_fixed or g_all:
+            alone = _scaled_units(cm, opts, n_ctx, scale_c, io_alone)
+            r_alone = io_backlog + sum(sum(alone[i][2][p_comp[i]:p_io[i] + 1]) for i in live)
+            if max(a_all + compute_later, r_total - b_all) >= max(step_fixed + compute_later, r_alone):
+                return [0] * b_req, step_fixed
+    take, a_sum, b_sum, g_taken = greedy(step_cap, max_units, 1)
+    group_taken = g_taken > 0
     if group_taken:
         more = all(p_comp[i] + 1 <= p_io[i] for i in group)
         if more:

@@ -95,7 +95,8 @@ class cf_timing(C.Structure):
 class cf_dynamic_stats(C.Structure):
     _fields_ = [("compute_steps", C.c_int32), ("compute_units", C.c_int32), ("io_units", C.c_int32),
                 ("scale_c_permille", C.c_int32), ("scale_io_permille", C.c_int32),
-                ("planned_tail", C.c_int32), ("compute_gap_ms", C.c_double)]
+                ("scale_io_alone_permille", C.c_int32), ("planned_tail", C.c_int32),
+                ("last_step_merged", C.c_int32), ("compute_gap_ms", C.c_double)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -124,7 +125,8 @@ PLAN_HYBRID, PLAN_ALL_LOAD, PLAN_ALL_RECOMPUTE = 0, 1, 2
 
 
 class cf_dynamic_opts(C.Structure):
-    _fields_ = [("step_cap_ps", C.c_int64), ("order", C.c_int32), ("reserved", C.c_int32)]
+    _fields_ = [("step_cap_ps", C.c_int64), ("order", C.c_int32), ("units_per_request", C.c_int32),
+                ("overlap_comp_permille", C.c_int32), ("overlap_io_permille", C.c_int32)]
 
 
 ORDER_CHEAPEST, ORDER_SHORTEST = 0, 1
@@ -164,7 +166,7 @@ lib.cf_dynamic_io_pick.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int3
 lib.cf_dynamic_claim.argtypes = [_P(cf_cost_model), _P(cf_plan_opts), C.c_int32, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                  C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
-                                 C.c_void_p, _P(C.c_int64)]
+                                 C.c_int32, C.c_int32, C.c_void_p, _P(C.c_int64)]
 lib.cf_cache_create.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                 _P(C.c_void_p)]
 lib.cf_cache_destroy.argtypes = [C.c_void_p]
@@ -345,7 +347,7 @@ def dynamic_io_pick(cost, opts, n_ctx, p_comp, p_io, closed=None, io_backlog_ps=
 
 def dynamic_claim(cost, opts, n_ctx, p_comp, p_io, closed=None, io_backlog_ps=0,
                   scale_c_permille=1000, scale_io_permille=1000, step_fixed_ps=0, step_cap_ps=0,
-                  order=0, compute_later_ps=0):
+                  order=0, compute_later_ps=0, max_units=1, io_alone_permille=0):
     """-> (take list, predicted step ps)"""
     n, pc, pio = _i32(n_ctx), _i32(p_comp), _i32(p_io)
     cl = _closed(closed, len(n))
@@ -354,8 +356,8 @@ def dynamic_claim(cost, opts, n_ctx, p_comp, p_io, closed=None, io_backlog_ps=0,
     _check(lib.cf_dynamic_claim(C.byref(cost), C.byref(opts), len(n), n.ctypes.data, pc.ctypes.data,
                                 pio.ctypes.data, cl.ctypes.data, int(io_backlog_ps),
                                 int(step_fixed_ps), int(compute_later_ps), int(step_cap_ps), int(order),
-                                int(scale_c_permille), int(scale_io_permille), take.ctypes.data,
-                                C.byref(ps)), "cf_dynamic_claim")
+                                int(scale_c_permille), int(scale_io_permille), int(max_units),
+                                int(io_alone_permille), take.ctypes.data, C.byref(ps)), "cf_dynamic_claim")
     return [int(t) for t in take[:len(n)]], ps.value
 
 
@@ -503,7 +505,7 @@ class Ctx:
         return tm.as_dict()
 
     def restore_dynamic(self, cache, requests, cost, opts, logits_ptr, step_cap_ps=0,
-                        order=ORDER_CHEAPEST):
+                        order=ORDER_CHEAPEST, units_per_request=0, overlap=None):
         """Run-time scheduled restore.  Returns (splits [(mode,k,cut)], timing dict, stats dict)."""
         b = len(requests)
         keep = []
@@ -518,7 +520,9 @@ class Ctx:
         sp = (cf_split * max(b, 1))()
         tm = cf_timing()
         st = cf_dynamic_stats()
-        dyn = cf_dynamic_opts(int(step_cap_ps), int(order), 0)
+        dyn = cf_dynamic_opts(int(step_cap_ps), int(order), int(units_per_request),
+                              overlap.comp_permille if overlap is not None else 0,
+                              overlap.io_permille if overlap is not None else 0)
         _check(lib.cf_restore_dynamic(self.handle, cache.handle, b, arr, C.byref(cost), C.byref(opts),
                                       C.byref(dyn), logits_ptr or None, sp, C.byref(tm), C.byref(st)),
                "cf_restore_dynamic")

@@ -132,7 +132,9 @@ struct cf_ctx {
     std::vector<hipEvent_t> ev_wait;  // compute stream: before / after its wait for layer l's loads (2 per layer)
     std::vector<char> waited;         // layers whose wait was recorded in the current call
     std::vector<hipEvent_t> dyn_events;   // run-time scheduler: loads in flight + the compute step
-    int dyn_scale_c = 1000, dyn_scale_io = 1000;   // measured/predicted ratios carried from call to call
+    // run-time scheduler: ratios measured / predicted carried from call to call -- the compute
+    // engine's, the channel's beside a recomputing engine, the channel's on its own
+    int dyn_scale_c = 1000, dyn_scale_io = 1000, dyn_scale_io_alone = 1000;
     int n_last = 0;                   // requests whose final hidden row the last call left in h_last
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
@@ -763,6 +765,55 @@ struct DmaOp {                // a run of whole pages that is contiguous in the 
     size_t bytes;
 };
 constexpr size_t DMA_MIN_BYTES = (size_t)4 << 20;   // shorter transfers do not reach link speed
+
+// The load of tokens [lo, hi) of one request in one layer, split by engine.  Whole pages whose
+// pool slots are consecutive (the usual case: the allocator hands out the lowest free ids in
+// order) go as ONE DMA transfer straight into the pool -- no kernel, no compute unit taken from
+// the GEMMs running beside the loads -- when `use_dma` and the transfer is long enough to reach
+// link speed.  A first page that is only partly loaded (unaligned split), a last page whose tail
+// slots are not part of the range, and short or scattered runs go through the load kernel, which
+// writes slot by slot.  host_dev_layer / host_layer: page 0 of this layer in the request's host
+// block, as the device and as the host address it; pool_layer: page 0 of the layer in the pool.
+void split_load_run(std::vector<PageJob>& jobs, std::vector<DmaOp>& dma, LayerLoad& ll, const int32_t* pt_i,
+                    int pt_off_i, const char* host_dev_layer, const char* host_layer, char* pool_layer,
+                    size_t pb, int model_layer, int lo, int hi, bool use_dma) {
+    const int j = lo / CF_PAGE_TOKENS, j1 = (int)ceil_div(hi, CF_PAGE_TOKENS);
+    auto kernel_job = [&](int ja, int jb) {      // pages [ja, jb) through the load kernel
+        if (jb <= ja) return;
+        PageJob job;
+        job.staging_off = (int64_t)(uintptr_t)(host_dev_layer + (size_t)ja * pb);
+        job.layer = model_layer;
+        job.pt_off = pt_off_i;
+        job.page_first = ja;
+        job.n_pages = jb - ja;
+        job.tok_first = std::max(lo, ja * CF_PAGE_TOKENS);
+        job.tok_end = std::min(hi, jb * CF_PAGE_TOKENS);
+        job.block_first = ll.n_vblocks;
+        job.pad = 0;
+        jobs.push_back(job);
+        ++ll.n_jobs;
+        ll.n_vblocks += (int)ceil_div((int64_t)(jb - ja) * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
+    };
+    int ja = j, jb = j1, kfirst = j;              // [kfirst, .) accumulates kernel pages
+    if (use_dma) {
+        if (lo % CF_PAGE_TOKENS != 0) ++ja;
+        if (hi % CF_PAGE_TOKENS != 0) --jb;
+        for (int p0 = ja; p0 < jb;) {
+            int p1 = p0 + 1;
+            while (p1 < jb && pt_i[p1] == pt_i[p1 - 1] + 1) ++p1;
+            const size_t seg = (size_t)(p1 - p0) * pb;
+            if (seg >= DMA_MIN_BYTES) {
+                kernel_job(kfirst, p0);
+                kfirst = p1;
+                dma.push_back(DmaOp{pool_layer + (size_t)pt_i[p0] * pb, host_layer + (size_t)p0 * pb, seg});
+                ++ll.n_dma;
+            }
+            p0 = p1;
+        }
+    }
+    kernel_job(kfirst, j1);
+    ll.bytes += (size_t)(j1 - j) * pb;
+}
 struct SlotPlan {
     int slot;
     int op_first, n_ops;
@@ -1006,51 +1057,10 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
                 if (layer_loads.empty() || layer_loads.back().layer != l)
                     layer_loads.push_back(LayerLoad{l, (int)jobs.size(), 0, 0, 0, (int)dma_ops.size(), 0});
                 LayerLoad& ll = layer_loads.back();
-                const char* host_run = host_dev[i] + (size_t)(Lb + l) * np_ctx * pb;     // page 0 of this layer
-                auto kernel_job = [&](int ja, int jb) {      // pages [ja, jb) through the load kernel
-                    if (jb <= ja) return;
-                    PageJob job;
-                    job.staging_off = (int64_t)(uintptr_t)(host_run + (size_t)ja * pb);
-                    job.layer = Lb + l;
-                    job.pt_off = pt_off[i];
-                    job.page_first = ja;
-                    job.n_pages = jb - ja;
-                    job.tok_first = std::max(lo, ja * CF_PAGE_TOKENS);
-                    job.tok_end = std::min(hi, jb * CF_PAGE_TOKENS);
-                    job.block_first = ll.n_vblocks;
-                    job.pad = 0;
-                    jobs.push_back(job);
-                    ++ll.n_jobs;
-                    ll.n_vblocks += (int)ceil_div((int64_t)(jb - ja) * (int64_t)(pb / 16), PAGE_LOAD_UNIT_VECS);
-                };
-                // Whole pages whose pool slots are consecutive (the usual case: the allocator hands
-                // out the lowest free ids in order) go as ONE DMA transfer straight into the pool --
-                // no kernel, no compute unit taken from the GEMMs running beside the loads -- when
-                // the transfer is long enough to reach link speed.  A first page that is only
-                // partly loaded (unaligned split) and a last page whose tail slots belong to the new
-                // turn go through the load kernel, which writes slot by slot; so do short or
-                // scattered runs.
-                const bool use_dma = c->load_path == 0;
-                int ja = j, jb = j1, kfirst = j;              // [kfirst, .) accumulates kernel pages
-                if (use_dma) {
-                    if (lo % CF_PAGE_TOKENS != 0) ++ja;
-                    if (hi % CF_PAGE_TOKENS != 0) --jb;
-                    for (int p0 = ja; p0 < jb;) {
-                        int p1 = p0 + 1;
-                        while (p1 < jb && pt[i][p1] == pt[i][p1 - 1] + 1) ++p1;
-                        const size_t seg = (size_t)(p1 - p0) * pb;
-                        if (seg >= DMA_MIN_BYTES) {
-                            kernel_job(kfirst, p0);
-                            kfirst = p1;
-                            char* dst = (char*)cache->pool + ((size_t)(Lb + l) * cache->n_pages + pt[i][p0]) * pb;
-                            dma_ops.push_back(DmaOp{dst, (const char*)reqs[i].host_kv + ((size_t)(Lb + l) * np_ctx + p0) * pb, seg});
-                            ++ll.n_dma;
-                        }
-                        p0 = p1;
-                    }
-                }
-                kernel_job(kfirst, j1);
-                ll.bytes += (size_t)(j1 - j) * pb;
+                split_load_run(jobs, dma_ops, ll, pt[i], pt_off[i], host_dev[i] + (size_t)(Lb + l) * np_ctx * pb,
+                               (const char*)reqs[i].host_kv + (size_t)(Lb + l) * np_ctx * pb,
+                               (char*)cache->pool + (size_t)(Lb + l) * cache->n_pages * pb, pb, Lb + l, lo, hi,
+                               c->load_path == 0);
                 loaded_bytes += (int64_t)(j1 - j) * pb;
                 continue;
             }
@@ -1324,9 +1334,14 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
 // and gives the compute stream one step at a time.
 namespace {
 
-struct DynUnitLoad {          // one I/O unit = one load-kernel launch
+struct DynUnitLoad {          // one I/O unit: the jobs of its load-kernel launch, and whether DMA can move it
     int job_first, n_jobs, n_vblocks;
     size_t bytes;
+    // token-wise units: pages [page_first, page_first + n_pages) of the request per layer;
+    // dma_ok: whole pages with consecutive pool ids (one transfer per layer can carry them);
+    // joins_prev: the pool id of its first page follows the last page of the unit before it
+    int page_first = 0, n_pages = 0;
+    bool dma_ok = false, joins_prev = false;
 };
 
 double now_ms() {
@@ -1354,8 +1369,17 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     const size_t es = elem_bytes(m.dtype), pb = cache->page_bytes;
     const int64_t step_cap = dyn ? dyn->step_cap_ps : 0;
     const int32_t order = dyn ? dyn->order : CF_ORDER_CHEAPEST;
-    if (dyn && (dyn->step_cap_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST)))
-        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: bad step cap or claim order");
+    const int32_t units_cap = dyn ? dyn->units_per_request : 0;
+    if (dyn && (dyn->step_cap_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST) ||
+                dyn->units_per_request < 0 || dyn->overlap_comp_permille < 0 || dyn->overlap_io_permille < 0))
+        return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: bad step cap, claim order, unit limit or overlap factor");
+    if (dyn && (dyn->overlap_comp_permille > 0 || dyn->overlap_io_permille > 0)) {
+        // the overlap model says how much slower each engine runs beside the other: the ratios
+        // measured / predicted of the side-by-side case restart from there, the channel's own at 1
+        c->dyn_scale_c = dyn->overlap_comp_permille > 0 ? dyn->overlap_comp_permille : 1000;
+        c->dyn_scale_io = dyn->overlap_io_permille > 0 ? dyn->overlap_io_permille : 1000;
+        c->dyn_scale_io_alone = 1000;
+    }
     if (C <= 0 || C % CF_PAGE_TOKENS != 0)
         return fail(CF_ERR_INVALID_ARG, "cf_restore_dynamic: chunk_tokens must be a positive multiple of %d",
                     CF_PAGE_TOKENS);
@@ -1507,6 +1531,12 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 DynUnitLoad ul{(int)jobs.size(), 0, 0, 0};
                 int lo = u * C, hi = std::min(n_ctx[i], lo + C);
                 for (int l = 0; l < L; ++l) add_job(ul, i, l, lo, hi);
+                ul.page_first = lo / CF_PAGE_TOKENS;
+                ul.n_pages = (int)ceil_div(hi, CF_PAGE_TOKENS) - ul.page_first;
+                ul.dma_ok = c->load_path == 0 && hi % CF_PAGE_TOKENS == 0;
+                for (int pg = ul.page_first + 1; ul.dma_ok && pg < ul.page_first + ul.n_pages; ++pg)
+                    ul.dma_ok = pt[i][pg] == pt[i][pg - 1] + 1;
+                ul.joins_prev = ul.page_first > 0 && pt[i][ul.page_first] == pt[i][ul.page_first - 1] + 1;
                 tw_units[i].push_back(ul);
             }
         } else {
@@ -1539,10 +1569,13 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     // so that the claim is made as late as possible)
     constexpr int IO_DEPTH = 8;
     constexpr int64_t IO_LOOKAHEAD_PS = 4000000000;
+    constexpr size_t IO_MERGE_BYTES = (size_t)256 << 20;
+    constexpr size_t IO_MERGE_RUN_BYTES = (size_t)8 << 20;
     // events [0, IO_DEPTH): end of the load in that slot; [IO_DEPTH]: the compute step;
     // (IO_DEPTH, 2 IO_DEPTH]: start of the load in that slot (its duration is read on the GPU's
     // clock: the host sees completions late whenever it is busy enqueuing a step)
-    while ((int)c->dyn_events.size() < 2 * IO_DEPTH + 1) {
+    // [2 IO_DEPTH + 1]: start of the planned tail's loads
+    while ((int)c->dyn_events.size() < 2 * IO_DEPTH + 2) {
         hipEvent_t e = nullptr;
         CF_HIP(hipEventCreate(&e));
         c->dyn_events.push_back(e);
@@ -1550,6 +1583,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     hipEvent_t ev_step = c->dyn_events[IO_DEPTH];
 
     char* md = c->meta_dev();
+    std::fill(c->waited.begin(), c->waited.end(), 0);
     CF_HIP(hipEventRecord(c->ev_start, c->cs));
     CF_HIP(hipMemcpyAsync(md, c->meta_host, step_off, hipMemcpyHostToDevice, c->cs));
     CF_HIP(hipEventRecord(c->ev_meta, c->cs));
@@ -1578,18 +1612,26 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     // A request whose cache is complete (pointers crossed, its loads landed, its last recompute
     // step done) has its new-turn rows prefilled in the next compute step, beside whatever else
     // that step recomputes: the new turn of early finishers overlaps the loads of the others.
-    struct Flight { int64_t pred_ps; int req; double t_issue; };  // req: the token-wise request, or -1 = layer-wise group
+    // req: the token-wise request, or -1 = layer-wise group; beside: issued while a recompute step ran
+    struct Flight { int64_t pred_ps; int req; double t_issue; bool beside; };
     std::deque<Flight> io_flight;                 // loads in flight, oldest first
     int64_t io_issued = 0, io_retired = 0;        // event of load k: dyn_events[k % IO_DEPTH]
-    int64_t io_pred_done = 0;                     // predicted ps of the retired loads
-    double io_t_last = 0, io_busy_ms = 0;         // host clock: latest completion; time the channel was busy
+    // predicted ps / measured ms of the retired loads, by whether a recompute step ran beside them
+    int64_t io_pred_beside = 0, io_pred_alone = 0;
+    double io_ms_beside = 0, io_ms_alone = 0;
+    double io_t_last = 0;                         // host clock: latest completion
     int64_t c_pred_done = 0, step_pred = 0;
     double c_meas_done_ms = 0, step_t0 = 0, gap_ms = 0, last_step_end = 0;
     bool step_running = false, ask = true;        // ask: state changed since the last declined claim
-    bool force_io = false, tail_ran = false;
+    bool step_has_rec = false;                    // the running step recomputes (contends with the channel)
+    bool force_io = false, tail_ran = false, merged_last = false;
+    bool tail_timed = false, tail_beside = false;
+    int64_t tail_pred = 0;                        // predicted ps of the planned tail's loads
     // the ratios measured / predicted start from what the previous call on this context saw
-    int scale_c = c->dyn_scale_c, scale_io = c->dyn_scale_io;
+    int scale_c = c->dyn_scale_c, scale_io = c->dyn_scale_io, scale_io_alone = c->dyn_scale_io_alone;
     int n_steps = 0, n_cunits = 0;
+    // the channel's scale as things stand: beside a recomputing step, or on its own
+    auto sio_now = [&]() { return step_has_rec ? scale_io : scale_io_alone; };
     int64_t loaded_bytes = 0;
     int lw_layer = 0;                             // next layer of the layer-wise group
     std::vector<uint8_t> closed(B, 0);
@@ -1633,21 +1675,29 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 (void)hipGetLastError();
                 load_ms = (float)(now_ms() - std::max(io_flight.front().t_issue, io_t_last));
             }
-            io_busy_ms += load_ms;
             io_t_last = now_ms();
-            io_pred_done += io_flight.front().pred_ps;
+            if (io_flight.front().beside || step_has_rec) {
+                io_ms_beside += load_ms;
+                io_pred_beside += io_flight.front().pred_ps;
+                if (io_pred_beside > 0 && io_ms_beside > 0)
+                    scale_io = clamp_scale(io_ms_beside * 1e9 / (double)io_pred_beside);
+            } else {
+                io_ms_alone += load_ms;
+                io_pred_alone += io_flight.front().pred_ps;
+                if (io_pred_alone > 0 && io_ms_alone > 0)
+                    scale_io_alone = clamp_scale(io_ms_alone * 1e9 / (double)io_pred_alone);
+            }
             int r = io_flight.front().req;
             if (r >= 0) --io_pending[r];
             else for (int i : lw_members) --io_pending[i];
             io_flight.pop_front();
             ++io_retired;
-            if (io_pred_done > 0 && io_busy_ms > 0)
-                scale_io = clamp_scale(io_busy_ms * 1e9 / (double)io_pred_done);
             changed = 1;
         }
         while ((int)io_flight.size() < IO_DEPTH) {
+            const int sio = sio_now();
             int64_t backlog = 0;
-            for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * scale_io / 1000);
+            for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * sio / 1000);
             if (!io_flight.empty() && backlog >= IO_LOOKAHEAD_PS) break;
             int64_t busy = 0;
             if (step_running)
@@ -1657,26 +1707,75 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             force_io = false;
             int32_t pick = -1;
             cf_dynamic_io_pick(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
-                               busy, scale_c, scale_io, &pick);
+                               busy, scale_c, sio, &pick);
             if (pick < 0) break;
-            const DynUnitLoad* ul;
+            // A token-wise claim grows by the units below it, as long as the same test keeps
+            // naming the same request, up to IO_MERGE_BYTES: long runs of consecutive pages
+            // can go by DMA, and either way the channel runs at link speed only on long transfers.
+            std::vector<int> us;                  // token-wise: the units of this claim, far end first
+            size_t bytes = 0;
+            int64_t pred = 0;
             int who;
             if (mode[pick] == CF_TOKEN_WISE) {
-                ul = &tw_units[pick][p_io[pick]];
-                --p_io[pick];
-                ++io_pending[pick];
                 who = pick;
+                while (true) {
+                    const DynUnitLoad& u = tw_units[pick][p_io[pick]];
+                    us.push_back(p_io[pick]);
+                    --p_io[pick];
+                    bytes += u.bytes;
+                    pred += unit_load_ps(u.bytes);
+                    // long enough as a whole, and per layer (a unit's bytes are spread over L runs)
+                    if ((bytes >= IO_MERGE_BYTES && bytes >= (size_t)L * IO_MERGE_RUN_BYTES) ||
+                        bytes >= 4 * IO_MERGE_BYTES || p_comp[pick] > p_io[pick])
+                        break;
+                    int32_t again = -1;
+                    cf_dynamic_io_pick(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(),
+                                       backlog + (int64_t)((__int128)pred * sio / 1000), busy, scale_c, sio, &again);
+                    if (again != pick) break;
+                }
+                ++io_pending[pick];
             } else {
-                ul = &lw_units[p_io[pick]];
-                for (int i : lw_members) { --p_io[i]; ++io_pending[i]; }
+                bytes = lw_units[p_io[pick]].bytes;
+                pred = unit_load_ps(bytes);
+                for (int i : lw_members) ++io_pending[i];
                 who = -1;
             }
-            c->prof_begin(CF_K_H2D_COPY, (double)ul->bytes, c->ps);
+            c->prof_begin(CF_K_H2D_COPY, (double)bytes, c->ps);
             if (hipEventRecord(c->dyn_events[IO_DEPTH + 1 + io_issued % IO_DEPTH], c->ps) != hipSuccess) return -1;
-            launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ul->job_first,
-                             ul->n_jobs, ul->n_vblocks, c->load_wgs, (const int32_t*)md, g);
+            auto kernel_load = [&](const DynUnitLoad& ul) {
+                launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ul.job_first,
+                                 ul.n_jobs, ul.n_vblocks, c->load_wgs, (const int32_t*)md, g);
+            };
+            if (who >= 0) {
+                // bottom unit first; consecutive units whose pages follow one another in the pool
+                // form one run: a transfer per layer if that is long enough, else their kernels
+                const int np_ctx = (int)ceil_div(n_ctx[pick], CF_PAGE_TOKENS);
+                for (size_t k = us.size(); k > 0;) {
+                    const DynUnitLoad& first = tw_units[pick][us[k - 1]];
+                    size_t e = k - 1;             // the run is us[e .. k-1], ascending as e falls
+                    int pages = first.n_pages;
+                    if (first.dma_ok)
+                        while (e > 0 && tw_units[pick][us[e - 1]].dma_ok && tw_units[pick][us[e - 1]].joins_prev) {
+                            --e;
+                            pages += tw_units[pick][us[e]].n_pages;
+                        }
+                    if (first.dma_ok && (size_t)pages * pb >= DMA_MIN_BYTES) {
+                        for (int l = 0; l < L; ++l)
+                            if (hipMemcpyAsync((char*)cache->pool + ((size_t)l * cache->n_pages + pt[pick][first.page_first]) * pb,
+                                               (const char*)reqs[pick].host_kv + ((size_t)l * np_ctx + first.page_first) * pb,
+                                               (size_t)pages * pb, hipMemcpyHostToDevice, c->ps) != hipSuccess)
+                                return -1;
+                    } else {
+                        for (size_t q = k; q > e; --q) kernel_load(tw_units[pick][us[q - 1]]);
+                    }
+                    k = e;
+                }
+            } else {
+                kernel_load(lw_units[p_io[pick]]);
+                for (int i : lw_members) --p_io[i];
+            }
             if (c->throttle_gbs > 0) {
-                paced_bytes += (double)ul->bytes;
+                paced_bytes += (double)bytes;
                 launch_pace_wait(c->ps, c->pace_dev(),
                                  (unsigned long long)(paced_bytes / (c->throttle_gbs * 1e9) * c->wall_hz));
             }
@@ -1684,8 +1783,8 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             if (hipEventRecord(c->dyn_events[io_issued % IO_DEPTH], c->ps) != hipSuccess ||
                 hipEventRecord(c->ev_copy, c->ps) != hipSuccess)       // the latest record stands
                 return -1;
-            io_flight.push_back(Flight{unit_load_ps(ul->bytes), who, now_ms()});
-            loaded_bytes += (int64_t)ul->bytes;
+            io_flight.push_back(Flight{pred, who, now_ms(), step_has_rec});
+            loaded_bytes += (int64_t)bytes;
             ++io_issued;
             changed = 1;
         }
@@ -1693,29 +1792,61 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     };
     std::function<int()> between_layers = [&]() { return pump_io() < 0 ? -1 : 0; };
 
+    // Recompute segments of a step: take[i] consecutive chunks of token-wise request i, from its
+    // compute pointer on, as one segment; the pointer moves past them.
+    auto add_recompute = [&](Phase& step, std::vector<int32_t>& ids, std::vector<int32_t>& pos,
+                             std::vector<int32_t>& slot, const std::vector<int32_t>& tk) {
+        bool any = false;
+        for (int i = 0; i < B; ++i) {
+            if (!tk[i] || mode[i] != CF_TOKEN_WISE) continue;
+            const int lo = p_comp[i] * C, hi = std::min(n_ctx[i], lo + tk[i] * C);
+            add_segment(step, ids, pos, slot, i, reqs[i].ctx_tokens + lo, hi - lo, lo, L, false);
+            p_comp[i] += tk[i];
+            n_cunits += tk[i];
+            in_step[i] = 1;
+            any = true;
+        }
+        return any;
+    };
+
     // The planned tail.  Once the compute engine will take nothing more, the schedule is known,
     // so the rest is laid out like a planned restore: the channel gets every unclaimed cell,
     // layer by layer from the bottom with an event per layer, and the new turn of every request
     // not yet prefilled is enqueued right away (behind the running step, if there is one); its
     // attention in layer l waits for that layer's event only.  `fresh`: requests known to be
-    // restored already (merged into the list of all that are not prefilled).
-    auto launch_tail = [&](std::vector<int> fresh, int64_t pred_ps, bool behind_step) -> int {
+    // restored already (merged into the list of all that are not prefilled).  `last_take`: the
+    // units of the compute engine's last recompute step, when that step was recognised as the
+    // last before it was launched -- it then runs in the same pass as the new turns, the way a
+    // planned restore packs them.
+    auto launch_tail = [&](std::vector<int> fresh, int64_t pred_ps, bool behind_step,
+                           const std::vector<int32_t>* last_take) -> int {
         Phase step;
         std::vector<int32_t> ids, pos, slot, last_idx;
+        const bool with_rec = last_take && add_recompute(step, ids, pos, slot, *last_take);
         std::vector<PageJob> tjobs;
-        std::vector<DynUnitLoad> tlayers(L, DynUnitLoad{0, 0, 0, 0});
-        jobs.swap(tjobs);                         // add_job appends to `jobs`
+        std::vector<DmaOp> tdma;
+        std::vector<LayerLoad> tlayers(L);
         for (int l = 0; l < L; ++l) {
-            tlayers[l].job_first = (int)jobs.size();
+            tlayers[l] = LayerLoad{l, (int)tjobs.size(), 0, 0, 0, (int)tdma.size(), 0};
             for (int i = 0; i < B; ++i) {
                 if (p_comp[i] > p_io[i]) continue;
-                if (mode[i] == CF_TOKEN_WISE)
-                    add_job(tlayers[l], i, l, p_comp[i] * C, std::min(n_ctx[i], (p_io[i] + 1) * C));
-                else if (l >= p_comp[i] && l <= p_io[i])
-                    add_job(tlayers[l], i, l, 0, n_ctx[i]);
+                int lo, hi;
+                if (mode[i] == CF_TOKEN_WISE) {
+                    lo = p_comp[i] * C;
+                    hi = std::min(n_ctx[i], (p_io[i] + 1) * C);
+                } else if (l >= p_comp[i] && l <= p_io[i]) {
+                    lo = 0;
+                    hi = n_ctx[i];
+                } else {
+                    continue;
+                }
+                const int np_ctx = (int)ceil_div(n_ctx[i], CF_PAGE_TOKENS);
+                split_load_run(tjobs, tdma, tlayers[l], pt[i], pt_off[i], host_dev[i] + (size_t)l * np_ctx * pb,
+                               (const char*)reqs[i].host_kv + (size_t)l * np_ctx * pb,
+                               (char*)cache->pool + (size_t)l * cache->n_pages * pb, pb, l, lo, hi,
+                               c->load_path == 0);
             }
         }
-        jobs.swap(tjobs);
         for (int i = 0; i < B; ++i) {
             if (p_comp[i] <= p_io[i]) p_io[i] = p_comp[i] - 1;     // claimed by the channel
             if (prefilled[i]) continue;
@@ -1741,11 +1872,27 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                                   hipMemcpyHostToDevice, c->ps));
         CF_HIP(hipMemcpyAsync(md + off_rows, c->meta_host + off_rows, mw.off - off_rows,
                               hipMemcpyHostToDevice, c->cs));
+        // Layer l's loads go onto the copy stream right before layer l's kernels go onto the
+        // compute stream (a layer's event is recorded before anything waits for it; the host,
+        // which issues a transfer per request and layer, never holds the compute stream back).
         std::vector<hipEvent_t> ready(L);
-        for (int l = 0; l < L; ++l) {
-            const DynUnitLoad& tl = tlayers[l];
-            if (tl.n_jobs > 0) {
+        for (int l = 0; l < L; ++l) ready[l] = c->ev_layer[l];
+        int tail_next = 0;
+        auto feed_layer = [&]() -> int {
+            if (tail_next >= L) return 0;
+            if (tail_next == 0) {
+                // the tail's loads are timed as one: from here to the copy stream's end
+                if (hipEventRecord(c->dyn_events[2 * IO_DEPTH + 1], c->ps) != hipSuccess) return -1;
+                tail_timed = true;
+                tail_beside = step_has_rec || with_rec;
+            }
+            const LayerLoad& tl = tlayers[tail_next];
+            if (tl.n_jobs > 0 || tl.n_dma > 0) {
                 c->prof_begin(CF_K_H2D_COPY, (double)tl.bytes, c->ps);
+                for (int k = 0; k < tl.n_dma; ++k) {
+                    const DmaOp& op = tdma[tl.dma_first + k];
+                    if (hipMemcpyAsync(op.dst, op.src, op.bytes, hipMemcpyHostToDevice, c->ps) != hipSuccess) return -1;
+                }
                 launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs) + tl.job_first,
                                  tl.n_jobs, tl.n_vblocks, c->load_wgs, (const int32_t*)md, g);
                 if (c->throttle_gbs > 0) {
@@ -1755,13 +1902,15 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 }
                 c->prof_end(CF_K_H2D_COPY, c->ps);
                 loaded_bytes += (int64_t)tl.bytes;
+                tail_pred += unit_load_ps(tl.bytes);
                 ++io_issued;
             }
             // behind everything the copy stream was given so far, units in flight included
-            CF_HIP(hipEventRecord(c->ev_layer[l], c->ps));
-            ready[l] = c->ev_layer[l];
-        }
-        CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+            if (hipEventRecord(c->ev_layer[tail_next], c->ps) != hipSuccess) return -1;
+            ++tail_next;
+            return 0;
+        };
+        const std::function<int()> feed = [&]() -> int { return (pump_io() < 0 || feed_layer() < 0) ? -1 : 0; };
         if (!behind_step) {
             double t_launch = now_ms();
             if (n_steps > 0) gap_ms += t_launch - last_step_end;
@@ -1771,8 +1920,13 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         }
         step_pred += pred_ps;
         step_running = true;
-        int rc2 = run_phase(c, cache, step, L, ready.data(), nullptr, 0, lw.T, nullptr);
+        step_has_rec = step_has_rec || with_rec;
+        int rc2 = run_phase(c, cache, step, L, ready.data(), nullptr, 0, lw.T, &feed);
         if (rc2) return bail(rc2);
+        while (tail_next < L)
+            if (feed_layer() < 0) return bail(fail(CF_ERR_HIP, "cf_restore_dynamic: enqueuing a load failed"));
+        CF_HIP(hipEventRecord(c->ev_copy, c->ps));
+        if (with_rec) CF_HIP(hipEventRecord(c->ev_comp, c->cs));
         // final norm of every request's last row into its LM-head slot (last_idx[k] belongs to
         // fresh[k]); the last layer's down-proj result is still pending in dl
         for (size_t k = 0; k < fresh.size(); ++k) {
@@ -1789,8 +1943,12 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         }
         CF_HIP(hipEventRecord(ev_step, c->cs));   // the running step, if any, now ends here
         tail_ran = true;
+        merged_last = merged_last || with_rec;
         return CF_OK;
     };
+
+    // rows a step may hold beside the layer-wise group's and every request's new turn
+    const int64_t step_rows_cap = (int64_t)c->opts.max_tokens - lw.T - sum_new;
 
     while (true) {
         bool progressed = false;
@@ -1806,6 +1964,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             c_pred_done += step_pred;
             if (c_pred_done > 0) scale_c = clamp_scale(c_meas_done_ms * 1e9 / (double)c_pred_done);
             step_running = false;
+            step_has_rec = false;
             std::fill(in_step.begin(), in_step.end(), 0);
             progressed = ask = true;
         }
@@ -1833,36 +1992,75 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 fixed += floor_ps;
                 if (later > 0) later += floor_ps;
             }
+            // the channel is priced as it runs beside a recomputing engine; what the units must
+            // beat is the channel on its own
             int64_t backlog = 0, pred = 0;
             for (const Flight& f : io_flight) backlog += (int64_t)((__int128)f.pred_ps * scale_io / 1000);
             cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(), backlog,
-                             fixed, later, step_cap, order, scale_c, scale_io, take.data(), &pred);
+                             fixed, later, step_cap, order, scale_c, scale_io, units_cap, scale_io_alone,
+                             take.data(), &pred);
+            // a step holds no more rows than the workspace has for it: the rest stays unclaimed
+            {
+                int64_t rows = 0;
+                for (int i = 0; i < B; ++i) {
+                    if (!take[i] || mode[i] != CF_TOKEN_WISE) continue;
+                    const int lo = p_comp[i] * C;
+                    while (take[i] > 0 && rows + std::min(n_ctx[i], lo + take[i] * C) - lo > step_rows_cap) --take[i];
+                    if (take[i] > 0) rows += std::min(n_ctx[i], lo + take[i] * C) - lo;
+                }
+            }
             Phase step;
             std::vector<int32_t> ids, pos, slot, last_idx;
             bool lw_take = false, lw_last = false, any_rec = false, any_live = false;
             for (int i = 0; i < B; ++i) {
                 any_rec |= take[i] != 0;
                 any_live |= p_comp[i] <= p_io[i];
-            }
-            if (!any_rec && any_live && want_new) {
-                // idle and nothing worth taking: the rest is the channel's
-                int rc2 = launch_tail(fresh, fixed + later, false);
-                if (rc2) return bail(rc2);
-                continue;
-            }
-            for (int i = 0; i < B; ++i) {
-                if (!take[i]) continue;
-                in_step[i] = 1;
-                if (mode[i] == CF_TOKEN_WISE) {
-                    int lo = p_comp[i] * C, hi = std::min(n_ctx[i], lo + C);
-                    add_segment(step, ids, pos, slot, i, reqs[i].ctx_tokens + lo, hi - lo, lo, L, false);
-                    ++p_comp[i];
-                    ++n_cunits;
-                } else {
+                if (take[i] && mode[i] != CF_TOKEN_WISE) {
                     lw_take = true;
                     lw_last = take[i] == 2;
                 }
             }
+            if (!any_rec && any_live && want_new) {
+                // idle and nothing worth taking: the rest is the channel's
+                int rc2 = launch_tail(fresh, fixed + later, false, nullptr);
+                if (rc2) return bail(rc2);
+                continue;
+            }
+            // Will there be anything to take when this step is over?  Ask for the state it
+            // leaves behind, with the step's own duration counted as work still ahead (the
+            // channel keeps loading meanwhile).  If not, this is the last recompute step and the
+            // rest of the schedule is known now.  Without a layer-wise group the step then carries
+            // the planned tail itself: one pass holds the recompute rows and every outstanding
+            // new turn, beside the remaining loads laid out layer by layer.  With a group (whose
+            // rows keep their own place in the workspace) the tail follows as a pass of its own.
+            bool last_step = false;
+            if (any_rec && want_new) {
+                std::vector<int32_t> pc2(p_comp);
+                for (int i = 0; i < B; ++i)
+                    if (take[i]) pc2[i] += mode[i] == CF_TOKEN_WISE ? take[i] : 1;
+                bool live_left = false;
+                for (int i = 0; i < B; ++i)
+                    live_left |= pc2[i] <= p_io[i] && !(closed[i] || (mode[i] != CF_TOKEN_WISE && take[i] == 2));
+                last_step = true;
+                if (live_left) {
+                    std::vector<int32_t> take2(B, 0);
+                    std::vector<uint8_t> closed2(closed);
+                    for (int i = 0; i < B; ++i)
+                        if (take[i] == 2 && mode[i] != CF_TOKEN_WISE) closed2[i] = 1;
+                    cf_dynamic_claim(cost, opts, B, n_ctx.data(), pc2.data(), p_io.data(), closed2.data(), backlog,
+                                     0, later + pred, 0, order, scale_c, scale_io, units_cap, 0, take2.data(),
+                                     nullptr);
+                    for (int i = 0; i < B; ++i) last_step &= take2[i] == 0;
+                }
+            }
+            if (last_step && !lw_take && lw_members.empty()) {
+                std::fill(in_step.begin(), in_step.end(), 0);
+                int rc2 = launch_tail(fresh, pred + later, false, &take);
+                if (rc2) return bail(rc2);
+                progressed = true;
+                continue;
+            }
+            add_recompute(step, ids, pos, slot, take);
             for (int i : fresh) {               // packed after the recompute rows
                 add_segment(step, ids, pos, slot, i, reqs[i].new_tokens, reqs[i].n_new, n_ctx[i], L, true);
                 last_idx.push_back(step.T - 1);
@@ -1873,9 +2071,11 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 step_t0 = t_launch;
                 step_pred = pred;
                 step_running = true;            // pump_io (between layers) sees the step as running
+                step_has_rec = any_rec;
                 if (lw_take) {
                     // layer lw_layer of the group: in full if the group goes on, else up to its K/V write
                     for (Segment& sg : lw.segs) sg.layers = lw_layer + (lw_last ? 1 : 2);
+                    for (int i : lw_members) in_step[i] = 1;
                     int rc2 = run_phase(c, cache, lw, lw_layer + 1, nullptr, nullptr, lw_layer, 0, &between_layers);
                     if (rc2) return bail(rc2);
                     for (int i : lw_members) {
@@ -1914,27 +2114,12 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 if (any_rec) CF_HIP(hipEventRecord(c->ev_comp, c->cs));
                 ++n_steps;
                 progressed = true;
-                // Will there be anything to take when this step is over?  Ask for the state it
-                // leaves behind, with the step's own duration counted as work still ahead (the
-                // channel keeps loading meanwhile).  If not, this was the last recompute step:
-                // the rest is planned now and enqueued behind it, so that neither stream waits
-                // for the host to notice the step's end.
-                if (any_rec && want_new) {
-                    bool live_left = false;
-                    for (int i = 0; i < B; ++i) live_left |= p_comp[i] <= p_io[i];
-                    if (live_left) {
-                        int64_t later_all = later;       // new turns not in this step
-                        std::vector<int32_t> take2(B, 0);
-                        cf_dynamic_claim(cost, opts, B, n_ctx.data(), p_comp.data(), p_io.data(), closed.data(),
-                                         backlog, 0, later_all + pred, 0, order, scale_c, scale_io, take2.data(),
-                                         nullptr);
-                        bool any2 = false;
-                        for (int i = 0; i < B; ++i) any2 |= take2[i] != 0;
-                        if (!any2) {
-                            int rc3 = launch_tail({}, later_all, true);
-                            if (rc3) return bail(rc3);
-                        }
-                    }
+                // the last recompute step of a batch with a layer-wise group: the rest is planned
+                // now and enqueued behind it, so that neither stream waits for the host to notice
+                // the step's end
+                if (last_step) {
+                    int rc3 = launch_tail({}, later, true, nullptr);
+                    if (rc3) return bail(rc3);
                 }
             }
         }
@@ -1963,6 +2148,35 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     CF_HIP(hipStreamSynchronize(c->cs));
     CF_HIP(hipStreamSynchronize(c->ps));
     c->prof_collect();
+    // the time the compute stream stood waiting for a layer's loads (the pass that carried the
+    // planned tail) is not compute time: taken off before the ratio is carried to the next call
+    float wait_ms = 0;
+    for (int l = 0; l < L; ++l) {
+        if (!c->waited[l]) continue;
+        float w = 0;
+        if (hipEventElapsedTime(&w, c->ev_wait[2 * l], c->ev_wait[2 * l + 1]) == hipSuccess) wait_ms += w;
+        else (void)hipGetLastError();
+    }
+    if (tail_timed && tail_pred > 0) {
+        float t_tail = 0;
+        if (hipEventElapsedTime(&t_tail, c->dyn_events[2 * IO_DEPTH + 1], c->ev_copy) == hipSuccess && t_tail > 0) {
+            if (tail_beside) {
+                io_ms_beside += t_tail;
+                io_pred_beside += tail_pred;
+                scale_io = clamp_scale(io_ms_beside * 1e9 / (double)io_pred_beside);
+            } else {
+                io_ms_alone += t_tail;
+                io_pred_alone += tail_pred;
+                scale_io_alone = clamp_scale(io_ms_alone * 1e9 / (double)io_pred_alone);
+            }
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    if (wait_ms > 0 && c_pred_done > 0) {
+        c_meas_done_ms = std::max(0.0, c_meas_done_ms - wait_ms);
+        if (c_meas_done_ms > 0) scale_c = clamp_scale(c_meas_done_ms * 1e9 / (double)c_pred_done);
+    }
 
     // ---- what came out
     const double lin = linear_flops_per_token_layer(m);
@@ -2004,6 +2218,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         timing->restore_ms = std::max(t_comp, t_copy);
         timing->suffix_ms = t_end - timing->restore_ms;
         timing->total_ms = t_end;
+        timing->compute_wait_ms = wait_ms;
         timing->recompute_flops = fr;
         timing->suffix_flops = fs;
         timing->loaded_bytes = loaded_bytes;
@@ -2016,11 +2231,22 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         stats->io_units = (int32_t)io_issued;
         stats->scale_c_permille = scale_c;
         stats->scale_io_permille = scale_io;
+        stats->scale_io_alone_permille = scale_io_alone;
         stats->compute_gap_ms = gap_ms;
         stats->planned_tail = tail_ran ? 1 : 0;
+        stats->last_step_merged = merged_last ? 1 : 0;
     }
-    c->dyn_scale_c = scale_c;
-    c->dyn_scale_io = scale_io;
+    // What the next call starts from.  A call's ratio depends on how much it claimed (the cost
+    // model's error is not the same for every unit: a few more rows can cost the GEMMs a whole
+    // extra round of tiles), and the claim on the ratio, so a ratio taken over whole flips
+    // between a large and a small claim from call to call.  One unit too many on the compute
+    // engine costs a multiple of what one too few does (a chunk takes several times longer to
+    // recompute than to load), so its ratio follows a rise at once and a fall an eighth of the
+    // way; the channel's ratios move halfway.
+    if (c_pred_done > 0)
+        c->dyn_scale_c = scale_c >= c->dyn_scale_c ? scale_c : c->dyn_scale_c - (c->dyn_scale_c - scale_c) / 8;
+    if (io_pred_beside > 0) c->dyn_scale_io = (c->dyn_scale_io + scale_io + 1) / 2;
+    if (io_pred_alone > 0) c->dyn_scale_io_alone = (c->dyn_scale_io_alone + scale_io_alone + 1) / 2;
     return CF_OK;
 }
 

@@ -560,15 +560,16 @@ extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* o
                                 const uint8_t* compute_closed, int64_t io_backlog_ps,
                                 int64_t step_fixed_ps, int64_t compute_later_ps, int64_t step_cap_ps,
                                 int32_t order,
-                                int32_t scale_c_permille, int32_t scale_io_permille, int32_t* take,
-                                int64_t* step_ps) {
+                                int32_t scale_c_permille, int32_t scale_io_permille, int32_t max_units,
+                                int32_t io_alone_permille, int32_t* take, int64_t* step_ps) {
     DynState st;
     int rc = dyn_setup("cf_dynamic_claim", cost, opts, B, n_ctx, p_comp, p_io, io_backlog_ps, step_fixed_ps,
                        scale_c_permille, scale_io_permille, &st);
     if (rc) return rc;
     if (B > 0 && !take) return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: null take");
-    if (step_cap_ps < 0 || compute_later_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST))
-        return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: bad step cap, later work or order");
+    if (step_cap_ps < 0 || compute_later_ps < 0 || (order != CF_ORDER_CHEAPEST && order != CF_ORDER_SHORTEST) ||
+        max_units < 0 || io_alone_permille < 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_dynamic_claim: bad step cap, later work, order, unit limit or scale");
     const std::vector<Units>& req = st.req;
 
     // R: when the I/O channel would be done if the compute engine took nothing more
@@ -576,37 +577,30 @@ extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* o
     for (int i = 0; i < B; ++i)
         for (int u = p_comp[i]; u <= p_io[i]; ++u) R += st.sio(req[i].b[u]);
 
-    // candidates: the next unit of every open token-wise request, and the next layer of all
-    // open layer-wise requests together (they move through the layers as one packed batch)
-    struct Item { int first; bool group; int64_t a, b, rem; };   // rem: recomputation still ahead of it
-    std::vector<Item> items;
-    Item grp{-1, true, 0, 0, 0};
-    int64_t a_next = 0;                  // the group's unit after this one
+    // candidates: the next unit of every open token-wise request (behind the units the pass
+    // already holds of it), and the next layer of all open layer-wise requests together (they
+    // move through the layers as one packed batch; a step runs one layer of them)
+    std::vector<int> group;
     int64_t grp_full = 0, grp_kv = 0;    // what the group's layer costs to run in full / up to its K/V write
+    int64_t a_next = 0;
     bool has_next = true;
+    std::vector<char> cand(B, 0);        // open token-wise requests
     for (int i = 0; i < B; ++i) {
         take[i] = 0;
         if (p_comp[i] > p_io[i] || (compute_closed && compute_closed[i])) continue;
-        if (req[i].mode == CF_TOKEN_WISE) {
-            items.push_back(Item{i, false, st.sc(req[i].a(p_comp[i])), st.sio(req[i].b[p_comp[i]]),
-                                 req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[p_comp[i]]});
-        } else {
-            if (grp.first < 0) grp.first = i;
-            grp.rem += req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[p_comp[i]];
-            grp.a += st.sc(req[i].a(p_comp[i]));
-            grp.b += st.sio(req[i].b[p_comp[i]]);
-            int64_t full = layer_pass_cost(*cost, 1, n_ctx[i], 0);
-            grp_full += st.sc(full);
-            grp_kv += st.sc(opts->kv_only_permille > 0 ? kv_only_cost(*cost, opts->kv_only_permille, n_ctx[i]) : full);
-            if (p_comp[i] + 1 <= p_io[i]) a_next += st.sc(req[i].a(p_comp[i] + 1));
-            else has_next = false;
-        }
+        if (req[i].mode == CF_TOKEN_WISE) { cand[i] = 1; continue; }
+        group.push_back(i);
+        int64_t full = layer_pass_cost(*cost, 1, n_ctx[i], 0);
+        grp_full += st.sc(full);
+        grp_kv += st.sc(opts->kv_only_permille > 0 ? kv_only_cost(*cost, opts->kv_only_permille, n_ctx[i]) : full);
+        if (p_comp[i] + 1 <= p_io[i]) a_next += st.sc(req[i].a(p_comp[i] + 1));
+        else has_next = false;
     }
-    if (grp.first >= 0) items.push_back(grp);
     // CHEAPEST: least recomputation per unit of I/O time saved first (a1/b1 < a2/b2);
     // SHORTEST: least recomputation still ahead first, so that requests finish one after the
     // other and their new turns can start while the channel works on the long ones; then by index
-    std::stable_sort(items.begin(), items.end(), [order](const Item& x, const Item& y) {
+    struct Item { int first; bool group; int64_t a, b, rem; };
+    auto before = [order](const Item& x, const Item& y) {
         if (order == CF_ORDER_SHORTEST) {
             if (x.rem != y.rem) return x.rem < y.rem;
         } else {
@@ -614,32 +608,90 @@ extern "C" int cf_dynamic_claim(const cf_cost_model* cost, const cf_plan_opts* o
             if (l != r) return l < r;
         }
         return x.first < y.first;
-    });
-    // a candidate is taken if the step, with it -- and with compute_later_ps of work the
-    // compute engine has to do after the step in any case -- still ends no later than the
-    // channel would need for everything the step so far leaves to it
-    // (the step starts out with step_fixed_ps of work it carries in any case)
-    int64_t A = step_fixed_ps, Bs = 0;
-    bool grp_taken = false;
-    for (const Item& it : items) {
-        // a capped step stops growing once it is long enough (it always gets its first unit)
-        if (step_cap_ps > 0 && A >= step_cap_ps && A > step_fixed_ps) break;
-        if (A + it.a + compute_later_ps > R - Bs) continue;
-        A += it.a;
-        Bs += it.b;
-        if (it.group) grp_taken = true;
-        else take[it.first] = 1;
+    };
+    // One pass of the rule.  The best-ranked candidate is taken if the pass, with it -- and with
+    // compute_later_ps of work the compute engine has to do afterwards in any case -- still ends
+    // no later than the channel would need for everything the pass so far leaves to it (the
+    // pass starts out with step_fixed_ps of work it carries in any case); otherwise its request
+    // is out.  cap: the pass stops growing once it is this long (0: never; it always gets its
+    // first unit); limit: most units of one request (0: no limit); group_depth: how many layers
+    // of the layer-wise group the pass may take.
+    struct Pass { int64_t A, Bs; int g_taken; };
+    auto greedy = [&](int64_t cap, int limit, int group_depth, int32_t* tk) {
+        std::vector<int> front(p_comp, p_comp + B);
+        std::vector<char> out(B, 0);
+        std::vector<int32_t> n_taken(B, 0);
+        Pass ps{step_fixed_ps, 0, 0};
+        bool g_open = !group.empty();
+        while (true) {
+            if (cap > 0 && ps.A >= cap && ps.A > step_fixed_ps) break;
+            bool have = false;
+            Item best{};
+            for (int i = 0; i < B; ++i) {
+                if (!cand[i] || out[i] || front[i] > p_io[i] || (limit > 0 && n_taken[i] >= limit)) continue;
+                Item it{i, false, st.sc(req[i].a(front[i])), st.sio(req[i].b[front[i]]),
+                        req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[front[i]]};
+                if (!have || before(it, best)) { best = it; have = true; }
+            }
+            bool g_cand = g_open && ps.g_taken < group_depth;
+            if (g_cand)
+                for (int i : group) g_cand = g_cand && p_comp[i] + ps.g_taken <= p_io[i];
+            if (g_cand) {
+                Item it{group[0], true, 0, 0, 0};
+                for (int i : group) {
+                    const int u = p_comp[i] + ps.g_taken;
+                    it.a += st.sc(req[i].a(u));
+                    it.b += st.sio(req[i].b[u]);
+                    it.rem += req[i].a_prefix[p_io[i] + 1] - req[i].a_prefix[u];
+                }
+                if (!have || before(it, best)) { best = it; have = true; }
+            }
+            if (!have) break;
+            if (ps.A + best.a + compute_later_ps <= R - ps.Bs) {
+                ps.A += best.a;
+                ps.Bs += best.b;
+                if (best.group) ++ps.g_taken;
+                else { ++n_taken[best.first]; ++front[best.first]; }
+            } else if (best.group) {
+                g_open = false;
+            } else {
+                out[best.first] = 1;
+            }
+        }
+        if (tk) for (int i = 0; i < B; ++i) tk[i] = n_taken[i];
+        return ps;
+    };
+    // contention: scale_io prices the channel beside a recomputing engine, io_alone the channel
+    // on its own.  Nothing is taken unless recomputing pays for the slowdown it causes, judged
+    // on everything the engine would take from this state (a capped step is the first of
+    // several: what counts is where the engine ends up, not what one step holds).
+    if (io_alone_permille > 0) {
+        const Pass all = greedy(0, 0, INT32_MAX, nullptr);
+        if (all.A > step_fixed_ps || all.g_taken > 0) {
+            int64_t R_alone = io_backlog_ps;
+            for (int i = 0; i < B; ++i)
+                for (int u = p_comp[i]; u <= p_io[i]; ++u)
+                    R_alone += (int64_t)(((__int128)req[i].b[u] * io_alone_permille) / 1000);
+            if (std::max(all.A + compute_later_ps, R - all.Bs) >= std::max(step_fixed_ps + compute_later_ps, R_alone)) {
+                if (step_ps) *step_ps = step_fixed_ps;
+                return CF_OK;
+            }
+        }
     }
+    const Pass step = greedy(step_cap_ps, max_units, 1, take);
+    int64_t A = step.A;
+    const int64_t Bs = step.Bs;
+    const bool grp_taken = step.g_taken > 0;
+    int64_t grp_a = 0;
+    for (int i : group) grp_a += st.sc(req[i].a(p_comp[i]));
     if (grp_taken) {
         // 1: go through the whole layer (the next one looks worth taking too); 2: stop after
         // the K/V write, this is the group's last recomputed layer
         bool more = has_next && A + a_next + compute_later_ps <= R - Bs;
-        for (int i = 0; i < B; ++i)
-            if (p_comp[i] <= p_io[i] && req[i].mode == CF_LAYER_WISE && !(compute_closed && compute_closed[i]))
-                take[i] = more ? 1 : 2;
+        for (int i : group) take[i] = more ? 1 : 2;
         // unit prices charge a layer's attention and MLP to the NEXT layer's unit; the step
         // itself runs this layer in full (1) or up to its K/V write (2)
-        A += (more ? grp_full : grp_kv) - grp.a;
+        A += (more ? grp_full : grp_kv) - grp_a;
     }
     if (step_ps) *step_ps = A;
     return CF_OK;

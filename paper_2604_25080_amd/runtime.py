@@ -123,7 +123,8 @@ class Session:
                                     self.logits.data_ptr() if want_logits else 0)
         return (self.logits[:len(requests)] if want_logits else None), tm
 
-    def restore_dynamic(self, requests, cost, opts, want_logits=True, step_cap_ps=0, order=0):
+    def restore_dynamic(self, requests, cost, opts, want_logits=True, step_cap_ps=0, order=0,
+                        units_per_request=0, overlap=None):
         """Restore without a precomputed split: the engines claim units at run time.
         Returns (logits or None, splits [(mode,k,cut)], timing dict, stats dict)."""
         torch.cuda.current_stream(self.device).synchronize()
@@ -132,13 +133,17 @@ class Session:
                 for r in requests]
         splits, tm, st = self.ctx.restore_dynamic(self.cache, reqs, cost, opts,
                                                   self.logits.data_ptr() if want_logits else 0,
-                                                  step_cap_ps, order)
+                                                  step_cap_ps, order, units_per_request, overlap)
         return (self.logits[:len(requests)] if want_logits else None), splits, tm, st
 
     # -------------------------------------------------------------- introspection
-    def read_pages(self, req_id, n_tokens):
-        """Raw page bytes of a request: uint8 numpy [L, n_pages_req, page_bytes]."""
+    def read_pages(self, req_id, n_tokens, layers=None):
+        """Raw page bytes of a request: uint8 numpy [L, n_pages_req, page_bytes] (or only the
+        listed layers, in that order)."""
         table = self.cache.page_table(req_id)[:-(-n_tokens // cf.PAGE_TOKENS)]
         view = self.pool.view(self.shape.n_layers, self.n_pages, self.page_bytes)
         idx = torch.tensor(table, dtype=torch.long, device=self.device)
+        if layers is not None:
+            lidx = torch.tensor(list(layers), dtype=torch.long, device=self.device)
+            return view[lidx[:, None], idx[None, :]].cpu().numpy()
         return view[:, idx].cpu().numpy()

@@ -43,8 +43,8 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_model_desc) == 40
     assert ctypes.sizeof(cf.cf_request) == 48
     assert ctypes.sizeof(cf.cf_timing) == 64
-    assert ctypes.sizeof(cf.cf_dynamic_stats) == 32
-    assert ctypes.sizeof(cf.cf_dynamic_opts) == 16
+    assert ctypes.sizeof(cf.cf_dynamic_stats) == 40
+    assert ctypes.sizeof(cf.cf_dynamic_opts) == 24
     assert ctypes.sizeof(cf.cf_overlap_model) == 8
     assert ctypes.sizeof(cf.cf_batch_plan_opts) == 24
     assert ctypes.sizeof(cf.cf_batch_plan) == 72
@@ -209,7 +209,7 @@ def test_planning_policy_matches_oracle_on_random_batches_and_hand_cases():
 
 def test_run_time_scheduling_calls_match_oracle_on_random_states():
     rng = np.random.default_rng(44)
-    n_cases = 0
+    n_cases = n_multi = n_given_back = 0
     for it in range(400):
         d = dict(f_c=int(rng.integers(0, 50_000_000)), alpha=int(rng.integers(100_000, 2_000_000)),
                  beta=int(rng.integers(0, 60_000)), f_io=int(rng.integers(0, 20_000_000)),
@@ -232,14 +232,22 @@ def test_run_time_scheduling_calls_match_oracle_on_random_states():
         cap = int(rng.integers(0, 2) * rng.integers(0, 10 ** 10))
         order = int(rng.integers(0, 2))
         later = int(rng.integers(0, 2) * rng.integers(0, 10 ** 10))
-        want_take, want_a = P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later)
-        got_take, got_a = cf.dynamic_claim(ccm, opts_c, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later)
-        assert (got_take, got_a) == (want_take, want_a), (it, n, pc, pio)
+        max_units = int(rng.choice([0, 1, 1, 2, 3]))
+        alone = int(rng.integers(0, 2) * rng.integers(250, 4001))
+        want_take, want_a = P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later,
+                                            max_units, alone)
+        got_take, got_a = cf.dynamic_claim(ccm, opts_c, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later,
+                                           max_units, alone)
+        assert (got_take, got_a) == (want_take, want_a), (it, n, pc, pio, max_units, alone)
+        n_multi += max(want_take, default=0) > 1 and any(t > 2 for t in want_take)
+        n_given_back += alone > 0 and not any(want_take) and any(
+            P.dynamic_claim(ocm, opts_o, n, pc, pio, closed, backlog, sc, sio, fixed, cap, order, later, max_units, 0)[0])
         want = P.io_pick(ocm, opts_o, n, pc, pio, closed, backlog, busy, sc, sio)
         got = cf.dynamic_io_pick(ccm, opts_c, n, pc, pio, closed, backlog, busy, sc, sio)
         assert got == want, (it, n, pc, pio)
         n_cases += any(want_take) + (want >= 0)
     assert n_cases > 200         # the states are not all trivial
+    assert n_multi > 10 and n_given_back > 10     # steps with several chunks of a request; units given back
     cm = cf.cost_model(**hand_cost_model("balanced"))
     with pytest.raises(cf.CfError) as e:
         cf.dynamic_claim(cm, cf.plan_opts(512, 0, 32, 4096), [1000], [3], [1], None, 0)    # 2 units only

@@ -325,6 +325,59 @@ def test_dynamic_claim_step_cap_and_shortest_first_order():
     assert finished == [1, 2, 0]
 
 
+def test_dynamic_claim_several_chunks_of_a_request_and_units_given_back_hand_cases():
+    """Hand values for the two later parts of the rule: a step may hold consecutive chunks of one
+    request, and what it chose is given back unless it pays for the contention it causes."""
+    cm = P.CostModel(f_c=0, alpha=10, beta=1024, f_io=0, gamma=1 << 20)
+    opts = P.PlanOpts(16, 0, 2, 1, P.TOKEN_WISE)             # unit: 16 tokens through 2 layers
+    a, b, _ = P.unit_costs(cm, opts, 64, P.TOKEN_WISE)
+    # chunk u costs 2 * (10 * 16 + 1024 * ceil(pairs / 1024)), pairs = 16 * 16u + 136 -> 1 block each
+    assert a == [2368] * 4 and b == [32] * 4
+    big = 10 ** 6
+    # one unit per request (the default), two, no limit: the chunks are taken from the pointer on
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=big) == ([1], 2368)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=big, max_units=2) == ([2], 4736)
+    assert P.dynamic_claim(cm, opts, [64], [1], [3], io_backlog=big, max_units=0) == ([3], 7104)
+    # the test runs unit by unit: R = 5000 + 4 * 32 = 5128; 2368 <= 5128; 4736 <= 5128 - 32;
+    # 7104 > 5128 - 64
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, max_units=0) == ([2], 4736)
+    # two requests, the cheaper ratio first: request 1's chunks are short (8 tokens: a = 2 * (80 +
+    # 1024) = 2208, b = 16; 2208 / 16 > 2368 / 32), so request 0 is walked to its end first
+    n2 = [64, 8]
+    a1, b1, _ = P.unit_costs(cm, opts, 8, P.TOKEN_WISE)
+    assert a1 == [2208] and b1 == [16]
+    assert P.dynamic_claim(cm, opts, n2, [0, 0], [3, 0], io_backlog=big, max_units=0) == ([4, 1], 4 * 2368 + 2208)
+    assert P.dynamic_claim(cm, opts, n2, [0, 0], [3, 0], io_backlog=big, max_units=0, step_cap=4736) == ([2, 0], 4736)
+    # a cap reached inside a request stops the whole step, the other request is not started
+    assert P.dynamic_claim(cm, opts, n2, [0, 0], [3, 0], io_backlog=big, max_units=3, step_cap=4737)[0] == [3, 0]
+    # contention.  Beside a recomputing engine the channel runs at scale 2000, alone at 1000:
+    # R = 5000 + 4 * 64 = 5256 beside, R_alone = 5000 + 4 * 32 = 5128.  Two units are chosen
+    # (2368 <= 5256, 4736 <= 5256 - 64, 7104 > 5256 - 128); with them the restoration ends at
+    # max(4736, 5256 - 128) = 5128, not before the 5128 of the channel alone: given back
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0) == ([2], 4736)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0,
+                           io_alone=1000) == ([0], 0)
+    # one picosecond less alone-time to beat is still a tie; a channel that is slower on its own
+    # (scale 1032: R_alone = 5000 + 4 * 33 = 5132) is beaten by 5128 and the units stay
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0,
+                           io_alone=1032) == ([2], 4736)
+    # work that waits after the step counts on both sides: 4736 + 400 = 5136 > 5132 loses ...
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0,
+                           io_alone=1032, compute_later=400) == ([0], 0)
+    # A capped step is the first of several: whether recomputing pays is judged on everything
+    # the engine would take (the two units above), not on the one unit the cap lets through --
+    # which by itself, max(2368, 5256 - 64) = 5192, would not beat the 5132 of the channel alone
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0,
+                           io_alone=1032, step_cap=2368) == ([1], 2368)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=1,
+                           io_alone=1032) == ([1], 2368)
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=1,
+                           io_alone=1000) == ([0], 0)
+    # ... and the step's fixed work is reported when the units are given back
+    assert P.dynamic_claim(cm, opts, [64], [0], [3], io_backlog=5000, scale_io=2000, max_units=0,
+                           io_alone=1000, step_fixed=7) == ([0], 7)
+
+
 def test_dynamic_claim_layer_wise_group_and_last_layer_mark():
     cm = P.CostModel(f_c=0, alpha=10, beta=0, f_io=0, gamma=1 << 20)
     opts = P.PlanOpts(16, 0, 4, 1, P.LAYER_WISE)            # units: 4 layers over all tokens
