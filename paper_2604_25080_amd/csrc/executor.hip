@@ -112,7 +112,7 @@ struct cf_ctx {
     Carve cv;
     char* meta_host = nullptr;
     hipEvent_t ev_start = nullptr, ev_meta = nullptr, ev_comp = nullptr, ev_copy = nullptr,
-               ev_end = nullptr, ev_scat = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
+               ev_end = nullptr, ev_scat = nullptr, ev_t0 = nullptr, ev_t1 = nullptr, ev_q2 = nullptr;
     hipEvent_t ev_filled[N_STAGING_SLOTS] = {}, ev_free[N_STAGING_SLOTS] = {};
     bool simple_only = false;
     bool pipelined = true;            // new-turn rows ride along with the recompute pass
@@ -135,6 +135,7 @@ struct cf_ctx {
     // run-time scheduler: ratios measured / predicted carried from call to call -- the compute
     // engine's, the channel's beside a recomputing engine, the channel's on its own
     int dyn_scale_c = 1000, dyn_scale_io = 1000, dyn_scale_io_alone = 1000;
+    int dma_queues = 2;                   // streams a layer's DMA transfers are spread over (1 or 2)
     int n_last = 0;                   // requests whose final hidden row the last call left in h_last
 
     // per-kernel-class timing (cf_ctx_profile): event pairs around selected launches
@@ -250,7 +251,7 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
     c->own_ss = true;
     CF_HIP_CTX(hipHostMalloc((void**)&c->meta_host, cv.meta_bytes, hipHostMallocDefault));
     hipEvent_t* evs[] = {&c->ev_start, &c->ev_meta, &c->ev_comp, &c->ev_copy, &c->ev_end,
-                         &c->ev_scat, &c->ev_t0, &c->ev_t1};
+                         &c->ev_scat, &c->ev_t0, &c->ev_t1, &c->ev_q2};
     for (hipEvent_t* e : evs) CF_HIP_CTX(hipEventCreate(e));
     for (int i = 0; i < N_STAGING_SLOTS; ++i) {
         CF_HIP_CTX(hipEventCreateWithFlags(&c->ev_filled[i], hipEventDisableTiming));
@@ -284,7 +285,7 @@ extern "C" int cf_ctx_create(const cf_model_desc* desc, const cf_weights* weight
 extern "C" void cf_ctx_destroy(cf_ctx* c) {
     if (!c) return;
     hipEvent_t evs[] = {c->ev_start, c->ev_meta, c->ev_comp, c->ev_copy, c->ev_end,
-                        c->ev_scat, c->ev_t0, c->ev_t1};
+                        c->ev_scat, c->ev_t0, c->ev_t1, c->ev_q2};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
     for (int i = 0; i < N_STAGING_SLOTS; ++i) {
@@ -766,6 +767,33 @@ struct DmaOp {                // a run of whole pages that is contiguous in the 
 };
 constexpr size_t DMA_MIN_BYTES = (size_t)4 << 20;   // shorter transfers do not reach link speed
 
+// A layer's DMA transfers, alternating between the copy stream and the library's own stream: a
+// transfer has a few microseconds of set-up during which the link idles, and two queues let one
+// transfer's set-up hide under the other's data.  The second queue may not run ahead into the
+// next layer (the layers must complete in order: the new turn's attention waits for them one by
+// one), so it first waits for the end of the previous layer's loads on the copy stream
+// (`ev_prev`, recorded by end_layer_dma below), and the copy stream waits for the second queue
+// before it goes on.  One queue when `two` is false (a paced link: the pacing kernel must see
+// every byte in order).
+int issue_layer_dma(hipStream_t ps, hipStream_t ss, hipEvent_t ev_prev, hipEvent_t ev_join, bool two,
+                    bool& prev_recorded, const DmaOp* ops, int n) {
+    two = two && n > 1;
+    if (two && prev_recorded && hipStreamWaitEvent(ss, ev_prev, 0) != hipSuccess) return -1;
+    for (int k = 0; k < n; ++k)
+        if (hipMemcpyAsync(ops[k].dst, ops[k].src, ops[k].bytes, hipMemcpyHostToDevice,
+                           (two && (k & 1)) ? ss : ps) != hipSuccess)
+            return -1;
+    if (two && (hipEventRecord(ev_join, ss) != hipSuccess || hipStreamWaitEvent(ps, ev_join, 0) != hipSuccess))
+        return -1;
+    return 0;
+}
+// after everything of the layer is on the copy stream
+int end_layer_dma(hipStream_t ps, hipEvent_t ev_prev, bool& prev_recorded) {
+    if (hipEventRecord(ev_prev, ps) != hipSuccess) return -1;
+    prev_recorded = true;
+    return 0;
+}
+
 // The load of tokens [lo, hi) of one request in one layer, split by engine.  Whole pages whose
 // pool slots are consecutive (the usual case: the allocator hands out the lowest free ids in
 // order) go as ONE DMA transfer straight into the pool -- no kernel, no compute unit taken from
@@ -1158,18 +1186,18 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
         layer_loaded[layer_loads[k].layer] = 1;
     }
     size_t loads_enqueued = 0;
+    bool q2_recorded = false;
     auto enqueue_load = [&](const LayerLoad& ll) -> int {
         c->prof_begin(CF_K_H2D_COPY, (double)ll.bytes, c->ps);
-        for (int k = 0; k < ll.n_dma; ++k) {
-            const DmaOp& op = dma_ops[ll.dma_first + k];
-            if (hipMemcpyAsync(op.dst, op.src, op.bytes, hipMemcpyHostToDevice, c->ps) != hipSuccess) return -1;
-        }
+        if (issue_layer_dma(c->ps, c->ss, c->ev_q2, c->ev_scat, c->dma_queues > 1 && c->throttle_gbs <= 0,
+                            q2_recorded, dma_ops.data() + ll.dma_first, ll.n_dma) < 0)
+            return -1;
         launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs) + ll.job_first,
                          ll.n_jobs, ll.n_vblocks, c->load_wgs, (const int32_t*)md, g);
         pace((double)ll.bytes);
         c->prof_end(CF_K_H2D_COPY, c->ps);
         if (merged && hipEventRecord(c->ev_layer[ll.layer], c->ps) != hipSuccess) return -1;
-        return 0;
+        return end_layer_dma(c->ps, c->ev_q2, q2_recorded);
     };
     // Sequential join: everything is enqueued here, from the top layer down.  Pipelined join: the
     // loads of layer l are enqueued just before the compute stream's layer l (see below), so that
@@ -1878,6 +1906,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         std::vector<hipEvent_t> ready(L);
         for (int l = 0; l < L; ++l) ready[l] = c->ev_layer[l];
         int tail_next = 0;
+        bool tail_q2_recorded = false;
         auto feed_layer = [&]() -> int {
             if (tail_next >= L) return 0;
             if (tail_next == 0) {
@@ -1889,10 +1918,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             const LayerLoad& tl = tlayers[tail_next];
             if (tl.n_jobs > 0 || tl.n_dma > 0) {
                 c->prof_begin(CF_K_H2D_COPY, (double)tl.bytes, c->ps);
-                for (int k = 0; k < tl.n_dma; ++k) {
-                    const DmaOp& op = tdma[tl.dma_first + k];
-                    if (hipMemcpyAsync(op.dst, op.src, op.bytes, hipMemcpyHostToDevice, c->ps) != hipSuccess) return -1;
-                }
+                if (issue_layer_dma(c->ps, c->ss, c->ev_q2, c->ev_scat, c->dma_queues > 1 && c->throttle_gbs <= 0,
+                                    tail_q2_recorded, tdma.data() + tl.dma_first, tl.n_dma) < 0)
+                    return -1;
                 launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs) + tl.job_first,
                                  tl.n_jobs, tl.n_vblocks, c->load_wgs, (const int32_t*)md, g);
                 if (c->throttle_gbs > 0) {
@@ -1904,6 +1932,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 loaded_bytes += (int64_t)tl.bytes;
                 tail_pred += unit_load_ps(tl.bytes);
                 ++io_issued;
+                if (end_layer_dma(c->ps, c->ev_q2, tail_q2_recorded) < 0) return -1;
             }
             // behind everything the copy stream was given so far, units in flight included
             if (hipEventRecord(c->ev_layer[tail_next], c->ps) != hipSuccess) return -1;
@@ -1950,9 +1979,15 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     // rows a step may hold beside the layer-wise group's and every request's new turn
     const int64_t step_rows_cap = (int64_t)c->opts.max_tokens - lw.T - sum_new;
 
+    // The compute engine is asked first: if its first step turns out to be its last, the whole
+    // schedule is known before anything is loaded, and every load goes out layer by layer (a
+    // chunk claimed by the channel ahead of that, all its layers in one piece, would hold back
+    // the bottom layers that the new turn waits for).
+    bool first_round = true;
     while (true) {
         bool progressed = false;
-        int pio_rc = pump_io();
+        int pio_rc = first_round ? 0 : pump_io();
+        first_round = false;
         if (pio_rc < 0) return bail(fail(CF_ERR_HIP, "cf_restore_dynamic: the copy stream failed"));
         if (pio_rc > 0) progressed = ask = true;
         // compute engine: retire the step ...
