@@ -517,7 +517,8 @@ def main():
 
     if extras:
         short = lambda r: {k: r[k] for k in ("workload", "steps", "ms_per_step", "restored_tokens_per_s", "ttft_ms",
-                                             "plan_kind", "recompute", "copy", "splits")}
+                                             "compute_stream_ms", "copy_stream_ms", "plan_kind", "recompute", "copy",
+                                             "splits")}
         configs = {}
         # configuration 4 under the two extremes (the recompute-only and load-only baselines)
         for plan in ("all_load", "all_recompute"):

@@ -1648,7 +1648,11 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     int64_t io_pred_beside = 0, io_pred_alone = 0;
     double io_ms_beside = 0, io_ms_alone = 0;
     double io_t_last = 0;                         // host clock: latest completion
+    // c_pred_done: what the finished steps were predicted to take at scale 1 (a step's prediction
+    // is made at the scale of the moment, which is taken out again: the ratio measured /
+    // predicted is the scale itself, not a correction of the scale in use)
     int64_t c_pred_done = 0, step_pred = 0;
+    int step_scale = 1000;                        // the compute scale the running step was predicted at
     double c_meas_done_ms = 0, step_t0 = 0, gap_ms = 0, last_step_end = 0;
     bool step_running = false, ask = true;        // ask: state changed since the last declined claim
     bool step_has_rec = false;                    // the running step recomputes (contends with the channel)
@@ -1945,6 +1949,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
             if (n_steps > 0) gap_ms += t_launch - last_step_end;
             step_t0 = t_launch;
             step_pred = 0;
+            step_scale = scale_c;
             ++n_steps;
         }
         step_pred += pred_ps;
@@ -1996,7 +2001,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         if (step_dn > 0) {
             last_step_end = now_ms();
             c_meas_done_ms += last_step_end - step_t0;
-            c_pred_done += step_pred;
+            c_pred_done += (int64_t)((__int128)step_pred * 1000 / step_scale);
             if (c_pred_done > 0) scale_c = clamp_scale(c_meas_done_ms * 1e9 / (double)c_pred_done);
             step_running = false;
             step_has_rec = false;
@@ -2105,6 +2110,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 if (n_steps > 0) gap_ms += t_launch - last_step_end;
                 step_t0 = t_launch;
                 step_pred = pred;
+                step_scale = scale_c;
                 step_running = true;            // pump_io (between layers) sees the step as running
                 step_has_rec = any_rec;
                 if (lw_take) {
