@@ -244,13 +244,15 @@ int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* overlap,
  * read as slow compute, move work to the channel and make the wait longer).  The compute measurement is
  * meas_compute_ps, except under the pipelined join when the call ended more
  * than 2 % after the copy stream did (the compute stream was the last to
- * finish, new turn included): then it is meas_total_ps.  A hybrid ran both engines side by side, so its ratios
- * measured / predicted correct the overlap model (each ratio clamped to
- * [1/4, 4] per call, the factors to [500, 8000]); an extreme ran one engine
- * alone, so its ratio corrects that engine's coefficients of the cost model
- * (as cf_cost_feedback does), and the overlap factors move an eighth of the
- * way back to 1000: an extreme teaches nothing about contention, and one bad
- * sample must not rule the hybrid out for good.                             */
+ * finish, new turn included): then it is meas_total_ps.  A hybrid ran both
+ * engines side by side, so its ratios measured / predicted correct the overlap
+ * model (one call moves a factor by 5/4 or 4/5 at most: the first hybrid
+ * after a cold start can measure far off on both engines at once; the factors
+ * stay in [500, 8000]); an extreme ran one engine alone, so its ratio corrects
+ * that engine's coefficients of the cost model (as cf_cost_feedback does), and
+ * the overlap factors move a quarter of the way back to 1000: an extreme
+ * teaches nothing about contention, nothing measures the factors while one is
+ * chosen, and a bad sample must not rule the hybrid out for good.           */
 int cf_plan_feedback(cf_cost_model* cost, cf_overlap_model* overlap, const cf_batch_plan* info,
                      int64_t meas_compute_ps, int64_t meas_copy_ps, int64_t meas_total_ps,
                      int64_t meas_wait_ps);

@@ -370,14 +370,15 @@ def plan_batch(cm, overlap, model, chunk_tokens, l_delta, force_mode, io_key, pi
 
 def plan_feedback(cm, overlap, info, meas_compute, meas_copy, meas_total, meas_wait=0):
     """-> (cost model, overlap) after an executed batch.  A hybrid's ratios measured/predicted
-    correct the overlap factors (ratio clamped to [1/4, 4], factors to [500, 8000]); an extreme's
-    ratio corrects the coefficients of the engine that ran alone (cost_feedback) and lets the
-    overlap factors relax towards 1000."""
+    correct the overlap factors (one batch moves a factor by at most 5/4 or 4/5 -- the first
+    hybrid after a cold start can measure far off on both engines at once --, factors stay in
+    [500, 8000]); an extreme's ratio corrects the coefficients of the engine that ran alone
+    (cost_feedback) and lets the overlap factors relax towards 1000."""
     def ratio(v, num, den):
-        if num > 4 * den:
-            num, den = 4, 1
-        if 4 * num < den:
-            num, den = 1, 4
+        if 4 * num > 5 * den:
+            num, den = 5, 4
+        if 5 * num < 4 * den:
+            num, den = 4, 5
         return (v * num + den // 2) // den
     meas_comp = meas_total if (info["pipelined_join"] and meas_total * 100 > meas_copy * 102) else meas_compute
     meas_comp = max(0, meas_comp - meas_wait)     # time the compute stream stood waiting for loads is not compute
@@ -388,9 +389,9 @@ def plan_feedback(cm, overlap, info, meas_compute, meas_copy, meas_total, meas_w
         if info["t_io"] > 0 and meas_copy > 0:
             io_pm = min(8000, max(500, ratio(io_pm, meas_copy, info["t_io"])))
         return cm, (comp_pm, io_pm)
-    # an extreme teaches nothing about contention: what was learned ages, an eighth of the way
-    # back to 1000 per such batch
-    relax = lambda pm: pm - (pm - 1000) // 8 if pm >= 1000 else pm + (1000 - pm) // 8
+    # an extreme teaches nothing about contention: what was learned ages, a quarter of the way
+    # back to 1000 per such batch (nothing measures the factors while an extreme is chosen)
+    relax = lambda pm: pm - (pm - 1000) // 4 if pm >= 1000 else pm + (1000 - pm) // 4
     overlap = (relax(comp_pm), relax(io_pm))
     if info["kind"] == PLAN_ALL_LOAD:
         return cost_feedback(cm, 0, 0, info["t_io"], meas_copy), overlap

@@ -321,9 +321,10 @@ int64_t scale_permille(int64_t v, int64_t permille) {          // round to neare
     return (int64_t)(((__int128)v * permille + 500) / 1000);
 }
 
-int64_t ratio_scale(int64_t v, int64_t num, int64_t den) {     // v * num / den, ratio clamped to [1/4, 4]
-    if (num > 4 * den) { num = 4; den = 1; }
-    if (4 * num < den) { num = 1; den = 4; }
+// v * num / den with the ratio clamped to [4/5, 5/4]: how far one batch may move an overlap factor
+int64_t ratio_step(int64_t v, int64_t num, int64_t den) {
+    if (4 * num > 5 * den) { num = 5; den = 4; }
+    if (5 * num < 4 * den) { num = 4; den = 5; }
     return (int64_t)(((__int128)v * num + den / 2) / den);
 }
 
@@ -468,16 +469,17 @@ extern "C" int cf_plan_feedback(cf_cost_model* cost, cf_overlap_model* overlap, 
     if (info->kind == CF_PLAN_HYBRID) {
         if (info->t_comp > 0 && meas_comp > 0)
             overlap->comp_permille = (int32_t)std::min<int64_t>(
-                8000, std::max<int64_t>(500, ratio_scale(overlap->comp_permille, meas_comp, info->t_comp)));
+                8000, std::max<int64_t>(500, ratio_step(overlap->comp_permille, meas_comp, info->t_comp)));
         if (info->t_io > 0 && meas_copy_ps > 0)
             overlap->io_permille = (int32_t)std::min<int64_t>(
-                8000, std::max<int64_t>(500, ratio_scale(overlap->io_permille, meas_copy_ps, info->t_io)));
+                8000, std::max<int64_t>(500, ratio_step(overlap->io_permille, meas_copy_ps, info->t_io)));
         return CF_OK;
     }
     // An extreme ran one engine alone: its ratio corrects that engine's own coefficients, and it
-    // teaches nothing about contention -- what was learned about that ages: the factors move an
-    // eighth of the way back to 1000, so that one bad sample cannot rule the hybrid out for good.
-    auto relax = [](int32_t pm) { return pm >= 1000 ? pm - (pm - 1000) / 8 : pm + (1000 - pm) / 8; };
+    // teaches nothing about contention -- what was learned about that ages: the factors move a
+    // quarter of the way back to 1000, so that a bad sample cannot rule the hybrid out for good
+    // (while an extreme is chosen the factors are not measured at all).
+    auto relax = [](int32_t pm) { return pm >= 1000 ? pm - (pm - 1000) / 4 : pm + (1000 - pm) / 4; };
     overlap->comp_permille = relax(overlap->comp_permille);
     overlap->io_permille = relax(overlap->io_permille);
     if (info->kind == CF_PLAN_ALL_LOAD)

@@ -273,6 +273,84 @@ def test_small_shape_end_to_end_on_the_big_gemm_tile(shape_name):
         sess.close()
 
 
+def _token_bits(shape, raw, n_tokens):
+    """raw uint8 [L, P, page_bytes] of a bf16 cache -> (K, V) uint16 [L, n_tokens, Hkv, hd]: the
+    stored bits, token-major (K part [head][slot][hd], V part [head][hd][slot] in a page)."""
+    L, P, _ = raw.shape
+    hk, hd = shape.n_kv_heads, shape.head_dim
+    vals = np.ascontiguousarray(raw).view(np.uint16).reshape(L, P, -1)
+    half = hk * 16 * hd
+    k = vals[:, :, :half].reshape(L, P, hk, 16, hd).transpose(0, 1, 3, 2, 4).reshape(L, P * 16, hk, hd)
+    v = vals[:, :, half:].reshape(L, P, hk, hd, 16).transpose(0, 1, 4, 2, 3).reshape(L, P * 16, hk, hd)
+    return k[:, :n_tokens], v[:, :n_tokens]
+
+
+def test_long_loads_move_the_host_bytes_on_every_load_path():
+    """Loads long enough for the DMA split of the direct path (whole pages with consecutive pool
+    ids, 4 MiB or more per request and layer -- here 375 pages of 16 KiB) with everything that
+    breaks a run: a ragged last page whose tail slots belong to the new turn, a split in the
+    middle of a page, a pool fragmented by earlier traffic (short runs that stay with the load
+    kernel), two requests per layer (two DMA queues).  The host blocks hold random bytes; what
+    must come out is those bytes in every loaded cell, and the fill pattern in every slot of the
+    request's pages that no token of the context owns -- on the direct path, on the load kernel
+    alone and on the staged path alike."""
+    from paper_2604_25080_amd.runtime import Session
+    shape = SHAPES["mini-bf16"]
+    L = shape.n_layers
+    ws = WeightSource(shape, 77, cache=True)
+    n_ctx, n_new, k_split = [6005, 4700], [40, 40], [0, 37]
+    rng = np.random.default_rng(5)
+    ctx_tokens = [rng.integers(0, shape.vocab, size=n).astype(np.int32) for n in n_ctx]
+    new_tokens = [rng.integers(0, shape.vocab, size=m).astype(np.int32) for m in n_new]
+    sess = Session(shape, ws, max_batch=2, max_tokens=1024, max_positions=max(n_ctx) + 64, n_pages=1400,
+                   chunk_rows=1024, pool_fill=0xEE, staging_bytes=1 << 20)
+    try:
+        host = []
+        for n in n_ctx:
+            t = sess.pinned(sess.host_kv_bytes(n))
+            t.copy_(torch.from_numpy(rng.integers(0, 256, size=t.numel(), dtype=np.uint8)))
+            host.append(t)
+        for fragmented in (False, True):
+            for path in (0, 2, 1):
+                sess.ctx.set_load_path(path)
+                sess.pool.fill_(0xEE)
+                held = []
+                if fragmented:      # scattered small allocations, every other one freed again
+                    for j in range(60):
+                        sess.cache.alloc(500 + j, 16 * (1 + j % 7))
+                    for j in range(0, 60, 2):
+                        sess.cache.free(500 + j)
+                    held = list(range(501, 560, 2))
+                reqs = []
+                for i in range(2):
+                    sess.cache.alloc(1 + i, n_ctx[i] + n_new[i])
+                    reqs.append(dict(req_id=1 + i, ctx_tokens=ctx_tokens[i], new_tokens=new_tokens[i], host_kv=host[i]))
+                try:
+                    tables = [sess.cache.page_table(1 + i) for i in range(2)]
+                    consecutive = [all(b == a + 1 for a, b in zip(t, t[1:])) for t in tables]
+                    assert all(consecutive) != fragmented      # the churn did break the runs up
+                    sess.restore(reqs, [(0, k_split[i], L) for i in range(2)], want_logits=False)
+                    for i in range(2):
+                        n, k0 = n_ctx[i], k_split[i]
+                        alloc = n + n_new[i]
+                        gk, gv = _token_bits(shape, sess.read_pages(1 + i, alloc), -(-alloc // 16) * 16)
+                        hk, hv = _token_bits(shape, host[i].numpy()[:sess.host_kv_bytes(n)].reshape(L, -1, sess.page_bytes), n)
+                        for l in range(L):
+                            assert np.array_equal(gk[l, k0:n], hk[l, k0:n]) and np.array_equal(gv[l, k0:n], hv[l, k0:n]), \
+                                f"request {i} layer {l} path {path} fragmented {fragmented}: loaded cells differ from the host block"
+                            # no token of the context owns these slots (the new turn did not run)
+                            assert (gk[l, n:] == 0xEEEE).all() and (gv[l, n:] == 0xEEEE).all(), \
+                                f"request {i} layer {l} path {path}: a slot past the context was written"
+                finally:
+                    for i in range(2):
+                        sess.cache.free(1 + i)
+                    for r in held:
+                        sess.cache.free(r)
+    finally:
+        sess.ctx.set_load_path(0)
+        sess.close()
+
+
 def test_stage_restore_from_boundary_activations(mini):
     """One pipeline stage's share (Sec. 3.2): the context is restricted to layers [b, e), recompute
     starts from the oracle's hidden states entering layer b, loads cover only the stage's layers

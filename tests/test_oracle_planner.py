@@ -585,31 +585,36 @@ def test_policy_new_turn_on_the_compute_clock():
 def test_policy_feedback_hand_values():
     info = dict(kind=P.PLAN_HYBRID, pipelined_join=1, t_comp=53328, t_io=61440)
     # the call ended well after the copy stream: its end is the compute measurement
-    cm, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 80000)
-    assert cm == HAND_COST and ov == (1500, 1000)            # 80000 / 53328 = 1.50015
+    cm, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 64000)
+    assert cm == HAND_COST and ov == (1200, 1000)            # 64000 / 53328 = 1.2001
     # ... not with the sequential join, and not when both streams ended together
-    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), dict(info, pipelined_join=0), 60000, 61440, 80000)
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), dict(info, pipelined_join=0), 60000, 61440, 64000)
     assert ov == (1125, 1000)                                 # 60000 / 53328 = 1.1251
     _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 62000)
     assert ov == (1125, 1000)
-    # time the compute stream stood waiting for loads is taken off: (80000 - 26672) / 53328 = 1
-    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 80000, 26672)
+    # time the compute stream stood waiting for loads is taken off: (64000 - 10672) / 53328 = 1
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 64000, 10672)
     assert ov == (1000, 1000)
-    # ratios are clamped to 4 per call and the factors to [500, 8000]
-    _, ov = P.plan_feedback(HAND_COST, (1000, 3000), info, 533280, 614400, 533280)
-    assert ov == (4000, 8000)
-    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 53, 61, 53)
-    assert ov == (500, 500)
+    # one batch moves a factor by 5/4 or 4/5 at most (80000 / 53328 = 1.5: taken as 1.25) ...
+    _, ov = P.plan_feedback(HAND_COST, (1000, 1000), info, 60000, 61440, 80000)
+    assert ov == (1250, 1000)
+    _, ov = P.plan_feedback(HAND_COST, (1100, 1000), info, 30000, 30720, 30000)
+    assert ov == (880, 800)
+    # ... and the factors stay in [500, 8000]
+    _, ov = P.plan_feedback(HAND_COST, (7000, 3000), info, 533280, 614400, 533280)
+    assert ov == (8000, 3750)
+    _, ov = P.plan_feedback(HAND_COST, (600, 1000), info, 53, 61, 53)
+    assert ov == (500, 800)
     # an extreme corrects the coefficients of the engine that ran alone
     cm, ov = P.plan_feedback(HAND_COST, (1200, 1300), dict(kind=P.PLAN_ALL_LOAD, pipelined_join=1, t_comp=0, t_io=81920),
                              0, 98304, 98304)
-    assert ov == (1175, 1263) and cm.gamma == (20 << 20) * 6 // 5 and cm.alpha == 1000     # 200/8, 300/8 back
+    assert ov == (1150, 1225) and cm.gamma == (20 << 20) * 6 // 5 and cm.alpha == 1000     # 200/4, 300/4 back
     cm, ov = P.plan_feedback(HAND_COST, (1200, 1300), dict(kind=P.PLAN_ALL_RECOMPUTE, pipelined_join=1, t_comp=85312, t_io=0),
                              85312, 0, 127968)
-    assert cm.alpha == 1500 and cm.gamma == 20 << 20 and ov == (1175, 1263)
+    assert cm.alpha == 1500 and cm.gamma == 20 << 20 and ov == (1150, 1225)
     _, ov = P.plan_feedback(HAND_COST, (600, 1000), dict(kind=P.PLAN_ALL_LOAD, pipelined_join=1, t_comp=0, t_io=81920),
                             0, 81920, 81920)
-    assert ov == (650, 1000)
+    assert ov == (700, 1000)
 
 
 def test_simulated_run_time_scheduling_hand_traces():
