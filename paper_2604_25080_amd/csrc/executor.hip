@@ -1628,6 +1628,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
     auto bail = [&](int code) {
         (void)hipStreamSynchronize(c->cs);
         (void)hipStreamSynchronize(c->ps);
+        (void)hipStreamSynchronize(c->ss);       // the second DMA queue of the planned tail
         (void)hipGetLastError();
         c->prof_collect();
         return code;
