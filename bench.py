@@ -314,7 +314,8 @@ class Bench:
             splits = [(0, k, c) for k, c in batch.forced_splits]
         elif plan in ("planner", "per_request"):
             bo = cf.batch_plan_opts(batch.chunk_tokens, self.l_delta, batch.forced_mode,
-                                    pipelined_join=not args.sequential_join, stage_layers=L if stage else 0)
+                                    pipelined_join=not args.sequential_join, stage_layers=L if stage else 0,
+                                    stage_first_layer=stage[0] if stage else 0)
             if plan == "planner":
                 splits, info = cf.plan_batch(self.cost, self.overlap, self.desc, bo, batch.n_ctx, batch.n_new)
             else:   # comparison plan: every request planned alone, as if it had both engines to itself

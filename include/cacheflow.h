@@ -108,6 +108,16 @@ typedef struct cf_plan_opts {
                                          adds a K/V-only one).  Set it to 1000 x the
                                          K/V-projection share of a layer's linear
                                          FLOPs                                       */
+    int32_t boundary_bytes_per_token; /* 0: recompute starts from token ids.  > 0: a
+                                         pipeline stage above layer 0 (Sec. 3.2)
+                                         recomputes from cached stage-input hidden
+                                         states, which cross the same host link as the
+                                         KV: every recompute claim also costs the I/O
+                                         channel ceil(tokens * this * gamma / 2^20) --
+                                         the tokens of a token-wise chunk; all tokens of
+                                         a layer-wise request at its first claimed
+                                         layer, nothing after that.  float32 rows:
+                                         4 * d_model                                  */
 } cf_plan_opts;
 
 typedef struct cf_split {
@@ -192,6 +202,10 @@ typedef struct cf_batch_plan_opts {
                                   turn runs after both engines are done               */
     int32_t stage_layers;      /* 0: the whole model; else the number of layers of the
                                   pipeline stage that is planned (cf_ctx_set_stage)   */
+    int32_t stage_first_layer; /* first layer of that stage; above 0 the stage recomputes
+                                  from boundary activations (float32 rows of d_model),
+                                  whose transfer is charged to the I/O channel
+                                  (cf_plan_opts.boundary_bytes_per_token)             */
 } cf_batch_plan_opts;
 
 enum cf_plan_kind { CF_PLAN_HYBRID = 0, CF_PLAN_ALL_LOAD = 1, CF_PLAN_ALL_RECOMPUTE = 2 };

@@ -64,6 +64,9 @@ class PlanOpts:
     io_key: int = KEY_REMAINING_COST
     kv_only_permille: int = 0       # > 0: the last recomputed layer of a request costs only
                                     # its K/V projection, this many permille of alpha*t
+    boundary_bytes_per_token: int = 0   # > 0: a pipeline stage above layer 0 (Sec. 3.2) recomputes
+                                    # from cached stage-input hidden states that cross the same
+                                    # link as the KV: a recompute claim also costs the channel
 
 
 def ceil_div(a, b):
@@ -121,6 +124,21 @@ def unit_costs(cm, opts, n, mode):
     return a, b, tok
 
 
+def boundary_costs(cm, opts, n, mode):
+    """c[u]: channel time a RECOMPUTE claim of unit u costs -- the boundary-activation rows of the
+    tokens it recomputes, ceil(tokens * bytes * gamma / 2^20), no per-transfer term.  A
+    token-wise chunk brings its own tokens; a layer-wise request brings all its tokens with the
+    first layer it recomputes and nothing after that."""
+    if n <= 0:
+        return []
+    bb = opts.boundary_bytes_per_token
+    cost = lambda t: ceil_div(t * bb * cm.gamma, 1 << 20) if bb > 0 else 0
+    if mode == TOKEN_WISE:
+        c = opts.chunk_tokens
+        return [cost(min((u + 1) * c, n) - u * c) for u in range(ceil_div(n, c))]
+    return [cost(n)] + [0] * (opts.n_layers - 1)
+
+
 def _split_of(opts, n, mode, p_comp):
     if mode == TOKEN_WISE:
         return (mode, min(p_comp * opts.chunk_tokens, n), opts.n_layers)
@@ -135,10 +153,11 @@ def plan(cm, opts, n_ctx, trace=None):
     b_req = len(n_ctx)
     modes = [request_mode(opts, n) for n in n_ctx]
     costs = [unit_costs(cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
+    bcost = [boundary_costs(cm, opts, n_ctx[i], modes[i]) for i in range(b_req)]
     p_comp = [0] * b_req
     p_io = [len(costs[i][0]) - 1 for i in range(b_req)]
     t_c, t_io = cm.s_c, cm.s_io        # each engine's clock starts after its start-up
-    n_c = n_io = 0
+    n_c = n_io = n_boundary = 0
     rr = 0
     n_claims = 0
 
@@ -179,6 +198,9 @@ def plan(cm, opts, n_ctx, trace=None):
             if trace is not None:
                 trace.append((0, ic, p_comp[ic]))
             t_c = fin_c
+            # the boundary rows of what is recomputed travel over the channel
+            t_io += bcost[ic][p_comp[ic]]
+            n_boundary += bcost[ic][p_comp[ic]] > 0
             n_c += 1
             p_comp[ic] += 1
             rr = (ic + 1) % b_req
@@ -192,7 +214,7 @@ def plan(cm, opts, n_ctx, trace=None):
 
     if n_c == 0:
         t_c = 0            # an engine that claimed nothing never started
-    if n_io == 0:
+    if n_io == 0 and n_boundary == 0:
         t_io = 0
 
     splits = [_split_of(opts, n_ctx[i], modes[i], p_comp[i]) for i in range(b_req)]
@@ -208,10 +230,11 @@ def split_times(cm, opts, n_ctx, unit_splits, modes=None):
     for i, n in enumerate(n_ctx):
         mode = request_mode(opts, n) if modes is None else modes[i]
         a, b, _ = unit_costs(cm, opts, n, mode)
+        c_b = sum(boundary_costs(cm, opts, n, mode)[:unit_splits[i]])
         t_c += sum(a[:unit_splits[i]])
-        t_io += sum(b[unit_splits[i]:])
+        t_io += sum(b[unit_splits[i]:]) + c_b
         any_c |= len(a[:unit_splits[i]]) > 0
-        any_io |= len(b[unit_splits[i]:]) > 0
+        any_io |= len(b[unit_splits[i]:]) > 0 or c_b > 0
     return (t_c + cm.s_c if any_c else 0), (t_io + cm.s_io if any_io else 0)
 
 
@@ -314,14 +337,16 @@ def kv_share_permille(d_model, n_q_heads, n_kv_heads, head_dim, d_ffn):
 
 
 def plan_batch(cm, overlap, model, chunk_tokens, l_delta, force_mode, io_key, pipelined_join, n_ctx,
-               n_new=None, stage_layers=0):
+               n_new=None, stage_layers=0, stage_first_layer=0):
     """overlap = (comp_permille, io_permille); model = (n_layers, d_model, n_q_heads, n_kv_heads,
-    head_dim, d_ffn, elem_bytes).  Returns (splits, info dict)."""
+    head_dim, d_ffn, elem_bytes).  A stage above layer 0 recomputes from float32 boundary rows of
+    d_model values, charged to the channel.  Returns (splits, info dict)."""
     n_layers, d_model, hq, hkv, hd, ffn, esz = model
     comp_pm, io_pm = overlap
     L = stage_layers if stage_layers > 0 else n_layers
     opts = PlanOpts(chunk_tokens, l_delta, L, 2 * hkv * hd * esz, force_mode, io_key,
-                    kv_share_permille(d_model, hq, hkv, hd, ffn))
+                    kv_share_permille(d_model, hq, hkv, hd, ffn),
+                    4 * d_model if stage_layers > 0 and stage_first_layer > 0 else 0)
     base = CostModel(cm.f_c, cm.alpha, cm.beta, cm.f_io, cm.gamma, cm.s_c, cm.s_io)
     if stage_layers > 0:
         base.s_c = cm.s_c * L // n_layers
@@ -351,9 +376,9 @@ def plan_batch(cm, overlap, model, chunk_tokens, l_delta, force_mode, io_key, pi
     modes = [request_mode(opts, n) for n in n_ctx]
     n_units = [len(unit_costs(base, opts, n, m)[0]) for n, m in zip(n_ctx, modes)]
     _, l_io = split_times(base, opts, n_ctx, [0] * len(n_ctx), modes)
-    r_c, _ = split_times(base, opts, n_ctx, n_units, modes)
+    r_c, r_io = split_times(base, opts, n_ctx, n_units, modes)     # r_io: boundary rows, if any
     tl = times(base.s_c, pre, 0, l_io)
-    tr = times(base.s_c, pre, (r_c + (pre if pipelined_join else 0)) if r_c > 0 else 0, 0)
+    tr = times(base.s_c, pre, (r_c + (pre if pipelined_join else 0)) if r_c > 0 else 0, r_io)
     sp_l = [(m, 0, L) if m == TOKEN_WISE else (m, n, 0) for m, n in zip(modes, n_ctx)]
     sp_r = [(m, n, L) for m, n in zip(modes, n_ctx)]
     kind = PLAN_HYBRID if (recomputes and loads) else (PLAN_ALL_LOAD if not recomputes else PLAN_ALL_RECOMPUTE)
@@ -363,7 +388,7 @@ def plan_batch(cm, overlap, model, chunk_tokens, l_delta, force_mode, io_key, pi
     if tr[1] < best:
         kind, best = PLAN_ALL_RECOMPUTE, tr[1]
     info = dict(kind=kind, kv_only_permille=opts.kv_only_permille, pipelined_join=1 if pipelined_join else 0,
-                prefill_ps=pre, t_comp=(th, tl, tr)[kind][0], t_io=(st_h["t_io"], l_io, 0)[kind], ttft=best,
+                prefill_ps=pre, t_comp=(th, tl, tr)[kind][0], t_io=(st_h["t_io"], l_io, r_io)[kind], ttft=best,
                 ttft_hybrid=th[1], ttft_all_load=tl[1], ttft_all_recompute=tr[1])
     return (sp_h, sp_l, sp_r)[kind], info
 

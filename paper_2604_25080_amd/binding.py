@@ -38,7 +38,7 @@ class cf_cost_model(C.Structure):
 class cf_plan_opts(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("chunk_tokens", "l_delta", "n_layers",
                                          "kv_bytes_per_token_layer", "force_mode", "io_key",
-                                         "kv_only_permille")]
+                                         "kv_only_permille", "boundary_bytes_per_token")]
 
 
 class cf_split(C.Structure):
@@ -108,7 +108,8 @@ class cf_overlap_model(C.Structure):
 
 class cf_batch_plan_opts(C.Structure):
     _fields_ = [("chunk_tokens", C.c_int32), ("l_delta", C.c_int32), ("force_mode", C.c_int32),
-                ("io_key", C.c_int32), ("pipelined_join", C.c_int32), ("stage_layers", C.c_int32)]
+                ("io_key", C.c_int32), ("pipelined_join", C.c_int32), ("stage_layers", C.c_int32),
+                ("stage_first_layer", C.c_int32)]
 
 
 class cf_batch_plan(C.Structure):
@@ -240,9 +241,9 @@ def cost_model(f_c, alpha, beta, f_io, gamma, s_c=0, s_io=0):
 
 
 def plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode=-1,
-              io_key=CF_KEY_REMAINING_COST, kv_only_permille=0):
+              io_key=CF_KEY_REMAINING_COST, kv_only_permille=0, boundary_bytes_per_token=0):
     return cf_plan_opts(chunk_tokens, l_delta, n_layers, kv_bytes_per_token_layer, force_mode,
-                        io_key, kv_only_permille)
+                        io_key, kv_only_permille, boundary_bytes_per_token)
 
 
 def restore_plan(cost, opts, n_ctx, trace_cap=0):
@@ -266,9 +267,10 @@ def overlap_model(comp_permille=1000, io_permille=1000):
     return cf_overlap_model(int(comp_permille), int(io_permille))
 
 
-def batch_plan_opts(chunk_tokens, l_delta, force_mode=-1, io_key=0, pipelined_join=True, stage_layers=0):
+def batch_plan_opts(chunk_tokens, l_delta, force_mode=-1, io_key=0, pipelined_join=True, stage_layers=0,
+                    stage_first_layer=0):
     return cf_batch_plan_opts(int(chunk_tokens), int(l_delta), int(force_mode), int(io_key),
-                              int(bool(pipelined_join)), int(stage_layers))
+                              int(bool(pipelined_join)), int(stage_layers), int(stage_first_layer))
 
 
 def plan_batch(cost, overlap, desc, opts, n_ctx, n_new=None):

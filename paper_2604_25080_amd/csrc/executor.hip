@@ -596,8 +596,18 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
         for (size_t si = 0; si < ph.segs.size(); ++si) {
             const Segment& sg = ph.segs[si];
             if (sg.n_rows <= 0) continue;
-            CF_HIP(hipMemcpyAsync(h_rows + (size_t)sg.row0 * d, ph.seg_boundary[si],
-                                  (size_t)sg.n_rows * d * sizeof(float), hipMemcpyHostToDevice, c->cs));
+            // Pinned, device-mapped rows are read over the link by a copy kernel: a DMA copy on
+            // this stream can queue behind the load streams' long transfers on a shared engine.
+            hipPointerAttribute_t at;
+            void* dp = nullptr;
+            if (hipPointerGetAttributes(&at, ph.seg_boundary[si]) == hipSuccess && at.type == hipMemoryTypeHost &&
+                hipHostGetDevicePointer(&dp, const_cast<float*>(ph.seg_boundary[si]), 0) == hipSuccess && dp) {
+                launch_residual_rows(c->cs, h_rows + (size_t)sg.row0 * d, (const float*)dp, nullptr, sg.n_rows, d);
+            } else {
+                (void)hipGetLastError();
+                CF_HIP(hipMemcpyAsync(h_rows + (size_t)sg.row0 * d, ph.seg_boundary[si],
+                                      (size_t)sg.n_rows * d * sizeof(float), hipMemcpyHostToDevice, c->cs));
+            }
         }
     }
     for (int l = l_begin; l < n_layers_max; ++l) {

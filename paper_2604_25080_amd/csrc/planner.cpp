@@ -23,6 +23,7 @@ struct Units {
     int n = 0;                      // context tokens
     std::vector<int64_t> a_prefix;  // a_prefix[u] = sum of recompute cost of units < u
     std::vector<int64_t> b;         // load cost per unit
+    std::vector<int64_t> c_io;      // channel time a RECOMPUTE claim of the unit costs (boundary rows)
     std::vector<int64_t> tok_prefix;
     int m() const { return (int)b.size(); }
     int64_t a(int u) const { return a_prefix[u + 1] - a_prefix[u]; }
@@ -46,6 +47,14 @@ int64_t load_cost(const cf_cost_model& cm, int64_t bytes) {
     return cm.f_io + (int64_t)q;
 }
 
+// channel time of `tokens` boundary-activation rows (no per-transfer term: they ride with the
+// step's metadata)
+int64_t boundary_cost(const cf_cost_model& cm, const cf_plan_opts& o, int64_t tokens) {
+    if (o.boundary_bytes_per_token <= 0) return 0;
+    __int128 num = (__int128)tokens * o.boundary_bytes_per_token * cm.gamma;
+    return (int64_t)((num + ((__int128)1 << 20) - 1) >> 20);
+}
+
 int mode_of(const cf_plan_opts& o, int n) {
     if (o.force_mode == CF_TOKEN_WISE || o.force_mode == CF_LAYER_WISE) return o.force_mode;
     return n >= o.l_delta ? CF_TOKEN_WISE : CF_LAYER_WISE;
@@ -67,6 +76,7 @@ Units make_units(const cf_cost_model& cm, const cf_plan_opts& o, int n, int mode
                             : layer_pass_cost(cm, o.n_layers, t, s);
             u.a_prefix.push_back(u.a_prefix.back() + a);
             u.b.push_back(load_cost(cm, t * o.n_layers * (int64_t)o.kv_bytes_per_token_layer));
+            u.c_io.push_back(boundary_cost(cm, o, t));
             u.tok_prefix.push_back(u.tok_prefix.back() + t * o.n_layers);
         }
     } else {
@@ -76,6 +86,7 @@ Units make_units(const cf_cost_model& cm, const cf_plan_opts& o, int n, int mode
                                                            : layer_pass_cost(cm, 1, n, 0);
             u.a_prefix.push_back(u.a_prefix.back() + a);
             u.b.push_back(load_cost(cm, (int64_t)n * o.kv_bytes_per_token_layer));
+            u.c_io.push_back(l == 0 ? boundary_cost(cm, o, n) : 0);
             u.tok_prefix.push_back(u.tok_prefix.back() + n);
         }
     }
@@ -91,6 +102,8 @@ int check(const cf_cost_model* cm, const cf_plan_opts* o, int32_t B, const int32
                         who);
     if (o->kv_only_permille < 0 || o->kv_only_permille > 1000)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: kv_only_permille %d not in 0..1000", who, o->kv_only_permille);
+    if (o->boundary_bytes_per_token < 0)
+        return cf::fail(CF_ERR_INVALID_ARG, "%s: boundary_bytes_per_token < 0", who);
     if (o->io_key < 0 || o->io_key > CF_KEY_MARGINAL || o->force_mode < -1 || o->force_mode > 1)
         return cf::fail(CF_ERR_INVALID_ARG, "%s: bad io_key or force_mode", who);
     if (cm->f_c < 0 || cm->alpha < 0 || cm->beta < 0 || cm->f_io < 0 || cm->gamma < 0 ||
@@ -159,6 +172,7 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
     }
     int64_t t_c = cost->s_c, t_io = cost->s_io;   // clocks start after the engines' start-up
     int n_c = 0, n_io = 0;
+    bool boundary_moved = false;                  // the channel carried boundary rows
     int rr = 0, n_claims = 0, n_trace = 0;
     auto live = [&](int i) { return pc[i] <= pio[i]; };
 
@@ -172,6 +186,9 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
         if (fin_c <= fin_io) {
             cl = {0, ic, pc[ic]};
             t_c = fin_c;
+            // a stage above layer 0 recomputes from boundary rows that cross the host link
+            t_io += req[ic].c_io[pc[ic]];
+            boundary_moved |= req[ic].c_io[pc[ic]] > 0;
             ++n_c;
             ++pc[ic];
             if (!live(ic)) --n_live;
@@ -198,7 +215,7 @@ extern "C" int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* op
         }
     }
     if (n_c == 0) t_c = 0;     // an engine that claimed nothing never started
-    if (n_io == 0) t_io = 0;
+    if (n_io == 0 && !boundary_moved) t_io = 0;
     if (stats) {
         stats->t_comp = t_c;
         stats->t_io = t_io;
@@ -230,6 +247,10 @@ extern "C" int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts,
         if (n_comp > u.m()) n_comp = u.m();
         tc += u.a_prefix[n_comp];
         for (int v = n_comp; v < u.m(); ++v) tio += u.b[v];
+        for (int v = 0; v < n_comp; ++v) {
+            tio += u.c_io[v];
+            any_io |= u.c_io[v] > 0;
+        }
         any_c |= n_comp > 0;
         any_io |= n_comp < u.m();
     }
@@ -358,6 +379,10 @@ extern "C" int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* 
     po.force_mode = bo->force_mode;
     po.io_key = bo->io_key;
     po.kv_only_permille = (int32_t)((1000 * qkv + lin / 2) / lin);
+    po.boundary_bytes_per_token = (bo->stage_layers > 0 && bo->stage_first_layer > 0) ? (int32_t)(4 * d) : 0;
+    if (bo->stage_first_layer < 0 || bo->stage_first_layer + L > desc->n_layers)
+        return cf::fail(CF_ERR_INVALID_ARG, "cf_plan_batch: stage [%d, %d) outside the model's %d layers",
+                        bo->stage_first_layer, bo->stage_first_layer + L, desc->n_layers);
     int rc = check(cost, &po, B, n_ctx, "cf_plan_batch");
     if (rc) return rc;
     // a stage pays its share of the per-pass start-up and has no new turn of its own
@@ -425,7 +450,7 @@ extern "C" int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* 
     rc = cf_plan_eval(&base, &po, B, n_ctx, sp_r.data(), &r_c, &r_io);
     if (rc) return rc;
     const Times tl = times_of(base.s_c, prefill, 0, l_io);
-    const Times tr = times_of(base.s_c, prefill, r_c > 0 ? r_c + (piped ? prefill : 0) : 0, 0);
+    const Times tr = times_of(base.s_c, prefill, r_c > 0 ? r_c + (piped ? prefill : 0) : 0, r_io);   // boundary rows, if any
     const int64_t ttft_h = th.ttft, ttft_l = tl.ttft, ttft_r = tr.ttft;
     // 5. / 6. the best candidate
     int kind = CF_PLAN_HYBRID;
@@ -444,7 +469,7 @@ extern "C" int cf_plan_batch(const cf_cost_model* cost, const cf_overlap_model* 
         info->prefill_ps = prefill;
         const Times& tc = kind == CF_PLAN_HYBRID ? th : (kind == CF_PLAN_ALL_LOAD ? tl : tr);
         info->t_comp = tc.t_comp;
-        info->t_io = kind == CF_PLAN_HYBRID ? st_h.t_io : (kind == CF_PLAN_ALL_LOAD ? l_io : 0);
+        info->t_io = kind == CF_PLAN_HYBRID ? st_h.t_io : (kind == CF_PLAN_ALL_LOAD ? l_io : r_io);
         info->ttft = best;
         info->ttft_hybrid = ttft_h;
         info->ttft_all_load = ttft_l;

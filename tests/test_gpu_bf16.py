@@ -368,7 +368,9 @@ def test_stage_restore_from_boundary_activations(mini):
             reqs, splits = [], []
             for i, n in enumerate(b.n_ctx):
                 sess.cache.alloc(1 + i, n + b.n_new[i])
-                bh = torch.from_numpy(np.ascontiguousarray(hidden[i][lb], dtype=np.float32)).pin_memory()
+                bh = torch.from_numpy(np.ascontiguousarray(hidden[i][lb], dtype=np.float32))
+                if (lb, le) != (1, 2):        # pinned rows are read by a kernel, pageable ones by a DMA copy
+                    bh = bh.pin_memory()
                 reqs.append(dict(req_id=1 + i, ctx_tokens=b.ctx_tokens[i], new_tokens=b.new_tokens[i],
                                  host_kv=host[i], boundary_h=bh.data_ptr(), _keep=bh))
                 splits.append((0, int(rng.integers(0, n + 1)), int(rng.integers(0, le - lb + 1))))

@@ -19,9 +19,9 @@ def both_cost(d):
     return P.CostModel(**d), cf.cost_model(**d)
 
 
-def both_opts(chunk, l_delta, n_layers, kvb, mode=-1, key=0, kv_only=0):
-    return (P.PlanOpts(chunk, l_delta, n_layers, kvb, mode, key, kv_only),
-            cf.plan_opts(chunk, l_delta, n_layers, kvb, mode, key, kv_only))
+def both_opts(chunk, l_delta, n_layers, kvb, mode=-1, key=0, kv_only=0, boundary=0):
+    return (P.PlanOpts(chunk, l_delta, n_layers, kvb, mode, key, kv_only, boundary),
+            cf.plan_opts(chunk, l_delta, n_layers, kvb, mode, key, kv_only, boundary))
 
 
 # ------------------------------------------------------------------ C-ABI surface
@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_cost_model) == 56
-    assert ctypes.sizeof(cf.cf_plan_opts) == 28
+    assert ctypes.sizeof(cf.cf_plan_opts) == 32
     assert ctypes.sizeof(cf.cf_split) == 12
     assert ctypes.sizeof(cf.cf_plan_stats) == 32
     assert ctypes.sizeof(cf.cf_model_desc) == 40
@@ -46,7 +46,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cf.cf_dynamic_stats) == 40
     assert ctypes.sizeof(cf.cf_dynamic_opts) == 24
     assert ctypes.sizeof(cf.cf_overlap_model) == 8
-    assert ctypes.sizeof(cf.cf_batch_plan_opts) == 24
+    assert ctypes.sizeof(cf.cf_batch_plan_opts) == 28
     assert ctypes.sizeof(cf.cf_batch_plan) == 72
 
 
@@ -67,7 +67,8 @@ def test_planner_matches_oracle_on_random_batches():
         chunk = 16 * int(rng.integers(1, 40))
         oo, co = both_opts(chunk, int(rng.choice([0, 300, 2000, 10 ** 6])), int(rng.integers(1, 40)),
                            int(rng.choice([512, 4096, 1024])), int(rng.integers(-1, 2)),
-                           int(rng.integers(0, 3)), int(rng.choice([0, 0, 115, 98, 1000])))
+                           int(rng.integers(0, 3)), int(rng.choice([0, 0, 115, 98, 1000])),
+                           int(rng.choice([0, 0, 512, 16384, 32768])))
         n_ctx = [int(rng.integers(0, 6000)) for _ in range(int(rng.integers(1, 12)))]
         otrace = []
         osplits, ostats = P.plan(ocm, oo, n_ctx, trace=otrace)
@@ -95,7 +96,8 @@ def test_plan_eval_and_l_delta_match_oracle():
     for _ in range(100):
         d = hand_cost_model(str(rng.choice(["mi355x_like", "balanced", "slow_io", "uniform", "startup"])))
         ocm, ccm = both_cost(d)
-        oo, co = both_opts(64 * int(rng.integers(1, 9)), 0, int(rng.integers(1, 33)), 4096, int(rng.integers(0, 2)))
+        oo, co = both_opts(64 * int(rng.integers(1, 9)), 0, int(rng.integers(1, 33)), 4096, int(rng.integers(0, 2)),
+                           boundary=int(rng.choice([0, 16384])))
         n_ctx = [int(rng.integers(1, 5000)) for _ in range(3)]
         splits, _ = P.plan(ocm, oo, n_ctx)
         units = [(-(-s[1] // oo.chunk_tokens) if s[0] == 0 else s[2]) for s in splits]
@@ -179,10 +181,11 @@ def test_planning_policy_matches_oracle_on_random_batches_and_hand_cases():
         chunk = int(rng.choice([16, 256, 512]))
         l_delta = int(rng.choice([0, 1024, 4096]))
         mode, key, piped = int(rng.integers(-1, 2)), int(rng.integers(0, 3)), bool(rng.integers(0, 2))
-        stage = int(rng.integers(1, sh.n_layers + 1)) if trial % 7 == 0 else 0
-        want_sp, want = P.plan_batch(ocm, ov, model, chunk, l_delta, mode, key, piped, n_ctx, n_new, stage)
+        stage = int(rng.integers(1, sh.n_layers + 1)) if trial % 7 == 0 or trial % 11 == 0 else 0
+        first = int(rng.integers(0, sh.n_layers - stage + 1)) if stage else 0
+        want_sp, want = P.plan_batch(ocm, ov, model, chunk, l_delta, mode, key, piped, n_ctx, n_new, stage, first)
         cov = cf.overlap_model(*ov)
-        got_sp, info = cf.plan_batch(ccm, cov, desc, cf.batch_plan_opts(chunk, l_delta, mode, key, piped, stage),
+        got_sp, info = cf.plan_batch(ccm, cov, desc, cf.batch_plan_opts(chunk, l_delta, mode, key, piped, stage, first),
                                      n_ctx, n_new)
         assert got_sp == want_sp, (trial, got_sp, want_sp)
         got = info.as_dict()
@@ -205,6 +208,11 @@ def test_planning_policy_matches_oracle_on_random_batches_and_hand_cases():
     with pytest.raises(cf.CfError):
         cf.plan_batch(cf.cost_model(**hand_cost_model("startup")), cf.overlap_model(), cf.model_desc(sh),
                       cf.batch_plan_opts(512, 0, stage_layers=33), [4096])
+    with pytest.raises(cf.CfError):         # the stage must lie inside the model
+        cf.plan_batch(cf.cost_model(**hand_cost_model("startup")), cf.overlap_model(), cf.model_desc(sh),
+                      cf.batch_plan_opts(512, 0, stage_layers=8, stage_first_layer=25), [4096])
+    with pytest.raises(cf.CfError):
+        cf.restore_plan(cf.cost_model(**hand_cost_model("startup")), cf.plan_opts(512, 0, 32, 4096, boundary_bytes_per_token=-1), [4096])
 
 
 def test_run_time_scheduling_calls_match_oracle_on_random_states():

@@ -127,6 +127,78 @@ def test_last_recomputed_layer_costs_only_its_kv_projection():
         assert sum(k * c for _, k, c in s1) >= sum(k * c for _, k, c in s0)
 
 
+def test_boundary_rows_of_a_stage_above_layer_0_cost_the_channel_hand_cases():
+    """A stage above layer 0 recomputes from cached stage-input rows that cross the same link
+    as the KV (Sec. 3.2).  gamma = 2^20 makes a byte cost 1: by hand, a token-wise chunk costs
+    the channel tokens * bytes when it is RECOMPUTED, a layer-wise request all its rows at the
+    first layer it recomputes and nothing after.  Hand trace, one request, 4 units of 16 tokens,
+    a = 100 each, b = 16 tokens * 1 layer * 6 B = 96 each, boundary 2 B per token -> 32 per
+    recomputed chunk:
+      (0,0)   compute 100 vs I/O 96   -> I/O takes unit 3        t_io  96
+      (0,96)  100 vs 192              -> compute takes unit 0    t_c 100, t_io 96 + 32 = 128
+      (100,128) 200 vs 224            -> compute takes unit 1    t_c 200, t_io 160
+      (200,160) 300 vs 256            -> I/O takes unit 2        t_io 256
+    Without the term the fourth step is the same but the channel ends at 192."""
+    cm = P.CostModel(f_c=4, alpha=6, beta=0, f_io=0, gamma=1 << 20)
+    o = P.PlanOpts(16, 0, 3, 2, P.TOKEN_WISE, boundary_bytes_per_token=2)
+    assert P.boundary_costs(cm, o, 40, P.TOKEN_WISE) == [32, 32, 16]
+    assert P.boundary_costs(cm, o, 40, P.LAYER_WISE) == [80, 0, 0]
+    odd = P.CostModel(f_c=4, alpha=6, beta=0, f_io=9, gamma=(1 << 20) + 1)
+    assert P.boundary_costs(odd, o, 40, P.TOKEN_WISE) == [33, 33, 17]     # ceil, no f_io
+    assert P.boundary_costs(cm, P.PlanOpts(16, 0, 3, 2, P.TOKEN_WISE), 40, P.TOKEN_WISE) == [0, 0, 0]
+    a, b, _ = P.unit_costs(P.CostModel(f_c=0, alpha=0, beta=0, f_io=0, gamma=1 << 20), o, 64, P.TOKEN_WISE)
+    assert b == [96] * 4
+    # a = 100 per unit: f_c = 100 with ONE layer; b = 16 tokens * 1 layer * 6 B = 96
+    cm1 = P.CostModel(f_c=100, alpha=0, beta=0, f_io=0, gamma=1 << 20)
+    o1 = P.PlanOpts(16, 0, 1, 6, P.TOKEN_WISE, boundary_bytes_per_token=2)
+    trace = []
+    splits, st = P.plan(cm1, o1, [64], trace)
+    assert trace == [(1, 0, 3), (0, 0, 0), (0, 0, 1), (1, 0, 2)]
+    assert splits == [(P.TOKEN_WISE, 32, 1)] and (st["t_comp"], st["t_io"]) == (200, 256)
+    assert P.split_times(cm1, o1, [64], [2]) == (200, 256)
+    assert P.split_times(cm1, o1, [64], [4]) == (400, 128)    # all recomputed: the rows still travel
+    assert P.split_times(cm1, o1, [64], [0]) == (0, 384)
+    o0 = P.PlanOpts(16, 0, 1, 6, P.TOKEN_WISE)
+    splits, st = P.plan(cm1, o0, [64])
+    assert splits == [(P.TOKEN_WISE, 32, 1)] and (st["t_comp"], st["t_io"]) == (200, 192)
+    # layer-wise, 3 layers of 40 tokens: the first recomputed layer brings 80, the next nothing
+    ol = P.PlanOpts(16, 0, 3, 2, P.LAYER_WISE, boundary_bytes_per_token=2)
+    assert P.split_times(cm1, ol, [40], [1]) == (100, 2 * 80 + 80)
+    assert P.split_times(cm1, ol, [40], [2]) == (200, 80 + 80)
+    assert P.split_times(cm1, ol, [40], [3]) == (300, 80)
+
+
+def test_boundary_rows_plans_are_consistent_and_near_brute_force():
+    """The plan's clocks are those of its own splits; with boundary rows cheaper than the KV
+    they replace (any stage of two layers or more at these sizes) the two-pointer schedule stays
+    within one unit of the brute-force optimum; zero bytes change nothing."""
+    rng = np.random.default_rng(29)
+    n_equal = 0
+    trials = 300
+    for trial in range(trials):
+        cm = rand_cm(rng, startups=trial % 3 == 0)
+        L = int(rng.integers(2, 5))
+        kvb = int(rng.choice([512, 4096]))
+        bb = int(rng.integers(1, kvb * L)) if trial % 5 else 0
+        opts = P.PlanOpts(32, int(rng.choice([0, 64, 10_000])), L, kvb, boundary_bytes_per_token=bb)
+        n_ctx = [int(rng.integers(1, 32 * 5)) for _ in range(int(rng.integers(1, 4)))]
+        splits, st = P.plan(cm, opts, n_ctx)
+        units = [(-(-k // 32) if m == P.TOKEN_WISE else c) for (m, k, c) in splits]
+        assert P.split_times(cm, opts, n_ctx, units) == (st["t_comp"], st["t_io"]), (trial, n_ctx)
+        if bb == 0:
+            o0 = P.PlanOpts(32, opts.l_delta, L, kvb)
+            assert P.plan(cm, o0, n_ctx) == (splits, st)
+        best, _ = P.brute_force(cm, opts, n_ctx)
+        worst = 0
+        for n in n_ctx:
+            mode = P.request_mode(opts, n)
+            a, b, _ = P.unit_costs(cm, opts, n, mode)
+            worst = max(worst, max(a), max(b) + max(P.boundary_costs(cm, opts, n, mode)))
+        assert best <= st["makespan"] <= best + worst, (trial, n_ctx, cm, opts)
+        n_equal += st["makespan"] == best
+    assert n_equal > trials // 5
+
+
 def test_tiny_batches_shared_model_full_chunks_match_brute_force():
     rng = np.random.default_rng(22)
     for trial in range(400):
@@ -580,6 +652,14 @@ def test_policy_new_turn_on_the_compute_clock():
     # a pipeline stage of one of the two layers: half the start-up, no new turn of its own
     _, info = P.plan_batch(su, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64], [16], stage_layers=1)
     assert info["prefill_ps"] == 0 and info["ttft_all_recompute"] == 500 + 4 * 5328
+    # the same stage as the model's SECOND layer recomputes from float32 boundary rows (64 B per
+    # token, 16 * 64 * 20 = 20480 per chunk) over the link its KV (10240 per chunk) would take:
+    # every recomputed chunk costs the channel twice what loading it would, so recompute always
+    # wins the next claim, the channel ends at 4 * 20480, and loading everything (40960) is chosen
+    sp, info = P.plan_batch(su, (1000, 1000), HAND_MODEL, 16, 0, 0, 0, True, [64], [16], stage_layers=1,
+                            stage_first_layer=1)
+    assert info["ttft_all_recompute"] == 81920 and info["ttft_hybrid"] == 81920
+    assert info["kind"] == P.PLAN_ALL_LOAD and info["ttft"] == 40960 and sp == [(0, 0, 1)]
 
 
 def test_policy_feedback_hand_values():
