@@ -148,7 +148,9 @@ int cf_restore_plan(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t
 
 /* (t_comp, t_io) in ps of a given split vector under the cost model, with the
  * same unit accounting as the planner (k_tokens rounded up to whole chunks in
- * token-wise mode).  splits: host cf_split[B] whose `mode` fields are used.  */
+ * token-wise mode; with boundary_bytes_per_token set, t_io includes the
+ * boundary rows of what is recomputed, also when nothing is loaded).  splits:
+ * host cf_split[B] whose `mode` fields are used.                            */
 int cf_plan_eval(const cf_cost_model* cost, const cf_plan_opts* opts, int32_t B,
                  const int32_t* n_ctx, const cf_split* splits, int64_t* t_comp,
                  int64_t* t_io);
