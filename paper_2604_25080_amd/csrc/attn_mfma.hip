@@ -64,11 +64,22 @@ attention_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, float*
     constexpr int D_TILES = HD / 32;
     __shared__ __align__(16) char smem[2 * STAGE];
 
-    // heaviest work items (largest positions) are scheduled first
-    AttnWork w = work[gridDim.x - 1 - blockIdx.x];
+    // Workgroup ids are item-major and walk the work list backwards: the host lists the items of
+    // a launch lightest first (new-turn items: sorted by key tiles; recompute items: in row
+    // order, a request's later rows see more keys), and all head blocks of an item are dispatched
+    // before the next item's, so the launch ends with its lightest items on every head instead
+    // of a few long ones running alone.  Consecutive workgroups go to different
+    // XCDs, eight apart to the same one: the head blocks of an item are numbered so that those
+    // that share a KV head (and its K/V tiles in L2) are a multiple of the KV-head count apart.
+    const int n_blocks_h = n_q_heads / HPB;                          // head blocks per item
+    const int per_kv = (n_q_heads / g.n_kv_heads) / HPB;             // ... of which share a KV head
+    const int n_kv_b = n_blocks_h / per_kv;
+    const int item = blockIdx.x / n_blocks_h, hb = blockIdx.x % n_blocks_h;
+    AttnWork w = work[gridDim.x / n_blocks_h - 1 - item];
     int tid = threadIdx.x, lane = tid & 63;
     int wave = (tid >> 6) & 3;                     // which 32 query rows
-    int head = blockIdx.y * HPB + (tid >> 8);      // wavefronts 4-7 take the second head of the pair
+    // wavefronts 4-7 take the second head of the pair
+    int head = ((hb % n_kv_b) * per_kv + hb / n_kv_b) * HPB + (tid >> 8);
     int gk = head / (n_q_heads / g.n_kv_heads);    // the same KV head for both (group size is even)
     const int32_t* pt = page_tables + w.pt_off;
     int lq = lane & 31, lh = lane >> 5;
@@ -347,7 +358,7 @@ void launch_attention_mfma(hipStream_t s, const void* q, void* out, float* part_
                            int n_q_heads, KvGeom g) {
     if (n_work <= 0) return;
     const bool pair = attention_mfma_heads_per_block(n_q_heads, g.n_kv_heads) == 2;
-    dim3 grid(n_work, pair ? n_q_heads / 2 : n_q_heads);
+    dim3 grid((unsigned)n_work * (pair ? n_q_heads / 2 : n_q_heads));
     if (g.head_dim == 128 && pair)
         attention_mfma_kernel<128, 2><<<grid, 512, 0, s>>>((const bf16*)q, (bf16*)out, part_buf, (const bf16*)pool_layer, work, page_tables, n_q_heads, g);
     else if (g.head_dim == 128)

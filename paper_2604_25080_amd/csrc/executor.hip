@@ -521,6 +521,13 @@ void build_chunks(Phase& ph, int chunk_rows, const std::vector<int>& pt_off, int
         ci.n_work = (int)ph.work.size() - ci.work_off;
         ci.n_grp = (int)ph.groups.size() - ci.grp_off;
         if (n_items_rec == (int)items.size()) { ci.n_work_rec = ci.n_work; ci.n_grp_rec = ci.n_grp; }
+        // The kernel walks a launch's list backwards.  New-turn items (one launch per layer, contexts
+        // of very different lengths) are listed lightest first so that the launch starts with its
+        // longest items; recompute items stay in row order: a layer launches a prefix of them.
+        std::stable_sort(ph.work.begin() + ci.work_off + ci.n_work_rec, ph.work.end(),
+                         [](const AttnWork& a, const AttnWork& b) {
+                             return a.tile_end - a.tile_begin < b.tile_end - b.tile_begin;
+                         });
         ph.chunks.push_back(ci);
     }
 }
