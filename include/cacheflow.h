@@ -472,10 +472,12 @@ typedef struct cf_timing {
     float suffix_ms;      /* total_ms - restore_ms: what the new-turn prefill and
                              the logits add after restoration                    */
     float total_ms;       /* call start -> logits ready (batch TTFT)             */
-    float compute_wait_ms;/* of that, time the compute stream stood still waiting
-                             for loaded KV (pipelined join: the new-turn attention
-                             of a layer waits for that layer's loads); a compute
-                             stream that ends late because it WAITED is not slow  */
+    float compute_wait_ms;/* of compute_ms, time the compute stream stood still
+                             waiting for loaded KV (pipelined join: the new-turn
+                             attention of a layer waits for that layer's loads;
+                             waits above the last recomputed layer lie after
+                             compute_ms and are not counted); a compute stream
+                             that ends late because it WAITED is not slow         */
     double recompute_flops; /* algorithmic: linear layers + causal pairs needed  */
     double suffix_flops;
     int64_t loaded_bytes; /* KV bytes that crossed the host link                 */

@@ -1326,12 +1326,19 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     c->caprows_out = nullptr;         // one shot
     c->caprows_dev = nullptr;
     float wait_ms = 0;
+    int rec_layers = 0;               // layers in which context rows were still recomputed
+    for (const Segment& sg : rec.segs)
+        if (!sg.is_new) rec_layers = std::max(rec_layers, sg.layers);
     for (int l = 0; l < (int)c->waited.size(); ++l) {
         if (!c->waited[l]) continue;
+        c->waited[l] = 0;
+        // only the waits inside compute_ms count: those of the layers that still recomputed
+        // (a layer-wise cut ends the recompute early; the new-turn rows of the layers above it
+        // wait for their loads after the compute measurement has ended)
+        if (l >= rec_layers) continue;
         float w = 0;
         if (hipEventElapsedTime(&w, c->ev_wait[2 * l], c->ev_wait[2 * l + 1]) == hipSuccess) wait_ms += w;
         else (void)hipGetLastError();
-        c->waited[l] = 0;
     }
     if (timing) {
         float t_comp = 0, t_copy = 0, t_join = 0, t_end = 0;
