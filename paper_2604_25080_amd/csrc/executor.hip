@@ -1945,6 +1945,18 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         // metadata: behind a running step its arrays are still in use (the copy of them may not
         // even have left the pinned mirror yet), so the tail's go after them
         if (!behind_step) mw.off = step_off;
+        // as in the planned restore: when the load kernel only has the ragged ends, one launch
+        // ahead of the first transfer moves them for all layers (units numbered through)
+        int64_t tail_kernel_bytes = 0, tail_bytes = 0;
+        int tail_units = 0;
+        for (const PageJob& jb : tjobs) tail_kernel_bytes += (int64_t)jb.n_pages * (int64_t)pb;
+        for (const LayerLoad& tl : tlayers) tail_bytes += (int64_t)tl.bytes;
+        const bool tail_upfront = !tdma.empty() && tail_kernel_bytes > 0 && tail_kernel_bytes * 16 <= tail_bytes;
+        if (tail_upfront)
+            for (const LayerLoad& tl : tlayers) {
+                for (int k = 0; k < tl.n_jobs; ++k) tjobs[tl.job_first + k].block_first += tail_units;
+                tail_units += tl.n_vblocks;
+            }
         const size_t off_tjobs = mw.put(tjobs.data(), tjobs.size() * sizeof(PageJob));
         const size_t off_rows = mw.off;
         finish_phase(step, ids, pos, slot);
@@ -1972,6 +1984,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 if (hipEventRecord(c->dyn_events[2 * IO_DEPTH + 1], c->ps) != hipSuccess) return -1;
                 tail_timed = true;
                 tail_beside = step_has_rec || with_rec;
+                if (tail_upfront)
+                    launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs), (int)tjobs.size(),
+                                     tail_units, c->load_wgs, (const int32_t*)md, g);
             }
             const LayerLoad& tl = tlayers[tail_next];
             if (tl.n_jobs > 0 || tl.n_dma > 0) {
@@ -1979,8 +1994,9 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
                 if (issue_layer_dma(c->ps, c->ss, c->ev_q2, c->ev_scat, c->dma_queues > 1 && c->throttle_gbs <= 0,
                                     tail_q2_recorded, tdma.data() + tl.dma_first, tl.n_dma) < 0)
                     return -1;
-                launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs) + tl.job_first,
-                                 tl.n_jobs, tl.n_vblocks, c->load_wgs, (const int32_t*)md, g);
+                if (!tail_upfront)
+                    launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_tjobs) + tl.job_first,
+                                     tl.n_jobs, tl.n_vblocks, c->load_wgs, (const int32_t*)md, g);
                 if (c->throttle_gbs > 0) {
                     paced_bytes += (double)tl.bytes;
                     launch_pace_wait(c->ps, c->pace_dev(),
