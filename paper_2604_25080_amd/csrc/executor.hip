@@ -1144,22 +1144,20 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     // Direct path with DMA: what is left to the load kernel are the ragged ends of the runs (and
     // runs too short for a transfer).  A launch per layer would have each of them queue for
     // compute units behind the GEMM that happens to run (measured: 0.2 ms per layer for a few
-    // hundred KB, 7 ms of a 175 ms copy stream), so when they are a small part of the bytes ONE
-    // launch moves them all before the first transfer, while the GPU is still idle; the units of
-    // its jobs are then numbered through all layers.  With much of the volume on the kernel (a
-    // fragmented pool) the launches stay per layer: a layer's event must not wait for all loads.
+    // hundred KB, 7 ms of a 175 ms copy stream), so when they are a small part of the bytes (1/64:
+    // what goes first delays the first layer's loads) ONE launch moves them all before the first
+    // transfer, while the GPU is still idle; the units of its jobs are then numbered through all
+    // layers.  With more of the volume on the kernel (a fragmented pool, a short request whose
+    // runs stay under the transfer size) the launches stay per layer: a layer's event must not
+    // wait for all loads.  A paced link charges the bytes to their layers either way.
     int64_t kernel_bytes = 0;
     int upfront_units = 0;
     if (direct)
         for (const PageJob& jb : jobs) kernel_bytes += (int64_t)jb.n_pages * (int64_t)cache->page_bytes;
-    const bool upfront = direct && !dma_ops.empty() && kernel_bytes > 0 && kernel_bytes * 16 <= loaded_bytes;
+    const bool upfront = direct && !dma_ops.empty() && kernel_bytes > 0 && kernel_bytes * 64 <= loaded_bytes;
     if (upfront)
         for (LayerLoad& ll : layer_loads) {
-            for (int k = 0; k < ll.n_jobs; ++k) {
-                PageJob& jb = jobs[ll.job_first + k];
-                jb.block_first += upfront_units;
-                ll.bytes -= (size_t)jb.n_pages * cache->page_bytes;     // accounted to the one launch
-            }
+            for (int k = 0; k < ll.n_jobs; ++k) jobs[ll.job_first + k].block_first += upfront_units;
             upfront_units += ll.n_vblocks;
         }
     size_t off_jobs = mw.put(jobs.data(), jobs.size() * sizeof(PageJob));
@@ -1225,13 +1223,9 @@ extern "C" int cf_restore_batch(cf_ctx* c, cf_cache* cache, int32_t B, const cf_
     }
     size_t loads_enqueued = 0;
     bool q2_recorded = false;
-    if (upfront) {
-        c->prof_begin(CF_K_H2D_COPY, (double)kernel_bytes, c->ps);
+    if (upfront)
         launch_page_load(c->ps, m.dtype, cache->pool, (const PageJob*)(md + off_jobs), (int)jobs.size(),
                          upfront_units, c->load_wgs, (const int32_t*)md, g);
-        pace((double)kernel_bytes);
-        c->prof_end(CF_K_H2D_COPY, c->ps);
-    }
     auto enqueue_load = [&](const LayerLoad& ll) -> int {
         c->prof_begin(CF_K_H2D_COPY, (double)ll.bytes, c->ps);
         if (issue_layer_dma(c->ps, c->ss, c->ev_q2, c->ev_scat, c->dma_queues > 1 && c->throttle_gbs <= 0,
@@ -1951,7 +1945,7 @@ extern "C" int cf_restore_dynamic(cf_ctx* c, cf_cache* cache, int32_t B, const c
         int tail_units = 0;
         for (const PageJob& jb : tjobs) tail_kernel_bytes += (int64_t)jb.n_pages * (int64_t)pb;
         for (const LayerLoad& tl : tlayers) tail_bytes += (int64_t)tl.bytes;
-        const bool tail_upfront = !tdma.empty() && tail_kernel_bytes > 0 && tail_kernel_bytes * 16 <= tail_bytes;
+        const bool tail_upfront = !tdma.empty() && tail_kernel_bytes > 0 && tail_kernel_bytes * 64 <= tail_bytes;
         if (tail_upfront)
             for (const LayerLoad& tl : tlayers) {
                 for (int k = 0; k < tl.n_jobs; ++k) tjobs[tl.job_first + k].block_first += tail_units;
