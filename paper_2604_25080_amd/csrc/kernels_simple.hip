@@ -42,7 +42,10 @@ void launch_embed(hipStream_t s, int dtype, const void* E, const int32_t* tok, f
 // One 256-thread block per row; the row stays in registers between the two passes.
 // With `delta` the pending residual update is folded in first: h += delta (written
 // back unless the rows are gathered through row_idx), then the norm of the new h.
-template <typename T>
+// NV > 0: the row is exactly NV float4 per thread (d = 1024 NV), so nothing in the loops is
+// conditional and all of a thread's loads are in flight together; NV = 0: any d up to 8192.
+// Same order of additions either way, so the same bits.
+template <typename T, int NV>
 __global__ void __launch_bounds__(256)
 rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ delta,
                const float* __restrict__ gain, T* __restrict__ out, int d, float eps,
@@ -53,10 +56,27 @@ rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ delta,
     float* src = h + srow * d;
     const float* dsrc = delta ? delta + srow * d : nullptr;
     T* dst = out + (int64_t)t * d;
-    constexpr int MAXV = 8;                 // d <= 256*4*8 = 8192
+    constexpr int MAXV = NV > 0 ? NV : 8;   // d <= 256*4*8 = 8192
     float4 v[MAXV];
-    int nvec = d / 4;
+    int nvec = NV > 0 ? NV * 256 : d / 4;
     float ss = 0.f;
+    if constexpr (NV > 0) {
+        float4 dv[MAXV];
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i) v[i] = reinterpret_cast<const float4*>(src)[threadIdx.x + i * 256];
+        if (dsrc) {
+#pragma unroll
+            for (int i = 0; i < MAXV; ++i) dv[i] = reinterpret_cast<const float4*>(dsrc)[threadIdx.x + i * 256];
+#pragma unroll
+            for (int i = 0; i < MAXV; ++i) {
+                v[i].x += dv[i].x; v[i].y += dv[i].y; v[i].z += dv[i].z; v[i].w += dv[i].w;
+                if (!row_idx) reinterpret_cast<float4*>(src)[threadIdx.x + i * 256] = v[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i)
+            ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    } else
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
         int idx = threadIdx.x + i * 256;
@@ -92,9 +112,13 @@ void launch_rmsnorm(hipStream_t s, int dtype, float* h, const float* delta, cons
                     void* out, int T, int d, float eps, const int32_t* row_idx) {
     if (T <= 0) return;
     if (dtype == CF_F32)
-        rmsnorm_kernel<float><<<T, 256, 0, s>>>(h, delta, gain, (float*)out, d, eps, row_idx);
+        rmsnorm_kernel<float, 0><<<T, 256, 0, s>>>(h, delta, gain, (float*)out, d, eps, row_idx);
+    else if (d == 4096)
+        rmsnorm_kernel<bf16, 4><<<T, 256, 0, s>>>(h, delta, gain, (bf16*)out, d, eps, row_idx);
+    else if (d == 8192)
+        rmsnorm_kernel<bf16, 8><<<T, 256, 0, s>>>(h, delta, gain, (bf16*)out, d, eps, row_idx);
     else
-        rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(h, delta, gain, (bf16*)out, d, eps, row_idx);
+        rmsnorm_kernel<bf16, 0><<<T, 256, 0, s>>>(h, delta, gain, (bf16*)out, d, eps, row_idx);
 }
 
 // ---------------------------------------------------------------- simple GEMM
