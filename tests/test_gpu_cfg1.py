@@ -165,6 +165,31 @@ def test_cfg1_offload_returns_the_oracle_pages_on_both_paths(env):
             sess.cache.free(1 + i)
 
 
+def test_cfg1_waits_above_a_layer_cut_are_not_counted_as_waits_of_the_recompute(env):
+    """cf_timing.compute_ms ends with the last recomputed layer; compute_wait_ms is the part of it
+    that the stream stood waiting for loads.  With layer 0 recomputed, layer 1 loaded over a
+    slow link and the pipelined join, the new turn's attention in layer 1 waits for nearly the
+    whole copy -- after compute_ms has ended: none of that may show up in compute_wait_ms (the
+    policy subtracts it from compute_ms).  With every layer recomputed for a prefix and the rest
+    loaded, the same waits lie inside compute_ms and are reported."""
+    b, refs, ws, sess, host = env
+    L = b.shape.n_layers
+    assert L == 2
+    try:
+        rate = 0.004                              # GB/s: a copy of ~100 ms against ~1 ms of compute
+        sess.ctx.set_link_throttle(rate)
+        tm = run_and_check(env, [(n, 1) for n in b.n_ctx], seed=31)
+        floor_ms = tm["loaded_bytes"] / (rate * 1e9) * 1e3
+        assert tm["total_ms"] >= 0.9 * floor_ms > 5 * tm["compute_ms"], (tm, floor_ms)
+        assert tm["compute_wait_ms"] <= tm["compute_ms"], tm
+        tm = run_and_check(env, [(n // 2, L) for n in b.n_ctx], seed=32)
+        floor_ms = tm["loaded_bytes"] / (rate * 1e9) * 1e3
+        assert tm["compute_ms"] >= 0.5 * floor_ms, (tm, floor_ms)      # it ended late because it waited ...
+        assert 0.5 * tm["compute_ms"] <= tm["compute_wait_ms"] <= tm["compute_ms"], tm     # ... and says so
+    finally:
+        sess.ctx.set_link_throttle(0.0)
+
+
 def test_cfg1_link_throttle_paces_the_copy_stream_and_changes_no_result(env):
     b, refs, ws, sess, host = env
     rate = 0.05                                   # GB/s
