@@ -699,7 +699,7 @@ int run_phase(cf_ctx* c, cf_cache* cache, const Phase& ph, int n_layers_max,
                     if (part == 1 && layer_ready && layer_ready[l]) {
                         // the stall of the compute stream on the copy stream is timed (first wait
                         // of a layer: later chunks of the layer find the event complete)
-                        const bool timed = !c->waited[l] && row_base == 0;
+                        const bool timed = !c->waited[l];
                         if (timed) CF_HIP(hipEventRecord(c->ev_wait[2 * l], c->cs));
                         CF_HIP(hipStreamWaitEvent(c->cs, layer_ready[l], 0));
                         if (timed) {
